@@ -1,0 +1,111 @@
+"""Benchmark of the scheme-scoring hot path on one MI355X.
+
+One step = one aiq_eval_schemes call over the whole workload: scheme upload, weight
+quantization of every (layer, bit-width) the schemes use, the all-FP32 base pass, the
+scheme-batched forward of every layer, classifier head and agreement count.  Inputs
+are resident in HBM before the timed region.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(wl, budget_schemes=8, budget_images=192):
+    """The oracle as it stands on this host's cores, on a bounded sample of the same workload."""
+    import oracle
+    s = min(budget_schemes, wl["schemes"].shape[0])
+    n = min(budget_images, wl["images"].shape[0])
+    sch, img = wl["schemes"][:s], wl["images"][:n]
+    t0 = time.perf_counter()
+    oracle.eval_schemes(wl["desc"], wl["weights"], wl["biases"], img, sch, want_logits=False)
+    dt = time.perf_counter() - t0
+    return {"value": s * n / dt, "unit": "scheme-images/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {s} schemes x first {n} images of the workload (+ its FP32 base pass), {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=2, help="0..4; 2 = ResNet-20 greedy step (headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build scores schemes on ONE GPU; --gpus N with N > 1 is not supported "
+                 "(the (scheme, image) grid would shard across GPUs, see DESIGN.md)")
+
+    import numpy as np
+    import torch
+    import synth
+    import paper_2512_14090_amd as aiq
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; there is no CPU fallback")
+    torch.cuda.set_device(0)
+    aiq.load_library()
+    wl = synth.make_workload(args.workload)
+    S, L = wl["schemes"].shape
+    N = wl["images"].shape[0]
+    chunk = wl["chunk"]
+    model = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    images = torch.from_numpy(wl["images"]).cuda()
+    out = {"top1_base": torch.empty(N, dtype=torch.int32, device="cuda"),
+           "agree": torch.empty(S, dtype=torch.int32, device="cuda")}
+    stream = torch.cuda.current_stream()
+
+    def step():
+        return model.eval_schemes(images, wl["schemes"], chunk=chunk, out=out, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    model.profile_enable(True)
+    for c in range(5):
+        model.profile_read(c)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        r = step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    model.profile_enable(False)
+    prof = {name: model.profile_read(c) for c, name in
+            enumerate(("quantize", "conv_mfma", "depthwise", "head", "agree"))}
+    agree = r["agree"].cpu().numpy()
+
+    ms_per_step = dt / args.steps * 1e3
+    value = S * N * args.steps / dt
+    conv = prof["conv_mfma"]
+    achieved = conv["flops"] / (conv["total_ms"] * 1e-3) / 1e12 if conv["total_ms"] > 0 else 0.0
+    roofline = {"bound": "mfma", "kernel": "conv_mfma_kernel (3x3/1x1 implicit GEMM, fp32 MFMA)",
+                "achieved": achieved, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_MFMA_F32_TFLOPS, "traffic": None,
+                "launches": conv["launches"], "avg_launch_ms": conv["total_ms"] / max(conv["launches"], 1),
+                "algorithmic_gflop_per_launch": conv["flops"] / max(conv["launches"], 1) / 1e9,
+                "algorithmic_gbytes_per_launch": conv["bytes"] / max(conv["launches"], 1) / 1e9}
+    kernels = {k: {"launches": v["launches"], "ms_per_step": v["total_ms"] / args.steps,
+                   "gflop_per_step": v["flops"] / args.steps / 1e9, "gbyte_per_step": v["bytes"] / args.steps / 1e9}
+               for k, v in prof.items()}
+    line = {"metric": "scheme_images_per_sec", "value": value, "unit": "scheme-images/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": wl["name"], "schemes": int(S), "images": int(N), "chunk": int(chunk),
+                       "scheme_layers": int(L), "base_pass_in_step": True,
+                       "agree_min_max": [int(agree.min()), int(agree.max())] if S else []},
+            "roofline": roofline, "kernels": kernels}
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl)
+    model.close()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

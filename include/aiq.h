@@ -1,0 +1,162 @@
+/*
+ * aiq.h - C boundary of the MI355X scheme-scoring library (libaiq.so).
+ *
+ * Arithmetic-Intensity-Aware Quantization searches over per-layer bit-width
+ * schemes q = (q_1 .. q_L); every candidate is scored by (i) an analytic global
+ * arithmetic intensity and (ii) the accuracy of the model with each layer's
+ * weights quantized to q_i bits (paper: Introduction, items (i) and (ii);
+ * Approach, Problem Formulation; Search Over Mixed-Precision Schemes).  This
+ * library is the scoring step: weight quantize-dequantize, a batched forward
+ * pass of all candidate schemes, and top-1 agreement with the FP32 model.  The
+ * search loops stay with the caller.
+ *
+ * Conventions
+ *  - Plain C ABI.  No function throws; every function returns aiq_status.
+ *  - "device" pointers are HIP device memory owned by the caller; "host"
+ *    pointers are ordinary memory.  The library allocates device memory only in
+ *    aiq_model_create (weights and the per-bit-width weight bank) and frees it
+ *    in aiq_model_destroy.
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *    Device work is enqueued on it and not synchronised.
+ *  - Arguments are validated before any device work; on a non-OK status found
+ *    by validation no output buffer has been touched.
+ *  - One aiq_model must not be used from two threads at once.
+ *  - There is no CPU fallback: without a usable GPU every device entry point
+ *    returns AIQ_DEVICE_ERROR.
+ */
+#ifndef AIQ_H
+#define AIQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t aiq_status;
+enum {
+    AIQ_OK = 0,
+    AIQ_INVALID_ARG = 1,        /* null pointer, negative or zero size where not allowed */
+    AIQ_UNSUPPORTED_BITS = 2,   /* bit-width outside {32,16,8,6,4,2} */
+    AIQ_SHAPE_MISMATCH = 3,     /* graph shapes inconsistent, scheme length != L */
+    AIQ_WORKSPACE_TOO_SMALL = 4,
+    AIQ_DEVICE_ERROR = 5,       /* a HIP call failed; see aiq_last_hip_error() */
+    AIQ_UNSUPPORTED_LAYER = 6   /* layer kind / kernel size / stride the kernels do not cover */
+};
+
+/* Static, never NULL. */
+const char *aiq_status_str(aiq_status st);
+/* hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
+int32_t aiq_last_hip_error(void);
+
+/*
+ * One weighted layer of a straight-line graph with residual links.  Nodes are
+ * listed in execution order.  Activations are NHWC fp32.
+ */
+typedef struct {
+    int32_t kind;        /* 0 convolution (groups = 1), 1 depthwise convolution, 2 classifier
+                            (global average pool over hin x win, then a cout x cin matrix) */
+    int32_t cin, cout;
+    int32_t kh, kw;      /* 3x3 or 1x1 (classifier: 1, 1) */
+    int32_t stride;      /* 1 or 2 */
+    int32_t pad;         /* 1 for 3x3, 0 for 1x1 */
+    int32_t hin, win;    /* input spatial size */
+    int32_t input;       /* producing node, -1 = the network input */
+    int32_t residual;    /* node whose output is added before the activation, -1 = none */
+    int32_t act;         /* 0 none, 1 ReLU, 2 ReLU6 */
+    int32_t scheme_slot; /* position i of this layer in a scheme (q_1..q_L), -1 = always FP32 */
+} aiq_layer_desc;
+
+/*
+ * Analytic arithmetic intensity of one scheme (paper: Introduction item (i);
+ * Search Over Mixed-Precision Schemes, closing paragraph).  Host only, pure.
+ *   FLOPs_l = 2 * batch * Hout*Wout*Cout*(Cin/groups)*kh*kw    (classifier: 2*batch*Cin*Cout)
+ *   Bytes_l = n_weights_l * bits_l / 8 + 4 * batch * (in_elems_l + out_elems_l)
+ *   AI      = sum_l FLOPs_l / sum_l Bytes_l
+ * layers:  host, n_layers records.  scheme: host uint8[L], values in {32,16,8,6,4,2};
+ * layers with scheme_slot = -1 count at 32 bits.  flops_per_layer / bytes_per_layer:
+ * host double[n_layers], either may be NULL.  global_ai: host, required.
+ * Errors: INVALID_ARG (null, n_layers <= 0, batch < 1), SHAPE_MISMATCH (a scheme_slot >= L),
+ * UNSUPPORTED_BITS.
+ */
+aiq_status aiq_layer_ai(const aiq_layer_desc *layers, int32_t n_layers, const uint8_t *scheme, int32_t L,
+                        int32_t batch, double *flops_per_layer, double *bytes_per_layer, double *global_ai);
+
+/*
+ * Symmetric per-output-channel quantize -> dequantize of one weight matrix
+ * (paper: Problem Formulation, "bit-width q_i" per layer; the rule itself is
+ * this library's reading): for row c,
+ *   amax = max_k |w[c][k]|, qmax = 2^(bits-1)-1, s = amax/qmax (1 if amax = 0),
+ *   code = clamp(round-half-even(w/s), -qmax, qmax), w_dq = code * s,
+ * each step one IEEE binary32 operation.  bits = 32 copies w and sets s = 1.
+ * w, w_dq: device fp32 [cout][k] row-major (may not alias).  scales: device fp32 [cout].
+ * codes: device int32 [cout][k] or NULL; left untouched when bits = 32.
+ * cout = 0 or k = 0 is a valid no-op.  Asynchronous on hip_stream.
+ * Errors: INVALID_ARG, UNSUPPORTED_BITS, DEVICE_ERROR.
+ */
+aiq_status aiq_quantize_weights(const float *w, int32_t cout, int32_t k, int32_t bits, float *w_dq,
+                                float *scales, int32_t *codes, void *hip_stream);
+
+typedef struct aiq_model aiq_model; /* opaque */
+
+/*
+ * Builds a model: validates the graph, copies weights and biases to the device
+ * and allocates the weight bank (one slot per scheme layer and bit-width).
+ * layers: host.  w_host[l]: host fp32 [cout][k], k = (cin/groups)*kh*kw in (ci, ky, kx)
+ * order, BN already folded.  bias_host[l]: host fp32 [cout].  The network input is
+ * fp32 [hin][win][cin] of node 0 per image.  Synchronous.
+ * Errors: INVALID_ARG, SHAPE_MISMATCH, UNSUPPORTED_LAYER, DEVICE_ERROR.  *out is NULL on error.
+ */
+aiq_status aiq_model_create(const aiq_layer_desc *layers, int32_t n_layers, const float *const *w_host,
+                            const float *const *bias_host, aiq_model **out);
+void aiq_model_destroy(aiq_model *m); /* NULL-safe */
+
+/* L (number of scheme layers) and the classifier width; -1 for a NULL model. */
+int32_t aiq_model_scheme_layers(const aiq_model *m);
+int32_t aiq_model_classes(const aiq_model *m);
+
+/* Device bytes aiq_eval_schemes needs for S schemes processed chunk images at a time. */
+aiq_status aiq_eval_workspace_bytes(const aiq_model *m, int32_t S, int32_t chunk, size_t *bytes);
+
+/*
+ * Scores S candidate schemes on N images (paper: Search Over Mixed-Precision
+ * Schemes - the candidate configurations of one greedy iteration or one
+ * coordinate-descent sweep are scored together).  For every scheme s each scheme
+ * layer is quantized at schemes[s][slot] bits, the network is run on all images
+ * and agree[s] = #{n : argmax logits[s][n] == top1_base[n]} (lowest index wins ties).
+ *
+ * images:    device fp32 [N][hin][win][cin] (NHWC).
+ * schemes:   HOST uint8 [S][L]; read before the call returns.
+ * chunk:     images per pass through the network (>= 1); N need not be a multiple.
+ * top1_base: device int32 [N].  base_valid = 0: the library also runs the all-FP32
+ *            scheme and writes its top-1 here; base_valid = 1: read only.
+ * logits:    device fp32 [S][N][classes] or NULL.   top1: device int32 [S][N] or NULL.
+ * agree:     device int32 [S], overwritten.
+ * workspace: device, >= aiq_eval_workspace_bytes(m, S, chunk), 256-byte aligned.
+ * S = 0 or N = 0 is valid (agree is zero-filled).  Asynchronous on hip_stream.
+ * Errors: INVALID_ARG, UNSUPPORTED_BITS, WORKSPACE_TOO_SMALL, DEVICE_ERROR.
+ */
+aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const uint8_t *schemes, int32_t S,
+                            int32_t chunk, int32_t *top1_base, int32_t base_valid, float *logits,
+                            int32_t *top1, int32_t *agree, void *workspace, size_t workspace_bytes,
+                            void *hip_stream);
+
+/*
+ * Per-kernel timing for roofline reports.  While enabled, aiq_eval_schemes brackets
+ * every launch with HIP events on the launch stream.  aiq_profile_read waits for the
+ * recorded events, then returns for kernel class cls the number of launches, their
+ * summed duration and the algorithmic FLOPs and bytes they covered, and clears the
+ * record for that class.  Classes: 0 quantize, 1 dense convolution (MFMA),
+ * 2 depthwise convolution, 3 classifier head, 4 agreement count.
+ */
+enum { AIQ_K_QUANTIZE = 0, AIQ_K_CONV = 1, AIQ_K_DEPTHWISE = 2, AIQ_K_HEAD = 3, AIQ_K_AGREE = 4,
+       AIQ_K_CLASSES = 5 };
+aiq_status aiq_profile_enable(aiq_model *m, int32_t on);
+aiq_status aiq_profile_read(aiq_model *m, int32_t cls, int64_t *launches, double *total_ms, double *flops,
+                            double *bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AIQ_H */

@@ -1,0 +1,215 @@
+"""ctypes binding of libaiq.so: the same entry points as include/aiq.h, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libaiq.so")
+_lib = None
+
+EXPORTED_SYMBOLS = (
+    "aiq_status_str", "aiq_last_hip_error", "aiq_layer_ai", "aiq_quantize_weights", "aiq_model_create",
+    "aiq_model_destroy", "aiq_model_scheme_layers", "aiq_model_classes", "aiq_eval_workspace_bytes",
+    "aiq_eval_schemes", "aiq_profile_enable", "aiq_profile_read",
+)
+K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE = range(5)
+_DESC_INTS = 13
+
+
+class AiqError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what}: {code}")
+        self.code = code
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads the built library; builds it first only if nothing is built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build(force=True)
+    lib = C.CDLL(_LIB_PATH)
+    lib.aiq_status_str.restype = C.c_char_p
+    lib.aiq_status_str.argtypes = [C.c_int32]
+    lib.aiq_last_hip_error.restype = C.c_int32
+    lib.aiq_layer_ai.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                 C.POINTER(C.c_double)]
+    lib.aiq_quantize_weights.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p]
+    lib.aiq_model_create.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
+    lib.aiq_model_destroy.argtypes = [C.c_void_p]
+    lib.aiq_model_destroy.restype = None
+    lib.aiq_model_scheme_layers.argtypes = [C.c_void_p]
+    lib.aiq_model_classes.argtypes = [C.c_void_p]
+    lib.aiq_eval_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+    lib.aiq_eval_schemes.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
+                                     C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_size_t, C.c_void_p]
+    lib.aiq_profile_enable.argtypes = [C.c_void_p, C.c_int32]
+    lib.aiq_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double),
+                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    for name in EXPORTED_SYMBOLS:
+        getattr(lib, name)
+    _lib = lib
+    return lib
+
+
+def _check(st, what):
+    if st != 0:
+        lib = load_library()
+        msg = lib.aiq_status_str(st).decode()
+        if st == 5:
+            msg += f" (hipError {lib.aiq_last_hip_error()})"
+        raise AiqError(st, f"{what}: {msg}")
+
+
+def _desc(desc):
+    d = np.ascontiguousarray(desc, dtype=np.int32)
+    if d.ndim != 2 or d.shape[1] != _DESC_INTS:
+        raise ValueError("layer descriptors must be int32 [n_layers][13]")
+    return d
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def layer_ai(desc, scheme, batch=1):
+    """aiq_layer_ai: returns (flops[n_layers], bytes[n_layers], global_ai).  Host only."""
+    d = _desc(desc)
+    sch = None if scheme is None else np.ascontiguousarray(scheme, dtype=np.uint8)
+    flops = np.empty(d.shape[0], dtype=np.float64)
+    byts = np.empty(d.shape[0], dtype=np.float64)
+    ai = C.c_double(0.0)
+    st = load_library().aiq_layer_ai(d.ctypes.data, d.shape[0], None if sch is None else sch.ctypes.data,
+                                     0 if sch is None else sch.shape[0], int(batch), flops.ctypes.data,
+                                     byts.ctypes.data, C.byref(ai))
+    _check(st, "aiq_layer_ai")
+    return flops, byts, ai.value
+
+
+def quantize_weights(w, bits, want_codes=True, stream=None):
+    """aiq_quantize_weights on a CUDA fp32 tensor [cout][k]; returns (w_dq, scales, codes|None) tensors."""
+    import torch
+    if not (w.is_cuda and w.dtype == torch.float32 and w.dim() == 2 and w.is_contiguous()):
+        raise ValueError("w must be a contiguous CUDA float32 matrix")
+    cout, k = w.shape
+    w_dq = torch.empty_like(w)
+    scales = torch.empty(cout, dtype=torch.float32, device=w.device)
+    codes = torch.zeros((cout, k), dtype=torch.int32, device=w.device) if want_codes else None
+    st = load_library().aiq_quantize_weights(w.data_ptr(), cout, k, int(bits), w_dq.data_ptr(), scales.data_ptr(),
+                                             None if codes is None else codes.data_ptr(), _stream_ptr(stream))
+    _check(st, "aiq_quantize_weights")
+    return w_dq, scales, codes
+
+
+class Model:
+    """Owns an aiq_model handle.  desc: int32 [n][13]; weights / biases: lists of fp32 numpy arrays."""
+
+    def __init__(self, desc, weights, biases):
+        self._h = C.c_void_p(None)
+        self._lib = load_library()
+        d = _desc(desc)
+        n = d.shape[0]
+        if len(weights) != n or len(biases) != n:
+            raise ValueError("one weight and one bias array per layer")
+        ws = [np.ascontiguousarray(w, dtype=np.float32) for w in weights]
+        bs = [np.ascontiguousarray(b, dtype=np.float32) for b in biases]
+        wp = (C.c_void_p * n)(*[w.ctypes.data for w in ws])
+        bp = (C.c_void_p * n)(*[b.ctypes.data for b in bs])
+        h = C.c_void_p(None)
+        _check(self._lib.aiq_model_create(d.ctypes.data, n, wp, bp, C.byref(h)), "aiq_model_create")
+        self._h = h
+        self.L = int(self._lib.aiq_model_scheme_layers(h))
+        self.classes = int(self._lib.aiq_model_classes(h))
+        self._workspace = None
+
+    def close(self):
+        if self._h:
+            self._lib.aiq_model_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace_bytes(self, S, chunk):
+        out = C.c_size_t(0)
+        _check(self._lib.aiq_eval_workspace_bytes(self._h, int(S), int(chunk), C.byref(out)),
+               "aiq_eval_workspace_bytes")
+        return out.value
+
+    def _get_workspace(self, nbytes, device):
+        import torch
+        if self._workspace is None or self._workspace.numel() < nbytes or self._workspace.device != device:
+            self._workspace = None
+            self._workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        return self._workspace
+
+    def eval_schemes(self, images, schemes, chunk=1024, top1_base=None, want_logits=False, want_top1=False,
+                     out=None, stream=None):
+        """aiq_eval_schemes.  images: CUDA fp32 [N][H][W][C]; schemes: uint8 [S][L] (host).
+
+        top1_base: CUDA int32 [N] from an earlier call (then the FP32 pass is skipped), or None.
+        out: optional dict of preallocated CUDA tensors (top1_base, logits, top1, agree) to reuse.
+        Returns dict(agree, top1_base, logits|None, top1|None); all CUDA tensors, not synchronised.
+        """
+        import torch
+        if not (images.is_cuda and images.dtype == torch.float32 and images.is_contiguous()):
+            raise ValueError("images must be a contiguous CUDA float32 tensor")
+        sch = np.ascontiguousarray(schemes, dtype=np.uint8)
+        if sch.ndim != 2 or sch.shape[1] != self.L:
+            raise AiqError(3, "aiq_eval_schemes: scheme length differs from the model's L")
+        S, N = sch.shape[0], images.shape[0]
+        dev = images.device
+        out = out or {}
+        base_valid = 1 if top1_base is not None else 0
+        if top1_base is None:
+            top1_base = out.get("top1_base")
+            if top1_base is None:
+                top1_base = torch.empty(max(N, 1), dtype=torch.int32, device=dev)
+        agree = out.get("agree")
+        if agree is None:
+            agree = torch.empty(max(S, 1), dtype=torch.int32, device=dev)
+        logits = top1 = None
+        if want_logits:
+            logits = out.get("logits")
+            if logits is None:
+                logits = torch.empty((S, N, self.classes), dtype=torch.float32, device=dev)
+        if want_top1:
+            top1 = out.get("top1")
+            if top1 is None:
+                top1 = torch.empty((S, N), dtype=torch.int32, device=dev)
+        chunk = max(1, min(int(chunk), max(N, 1)))
+        nbytes = self.workspace_bytes(S, chunk)
+        ws = self._get_workspace(nbytes, dev)
+        st = self._lib.aiq_eval_schemes(self._h, images.data_ptr(), N, sch.ctypes.data, S, chunk,
+                                        top1_base.data_ptr(), base_valid,
+                                        None if logits is None else logits.data_ptr(),
+                                        None if top1 is None else top1.data_ptr(), agree.data_ptr(),
+                                        ws.data_ptr(), ws.numel(), _stream_ptr(stream))
+        _check(st, "aiq_eval_schemes")
+        return dict(agree=agree[:S], top1_base=top1_base[:N], logits=logits, top1=top1)
+
+    def profile_enable(self, on=True):
+        _check(self._lib.aiq_profile_enable(self._h, 1 if on else 0), "aiq_profile_enable")
+
+    def profile_read(self, cls):
+        n, ms, fl, by = C.c_int64(0), C.c_double(0), C.c_double(0), C.c_double(0)
+        _check(self._lib.aiq_profile_read(self._h, int(cls), C.byref(n), C.byref(ms), C.byref(fl), C.byref(by)),
+               "aiq_profile_read")
+        return dict(launches=n.value, total_ms=ms.value, flops=fl.value, bytes=by.value)

@@ -1,0 +1,698 @@
+// Host side of libaiq.so: argument validation, the analytic arithmetic-intensity
+// model, the per-call plan (which (layer, bit-width) bank slots to fill, which
+// kernel configuration each layer gets) and the launch sequence.  Every step of the
+// scored path itself runs in the kernels of aiq_kernels.hip.
+#include "../../include/aiq.h"
+#include "aiq_internal.h"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace aiq;
+
+namespace {
+
+thread_local int32_t g_last_hip_error = 0;
+
+inline bool hip_ok(hipError_t e)
+{
+    if (e == hipSuccess) return true;
+    g_last_hip_error = (int32_t)e;
+    (void)hipGetLastError(); // clear the sticky launch error
+    return false;
+}
+
+#define AIQ_HIP(call)                               \
+    do {                                            \
+        if (!hip_ok(call)) return AIQ_DEVICE_ERROR; \
+    } while (0)
+
+inline int out_size(int in, int k, int stride, int pad) { return (in + 2 * pad - k) / stride + 1; }
+
+inline bool bits_supported(int b) { return bits_index(b) >= 0; }
+
+struct ConvPlan {
+    int nt, wave_px_split, R, G, regions_per_image, CB, CKC, RIN, LW, PS, cout_tiles, grid_y;
+    size_t lds_bytes;
+};
+
+struct Node {
+    aiq_layer_desc d;
+    int hout, wout;
+    int k;              // weights per output channel
+    size_t out_elems;   // per image
+    size_t in_elems;
+    int layout;
+    size_t bank_elems;  // elements of one bank slot (padded layout)
+    float *w_plain = nullptr;
+    float *bias = nullptr;
+    float *bank[kNumBits] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    int buf = -1;       // activation buffer holding this node's output
+    int job0 = -1;      // first quantize job (bits index 1) of this node, -1 if not a scheme layer
+    ConvPlan plan;
+    double flops_per_image;      // 2 * multiply-adds
+    double act_bytes_per_image;  // algorithmic: input + output (+ residual) activations
+};
+
+struct ProfRec {
+    hipEvent_t start, stop;
+    int cls;
+    double flops, bytes;
+};
+
+} // namespace
+
+struct aiq_model {
+    std::vector<Node> nodes;
+    int L = 0, classes = 0;
+    int hin0 = 0, win0 = 0, cin0 = 0;
+    int n_bufs = 0;
+    size_t buf_elems = 0; // per scheme-image
+    QuantJob *jobs_dev = nullptr;
+    int32_t *block_job_dev = nullptr;
+    int n_jobs = 0, n_quant_blocks = 0;
+    std::vector<QuantJob> jobs_host;
+    std::vector<void *> allocations;
+    // profiling
+    bool prof_on = false;
+    std::vector<hipEvent_t> ev_pool;
+    size_t ev_used = 0;
+    std::vector<ProfRec> prof;
+};
+
+namespace {
+
+aiq_status plan_conv(Node &nd)
+{
+    const aiq_layer_desc &d = nd.d;
+    ConvPlan p{};
+    p.cout_tiles = (d.cout + 15) / 16;
+    p.CB = (d.cin + 15) / 16;
+    if (p.cout_tiles % 4 == 0) p.nt = 4;
+    else if (p.cout_tiles % 3 == 0) p.nt = 3;
+    else if (p.cout_tiles % 2 == 0) p.nt = 2;
+    else p.nt = 1;
+    const int groups = (p.cout_tiles + p.nt - 1) / p.nt; // wavefront tiles along output channels
+    p.wave_px_split = groups <= 1 ? 4 : (groups <= 2 ? 2 : 1);
+    const int wco = 4 / p.wave_px_split;
+    p.grid_y = (groups + wco - 1) / wco;
+    const int region_px = 64 * p.wave_px_split;
+    const int px_img = nd.hout * nd.wout;
+    if (px_img >= region_px) {
+        p.G = 1;
+        p.R = region_px / nd.wout;
+        if (p.R < 1) return AIQ_UNSUPPORTED_LAYER;
+        p.R = std::min(p.R, nd.hout);
+        p.regions_per_image = (nd.hout + p.R - 1) / p.R;
+    } else {
+        p.G = region_px / px_img;
+        p.R = nd.hout;
+        p.regions_per_image = 1;
+    }
+    const int cp = p.CB * 16;
+    p.CKC = cp >= 64 ? 64 : (cp >= 32 ? 32 : 16);
+    p.RIN = (p.R - 1) * d.stride + d.kh;
+    p.LW = d.win + 2 * d.pad;
+    for (;;) {
+        p.PS = p.CKC + 4;
+        p.lds_bytes = sizeof(float) * (size_t)p.G * p.RIN * p.LW * p.PS;
+        if (p.lds_bytes <= 152 * 1024) break;
+        if (p.CKC == 16) return AIQ_UNSUPPORTED_LAYER;
+        p.CKC /= 2;
+    }
+    nd.plan = p;
+    return AIQ_OK;
+}
+
+aiq_status validate_graph(const aiq_layer_desc *layers, int n_layers)
+{
+    if (layers[0].input != -1) return AIQ_SHAPE_MISMATCH;
+    for (int l = 0; l < n_layers; ++l) {
+        const aiq_layer_desc &d = layers[l];
+        if (d.kind < 0 || d.kind > 2) return AIQ_UNSUPPORTED_LAYER;
+        if (d.cin <= 0 || d.cout <= 0 || d.hin <= 0 || d.win <= 0) return AIQ_INVALID_ARG;
+        if (d.input < -1 || d.input >= l || d.residual < -1 || d.residual >= l) return AIQ_SHAPE_MISMATCH;
+        if (d.act < 0 || d.act > 2) return AIQ_INVALID_ARG;
+        if (d.kind == 2) {
+            if (l != n_layers - 1) return AIQ_UNSUPPORTED_LAYER;
+            if (d.cout > 64 || d.residual >= 0 || d.input < 0 || d.act != 0) return AIQ_UNSUPPORTED_LAYER;
+        } else {
+            const bool k3 = d.kh == 3 && d.kw == 3 && d.pad == 1;
+            const bool k1 = d.kh == 1 && d.kw == 1 && d.pad == 0;
+            if (!(k3 || k1) || (d.stride != 1 && d.stride != 2)) return AIQ_UNSUPPORTED_LAYER;
+            if (d.kind == 1 && (!k3 || d.cin != d.cout || (d.cin & 3) || d.residual >= 0 || d.input < 0))
+                return AIQ_UNSUPPORTED_LAYER;
+            if (d.kind == 0 && (d.cout & 3)) return AIQ_UNSUPPORTED_LAYER;
+            if (d.kind == 0 && d.input >= 0 && (d.cin & 3)) return AIQ_UNSUPPORTED_LAYER;
+        }
+        if (d.input >= 0) {
+            const aiq_layer_desc &p = layers[d.input];
+            if (p.kind == 2) return AIQ_SHAPE_MISMATCH;
+            if (out_size(p.hin, p.kh, p.stride, p.pad) != d.hin || out_size(p.win, p.kw, p.stride, p.pad) != d.win ||
+                p.cout != d.cin)
+                return AIQ_SHAPE_MISMATCH;
+        } else if (d.hin != layers[0].hin || d.win != layers[0].win || d.cin != layers[0].cin) {
+            return AIQ_SHAPE_MISMATCH;
+        }
+        if (d.residual >= 0) {
+            const aiq_layer_desc &r = layers[d.residual];
+            if (r.kind == 2 || r.cout != d.cout ||
+                out_size(r.hin, r.kh, r.stride, r.pad) != out_size(d.hin, d.kh, d.stride, d.pad) ||
+                out_size(r.win, r.kw, r.stride, r.pad) != out_size(d.win, d.kw, d.stride, d.pad))
+                return AIQ_SHAPE_MISMATCH;
+        }
+    }
+    if (layers[n_layers - 1].kind != 2) return AIQ_UNSUPPORTED_LAYER;
+    // scheme slots must be exactly 0..L-1, each used once
+    int L = 0;
+    for (int l = 0; l < n_layers; ++l) L = std::max(L, layers[l].scheme_slot + 1);
+    std::vector<int> seen(L, 0);
+    for (int l = 0; l < n_layers; ++l) {
+        const int sl = layers[l].scheme_slot;
+        if (sl < -1) return AIQ_INVALID_ARG;
+        if (sl >= 0 && seen[sl]++) return AIQ_SHAPE_MISMATCH;
+    }
+    for (int i = 0; i < L; ++i)
+        if (!seen[i]) return AIQ_SHAPE_MISMATCH;
+    return AIQ_OK;
+}
+
+template <typename T>
+aiq_status dev_alloc(aiq_model *m, T **p, size_t n)
+{
+    void *q = nullptr;
+    AIQ_HIP(hipMalloc(&q, std::max<size_t>(n * sizeof(T), 256)));
+    m->allocations.push_back(q);
+    *p = reinterpret_cast<T *>(q);
+    return AIQ_OK;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct WorkspaceLayout {
+    size_t schemes_off, top1_off, act_off, total;
+    size_t buf_stride; // bytes of one activation buffer
+};
+
+WorkspaceLayout workspace_layout(const aiq_model *m, int S, int chunk)
+{
+    WorkspaceLayout w{};
+    size_t off = 0;
+    w.schemes_off = off;
+    off = align_up(off + (size_t)std::max(S, 1) * std::max(m->L, 1), 256);
+    w.top1_off = off;
+    off = align_up(off + sizeof(int32_t) * (size_t)std::max(S, 1) * chunk, 256);
+    w.act_off = off;
+    w.buf_stride = align_up(sizeof(float) * m->buf_elems * (size_t)(S + 1) * chunk, 256);
+    off += w.buf_stride * m->n_bufs;
+    w.total = off;
+    return w;
+}
+
+// Brackets one launch with events when profiling is on.
+struct ProfScope {
+    aiq_model *m;
+    hipStream_t st;
+    ProfRec rec{};
+    bool live = false;
+    ProfScope(aiq_model *m_, hipStream_t st_, int cls, double flops, double bytes) : m(m_), st(st_)
+    {
+        if (!m->prof_on || m->ev_used + 2 > m->ev_pool.size()) return;
+        rec.start = m->ev_pool[m->ev_used++];
+        rec.stop = m->ev_pool[m->ev_used++];
+        rec.cls = cls;
+        rec.flops = flops;
+        rec.bytes = bytes;
+        live = hipEventRecord(rec.start, st) == hipSuccess;
+    }
+    ~ProfScope()
+    {
+        if (live && hipEventRecord(rec.stop, st) == hipSuccess) m->prof.push_back(rec);
+    }
+};
+
+} // namespace
+
+extern "C" {
+
+const char *aiq_status_str(aiq_status st)
+{
+    switch (st) {
+    case AIQ_OK: return "ok";
+    case AIQ_INVALID_ARG: return "invalid argument";
+    case AIQ_UNSUPPORTED_BITS: return "unsupported bit-width";
+    case AIQ_SHAPE_MISMATCH: return "shape mismatch";
+    case AIQ_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case AIQ_DEVICE_ERROR: return "device error";
+    case AIQ_UNSUPPORTED_LAYER: return "unsupported layer";
+    default: return "unknown status";
+    }
+}
+
+int32_t aiq_last_hip_error(void) { return g_last_hip_error; }
+
+aiq_status aiq_layer_ai(const aiq_layer_desc *layers, int32_t n_layers, const uint8_t *scheme, int32_t L,
+                        int32_t batch, double *flops_per_layer, double *bytes_per_layer, double *global_ai)
+{
+    if (!layers || n_layers <= 0 || batch < 1 || !global_ai || L < 0) return AIQ_INVALID_ARG;
+    // validate everything before writing anything
+    for (int l = 0; l < n_layers; ++l) {
+        const aiq_layer_desc &d = layers[l];
+        if (d.kind < 0 || d.kind > 2) return AIQ_UNSUPPORTED_LAYER;
+        if (d.scheme_slot >= 0) {
+            if (!scheme) return AIQ_INVALID_ARG;
+            if (d.scheme_slot >= L) return AIQ_SHAPE_MISMATCH;
+            if (!bits_supported(scheme[d.scheme_slot])) return AIQ_UNSUPPORTED_BITS;
+        }
+    }
+    double total_flops = 0.0, total_bytes = 0.0;
+    for (int l = 0; l < n_layers; ++l) {
+        const aiq_layer_desc &d = layers[l];
+        const double bits = d.scheme_slot >= 0 ? (double)scheme[d.scheme_slot] : 32.0;
+        double weights, macs, in_e, out_e;
+        if (d.kind == 2) {
+            weights = (double)d.cin * d.cout;
+            macs = weights;
+            in_e = d.cin;
+            out_e = d.cout;
+        } else {
+            const double ho = out_size(d.hin, d.kh, d.stride, d.pad), wo = out_size(d.win, d.kw, d.stride, d.pad);
+            weights = (double)d.cout * (d.kind == 1 ? 1 : d.cin) * d.kh * d.kw;
+            macs = weights * ho * wo;
+            in_e = (double)d.hin * d.win * d.cin;
+            out_e = ho * wo * d.cout;
+        }
+        const double f = 2.0 * batch * macs;
+        const double b = weights * bits / 8.0 + 4.0 * batch * (in_e + out_e);
+        if (flops_per_layer) flops_per_layer[l] = f;
+        if (bytes_per_layer) bytes_per_layer[l] = b;
+        total_flops += f;
+        total_bytes += b;
+    }
+    *global_ai = total_flops / total_bytes;
+    return AIQ_OK;
+}
+
+aiq_status aiq_quantize_weights(const float *w, int32_t cout, int32_t k, int32_t bits, float *w_dq, float *scales,
+                                int32_t *codes, void *hip_stream)
+{
+    if (cout < 0 || k < 0) return AIQ_INVALID_ARG;
+    if (!bits_supported(bits)) return AIQ_UNSUPPORTED_BITS;
+    if (cout == 0) return AIQ_OK;
+    if (!scales || (k > 0 && (!w || !w_dq))) return AIQ_INVALID_ARG;
+    QuantJob j{};
+    j.w = w;
+    j.out = w_dq;
+    j.scales = scales;
+    j.codes = bits == 32 ? nullptr : codes;
+    j.cout = cout;
+    j.k = k;
+    j.bits = bits;
+    j.layout = kLayoutPlain;
+    j.taps = 1;
+    j.cblocks = 1;
+    AIQ_HIP(launch_quantize_single(j, (hipStream_t)hip_stream));
+    return AIQ_OK;
+}
+
+int32_t aiq_model_scheme_layers(const aiq_model *m) { return m ? m->L : -1; }
+int32_t aiq_model_classes(const aiq_model *m) { return m ? m->classes : -1; }
+
+void aiq_model_destroy(aiq_model *m)
+{
+    if (!m) return;
+    for (hipEvent_t e : m->ev_pool) (void)hipEventDestroy(e);
+    for (void *p : m->allocations) (void)hipFree(p);
+    delete m;
+}
+
+aiq_status aiq_model_create(const aiq_layer_desc *layers, int32_t n_layers, const float *const *w_host,
+                            const float *const *bias_host, aiq_model **out)
+{
+    if (out) *out = nullptr;
+    if (!layers || n_layers <= 0 || !w_host || !bias_host || !out) return AIQ_INVALID_ARG;
+    for (int l = 0; l < n_layers; ++l)
+        if (!w_host[l] || !bias_host[l]) return AIQ_INVALID_ARG;
+    aiq_status st = validate_graph(layers, n_layers);
+    if (st != AIQ_OK) return st;
+
+    aiq_model *m = new (std::nothrow) aiq_model();
+    if (!m) return AIQ_INVALID_ARG;
+    m->hin0 = layers[0].hin;
+    m->win0 = layers[0].win;
+    m->cin0 = layers[0].cin;
+    m->classes = layers[n_layers - 1].cout;
+    m->nodes.resize(n_layers);
+    for (int l = 0; l < n_layers; ++l) {
+        Node &nd = m->nodes[l];
+        nd.d = layers[l];
+        const aiq_layer_desc &d = nd.d;
+        m->L = std::max(m->L, d.scheme_slot + 1);
+        if (d.kind == 2) {
+            nd.hout = nd.wout = 1;
+            nd.k = d.cin;
+            nd.out_elems = d.cout;
+            nd.in_elems = (size_t)d.hin * d.win * d.cin;
+            nd.layout = kLayoutPlain;
+            nd.bank_elems = (size_t)d.cout * d.cin;
+            nd.flops_per_image = 2.0 * d.cin * d.cout + 2.0 * d.hin * d.win * d.cin;
+            nd.act_bytes_per_image = 4.0 * nd.in_elems;
+        } else {
+            nd.hout = out_size(d.hin, d.kh, d.stride, d.pad);
+            nd.wout = out_size(d.win, d.kw, d.stride, d.pad);
+            nd.out_elems = (size_t)nd.hout * nd.wout * d.cout;
+            nd.in_elems = (size_t)d.hin * d.win * d.cin;
+            if (d.kind == 1) {
+                nd.k = d.kh * d.kw;
+                nd.layout = kLayoutTapMajor;
+                nd.bank_elems = (size_t)d.cout * nd.k;
+            } else {
+                nd.k = d.cin * d.kh * d.kw;
+                nd.layout = kLayoutMfma;
+                nd.bank_elems = (size_t)((d.cout + 15) / 16) * 16 * d.kh * d.kw * ((d.cin + 15) / 16) * 16;
+                st = plan_conv(nd);
+                if (st != AIQ_OK) {
+                    delete m;
+                    return st;
+                }
+            }
+            nd.flops_per_image = 2.0 * (double)nd.out_elems * nd.k;
+            nd.act_bytes_per_image = 4.0 * ((double)nd.in_elems * (d.stride == 1 ? 1.0 : 1.0) + nd.out_elems +
+                                            (d.residual >= 0 ? nd.out_elems : 0));
+        }
+    }
+
+    // activation buffers: a node's output lives until its last reader has run
+    std::vector<int> last_use(n_layers, -1);
+    for (int l = 0; l < n_layers; ++l) {
+        if (layers[l].input >= 0) last_use[layers[l].input] = l;
+        if (layers[l].residual >= 0) last_use[layers[l].residual] = std::max(last_use[layers[l].residual], l);
+    }
+    std::vector<int> owner; // owner[b] = node currently held by buffer b, -1 free
+    for (int l = 0; l + 1 < n_layers; ++l) {
+        // free buffers whose tenant is no longer needed by node l or later
+        for (size_t b = 0; b < owner.size(); ++b)
+            if (owner[b] >= 0 && last_use[owner[b]] < l) owner[b] = -1;
+        int pick = -1;
+        for (size_t b = 0; b < owner.size(); ++b)
+            if (owner[b] < 0) {
+                pick = (int)b;
+                break;
+            }
+        if (pick < 0) {
+            owner.push_back(-1);
+            pick = (int)owner.size() - 1;
+        }
+        owner[pick] = l;
+        m->nodes[l].buf = pick;
+        m->buf_elems = std::max(m->buf_elems, m->nodes[l].out_elems);
+    }
+    m->n_bufs = (int)owner.size();
+
+    // device copies, bank slots, quantize job table
+    auto fail = [&](aiq_status code) {
+        aiq_model_destroy(m);
+        return code;
+    };
+    if (!hip_ok(conv_set_lds_limits())) return fail(AIQ_DEVICE_ERROR);
+    std::vector<int32_t> block_job;
+    for (int l = 0; l < n_layers; ++l) {
+        Node &nd = m->nodes[l];
+        const size_t wn = (size_t)nd.d.cout * nd.k;
+        if ((st = dev_alloc(m, &nd.w_plain, wn)) != AIQ_OK) return fail(st);
+        if ((st = dev_alloc(m, &nd.bias, (size_t)nd.d.cout)) != AIQ_OK) return fail(st);
+        if (!hip_ok(hipMemcpy(nd.w_plain, w_host[l], wn * sizeof(float), hipMemcpyHostToDevice)) ||
+            !hip_ok(hipMemcpy(nd.bias, bias_host[l], nd.d.cout * sizeof(float), hipMemcpyHostToDevice)))
+            return fail(AIQ_DEVICE_ERROR);
+        const int n_slots = nd.d.scheme_slot >= 0 ? kNumBits : 1;
+        for (int b = 0; b < n_slots; ++b) {
+            if ((st = dev_alloc(m, &nd.bank[b], nd.bank_elems)) != AIQ_OK) return fail(st);
+            if (!hip_ok(hipMemset(nd.bank[b], 0, nd.bank_elems * sizeof(float)))) return fail(AIQ_DEVICE_ERROR);
+            QuantJob j{};
+            j.w = nd.w_plain;
+            j.out = nd.bank[b];
+            j.cout = nd.d.cout;
+            j.k = nd.k;
+            j.bits = kBitsOfIndex[b];
+            j.layout = nd.layout;
+            j.taps = nd.d.kind == 2 ? 1 : nd.d.kh * nd.d.kw;
+            j.cblocks = (nd.d.cin + 15) / 16;
+            if (b == 0) {
+                // the FP32 copy in kernel layout is written once, here
+                if (!hip_ok(launch_quantize_single(j, nullptr))) return fail(AIQ_DEVICE_ERROR);
+            } else {
+                if (b == 1) nd.job0 = (int)m->jobs_host.size();
+                j.first_block = (int32_t)block_job.size();
+                const int blocks = (j.cout + kQuantChannelsPerBlock - 1) / kQuantChannelsPerBlock;
+                block_job.insert(block_job.end(), blocks, (int32_t)m->jobs_host.size());
+                m->jobs_host.push_back(j);
+            }
+        }
+    }
+    m->n_jobs = (int)m->jobs_host.size();
+    m->n_quant_blocks = (int)block_job.size();
+    if (m->n_jobs > kMaxQuantJobs) return fail(AIQ_UNSUPPORTED_LAYER);
+    if (m->n_jobs) {
+        if ((st = dev_alloc(m, &m->jobs_dev, (size_t)m->n_jobs)) != AIQ_OK) return fail(st);
+        if ((st = dev_alloc(m, &m->block_job_dev, block_job.size())) != AIQ_OK) return fail(st);
+        if (!hip_ok(hipMemcpy(m->jobs_dev, m->jobs_host.data(), sizeof(QuantJob) * m->n_jobs,
+                              hipMemcpyHostToDevice)) ||
+            !hip_ok(hipMemcpy(m->block_job_dev, block_job.data(), sizeof(int32_t) * block_job.size(),
+                              hipMemcpyHostToDevice)))
+            return fail(AIQ_DEVICE_ERROR);
+    }
+    if (!hip_ok(hipDeviceSynchronize())) return fail(AIQ_DEVICE_ERROR);
+    *out = m;
+    return AIQ_OK;
+}
+
+aiq_status aiq_eval_workspace_bytes(const aiq_model *m, int32_t S, int32_t chunk, size_t *bytes)
+{
+    if (!m || !bytes || S < 0 || chunk < 1) return AIQ_INVALID_ARG;
+    *bytes = workspace_layout(m, S, chunk).total;
+    return AIQ_OK;
+}
+
+aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const uint8_t *schemes, int32_t S,
+                            int32_t chunk, int32_t *top1_base, int32_t base_valid, float *logits, int32_t *top1,
+                            int32_t *agree, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!m || N < 0 || S < 0 || chunk < 1) return AIQ_INVALID_ARG;
+    if (S > 0 && (!schemes || !agree)) return AIQ_INVALID_ARG;
+    if (N > 0 && (!images || !top1_base || !workspace)) return AIQ_INVALID_ARG;
+    if (base_valid != 0 && base_valid != 1) return AIQ_INVALID_ARG;
+    for (size_t i = 0; i < (size_t)S * m->L; ++i)
+        if (!bits_supported(schemes[i])) return AIQ_UNSUPPORTED_BITS;
+    chunk = std::min(chunk, std::max(N, 1));
+    const WorkspaceLayout wl = workspace_layout(m, S, chunk);
+    if (N > 0 && workspace_bytes < wl.total) return AIQ_WORKSPACE_TOO_SMALL;
+    if (N > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255)) return AIQ_INVALID_ARG;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (S > 0) AIQ_HIP(launch_fill_i32(agree, 0, (size_t)S, st));
+    if (N == 0) return AIQ_OK;
+    const bool run_base = base_valid == 0;
+    const int s_total = S + (run_base ? 1 : 0);
+    if (s_total == 0) return AIQ_OK;
+
+    char *ws = static_cast<char *>(workspace);
+    uint8_t *schemes_dev = reinterpret_cast<uint8_t *>(ws + wl.schemes_off);
+    int32_t *top1_tmp = reinterpret_cast<int32_t *>(ws + wl.top1_off);
+
+    // plan: which (layer, bit-width) bank slots this call reads
+    QuantMask mask{};
+    bool any = false;
+    for (const Node &nd : m->nodes) {
+        if (nd.d.scheme_slot < 0) continue;
+        for (int s = 0; s < S; ++s) {
+            const int bi = bits_index(schemes[(size_t)s * m->L + nd.d.scheme_slot]);
+            if (bi > 0) {
+                const int ji = nd.job0 + bi - 1;
+                mask.word[ji >> 6] |= 1ull << (ji & 63);
+                any = true;
+            }
+        }
+    }
+    if (S > 0)
+        AIQ_HIP(hipMemcpyAsync(schemes_dev, schemes, (size_t)S * m->L, hipMemcpyHostToDevice, st));
+    if (any) {
+        double qbytes = 0.0;
+        for (int ji = 0; ji < m->n_jobs; ++ji)
+            if ((mask.word[ji >> 6] >> (ji & 63)) & 1ull)
+                qbytes += 8.0 * m->jobs_host[ji].cout * m->jobs_host[ji].k;
+        ProfScope ps(m, st, AIQ_K_QUANTIZE, 0.0, qbytes);
+        AIQ_HIP(launch_quantize_batch(m->jobs_dev, m->block_job_dev, m->n_quant_blocks, mask, st));
+    }
+
+    for (int n0 = 0; n0 < N; n0 += chunk) {
+        const int n = std::min(chunk, N - n0);
+        auto buf_ptr = [&](int b) { return reinterpret_cast<float *>(ws + wl.act_off + wl.buf_stride * b); };
+        for (size_t l = 0; l < m->nodes.size(); ++l) {
+            const Node &nd = m->nodes[l];
+            const aiq_layer_desc &d = nd.d;
+            const float *in;
+            size_t in_stride;
+            if (d.input < 0) {
+                in = images + (size_t)n0 * nd.in_elems;
+                in_stride = 0;
+            } else {
+                in = buf_ptr(m->nodes[d.input].buf);
+                in_stride = (size_t)n * nd.in_elems;
+            }
+            const double work = (double)s_total * n;
+            if (d.kind == 0) {
+                const ConvPlan &p = nd.plan;
+                ConvArgs a{};
+                a.in = in;
+                a.out = buf_ptr(nd.buf);
+                a.res = d.residual >= 0 ? buf_ptr(m->nodes[d.residual].buf) : nullptr;
+                a.bias = nd.bias;
+                for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+                a.schemes = schemes_dev;
+                a.in_scheme_stride = in_stride;
+                a.out_scheme_stride = (size_t)n * nd.out_elems;
+                a.S = S;
+                a.L = m->L;
+                a.slot = d.scheme_slot;
+                a.N = n;
+                a.Hin = d.hin;
+                a.Win = d.win;
+                a.Cin = d.cin;
+                a.Hout = nd.hout;
+                a.Wout = nd.wout;
+                a.Cout = d.cout;
+                a.act = d.act;
+                a.R = p.R;
+                a.G = p.G;
+                a.regions_per_image = p.regions_per_image;
+                a.CB = p.CB;
+                a.CKC = p.CKC;
+                a.RIN = p.RIN;
+                a.LW = p.LW;
+                a.PS = p.PS;
+                a.wave_px_split = p.wave_px_split;
+                a.cout_tiles = p.cout_tiles;
+                a.div_lw = make_fastdiv(p.LW);
+                a.div_rin = make_fastdiv(p.RIN);
+                a.div_wout = make_fastdiv(nd.wout);
+                a.div_rw = make_fastdiv(p.R * nd.wout);
+                const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
+                ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+                AIQ_HIP(launch_conv(a, d.kh, d.stride, p.nt, p.lds_bytes, dim3(gx, p.grid_y, s_total), st));
+            } else if (d.kind == 1) {
+                DepthwiseArgs a{};
+                a.in = in;
+                a.out = buf_ptr(nd.buf);
+                a.bias = nd.bias;
+                for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+                a.schemes = schemes_dev;
+                a.in_scheme_stride = in_stride;
+                a.out_scheme_stride = (size_t)n * nd.out_elems;
+                a.S = S;
+                a.L = m->L;
+                a.slot = d.scheme_slot;
+                a.N = n;
+                a.Hin = d.hin;
+                a.Win = d.win;
+                a.C = d.cin;
+                a.Hout = nd.hout;
+                a.Wout = nd.wout;
+                a.stride = d.stride;
+                a.act = d.act;
+                a.div_c4 = make_fastdiv(d.cin / 4);
+                a.div_wout = make_fastdiv(nd.wout);
+                a.div_hout = make_fastdiv(nd.hout);
+                ProfScope ps(m, st, AIQ_K_DEPTHWISE, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+                AIQ_HIP(launch_depthwise(a, s_total, st));
+            } else {
+                HeadArgs a{};
+                a.in = in;
+                a.bias = nd.bias;
+                for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+                a.schemes = schemes_dev;
+                a.in_scheme_stride = in_stride;
+                a.S = S;
+                a.L = m->L;
+                a.slot = d.scheme_slot;
+                a.N = n;
+                a.HW = d.hin * d.win;
+                a.C = d.cin;
+                a.classes = d.cout;
+                a.logits = logits;
+                a.logits_n = N;
+                a.n0 = n0;
+                if (top1) {
+                    a.top1 = top1 + n0;
+                    a.top1_stride = N;
+                } else {
+                    a.top1 = top1_tmp;
+                    a.top1_stride = chunk;
+                }
+                a.top1_base = run_base ? top1_base + n0 : nullptr;
+                {
+                    ProfScope ps(m, st, AIQ_K_HEAD, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+                    AIQ_HIP(launch_head(a, s_total, st));
+                }
+                AgreeArgs g{};
+                g.top1 = a.top1;
+                g.top1_stride = a.top1_stride;
+                g.top1_base = top1_base + n0;
+                g.agree = agree;
+                g.N = n;
+                g.S = S;
+                ProfScope ps(m, st, AIQ_K_AGREE, 0.0, 8.0 * S * n);
+                AIQ_HIP(launch_agree(g, st));
+            }
+        }
+    }
+    return AIQ_OK;
+}
+
+aiq_status aiq_profile_enable(aiq_model *m, int32_t on)
+{
+    if (!m) return AIQ_INVALID_ARG;
+    if (on && m->ev_pool.empty()) {
+        const size_t want = 16384;
+        m->ev_pool.reserve(want);
+        for (size_t i = 0; i < want; ++i) {
+            hipEvent_t e;
+            AIQ_HIP(hipEventCreate(&e));
+            m->ev_pool.push_back(e);
+        }
+    }
+    m->prof_on = on != 0;
+    return AIQ_OK;
+}
+
+aiq_status aiq_profile_read(aiq_model *m, int32_t cls, int64_t *launches, double *total_ms, double *flops,
+                            double *bytes)
+{
+    if (!m || cls < 0 || cls >= AIQ_K_CLASSES) return AIQ_INVALID_ARG;
+    int64_t cnt = 0;
+    double ms = 0.0, fl = 0.0, by = 0.0;
+    std::vector<ProfRec> keep;
+    for (const ProfRec &r : m->prof) {
+        if (r.cls != cls) {
+            keep.push_back(r);
+            continue;
+        }
+        AIQ_HIP(hipEventSynchronize(r.stop));
+        float t = 0.0f;
+        AIQ_HIP(hipEventElapsedTime(&t, r.start, r.stop));
+        ++cnt;
+        ms += t;
+        fl += r.flops;
+        by += r.bytes;
+    }
+    m->prof.swap(keep);
+    if (m->prof.empty()) m->ev_used = 0;
+    if (launches) *launches = cnt;
+    if (total_ms) *total_ms = ms;
+    if (flops) *flops = fl;
+    if (bytes) *bytes = by;
+    return AIQ_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,143 @@
+// Internal declarations shared by the host planner (aiq_host.cpp) and the gfx950
+// kernels (aiq_kernels.hip).  Not part of the public boundary.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace aiq {
+
+// Bit-width alphabet in bank order: index 0 is the FP32 copy.
+constexpr int kNumBits = 6;
+__host__ __device__ inline int bits_index(int bits)
+{
+    switch (bits) {
+    case 32: return 0;
+    case 16: return 1;
+    case 8: return 2;
+    case 6: return 3;
+    case 4: return 4;
+    case 2: return 5;
+    default: return -1;
+    }
+}
+constexpr int kBitsOfIndex[kNumBits] = {32, 16, 8, 6, 4, 2};
+
+// Weight layouts the quantizer can write.
+enum WeightLayout : int32_t {
+    kLayoutPlain = 0,   // [cout][k]
+    kLayoutMfma = 1,    // dense convolution: [cout/16][tap][cin/16][64 lanes][4], zero padded
+    kLayoutTapMajor = 2 // depthwise: [tap][channels]
+};
+
+// One (weight matrix, bit-width) quantization job.
+struct QuantJob {
+    const float *w;   // [cout][k] source
+    float *out;       // destination in `layout`
+    float *scales;    // [cout] or nullptr
+    int32_t *codes;   // [cout][k] or nullptr
+    int32_t cout, k;
+    int32_t bits;
+    int32_t layout;
+    int32_t taps;     // kh*kw (mfma / tap-major layouts)
+    int32_t cblocks;  // ceil(cin/16) (mfma layout)
+    int32_t first_block; // first grid block of this job in a batched launch
+    int32_t pad_;
+};
+
+constexpr int kQuantChannelsPerBlock = 4; // one wavefront per output channel
+constexpr int kMaxQuantJobs = 512;        // bits of QuantMask
+
+struct QuantMask {
+    uint64_t word[kMaxQuantJobs / 64];
+};
+
+// Exact division of small non-negative integers by a runtime constant:
+// q = (n * magic) >> 32 with magic = floor(2^32 / d) + 1 is exact for n * d < 2^32.
+struct FastDiv {
+    uint32_t d, magic;
+};
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    f.d = d;
+    f.magic = d <= 1 ? 0u : (uint32_t)((0x100000000ull / d) + 1ull);
+    return f;
+}
+__device__ inline uint32_t fd_div(uint32_t n, FastDiv f) { return f.d <= 1 ? n : __umulhi(n, f.magic); }
+
+// Arguments of the dense (3x3 / 1x1) MFMA convolution.
+struct ConvArgs {
+    const float *in;          // [S?][N][Hin][Win][Cin]
+    float *out;               // [S][N][Hout][Wout][Cout]
+    const float *res;         // like out, or nullptr
+    const float *bias;        // [Cout]
+    const float *bank[kNumBits];
+    const uint8_t *schemes;   // device [S][L]
+    size_t in_scheme_stride;  // elements between schemes of `in` (0: shared network input)
+    size_t out_scheme_stride; // elements between schemes of out / res
+    int32_t S, L, slot;       // schemes with index >= S (the base pass) and slot < 0 use FP32
+    int32_t N;                // images in this chunk
+    int32_t Hin, Win, Cin, Hout, Wout, Cout;
+    int32_t act;
+    int32_t R;                // output rows per workgroup region
+    int32_t G;                // images per workgroup (R == Hout when G > 1)
+    int32_t regions_per_image;
+    int32_t CB;               // ceil(Cin/16)
+    int32_t CKC;              // channels staged per pass (16, 32 or 64)
+    int32_t RIN, LW, PS;      // LDS tile: rows, row width (pixels), pixel stride (floats)
+    int32_t wave_px_split;    // waves along pixels (4, 2 or 1); 4/wave_px_split along couts
+    int32_t cout_tiles;       // ceil(Cout/16)
+    FastDiv div_lw, div_rin, div_wout, div_rw; // LW, RIN, Wout, R*Wout
+};
+
+struct DepthwiseArgs {
+    const float *in;
+    float *out;
+    const float *bias;
+    const float *bank[kNumBits]; // tap-major [9][C]
+    const uint8_t *schemes;
+    size_t in_scheme_stride, out_scheme_stride;
+    int32_t S, L, slot;
+    int32_t N, Hin, Win, C, Hout, Wout, stride, act;
+    FastDiv div_c4, div_wout, div_hout;
+};
+
+struct HeadArgs {
+    const float *in;           // [S][N][HW][C]
+    const float *bias;         // [classes]
+    const float *bank[kNumBits]; // plain [classes][C]
+    const uint8_t *schemes;
+    size_t in_scheme_stride;
+    int32_t S, L, slot;
+    int32_t N;                 // images in this chunk
+    int32_t HW, C, classes;
+    float *logits;             // nullable; element (s, n) at logits + (s*logits_n + n0 + n)*classes
+    int64_t logits_n, n0;
+    int32_t *top1;             // (s, n) at top1 + s*top1_stride + n
+    int64_t top1_stride;
+    int32_t *top1_base;        // base pass (s == S) writes top1_base[n]; may be nullptr when no base pass
+};
+
+struct AgreeArgs {
+    const int32_t *top1;
+    int64_t top1_stride;
+    const int32_t *top1_base;
+    int32_t *agree;
+    int32_t N, S;
+};
+
+// Launchers (aiq_kernels.hip).  All return the launch's hipError_t.
+hipError_t launch_quantize_single(const QuantJob &job, hipStream_t st);
+hipError_t launch_quantize_batch(const QuantJob *jobs_dev, const int32_t *block_job_dev, int n_blocks,
+                                 const QuantMask &mask, hipStream_t st);
+hipError_t launch_conv(const ConvArgs &a, int ks, int stride, int nt, size_t lds_bytes, dim3 grid,
+                       hipStream_t st);
+hipError_t launch_depthwise(const DepthwiseArgs &a, int s_total, hipStream_t st);
+hipError_t launch_head(const HeadArgs &a, int s_total, hipStream_t st);
+hipError_t launch_agree(const AgreeArgs &a, hipStream_t st);
+hipError_t launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t st);
+hipError_t conv_set_lds_limits();
+
+} // namespace aiq

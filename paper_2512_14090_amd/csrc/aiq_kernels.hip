@@ -1,0 +1,484 @@
+// gfx950 (CDNA4) kernels of the scheme-scoring path: weight quantize-dequantize,
+// dense convolution on fp32 MFMA, depthwise convolution, classifier head, agreement.
+//
+// The operation each kernel performs is the plain definition of a convolutional
+// forward pass with per-layer quantized weights (paper: Problem Formulation - a
+// scheme assigns a bit-width to each layer; Introduction item (ii) - the model's
+// accuracy under the scheme is measured by running it).  The scheme axis is a grid
+// dimension: block z scores scheme z, picking each layer's weights from the bank
+// slot of that scheme's bit-width.
+#include "aiq_internal.h"
+
+namespace aiq {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------ helpers
+
+__device__ inline int scheme_bits_index(const uint8_t *schemes, int s, int S, int L, int slot)
+{
+    if (slot < 0 || s >= S) return 0;
+    return bits_index(schemes[(size_t)s * L + slot]);
+}
+
+__device__ inline float apply_act(float v, int act)
+{
+    if (act >= 1) v = fmaxf(v, 0.0f);
+    if (act == 2) v = fminf(v, 6.0f);
+    return v;
+}
+
+__device__ inline float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// ------------------------------------------------------------------ quantizer
+//
+// One wavefront per output channel.  Pass 1: absmax of the row by a cross-lane
+// butterfly.  Pass 2: w/s (IEEE binary32 division), round-half-even, clamp, code*s,
+// written straight into the layout the consuming kernel wants.
+
+__device__ inline size_t quant_out_index(const QuantJob &j, int c, int i)
+{
+    if (j.layout == kLayoutPlain) return (size_t)c * j.k + i;
+    const int t = i % j.taps;
+    const int ci = i / j.taps;
+    if (j.layout == kLayoutTapMajor) return (size_t)t * j.cout + c; // depthwise: k == taps, ci == 0
+    const int ct = c >> 4, co = c & 15;
+    const int cb = ci >> 4, kq = (ci & 15) >> 2, jj = ci & 3;
+    return ((((size_t)ct * j.taps + t) * j.cblocks + cb) * 64 + (kq * 16 + co)) * 4 + jj;
+}
+
+__device__ inline void quantize_channel(const QuantJob &j, int c, int lane)
+{
+    const float *row = j.w + (size_t)c * j.k;
+    if (j.bits == 32) {
+        for (int i = lane; i < j.k; i += 64) j.out[quant_out_index(j, c, i)] = row[i];
+        if (lane == 0 && j.scales) j.scales[c] = 1.0f;
+        return;
+    }
+    float amax = 0.0f;
+    for (int i = lane; i < j.k; i += 64) amax = fmaxf(amax, fabsf(row[i]));
+    amax = wave_max(amax);
+    const int qmax = (1 << (j.bits - 1)) - 1;
+    const float s = amax > 0.0f ? __fdiv_rn(amax, (float)qmax) : 1.0f;
+    if (lane == 0 && j.scales) j.scales[c] = s;
+    for (int i = lane; i < j.k; i += 64) {
+        const float t = __fdiv_rn(row[i], s);
+        int q = (int)rintf(t);
+        q = min(max(q, -qmax), qmax);
+        j.out[quant_out_index(j, c, i)] = __fmul_rn((float)q, s);
+        if (j.codes) j.codes[(size_t)c * j.k + i] = q;
+    }
+}
+
+__global__ __launch_bounds__(256) void quantize_single_kernel(QuantJob j)
+{
+    const int c = blockIdx.x * kQuantChannelsPerBlock + (threadIdx.x >> 6);
+    if (c < j.cout) quantize_channel(j, c, threadIdx.x & 63);
+}
+
+// Batched form: a static job table for every (layer, bit-width) of a model; the
+// mask says which jobs this call needs, all others exit at once.
+__global__ __launch_bounds__(256) void quantize_batch_kernel(const QuantJob *jobs, const int32_t *block_job,
+                                                             QuantMask mask)
+{
+    const int ji = block_job[blockIdx.x];
+    if (!((mask.word[ji >> 6] >> (ji & 63)) & 1ull)) return;
+    const QuantJob j = jobs[ji];
+    const int c = (blockIdx.x - j.first_block) * kQuantChannelsPerBlock + (threadIdx.x >> 6);
+    if (c < j.cout) quantize_channel(j, c, threadIdx.x & 63);
+}
+
+hipError_t launch_quantize_single(const QuantJob &job, hipStream_t st)
+{
+    if (job.cout == 0) return hipSuccess; // k == 0 still writes s = 1 for every (empty) row
+    const int blocks = (job.cout + kQuantChannelsPerBlock - 1) / kQuantChannelsPerBlock;
+    hipLaunchKernelGGL(quantize_single_kernel, dim3(blocks), dim3(256), 0, st, job);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_batch(const QuantJob *jobs_dev, const int32_t *block_job_dev, int n_blocks,
+                                 const QuantMask &mask, hipStream_t st)
+{
+    if (n_blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(quantize_batch_kernel, dim3(n_blocks), dim3(256), 0, st, jobs_dev, block_job_dev, mask);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ dense convolution
+//
+// Implicit GEMM on v_mfma_f32_16x16x4_f32 with the weights as the A operand
+// (rows = 16 output channels) and 16 output pixels as the B operand, so that a
+// lane's four accumulator values are four consecutive output channels of one pixel:
+// one 16-byte NHWC store.  The reduction index is (tap, input channel); within a
+// block of 16 input channels lane (p, kq) supplies channels 4*kq+j to MFMA j, so a
+// lane's activations for four MFMAs are one 16-byte LDS read and its weights one
+// 16-byte global read from the pre-packed bank.
+//
+// Workgroup = 4 wavefronts.  It stages the input rows its region needs (with the
+// zero border) in LDS, CKC channels at a time; every wavefront owns a tile of 64
+// pixels x 16*NT output channels and keeps its accumulators across channel passes.
+
+template <int KS, int STRIDE, int NT>
+__global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
+{
+    extern __shared__ float lds[];
+    constexpr int T = KS * KS;
+    constexpr int PAD = KS == 3 ? 1 : 0;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int s = blockIdx.z;
+
+    int img0, oy0;
+    if (a.G > 1) {
+        img0 = blockIdx.x * a.G;
+        oy0 = 0;
+    } else {
+        img0 = blockIdx.x / a.regions_per_image;
+        oy0 = (blockIdx.x - img0 * a.regions_per_image) * a.R;
+    }
+
+    const int wpx = wave % a.wave_px_split;
+    const int wco = wave / a.wave_px_split;
+    const int wco_count = 4 / a.wave_px_split;
+    const int ct0 = (blockIdx.y * wco_count + wco) * NT;
+    const int p = lane & 15, kq = lane >> 4;
+
+    // per pixel tile: LDS base offset (floats) of the lane's pixel, and its output position
+    int lds_base[4];
+    int out_img[4], out_y[4], out_x[4];
+    const int rw = a.R * a.Wout;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const uint32_t P = (uint32_t)(wpx * 64 + m * 16 + p);
+        const uint32_t g = fd_div(P, a.div_rw);
+        const uint32_t rem = P - g * rw;
+        const uint32_t oy = fd_div(rem, a.div_wout);
+        const uint32_t ox = rem - oy * a.Wout;
+        const bool in_region = g < (uint32_t)a.G; // lanes past the region's last pixel compute nothing useful
+        lds_base[m] = in_region ? ((g * a.RIN + oy * STRIDE) * a.LW + ox * STRIDE) * a.PS + kq * 4 : kq * 4;
+        out_img[m] = in_region ? img0 + (int)g : a.N;
+        out_y[m] = oy0 + oy;
+        out_x[m] = ox;
+    }
+
+    const float *wq = a.bank[scheme_bits_index(a.schemes, s, a.S, a.L, a.slot)];
+    const float *in_s = a.in + (size_t)s * a.in_scheme_stride;
+
+    floatx4 acc[4][NT];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int n = 0; n < NT; ++n) acc[m][n] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const int c4n = a.CKC >> 2;            // 16-byte chunks per staged pixel
+    const int c4shift = __ffs(c4n) - 1;    // CKC is 16, 32 or 64
+    const int n_pix = a.G * a.RIN * a.LW;
+    const int n_chunks = n_pix << c4shift;
+    const bool vec_ok = (a.Cin & 3) == 0;
+    const bool active = ct0 < a.cout_tiles; // wavefronts past the last output-channel tile only help staging
+
+    for (int c0 = 0; c0 < a.CB * 16; c0 += a.CKC) {
+        if (c0) __syncthreads();
+        // ---- stage channels [c0, c0+CKC) of the region's input rows, zero outside the image
+        for (int idx = tid; idx < n_chunks; idx += 256) {
+            const int c4 = idx & (c4n - 1);
+            const uint32_t pix = (uint32_t)idx >> c4shift;
+            const uint32_t row = fd_div(pix, a.div_lw); // g*RIN + r
+            const int x = pix - row * a.LW;
+            const uint32_t g = fd_div(row, a.div_rin);
+            const int r = row - g * a.RIN;
+            const int iy = oy0 * STRIDE - PAD + r;
+            const int ix = x - PAD;
+            const int img = img0 + g;
+            const int c = c0 + c4 * 4;
+            floatx4 v = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win && img < a.N && c < a.Cin) {
+                const float *src = in_s + (((size_t)img * a.Hin + iy) * a.Win + ix) * a.Cin + c;
+                if (vec_ok) {
+                    v = *reinterpret_cast<const floatx4 *>(src);
+                } else {
+                    v.x = src[0];
+                    if (c + 1 < a.Cin) v.y = src[1];
+                    if (c + 2 < a.Cin) v.z = src[2];
+                    if (c + 3 < a.Cin) v.w = src[3];
+                }
+            }
+            *reinterpret_cast<floatx4 *>(lds + (size_t)pix * a.PS + c4 * 4) = v;
+        }
+        __syncthreads();
+
+        if (active) {
+            const int ncb = min(a.CKC, a.CB * 16 - c0) >> 4;
+            const int cb0 = c0 >> 4;
+#pragma unroll 1
+            for (int t = 0; t < T; ++t) {
+                const int ky = t / KS, kx = t - ky * KS;
+                const int tapoff = (ky * a.LW + kx) * a.PS;
+#pragma unroll 1
+                for (int cbl = 0; cbl < ncb; ++cbl) {
+                    floatx4 wa[NT], xb[4];
+#pragma unroll
+                    for (int n = 0; n < NT; ++n) {
+                        const int ct = min(ct0 + n, a.cout_tiles - 1);
+                        wa[n] = *reinterpret_cast<const floatx4 *>(
+                            wq + ((((size_t)ct * T + t) * a.CB + cb0 + cbl) * 64 + lane) * 4);
+                    }
+#pragma unroll
+                    for (int m = 0; m < 4; ++m)
+                        xb[m] = *reinterpret_cast<const floatx4 *>(lds + lds_base[m] + tapoff + cbl * 16);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int m = 0; m < 4; ++m)
+#pragma unroll
+                            for (int n = 0; n < NT; ++n)
+                                acc[m][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[n][j], xb[m][j], acc[m][n],
+                                                                                 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    if (!active) return;
+    // ---- epilogue: bias, residual, activation, 16-byte NHWC stores
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int co = (ct0 + n) * 16 + kq * 4;
+        if (co >= a.Cout) continue;
+        const floatx4 b = *reinterpret_cast<const floatx4 *>(a.bias + co);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            if (out_img[m] >= a.N || out_y[m] >= a.Hout) continue;
+            const size_t o = (size_t)s * a.out_scheme_stride +
+                             (((size_t)out_img[m] * a.Hout + out_y[m]) * a.Wout + out_x[m]) * a.Cout + co;
+            floatx4 v = acc[m][n] + b;
+            if (a.res) v += *reinterpret_cast<const floatx4 *>(a.res + o);
+            v.x = apply_act(v.x, a.act);
+            v.y = apply_act(v.y, a.act);
+            v.z = apply_act(v.z, a.act);
+            v.w = apply_act(v.w, a.act);
+            *reinterpret_cast<floatx4 *>(a.out + o) = v;
+        }
+    }
+}
+
+template <int KS, int STRIDE, int NT>
+static hipError_t launch_conv_t(const ConvArgs &a, size_t lds_bytes, dim3 grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((conv_mfma_kernel<KS, STRIDE, NT>), grid, dim3(256), lds_bytes, st, a);
+    return hipGetLastError();
+}
+
+template <int KS, int STRIDE>
+static hipError_t launch_conv_nt(const ConvArgs &a, int nt, size_t lds_bytes, dim3 grid, hipStream_t st)
+{
+    switch (nt) {
+    case 1: return launch_conv_t<KS, STRIDE, 1>(a, lds_bytes, grid, st);
+    case 2: return launch_conv_t<KS, STRIDE, 2>(a, lds_bytes, grid, st);
+    case 3: return launch_conv_t<KS, STRIDE, 3>(a, lds_bytes, grid, st);
+    case 4: return launch_conv_t<KS, STRIDE, 4>(a, lds_bytes, grid, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_conv(const ConvArgs &a, int ks, int stride, int nt, size_t lds_bytes, dim3 grid, hipStream_t st)
+{
+    if (ks == 3 && stride == 1) return launch_conv_nt<3, 1>(a, nt, lds_bytes, grid, st);
+    if (ks == 3 && stride == 2) return launch_conv_nt<3, 2>(a, nt, lds_bytes, grid, st);
+    if (ks == 1 && stride == 1) return launch_conv_nt<1, 1>(a, nt, lds_bytes, grid, st);
+    if (ks == 1 && stride == 2) return launch_conv_nt<1, 2>(a, nt, lds_bytes, grid, st);
+    return hipErrorInvalidValue;
+}
+
+template <int KS, int STRIDE, int NT>
+static hipError_t set_lds_t()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<KS, STRIDE, NT>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
+// Dynamic LDS above 64 KB has to be allowed per kernel.
+hipError_t conv_set_lds_limits()
+{
+    hipError_t e = hipSuccess;
+#define AIQ_SET(KS, ST)                                             \
+    if (e == hipSuccess) e = set_lds_t<KS, ST, 1>();                \
+    if (e == hipSuccess) e = set_lds_t<KS, ST, 2>();                \
+    if (e == hipSuccess) e = set_lds_t<KS, ST, 3>();                \
+    if (e == hipSuccess) e = set_lds_t<KS, ST, 4>();
+    AIQ_SET(3, 1)
+    AIQ_SET(3, 2)
+    AIQ_SET(1, 1)
+    AIQ_SET(1, 2)
+#undef AIQ_SET
+    return e;
+}
+
+// ------------------------------------------------------------------ depthwise 3x3
+//
+// Bandwidth-bound: 18 FLOP per output element.  One thread produces four
+// consecutive channels of one output pixel (16-byte loads and stores along the
+// NHWC channel axis); neighbouring threads share input rows through L1/L2.
+
+__global__ __launch_bounds__(256) void depthwise3x3_kernel(DepthwiseArgs a)
+{
+    const int s = blockIdx.z, img = blockIdx.y;
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    const int c4n = a.C >> 2;
+    if (idx >= (uint32_t)(a.Hout * a.Wout * c4n)) return;
+    const uint32_t pix = fd_div(idx, a.div_c4);
+    const int c = (idx - pix * c4n) * 4;
+    const uint32_t oy = fd_div(pix, a.div_wout);
+    const int ox = pix - oy * a.Wout;
+    const float *wq = a.bank[scheme_bits_index(a.schemes, s, a.S, a.L, a.slot)];
+    const float *in = a.in + (size_t)s * a.in_scheme_stride + (size_t)img * a.Hin * a.Win * a.C;
+    floatx4 acc = *reinterpret_cast<const floatx4 *>(a.bias + c);
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky) {
+        const int iy = (int)oy * a.stride + ky - 1;
+        if (iy < 0 || iy >= a.Hin) continue;
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx) {
+            const int ix = ox * a.stride + kx - 1;
+            if (ix < 0 || ix >= a.Win) continue;
+            const floatx4 x = *reinterpret_cast<const floatx4 *>(in + ((size_t)iy * a.Win + ix) * a.C + c);
+            const floatx4 w = *reinterpret_cast<const floatx4 *>(wq + (size_t)(ky * 3 + kx) * a.C + c);
+            acc += x * w;
+        }
+    }
+    acc.x = apply_act(acc.x, a.act);
+    acc.y = apply_act(acc.y, a.act);
+    acc.z = apply_act(acc.z, a.act);
+    acc.w = apply_act(acc.w, a.act);
+    float *out = a.out + (size_t)s * a.out_scheme_stride + (((size_t)img * a.Hout + oy) * a.Wout + ox) * a.C + c;
+    *reinterpret_cast<floatx4 *>(out) = acc;
+}
+
+hipError_t launch_depthwise(const DepthwiseArgs &a, int s_total, hipStream_t st)
+{
+    const int per_img = a.Hout * a.Wout * (a.C >> 2);
+    dim3 grid((per_img + 255) / 256, a.N, s_total);
+    hipLaunchKernelGGL(depthwise3x3_kernel, grid, dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ classifier head
+//
+// One workgroup per (scheme, image): global average pool, the classes x C matrix,
+// argmax with the lowest index winning ties.
+
+constexpr int kMaxClasses = 64;
+
+__global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
+{
+    extern __shared__ float sm[]; // pooled[C] then partial[groups][C] scratch, then z[classes]
+    const int s = blockIdx.y, n = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float *x = a.in + (size_t)s * a.in_scheme_stride + (size_t)n * a.HW * a.C;
+    float *pooled = sm;
+    float *partial = sm + a.C;
+    float *z = partial + 256;
+
+    // threads are laid out [group][channel lane]; groups split the positions when C < 256
+    const int cw = a.C < 256 ? a.C : 256;
+    const int groups = 256 / cw;
+    const int grp = tid / cw, cl = tid - grp * cw;
+    const float inv = 1.0f / (float)a.HW;
+    for (int c = cl; c < a.C; c += cw) {
+        float acc = 0.0f;
+        if (grp < groups)
+            for (int i = grp; i < a.HW; i += groups) acc += x[(size_t)i * a.C + c];
+        if (groups > 1) {
+            __syncthreads();
+            partial[tid] = acc;
+            __syncthreads();
+            if (grp == 0) {
+                for (int g = 1; g < groups; ++g) acc += partial[g * cw + cl];
+                pooled[c] = acc * inv;
+            }
+        } else {
+            pooled[c] = acc * inv;
+        }
+    }
+    __syncthreads();
+
+    const float *w = a.bank[scheme_bits_index(a.schemes, s, a.S, a.L, a.slot)];
+    for (int j = wave; j < a.classes; j += 4) {
+        float acc = 0.0f;
+        for (int c = lane; c < a.C; c += 64) acc += pooled[c] * w[(size_t)j * a.C + c];
+        acc = wave_sum(acc);
+        if (lane == 0) z[j] = acc + a.bias[j];
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int best = 0;
+        for (int j = 1; j < a.classes; ++j)
+            if (z[j] > z[best]) best = j;
+        if (s < a.S) {
+            a.top1[(size_t)s * a.top1_stride + n] = best;
+        } else if (a.top1_base) {
+            a.top1_base[n] = best;
+        }
+    }
+    if (a.logits && s < a.S && tid < a.classes)
+        a.logits[((size_t)s * a.logits_n + a.n0 + n) * a.classes + tid] = z[tid];
+}
+
+hipError_t launch_head(const HeadArgs &a, int s_total, hipStream_t st)
+{
+    if (a.N == 0 || s_total == 0) return hipSuccess;
+    const size_t sm = sizeof(float) * ((size_t)a.C + 256 + kMaxClasses);
+    hipLaunchKernelGGL(head_kernel, dim3(a.N, s_total), dim3(256), sm, st, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ agreement
+
+__global__ __launch_bounds__(256) void agree_kernel(AgreeArgs a)
+{
+    const int s = blockIdx.y;
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    int hit = 0;
+    if (n < a.N) hit = a.top1[(size_t)s * a.top1_stride + n] == a.top1_base[n];
+    const int cnt = __popcll(__ballot(hit));
+    __shared__ int wsum[4];
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int tot = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+        if (tot) atomicAdd(a.agree + s, tot);
+    }
+}
+
+hipError_t launch_agree(const AgreeArgs &a, hipStream_t st)
+{
+    if (a.N == 0 || a.S == 0) return hipSuccess;
+    hipLaunchKernelGGL(agree_kernel, dim3((a.N + 255) / 256, a.S), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fill_i32_kernel(int32_t *p, int32_t v, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+hipError_t launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
+    return hipGetLastError();
+}
+
+} // namespace aiq

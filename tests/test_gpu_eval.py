@@ -1,0 +1,190 @@
+"""GPU parity: aiq_eval_schemes against the oracle on the benchmark workloads.
+
+Bars: logits within 1e-3 max relative error, top-1 identical except where the
+oracle's two best logits are nearly tied (relative margin < 1e-5), agreement
+counts equal up to the number of such near-ties.
+"""
+import numpy as np
+import pytest
+
+from parity import check_eval, logits_rel_error, near_tied
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2512_14090_amd as aiq
+    import oracle
+    import synth
+    aiq.load_library()
+    return dict(torch=torch, aiq=aiq, oracle=oracle, synth=synth)
+
+
+def _run_gpu(env, wl, schemes, chunk, top1_base=None, model=None):
+    torch, aiq = env["torch"], env["aiq"]
+    m = model or aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    img = torch.from_numpy(wl["images"]).cuda()
+    r = m.eval_schemes(img, schemes, chunk=chunk, want_logits=True, want_top1=True, top1_base=top1_base)
+    torch.cuda.synchronize()
+    out = {k: (None if v is None else v.cpu().numpy()) for k, v in r.items()}
+    if model is None:
+        m.close()
+    return out
+
+
+def _extra_schemes(wl, seed):
+    """The workload's schemes plus: all-FP32, every uniform width, and random mixes of all six widths."""
+    L = wl["L"]
+    rng = np.random.Generator(np.random.PCG64(seed))
+    rows = [wl["schemes"], np.full((1, L), 32, dtype=np.uint8)]
+    rows += [np.full((1, L), b, dtype=np.uint8) for b in (16, 8, 6, 4, 2)]
+    rows.append(rng.choice(np.array([32, 16, 8, 6, 4, 2], dtype=np.uint8), size=(3, L)))
+    return np.ascontiguousarray(np.concatenate(rows, axis=0))
+
+
+def test_resnet8_full_workload(env):
+    """Workload 0 at full size: 256 images, the seeded scheme plus uniform and mixed extras."""
+    wl = env["synth"].make_workload(0)
+    schemes = _extra_schemes(wl, 5)
+    print("resnet8 full: S=%d N=%d" % (schemes.shape[0], wl["images"].shape[0]), flush=True)
+    ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes)
+    gpu = _run_gpu(env, wl, schemes, chunk=1024)
+    err = check_eval(gpu, ref, 256)
+    print("max logit rel err %.3e agree gpu %s" % (err, gpu["agree"]), flush=True)
+    # the all-FP32 scheme (row 1) reproduces the base pass exactly
+    assert gpu["agree"][1] == 256
+
+
+@pytest.mark.parametrize("n,chunk", [(37, 16), (5, 1), (64, 64), (3, 1024)])
+def test_resnet8_ragged_chunks(env, n, chunk):
+    """N not a multiple of the chunk, of the images-per-workgroup grouping, or of anything else."""
+    wl = env["synth"].make_workload(0, n_images=n)
+    schemes = _extra_schemes(wl, 6)[:4]
+    print(f"resnet8 ragged n={n} chunk={chunk}", flush=True)
+    ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes)
+    gpu = _run_gpu(env, wl, schemes, chunk=chunk)
+    check_eval(gpu, ref, n)
+
+
+def test_resnet20_workload1(env):
+    """Workload 1 (ResNet-20, one scheme over {32,16,8,4}) on its first 96 images, chunked 64 + 32."""
+    wl = env["synth"].make_workload(1, n_images=96)
+    schemes = _extra_schemes(wl, 7)
+    print("resnet20: S=%d N=96" % schemes.shape[0], flush=True)
+    ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes)
+    gpu = _run_gpu(env, wl, schemes, chunk=64)
+    err = check_eval(gpu, ref, 96)
+    print("max logit rel err %.3e" % err, flush=True)
+
+
+def test_mobilenetv2_workload3(env):
+    """Workload 3 (MobileNetV2-32, 10 random layers at 4 bits) on 6 images, 5 of its schemes + extras."""
+    wl = env["synth"].make_workload(3, n_images=6, n_schemes=5)
+    schemes = np.concatenate([wl["schemes"], np.full((1, wl["L"]), 32, np.uint8), np.full((1, wl["L"]), 8, np.uint8),
+                              np.full((1, wl["L"]), 2, np.uint8)])
+    print("mobilenetv2: S=%d N=6" % schemes.shape[0], flush=True)
+    ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes)
+    gpu = _run_gpu(env, wl, schemes, chunk=4)
+    err = check_eval(gpu, ref, 6)
+    print("max logit rel err %.3e" % err, flush=True)
+
+
+def test_variant_models(env):
+    """PlainConvNet20 and HeavyEarlyResNet20 descriptors (64-channel layers at 32x32, stride-1 projection)."""
+    synth, oracle = env["synth"], env["oracle"]
+    for name, nodes in (("plain", synth.plain_convnet20()), ("heavy", synth.heavy_early_resnet20())):
+        rng = np.random.Generator(np.random.PCG64(99))
+        w, b = synth.make_model(nodes, rng)
+        images = synth.make_images(5, rng)
+        L = synth.n_scheme_layers(nodes)
+        wl = dict(desc=synth.desc_array(nodes), weights=w, biases=b, images=images, L=L,
+                  schemes=rng.choice(np.array([32, 8, 4], dtype=np.uint8), size=(2, L)))
+        print(f"variant {name}: L={L}", flush=True)
+        ref = oracle.eval_schemes(wl["desc"], w, b, images, wl["schemes"])
+        gpu = _run_gpu(env, wl, wl["schemes"], chunk=4)
+        check_eval(gpu, ref, 5)
+
+
+def test_greedy_step_full_size_sampled(env):
+    """Workload 2 in the benchmark's launch configuration (40 schemes x 1024 images, one chunk);
+    the oracle recomputes every scheme on a sample of images, properties cover the rest."""
+    torch = env["torch"]
+    wl = env["synth"].make_workload(2)
+    print("greedy step full size", flush=True)
+    gpu = _run_gpu(env, wl, wl["schemes"], chunk=1024)
+    rng = np.random.Generator(np.random.PCG64(3))
+    idx = np.sort(rng.choice(1024, 24, replace=False))
+    ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"][idx], wl["schemes"])
+    err = logits_rel_error(gpu["logits"][:, idx], ref["logits"])
+    assert err <= 1e-3, err
+    tie = near_tied(ref["logits"])
+    assert not ((gpu["top1"][:, idx] != ref["top1"]) & ~tie).any()
+    assert not ((gpu["top1_base"][idx] != ref["top1_base"]) & ~near_tied(ref["logits_base"])).any()
+    np.testing.assert_array_equal(gpu["agree"], (gpu["top1"] == gpu["top1_base"][None]).sum(axis=1))
+    # 8-bit single-layer changes keep more predictions than 4-bit changes of the same layer, on the whole
+    assert gpu["agree"][0::2].sum() >= gpu["agree"][1::2].sum()
+    print("sampled max logit rel err %.3e; agree %s" % (err, gpu["agree"]), flush=True)
+
+
+def test_cd_sweep_chunk_remainder_sampled(env):
+    """Workload 4's chunking (chunks of 1024 with a ragged last chunk) on 2100 images and 6 of its
+    schemes; the oracle checks images on both sides of every chunk boundary and in the tail."""
+    wl = env["synth"].make_workload(4, n_images=2100, n_schemes=6)
+    print("cd sweep chunks", flush=True)
+    gpu = _run_gpu(env, wl, wl["schemes"], chunk=1024)
+    idx = np.array([0, 1, 1022, 1023, 1024, 1025, 2046, 2047, 2048, 2049, 2098, 2099])
+    ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"][idx], wl["schemes"])
+    assert logits_rel_error(gpu["logits"][:, idx], ref["logits"]) <= 1e-3
+    assert not ((gpu["top1"][:, idx] != ref["top1"]) & ~near_tied(ref["logits"])).any()
+    np.testing.assert_array_equal(gpu["agree"], (gpu["top1"] == gpu["top1_base"][None]).sum(axis=1))
+
+
+def test_base_reuse_optional_outputs_and_determinism(env):
+    torch, aiq = env["torch"], env["aiq"]
+    wl = env["synth"].make_workload(0, n_images=50)
+    schemes = _extra_schemes(wl, 8)[:5]
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    img = torch.from_numpy(wl["images"]).cuda()
+    a = m.eval_schemes(img, schemes, chunk=32, want_logits=True, want_top1=True)
+    torch.cuda.synchronize()
+    a = {k: v.clone() for k, v in a.items()}
+    # same call again: identical bits (no float atomics, no order dependence)
+    b = m.eval_schemes(img, schemes, chunk=32, want_logits=True, want_top1=True)
+    torch.cuda.synchronize()
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+    # reuse the base top-1, drop the optional outputs, different chunking
+    c = m.eval_schemes(img, schemes, chunk=7, top1_base=a["top1_base"])
+    torch.cuda.synchronize()
+    assert c["logits"] is None and c["top1"] is None
+    assert torch.equal(c["agree"], a["agree"])
+    # a different chunk size changes nothing in the logits
+    d = m.eval_schemes(img, schemes, chunk=50, want_logits=True)
+    torch.cuda.synchronize()
+    assert torch.equal(d["logits"], a["logits"])
+    m.close()
+
+
+def test_empty_inputs_and_error_paths(env):
+    torch, aiq = env["torch"], env["aiq"]
+    wl = env["synth"].make_workload(0, n_images=4)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    img = torch.from_numpy(wl["images"]).cuda()
+    r = m.eval_schemes(img, np.zeros((0, wl["L"]), dtype=np.uint8), want_top1=True)
+    torch.cuda.synchronize()
+    assert r["agree"].numel() == 0 and r["top1_base"].numel() == 4
+    r = m.eval_schemes(img[:0], wl["schemes"])
+    torch.cuda.synchronize()
+    assert r["agree"].cpu().tolist() == [0]
+    bad = wl["schemes"].copy()
+    bad[0, 3] = 5
+    with pytest.raises(aiq.AiqError) as e:
+        m.eval_schemes(img, bad)
+    assert e.value.code == 2
+    with pytest.raises(aiq.AiqError) as e:
+        m.eval_schemes(img, np.full((1, wl["L"] + 1), 8, dtype=np.uint8))
+    assert e.value.code == 3
+    m.close()
