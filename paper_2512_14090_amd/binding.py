@@ -12,10 +12,11 @@ _lib = None
 
 EXPORTED_SYMBOLS = (
     "aiq_status_str", "aiq_last_hip_error", "aiq_layer_ai", "aiq_quantize_weights", "aiq_model_create",
-    "aiq_model_destroy", "aiq_model_scheme_layers", "aiq_model_classes", "aiq_eval_workspace_bytes",
+    "aiq_model_create_ex", "aiq_model_is_lds_resident", "aiq_model_destroy", "aiq_model_scheme_layers", "aiq_model_classes", "aiq_eval_workspace_bytes",
     "aiq_eval_schemes", "aiq_profile_enable", "aiq_profile_read",
 )
-K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE = range(5)
+K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED = range(6)
+MODEL_LAYERWISE = 1
 _DESC_INTS = 13
 
 
@@ -46,6 +47,9 @@ def load_library():
     lib.aiq_quantize_weights.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_void_p]
     lib.aiq_model_create.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
+    lib.aiq_model_create_ex.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32,
+                                        C.POINTER(C.c_void_p)]
+    lib.aiq_model_is_lds_resident.argtypes = [C.c_void_p]
     lib.aiq_model_destroy.argtypes = [C.c_void_p]
     lib.aiq_model_destroy.restype = None
     lib.aiq_model_scheme_layers.argtypes = [C.c_void_p]
@@ -118,7 +122,7 @@ def quantize_weights(w, bits, want_codes=True, stream=None):
 class Model:
     """Owns an aiq_model handle.  desc: int32 [n][13]; weights / biases: lists of fp32 numpy arrays."""
 
-    def __init__(self, desc, weights, biases):
+    def __init__(self, desc, weights, biases, layerwise=False):
         self._h = C.c_void_p(None)
         self._lib = load_library()
         d = _desc(desc)
@@ -130,8 +134,10 @@ class Model:
         wp = (C.c_void_p * n)(*[w.ctypes.data for w in ws])
         bp = (C.c_void_p * n)(*[b.ctypes.data for b in bs])
         h = C.c_void_p(None)
-        _check(self._lib.aiq_model_create(d.ctypes.data, n, wp, bp, C.byref(h)), "aiq_model_create")
+        _check(self._lib.aiq_model_create_ex(d.ctypes.data, n, wp, bp, MODEL_LAYERWISE if layerwise else 0,
+                                             C.byref(h)), "aiq_model_create_ex")
         self._h = h
+        self.lds_resident = bool(self._lib.aiq_model_is_lds_resident(h))
         self.L = int(self._lib.aiq_model_scheme_layers(h))
         self.classes = int(self._lib.aiq_model_classes(h))
         self._workspace = None

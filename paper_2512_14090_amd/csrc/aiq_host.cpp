@@ -75,6 +75,11 @@ struct aiq_model {
     int n_jobs = 0, n_quant_blocks = 0;
     std::vector<QuantJob> jobs_host;
     std::vector<void *> allocations;
+    // LDS-resident path (CIFAR-style ResNets)
+    bool fused = false;
+    std::vector<FusedOp> fused_ops;
+    FusedOp *fused_ops_dev = nullptr;
+    double fused_flops_per_image = 0.0;
     // profiling
     bool prof_on = false;
     std::vector<hipEvent_t> ev_pool;
@@ -124,6 +129,75 @@ aiq_status plan_conv(Node &nd)
     }
     nd.plan = p;
     return AIQ_OK;
+}
+
+// Recognises stem -> basic blocks (identity, or stride-2 with a 1x1 projection) -> classifier
+// with 16/32/64 channels at 32/16/8 pixels, and lays the tensors out in two LDS regions:
+// a block reads its input from one region, writes the intermediate to the other and the
+// block output back in place.  Returns false if the graph has any other shape.
+bool plan_fused(const std::vector<Node> &nodes, std::vector<FusedOp> &ops)
+{
+    const int n = (int)nodes.size();
+    auto is_conv = [&](int i, int k, int stride, int cin, int cout, int hin) {
+        const aiq_layer_desc &d = nodes[i].d;
+        return d.kind == 0 && d.kh == k && d.kw == k && d.stride == stride && d.cin == cin && d.cout == cout &&
+               d.hin == hin && d.win == hin;
+    };
+    if (n < 2 || !is_conv(0, 3, 1, 3, 16, 32) || nodes[0].d.residual >= 0) return false;
+    const int R[2] = {0, kFusedRegionFloats};
+    auto mk = [&](int type, int node, int src, int dst, int res, int res_padded, int zero_ring) {
+        FusedOp op{};
+        op.type = type;
+        op.slot = nodes[node].d.scheme_slot;
+        op.act = nodes[node].d.act;
+        op.src_off = src;
+        op.dst_off = dst;
+        op.res_off = res;
+        op.res_padded = res_padded;
+        op.zero_ring = zero_ring;
+        op.classes = nodes[node].d.cout;
+        ops.push_back(op);
+    };
+    ops.clear();
+    int reg = 0; // region holding the current block input
+    mk(kOpStem, 0, R[1], R[0], -1, 0, 0);
+    int cur = 0, c = 16, h = 32, i = 1;
+    while (i < n && nodes[i].d.kind != 2) {
+        const aiq_layer_desc &c1 = nodes[i].d;
+        if (c1.input != cur || c1.residual >= 0) return false;
+        const int ctype = c == 16 ? kOpC16 : (c == 32 ? kOpC32 : kOpC64);
+        if (is_conv(i, 3, 1, c, c, h)) {
+            if (i + 1 >= n || !is_conv(i + 1, 3, 1, c, c, h)) return false;
+            const aiq_layer_desc &c2 = nodes[i + 1].d;
+            if (c2.input != i || c2.residual != cur) return false;
+            mk(ctype, i, R[reg], R[1 - reg], -1, 0, 0);
+            mk(ctype, i + 1, R[1 - reg], R[reg], R[reg], 1, 0);
+            cur = i + 1;
+            i += 2;
+        } else if (c < 64 && is_conv(i, 3, 2, c, 2 * c, h)) {
+            if (i + 2 >= n || !is_conv(i + 1, 1, 2, c, 2 * c, h) || !is_conv(i + 2, 3, 1, 2 * c, 2 * c, h / 2))
+                return false;
+            const aiq_layer_desc &sc = nodes[i + 1].d, &c2 = nodes[i + 2].d;
+            if (sc.input != cur || sc.residual >= 0 || c2.input != i || c2.residual != i + 1) return false;
+            const int ho = h / 2, co = 2 * c;
+            const int t_floats = (co / 4) * (ho + 2) * (ho + 2) * 4;
+            if (t_floats + co * ho * ho > kFusedRegionFloats) return false;
+            mk(c == 16 ? kOpT16_32 : kOpT32_64, i, R[reg], R[1 - reg], -1, 0, 1);
+            mk(c == 16 ? kOpS16_32 : kOpS32_64, i + 1, R[reg], R[1 - reg] + t_floats, -1, 0, 0);
+            mk(co == 32 ? kOpC32 : kOpC64, i + 2, R[1 - reg], R[reg], R[1 - reg] + t_floats, 0, 1);
+            cur = i + 2;
+            c = co;
+            h = ho;
+            i += 3;
+        } else {
+            return false;
+        }
+    }
+    if (i != n - 1) return false;
+    const aiq_layer_desc &fc = nodes[i].d;
+    if (fc.kind != 2 || fc.input != cur || fc.cin != 64 || c != 64 || h != 8 || fc.hin != 8 || fc.win != 8) return false;
+    mk(kOpHead, i, R[reg], R[1 - reg], -1, 0, 0);
+    return true;
 }
 
 aiq_status validate_graph(const aiq_layer_desc *layers, int n_layers)
@@ -328,10 +402,19 @@ void aiq_model_destroy(aiq_model *m)
     delete m;
 }
 
+int32_t aiq_model_is_lds_resident(const aiq_model *m) { return m ? (m->fused ? 1 : 0) : -1; }
+
 aiq_status aiq_model_create(const aiq_layer_desc *layers, int32_t n_layers, const float *const *w_host,
                             const float *const *bias_host, aiq_model **out)
 {
+    return aiq_model_create_ex(layers, n_layers, w_host, bias_host, 0u, out);
+}
+
+aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, const float *const *w_host,
+                               const float *const *bias_host, uint32_t flags, aiq_model **out)
+{
     if (out) *out = nullptr;
+    if (flags & ~(uint32_t)AIQ_MODEL_LAYERWISE) return AIQ_INVALID_ARG;
     if (!layers || n_layers <= 0 || !w_host || !bias_host || !out) return AIQ_INVALID_ARG;
     for (int l = 0; l < n_layers; ++l)
         if (!w_host[l] || !bias_host[l]) return AIQ_INVALID_ARG;
@@ -384,6 +467,14 @@ aiq_status aiq_model_create(const aiq_layer_desc *layers, int32_t n_layers, cons
         }
     }
 
+    if (!(flags & AIQ_MODEL_LAYERWISE)) m->fused = plan_fused(m->nodes, m->fused_ops);
+    if (m->fused) {
+        Node &stem = m->nodes[0];
+        stem.layout = kLayoutStem;
+        stem.bank_elems = (size_t)((stem.d.cout + 15) / 16) * 9 * 64;
+        for (const Node &nd : m->nodes) m->fused_flops_per_image += nd.flops_per_image;
+    }
+
     // activation buffers: a node's output lives until its last reader has run
     std::vector<int> last_use(n_layers, -1);
     for (int l = 0; l < n_layers; ++l) {
@@ -409,14 +500,14 @@ aiq_status aiq_model_create(const aiq_layer_desc *layers, int32_t n_layers, cons
         m->nodes[l].buf = pick;
         m->buf_elems = std::max(m->buf_elems, m->nodes[l].out_elems);
     }
-    m->n_bufs = (int)owner.size();
+    m->n_bufs = m->fused ? 0 : (int)owner.size();
 
     // device copies, bank slots, quantize job table
     auto fail = [&](aiq_status code) {
         aiq_model_destroy(m);
         return code;
     };
-    if (!hip_ok(conv_set_lds_limits())) return fail(AIQ_DEVICE_ERROR);
+    if (!hip_ok(conv_set_lds_limits()) || !hip_ok(fused_set_lds_limit())) return fail(AIQ_DEVICE_ERROR);
     std::vector<int32_t> block_job;
     for (int l = 0; l < n_layers; ++l) {
         Node &nd = m->nodes[l];
@@ -460,6 +551,18 @@ aiq_status aiq_model_create(const aiq_layer_desc *layers, int32_t n_layers, cons
         if (!hip_ok(hipMemcpy(m->jobs_dev, m->jobs_host.data(), sizeof(QuantJob) * m->n_jobs,
                               hipMemcpyHostToDevice)) ||
             !hip_ok(hipMemcpy(m->block_job_dev, block_job.data(), sizeof(int32_t) * block_job.size(),
+                              hipMemcpyHostToDevice)))
+            return fail(AIQ_DEVICE_ERROR);
+    }
+    if (m->fused) {
+        // ops follow the node order with projections in place, so op o describes node o
+        for (size_t o = 0; o < m->fused_ops.size(); ++o) {
+            const Node &nd = m->nodes[o];
+            for (int b = 0; b < kNumBits; ++b) m->fused_ops[o].bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+            m->fused_ops[o].bias = nd.bias;
+        }
+        if ((st = dev_alloc(m, &m->fused_ops_dev, m->fused_ops.size())) != AIQ_OK) return fail(st);
+        if (!hip_ok(hipMemcpy(m->fused_ops_dev, m->fused_ops.data(), sizeof(FusedOp) * m->fused_ops.size(),
                               hipMemcpyHostToDevice)))
             return fail(AIQ_DEVICE_ERROR);
     }
@@ -529,6 +632,43 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
     for (int n0 = 0; n0 < N; n0 += chunk) {
         const int n = std::min(chunk, N - n0);
         auto buf_ptr = [&](int b) { return reinterpret_cast<float *>(ws + wl.act_off + wl.buf_stride * b); };
+        if (m->fused) {
+            FusedArgs a{};
+            a.ops = m->fused_ops_dev;
+            a.n_ops = (int32_t)m->fused_ops.size();
+            a.images = images + (size_t)n0 * m->nodes[0].in_elems;
+            a.schemes = schemes_dev;
+            a.S = S;
+            a.L = m->L;
+            a.N = n;
+            a.logits = logits;
+            a.logits_n = N;
+            a.n0 = n0;
+            if (top1) {
+                a.top1 = top1 + n0;
+                a.top1_stride = N;
+            } else {
+                a.top1 = top1_tmp;
+                a.top1_stride = chunk;
+            }
+            a.top1_base = run_base ? top1_base + n0 : nullptr;
+            const double work = (double)s_total * n;
+            {
+                ProfScope ps(m, st, AIQ_K_FUSED, m->fused_flops_per_image * work,
+                             work * 4.0 * (m->nodes[0].in_elems + m->classes));
+                AIQ_HIP(launch_fused(a, s_total, st));
+            }
+            AgreeArgs g{};
+            g.top1 = a.top1;
+            g.top1_stride = a.top1_stride;
+            g.top1_base = top1_base + n0;
+            g.agree = agree;
+            g.N = n;
+            g.S = S;
+            ProfScope ps(m, st, AIQ_K_AGREE, 0.0, 8.0 * S * n);
+            AIQ_HIP(launch_agree(g, st));
+            continue;
+        }
         for (size_t l = 0; l < m->nodes.size(); ++l) {
             const Node &nd = m->nodes[l];
             const aiq_layer_desc &d = nd.d;

@@ -28,7 +28,8 @@ constexpr int kBitsOfIndex[kNumBits] = {32, 16, 8, 6, 4, 2};
 enum WeightLayout : int32_t {
     kLayoutPlain = 0,   // [cout][k]
     kLayoutMfma = 1,    // dense convolution: [cout/16][tap][cin/16][64 lanes][4], zero padded
-    kLayoutTapMajor = 2 // depthwise: [tap][channels]
+    kLayoutTapMajor = 2, // depthwise: [tap][channels]
+    kLayoutStem = 3      // dense convolution with cin <= 4: [cout/16][tap][64 lanes], lane = ci*16 + co
 };
 
 // One (weight matrix, bit-width) quantization job.
@@ -139,5 +140,63 @@ hipError_t launch_head(const HeadArgs &a, int s_total, hipStream_t st);
 hipError_t launch_agree(const AgreeArgs &a, hipStream_t st);
 hipError_t launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t st);
 hipError_t conv_set_lds_limits();
+
+} // namespace aiq
+
+// ---------------------------------------------------------------- LDS-resident path
+//
+// CIFAR-style ResNets (3x3 convolutions of 16/32/64 channels at 32/16/8 pixels, basic
+// blocks, 1x1 stride-2 projections) keep every activation of one image in LDS.  One
+// workgroup scores one (scheme, image) pair: the op list below is interpreted in order,
+// each op reads and writes LDS regions, only the image, the weights and the logits touch
+// global memory.
+namespace aiq {
+
+enum FusedOpType : int32_t {
+    kOpStem = 0,     // 3x3, 3 -> 16, 32x32, image plane -> padded planes
+    kOpC16 = 1,      // 3x3, 16 -> 16 at 32x32
+    kOpT16_32 = 2,   // 3x3 stride 2, 16 -> 32, 32x32 -> 16x16
+    kOpS16_32 = 3,   // 1x1 stride 2, 16 -> 32 (projection, unpadded destination)
+    kOpC32 = 4,      // 3x3, 32 -> 32 at 16x16
+    kOpT32_64 = 5,   // 3x3 stride 2, 32 -> 64, 16x16 -> 8x8
+    kOpS32_64 = 6,   // 1x1 stride 2, 32 -> 64
+    kOpC64 = 7,      // 3x3, 64 -> 64 at 8x8
+    kOpHead = 8      // global average pool + classifier + argmax
+};
+
+struct FusedOp {
+    const float *bank[kNumBits];
+    const float *bias;
+    int32_t type;
+    int32_t slot;      // scheme slot or -1
+    int32_t act;
+    int32_t src_off;   // LDS offsets in floats
+    int32_t dst_off;
+    int32_t res_off;   // -1: no residual
+    int32_t res_padded; // residual region has the padded layout of the destination
+    int32_t zero_ring; // destination gets a new layout: clear its border first
+    int32_t classes;   // head only
+    int32_t pad_[3];
+};
+
+constexpr int kFusedThreads = 512;
+constexpr int kFusedRegionFloats = 18560; // 74 240 bytes: a padded 34x34x16 tensor, or 18x18x32 + 16x16x32
+constexpr int kFusedLdsBytes = 2 * kFusedRegionFloats * 4;
+
+struct FusedArgs {
+    const FusedOp *ops; // device
+    int32_t n_ops;
+    const float *images; // [N][32][32][3]
+    const uint8_t *schemes;
+    int32_t S, L, N;
+    float *logits;
+    int64_t logits_n, n0;
+    int32_t *top1;
+    int64_t top1_stride;
+    int32_t *top1_base;
+};
+
+hipError_t launch_fused(const FusedArgs &a, int s_total, hipStream_t st);
+hipError_t fused_set_lds_limit();
 
 } // namespace aiq

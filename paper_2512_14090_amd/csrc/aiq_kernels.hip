@@ -54,6 +54,7 @@ __device__ inline size_t quant_out_index(const QuantJob &j, int c, int i)
     const int t = i % j.taps;
     const int ci = i / j.taps;
     if (j.layout == kLayoutTapMajor) return (size_t)t * j.cout + c; // depthwise: k == taps, ci == 0
+    if (j.layout == kLayoutStem) return (((size_t)(c >> 4) * j.taps + t) * 64) + ci * 16 + (c & 15);
     const int ct = c >> 4, co = c & 15;
     const int cb = ci >> 4, kq = (ci & 15) >> 2, jj = ci & 3;
     return ((((size_t)ct * j.taps + t) * j.cblocks + cb) * 64 + (kq * 16 + co)) * 4 + jj;

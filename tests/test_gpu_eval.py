@@ -23,9 +23,14 @@ def env():
     return dict(torch=torch, aiq=aiq, oracle=oracle, synth=synth)
 
 
-def _run_gpu(env, wl, schemes, chunk, top1_base=None, model=None):
+PATHS = [pytest.param(False, id="lds_resident"), pytest.param(True, id="layerwise")]
+
+
+def _run_gpu(env, wl, schemes, chunk, top1_base=None, model=None, layerwise=False, expect_resident=None):
     torch, aiq = env["torch"], env["aiq"]
-    m = model or aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    m = model or aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=layerwise)
+    if expect_resident is not None:
+        assert m.lds_resident == expect_resident
     img = torch.from_numpy(wl["images"]).cuda()
     r = m.eval_schemes(img, schemes, chunk=chunk, want_logits=True, want_top1=True, top1_base=top1_base)
     torch.cuda.synchronize()
@@ -45,37 +50,40 @@ def _extra_schemes(wl, seed):
     return np.ascontiguousarray(np.concatenate(rows, axis=0))
 
 
-def test_resnet8_full_workload(env):
+@pytest.mark.parametrize("layerwise", PATHS)
+def test_resnet8_full_workload(env, layerwise):
     """Workload 0 at full size: 256 images, the seeded scheme plus uniform and mixed extras."""
     wl = env["synth"].make_workload(0)
     schemes = _extra_schemes(wl, 5)
     print("resnet8 full: S=%d N=%d" % (schemes.shape[0], wl["images"].shape[0]), flush=True)
     ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes)
-    gpu = _run_gpu(env, wl, schemes, chunk=1024)
+    gpu = _run_gpu(env, wl, schemes, chunk=1024, layerwise=layerwise, expect_resident=not layerwise)
     err = check_eval(gpu, ref, 256)
     print("max logit rel err %.3e agree gpu %s" % (err, gpu["agree"]), flush=True)
     # the all-FP32 scheme (row 1) reproduces the base pass exactly
     assert gpu["agree"][1] == 256
 
 
+@pytest.mark.parametrize("layerwise", PATHS)
 @pytest.mark.parametrize("n,chunk", [(37, 16), (5, 1), (64, 64), (3, 1024)])
-def test_resnet8_ragged_chunks(env, n, chunk):
+def test_resnet8_ragged_chunks(env, n, chunk, layerwise):
     """N not a multiple of the chunk, of the images-per-workgroup grouping, or of anything else."""
     wl = env["synth"].make_workload(0, n_images=n)
     schemes = _extra_schemes(wl, 6)[:4]
     print(f"resnet8 ragged n={n} chunk={chunk}", flush=True)
     ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes)
-    gpu = _run_gpu(env, wl, schemes, chunk=chunk)
+    gpu = _run_gpu(env, wl, schemes, chunk=chunk, layerwise=layerwise)
     check_eval(gpu, ref, n)
 
 
-def test_resnet20_workload1(env):
+@pytest.mark.parametrize("layerwise", PATHS)
+def test_resnet20_workload1(env, layerwise):
     """Workload 1 (ResNet-20, one scheme over {32,16,8,4}) on its first 96 images, chunked 64 + 32."""
     wl = env["synth"].make_workload(1, n_images=96)
     schemes = _extra_schemes(wl, 7)
     print("resnet20: S=%d N=96" % schemes.shape[0], flush=True)
     ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes)
-    gpu = _run_gpu(env, wl, schemes, chunk=64)
+    gpu = _run_gpu(env, wl, schemes, chunk=64, layerwise=layerwise, expect_resident=not layerwise)
     err = check_eval(gpu, ref, 96)
     print("max logit rel err %.3e" % err, flush=True)
 
@@ -87,7 +95,7 @@ def test_mobilenetv2_workload3(env):
                               np.full((1, wl["L"]), 2, np.uint8)])
     print("mobilenetv2: S=%d N=6" % schemes.shape[0], flush=True)
     ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes)
-    gpu = _run_gpu(env, wl, schemes, chunk=4)
+    gpu = _run_gpu(env, wl, schemes, chunk=4, expect_resident=False)
     err = check_eval(gpu, ref, 6)
     print("max logit rel err %.3e" % err, flush=True)
 
@@ -104,17 +112,18 @@ def test_variant_models(env):
                   schemes=rng.choice(np.array([32, 8, 4], dtype=np.uint8), size=(2, L)))
         print(f"variant {name}: L={L}", flush=True)
         ref = oracle.eval_schemes(wl["desc"], w, b, images, wl["schemes"])
-        gpu = _run_gpu(env, wl, wl["schemes"], chunk=4)
+        gpu = _run_gpu(env, wl, wl["schemes"], chunk=4, expect_resident=False)
         check_eval(gpu, ref, 5)
 
 
-def test_greedy_step_full_size_sampled(env):
+@pytest.mark.parametrize("layerwise", PATHS)
+def test_greedy_step_full_size_sampled(env, layerwise):
     """Workload 2 in the benchmark's launch configuration (40 schemes x 1024 images, one chunk);
     the oracle recomputes every scheme on a sample of images, properties cover the rest."""
     torch = env["torch"]
     wl = env["synth"].make_workload(2)
     print("greedy step full size", flush=True)
-    gpu = _run_gpu(env, wl, wl["schemes"], chunk=1024)
+    gpu = _run_gpu(env, wl, wl["schemes"], chunk=1024, layerwise=layerwise)
     rng = np.random.Generator(np.random.PCG64(3))
     idx = np.sort(rng.choice(1024, 24, replace=False))
     ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"][idx], wl["schemes"])
@@ -142,11 +151,12 @@ def test_cd_sweep_chunk_remainder_sampled(env):
     np.testing.assert_array_equal(gpu["agree"], (gpu["top1"] == gpu["top1_base"][None]).sum(axis=1))
 
 
-def test_base_reuse_optional_outputs_and_determinism(env):
+@pytest.mark.parametrize("layerwise", PATHS)
+def test_base_reuse_optional_outputs_and_determinism(env, layerwise):
     torch, aiq = env["torch"], env["aiq"]
     wl = env["synth"].make_workload(0, n_images=50)
     schemes = _extra_schemes(wl, 8)[:5]
-    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=layerwise)
     img = torch.from_numpy(wl["images"]).cuda()
     a = m.eval_schemes(img, schemes, chunk=32, want_logits=True, want_top1=True)
     torch.cuda.synchronize()
@@ -168,10 +178,11 @@ def test_base_reuse_optional_outputs_and_determinism(env):
     m.close()
 
 
-def test_empty_inputs_and_error_paths(env):
+@pytest.mark.parametrize("layerwise", PATHS)
+def test_empty_inputs_and_error_paths(env, layerwise):
     torch, aiq = env["torch"], env["aiq"]
     wl = env["synth"].make_workload(0, n_images=4)
-    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=layerwise)
     img = torch.from_numpy(wl["images"]).cuda()
     r = m.eval_schemes(img, np.zeros((0, wl["L"]), dtype=np.uint8), want_top1=True)
     torch.cuda.synchronize()
