@@ -17,28 +17,56 @@ namespace aiq {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-__device__ inline float fused_act(float v, int act)
+// Weight and bias pointers come out of the op table, so the compiler only knows them as
+// generic pointers; loading through an explicit global address space gives global_load
+// (counted by vmcnt only) instead of flat_load (which also holds up LDS waits).
+typedef const __attribute__((address_space(1))) floatx4 *gvec4_ptr;
+typedef const __attribute__((address_space(1))) float *gfloat_ptr;
+__device__ __forceinline__ floatx4 gload4(const float *p) { return *(gvec4_ptr)(p); }
+__device__ __forceinline__ float gload1(const float *p) { return *(gfloat_ptr)(p); }
+
+// Activation as a clamp to [lo, hi]: none = (-inf, inf), ReLU = (0, inf), ReLU6 = (0, 6).
+__device__ __forceinline__ floatx4 clamp4(floatx4 v, float lo, float hi)
 {
-    if (act >= 1) v = fmaxf(v, 0.0f);
-    if (act == 2) v = fminf(v, 6.0f);
+    v.x = fminf(fmaxf(v.x, lo), hi);
+    v.y = fminf(fmaxf(v.y, lo), hi);
+    v.z = fminf(fmaxf(v.z, lo), hi);
+    v.w = fminf(fmaxf(v.w, lo), hi);
     return v;
 }
+__device__ __forceinline__ float act_lo(int act) { return act >= 1 ? 0.0f : -__builtin_inff(); }
+__device__ __forceinline__ float act_hi(int act) { return act == 2 ? 6.0f : __builtin_inff(); }
+
+// Shape constants of the dense ops, indexed by FusedOpType (0 where not a dense convolution):
+// reduction steps (taps x 16-channel blocks) and output-channel tiles.  Used to prefetch the
+// first weights of the next op while the current one finishes.
+__device__ constexpr int kOpSteps[9] = {0, 9, 9, 1, 18, 18, 2, 36, 0};
+__device__ constexpr int kOpCoutTiles[9] = {0, 1, 2, 2, 2, 4, 4, 4, 0};
+constexpr int kWeightRing = 4; // weight chunks in flight per wavefront
 
 // One dense convolution, LDS -> LDS.  NW wavefronts; wavefront w owns output-channel tile
-// w % CT and MT pixel tiles; weights stream from global memory (L2-resident, MFMA operand
-// order) one tap ahead of their use.
+// w % CT and MT pixel tiles.  The reduction is a straight line of STEPS = taps x CB steps;
+// step k's activations (one 16-byte LDS read per pixel tile) are issued before step k-1's
+// MFMAs, its weights (one 16-byte global read, L2-resident, MFMA operand order) kWeightRing
+// steps ahead.  Weight chunk c always lives in ring slot c % kWeightRing; wr[] arrives holding
+// this op's first chunks (loaded while the previous op ran) and leaves holding those of the
+// next op (next_w; next_last = index of its last chunk), so no wavefront waits on L2 right after a barrier.
 template <int CIN, int COUT, int HIN, int STRIDE, int KS, bool DST_PADDED, int NW>
-__device__ __forceinline__ void fused_conv(const float *src, float *dst,
-                                           const float *res, bool res_padded,
+__device__ __forceinline__ void fused_conv(const float *src, float *dst, const float *res, bool res_padded,
                                            const float *__restrict__ wq, const float *__restrict__ bias, int act,
-                                           bool zero_ring, int tid)
+                                           bool zero_ring, int tid, floatx4 (&wr)[kWeightRing],
+                                           const float *__restrict__ next_w, int next_last)
 {
     constexpr int CB = CIN / 16, CT = COUT / 16, HO = HIN / STRIDE, PT = HO * HO / 16, T = KS * KS;
+    constexpr int STEPS = T * CB;
     constexpr int WPC = NW / CT;   // wavefronts per output-channel tile
     constexpr int MT = PT / WPC;   // pixel tiles per wavefront
     static_assert(NW % CT == 0 && PT % WPC == 0 && MT >= 1, "tiles must divide evenly");
     constexpr int PIN = HIN + 2, POUT = HO + 2;
     constexpr int SRC_PLANE = PIN * PIN * 4, DST_PLANE = (DST_PADDED ? POUT * POUT : HO * HO) * 4;
+    // the per-lane index arithmetic below depends only on tid; without this the compiler
+    // hoists it for every op type out of the op loop and runs out of registers
+    asm volatile("" : "+v"(tid));
     const int lane = tid & 63, wave = tid >> 6, p = lane & 15, kq = lane >> 4;
     const int ct = wave % CT, pg = wave / CT;
 
@@ -55,99 +83,121 @@ __device__ __forceinline__ void fused_conv(const float *src, float *dst,
         }
     }
 
-    int src_off[MT], out_y[MT], out_x[MT];
+    // per pixel tile: source offset of the lane's pixel; destination / residual offsets are
+    // recomputed where they are used (cheap shifts) rather than held across the reduction
+    int src_off[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
         const int P = (pg + i * WPC) * 16 + p;
         const int oy = P / HO, ox = P % HO;
-        out_y[i] = oy;
-        out_x[i] = ox;
         src_off[i] = kq * SRC_PLANE + ((oy * STRIDE) * PIN + ox * STRIDE) * 4 + (KS == 1 ? (PIN + 1) * 4 : 0);
     }
+    auto out_index = [&](int i, bool padded) {
+        const int P = (pg + i * WPC) * 16 + p;
+        const int oy = P / HO, ox = P % HO;
+        const int plane = ct * 4 + kq;
+        return padded ? plane * (POUT * POUT * 4) + ((oy + 1) * POUT + ox + 1) * 4
+                      : plane * (HO * HO * 4) + (oy * HO + ox) * 4;
+    };
+    const float *wbase = wq + ((size_t)ct * STEPS * 64 + lane) * 4;
+    const floatx4 bv = gload4(bias + ct * 16 + kq * 4);
+    const float lo = act_lo(act), hi = act_hi(act);
 
     floatx4 acc[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    const float *wbase = wq + ((size_t)ct * T * CB * 64 + lane) * 4;
-    const floatx4 bv = *reinterpret_cast<const floatx4 *>(bias + ct * 16 + kq * 4);
-    floatx4 wcur[CB], wnext[CB];
+    floatx4 xb[2][MT];
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) wcur[cb] = *reinterpret_cast<const floatx4 *>(wbase + cb * 256);
+    for (int i = 0; i < MT; ++i) xb[0][i] = *reinterpret_cast<const floatx4 *>(src + src_off[i]);
 
-#pragma unroll 1
-    for (int t = 0; t < T; ++t) {
-        if (t + 1 < T) {
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-                wnext[cb] = *reinterpret_cast<const floatx4 *>(wbase + ((t + 1) * CB + cb) * 256);
-        }
-        const int ky = t / KS, kx = t - ky * KS;
-        const int tapoff = (ky * PIN + kx) * 4;
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            floatx4 xb[MT];
+    for (int k = 0; k < STEPS; ++k) {
+        // keep each step's prefetches in that step: nothing is scheduled across this point
+        __builtin_amdgcn_sched_barrier(0);
+        const int cur = k & 1;
+        if (k + 1 < STEPS) {
+            const int t = (k + 1) / CB, cb = (k + 1) % CB;
+            const int off = ((t / KS) * PIN + (t % KS)) * 4 + cb * 4 * SRC_PLANE;
 #pragma unroll
             for (int i = 0; i < MT; ++i)
-                xb[i] = *reinterpret_cast<const floatx4 *>(src + src_off[i] + tapoff + cb * 4 * SRC_PLANE);
+                xb[cur ^ 1][i] = *reinterpret_cast<const floatx4 *>(src + src_off[i] + off);
+        } else if (res) {
+            // last step: the idle activation buffer receives the residual values
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int i = 0; i < MT; ++i)
-                    acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(wcur[cb][j], xb[i][j], acc[i], 0, 0, 0);
+            for (int i = 0; i < MT; ++i)
+                xb[cur ^ 1][i] = *reinterpret_cast<const floatx4 *>(res + out_index(i, res_padded));
+        }
+        const floatx4 w = wr[k % kWeightRing];
+        if (k + kWeightRing < STEPS) {
+            wr[k % kWeightRing] = gload4(wbase + (k + kWeightRing) * 256);
+        } else {
+            // this ring slot is free from here on: fetch the next op's chunk that lives in it
+            // (branch-free: a chunk index past the next op's last one re-reads its last chunk)
+            wr[k % kWeightRing] = gload4(next_w + min(k % kWeightRing, next_last) * 256);
         }
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) wcur[cb] = wnext[cb];
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w[j], xb[cur][i][j], acc[i], 0, 0, 0);
     }
-
+    __builtin_amdgcn_sched_barrier(0);
+    // ops with fewer steps than ring slots (1x1 projections) never used the upper slots
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-        const int plane = ct * 4 + kq;
-        const int didx = plane * DST_PLANE +
-                         (DST_PADDED ? ((out_y[i] + 1) * POUT + out_x[i] + 1) : (out_y[i] * HO + out_x[i])) * 4;
-        floatx4 v = acc[i] + bv;
-        if (res) {
-            const int ridx = res_padded ? plane * (POUT * POUT * 4) + ((out_y[i] + 1) * POUT + out_x[i] + 1) * 4
-                                        : plane * (HO * HO * 4) + (out_y[i] * HO + out_x[i]) * 4;
-            v += *reinterpret_cast<const floatx4 *>(res + ridx);
-        }
-        v.x = fused_act(v.x, act);
-        v.y = fused_act(v.y, act);
-        v.z = fused_act(v.z, act);
-        v.w = fused_act(v.w, act);
-        *reinterpret_cast<floatx4 *>(dst + didx) = v;
+    for (int nk = STEPS; nk < kWeightRing; ++nk) wr[nk] = gload4(next_w + min(nk, next_last) * 256);
+
+    constexpr int RB = (STEPS & 1); // buffer that received the residual: (STEPS-1)&1 ^ 1
+    if (res) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+            *reinterpret_cast<floatx4 *>(dst + out_index(i, DST_PADDED)) = clamp4(acc[i] + bv + xb[RB][i], lo, hi);
+    } else {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+            *reinterpret_cast<floatx4 *>(dst + out_index(i, DST_PADDED)) = clamp4(acc[i] + bv, lo, hi);
     }
 }
 
 // Stem: 3 input channels held as one plane of (r, g, b, 0) pixels; one MFMA per tap
 // (reduction = the 4 floats of a pixel).  Weights: [tap][64 lanes], lane = kq*16 + co.
 template <int NW>
-__device__ __forceinline__ void fused_stem(const float *__restrict__ src, float *__restrict__ dst,
-                                           const float *__restrict__ wq, const float *__restrict__ bias, int act,
-                                           int tid)
+__device__ __forceinline__ void fused_stem(const float *src, float *dst, const float *__restrict__ wq,
+                                           const float *__restrict__ bias, int act, int tid)
 {
-    constexpr int H = 32, PIN = 34, PT = H * H / 16, MT = PT / NW, DST_PLANE = PIN * PIN * 4;
+    constexpr int H = 32, PIN = 34, PT = H * H / 16, MT = PT / NW, DST_PLANE = PIN * PIN * 4, GROUP = 4;
+    static_assert(MT % GROUP == 0, "pixel tiles per wavefront must be a multiple of the group");
+    asm volatile("" : "+v"(tid)); // keep the index arithmetic inside the op (see fused_conv)
     const int lane = tid & 63, wave = tid >> 6, p = lane & 15, kq = lane >> 4;
     float w[9];
 #pragma unroll
-    for (int t = 0; t < 9; ++t) w[t] = wq[t * 64 + lane];
-    const floatx4 bv = *reinterpret_cast<const floatx4 *>(bias + kq * 4);
-#pragma unroll 2
-    for (int i = 0; i < MT; ++i) {
-        const int P = (wave + i * NW) * 16 + p;
-        const int oy = P / H, ox = P % H;
-        floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < 9; ++t) w[t] = gload1(wq + t * 64 + lane);
+    const floatx4 bv = gload4(bias + kq * 4);
+#pragma unroll 1
+    for (int g = 0; g < MT; g += GROUP) {
+        float x[GROUP][9];
 #pragma unroll
-        for (int t = 0; t < 9; ++t) {
-            const float x = src[((oy + t / 3) * PIN + ox + t % 3) * 4 + kq];
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w[t], x, acc, 0, 0, 0);
+        for (int i = 0; i < GROUP; ++i) {
+            const int P = (wave + (g + i) * NW) * 16 + p;
+            const int oy = P / H, ox = P % H;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) x[i][t] = src[((oy + t / 3) * PIN + ox + t % 3) * 4 + kq];
         }
-        floatx4 v = acc + bv;
-        v.x = fused_act(v.x, act);
-        v.y = fused_act(v.y, act);
-        v.z = fused_act(v.z, act);
-        v.w = fused_act(v.w, act);
-        *reinterpret_cast<floatx4 *>(dst + kq * DST_PLANE + ((oy + 1) * PIN + ox + 1) * 4) = v;
+        floatx4 acc[GROUP];
+#pragma unroll
+        for (int i = 0; i < GROUP; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int i = 0; i < GROUP; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w[t], x[i][t], acc[i], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < GROUP; ++i) {
+            const int P = (wave + (g + i) * NW) * 16 + p;
+            const int oy = P / H, ox = P % H;
+            *reinterpret_cast<floatx4 *>(dst + kq * DST_PLANE + ((oy + 1) * PIN + ox + 1) * 4) =
+                clamp4(acc[i] + bv, act_lo(act), act_hi(act));
+        }
     }
 }
 
@@ -158,50 +208,133 @@ __device__ inline float fused_wave_sum(float v)
     return v;
 }
 
+// Per-op record for THIS workgroup's scheme, built once at kernel start so that the op loop
+// never chases pointers through global memory right after a barrier.
+struct OpRT {
+    uint32_t w_lo, w_hi;     // weights of the scheme's bit-width, kernel layout
+    uint32_t b_lo, b_hi;     // bias
+    int32_t type, act, src_off, dst_off;
+    int32_t res_off, flags, classes, pad_;
+};
+
+__device__ __forceinline__ OpRT uniform_op(const OpRT &v)
+{
+    OpRT r;
+    r.w_lo = __builtin_amdgcn_readfirstlane(v.w_lo);
+    r.w_hi = __builtin_amdgcn_readfirstlane(v.w_hi);
+    r.b_lo = __builtin_amdgcn_readfirstlane(v.b_lo);
+    r.b_hi = __builtin_amdgcn_readfirstlane(v.b_hi);
+    r.type = __builtin_amdgcn_readfirstlane(v.type);
+    r.act = __builtin_amdgcn_readfirstlane(v.act);
+    r.src_off = __builtin_amdgcn_readfirstlane(v.src_off);
+    r.dst_off = __builtin_amdgcn_readfirstlane(v.dst_off);
+    r.res_off = __builtin_amdgcn_readfirstlane(v.res_off);
+    r.flags = __builtin_amdgcn_readfirstlane(v.flags);
+    r.classes = __builtin_amdgcn_readfirstlane(v.classes);
+    r.pad_ = 0;
+    return r;
+}
+__device__ __forceinline__ const float *op_ptr(uint32_t lo, uint32_t hi)
+{
+    return reinterpret_cast<const float *>(((uint64_t)hi << 32) | lo);
+}
+
 template <int NW>
 __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
 {
     extern __shared__ float lds[];
+    __shared__ OpRT s_ops[kFusedMaxOps];
     const int tid = threadIdx.x;
     const int n = blockIdx.x, s = blockIdx.y;
 
-    // clear both regions (borders must be zero), then bring in the image as (r, g, b, 0) pixels
+    // the image goes to registers first so that its HBM latency overlaps the LDS clear
+    constexpr int IMG_PER_THREAD = 3072 / (NW * 64);
+    static_assert(3072 % (NW * 64) == 0, "image elements must divide among the threads");
+    float img_r[IMG_PER_THREAD];
+    {
+        const float *img = a.images + (size_t)n * 3072;
+#pragma unroll
+        for (int q = 0; q < IMG_PER_THREAD; ++q) img_r[q] = img[tid + q * NW * 64];
+    }
+    if (tid < a.n_ops) {
+        const FusedOp &op = a.ops[tid];
+        int bi = 0;
+        if (op.slot >= 0 && s < a.S) bi = bits_index(a.schemes[(size_t)s * a.L + op.slot]);
+        const uint64_t w = reinterpret_cast<uint64_t>(op.bank[bi]), bptr = reinterpret_cast<uint64_t>(op.bias);
+        OpRT r;
+        r.w_lo = (uint32_t)w;
+        r.w_hi = (uint32_t)(w >> 32);
+        r.b_lo = (uint32_t)bptr;
+        r.b_hi = (uint32_t)(bptr >> 32);
+        r.type = op.type;
+        r.act = op.act;
+        r.src_off = op.src_off;
+        r.dst_off = op.dst_off;
+        r.res_off = op.res_off;
+        r.flags = (op.res_padded ? 1 : 0) | (op.zero_ring ? 2 : 0);
+        r.classes = op.classes;
+        r.pad_ = 0;
+        s_ops[tid] = r;
+    }
+    // clear both regions (borders must be zero), then store the image as (r, g, b, 0) pixels
     for (int i = tid; i < kFusedLdsBytes / 16; i += NW * 64)
         reinterpret_cast<floatx4 *>(lds)[i] = floatx4{0.f, 0.f, 0.f, 0.f};
     __syncthreads();
+    OpRT cur = uniform_op(s_ops[0]);
     {
-        const float *img = a.images + (size_t)n * 3072;
-        float *plane = lds + a.ops[0].src_off;
-        for (int e = tid; e < 3072; e += NW * 64) {
+        float *plane = lds + cur.src_off;
+#pragma unroll
+        for (int q = 0; q < IMG_PER_THREAD; ++q) {
+            const int e = tid + q * NW * 64;
             const int pix = e / 3, c = e - pix * 3;
             const int y = pix >> 5, x = pix & 31;
-            plane[((y + 1) * 34 + x + 1) * 4 + c] = img[e];
+            plane[((y + 1) * 34 + x + 1) * 4 + c] = img_r[q];
         }
     }
+    OpRT nxt_raw = s_ops[a.n_ops > 1 ? 1 : 0]; // stays in flight until the next iteration needs it
     __syncthreads();
 
+    floatx4 wr[kWeightRing];
+#pragma unroll
+    for (int j = 0; j < kWeightRing; ++j) wr[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const int lane = tid & 63, wave = tid >> 6;
+
     for (int o = 0; o < a.n_ops; ++o) {
-        const FusedOp &op = a.ops[o];
-        int bi = 0;
-        if (op.slot >= 0 && s < a.S) bi = bits_index(a.schemes[(size_t)s * a.L + op.slot]);
-        const float *wq = op.bank[bi];
-        const float *src = lds + op.src_off;
-        float *dst = lds + op.dst_off;
-        const float *res = op.res_off >= 0 ? lds + op.res_off : nullptr;
-        const bool rp = op.res_padded != 0, zr = op.zero_ring != 0;
-        switch (op.type) {
-        case kOpStem: fused_stem<NW>(src, dst, wq, op.bias, op.act, tid); break;
-        case kOpC16: fused_conv<16, 16, 32, 1, 3, true, NW>(src, dst, res, rp, wq, op.bias, op.act, zr, tid); break;
-        case kOpT16_32: fused_conv<16, 32, 32, 2, 3, true, NW>(src, dst, res, rp, wq, op.bias, op.act, zr, tid); break;
-        case kOpS16_32: fused_conv<16, 32, 32, 2, 1, false, NW>(src, dst, res, rp, wq, op.bias, op.act, zr, tid); break;
-        case kOpC32: fused_conv<32, 32, 16, 1, 3, true, NW>(src, dst, res, rp, wq, op.bias, op.act, zr, tid); break;
-        case kOpT32_64: fused_conv<32, 64, 16, 2, 3, true, NW>(src, dst, res, rp, wq, op.bias, op.act, zr, tid); break;
-        case kOpS32_64: fused_conv<32, 64, 16, 2, 1, false, NW>(src, dst, res, rp, wq, op.bias, op.act, zr, tid); break;
-        case kOpC64: fused_conv<64, 64, 8, 1, 3, true, NW>(src, dst, res, rp, wq, op.bias, op.act, zr, tid); break;
+        const OpRT nxt = uniform_op(nxt_raw);
+        nxt_raw = s_ops[o + 2 < a.n_ops ? o + 2 : a.n_ops - 1];
+        const float *wq = op_ptr(cur.w_lo, cur.w_hi);
+        const float *bias = op_ptr(cur.b_lo, cur.b_hi);
+        const float *src = lds + cur.src_off;
+        float *dst = lds + cur.dst_off;
+        const float *res = cur.res_off >= 0 ? lds + cur.res_off : nullptr;
+        const bool rp = (cur.flags & 1) != 0, zr = (cur.flags & 2) != 0;
+        // first weight chunks of the next dense op, fetched while this op runs; when there is
+        // none the prefetch harmlessly re-reads chunk 0 of this op's own weights
+        const float *next_w = wq + lane * 4;
+        int next_last = 0;
+        if (o + 1 < a.n_ops && kOpSteps[nxt.type] > 0) {
+            const int ns = kOpSteps[nxt.type];
+            const int nct = wave & (kOpCoutTiles[nxt.type] - 1);
+            next_w = op_ptr(nxt.w_lo, nxt.w_hi) + ((size_t)nct * ns * 64 + lane) * 4;
+            next_last = ns - 1;
+        }
+        switch (cur.type) {
+        case kOpStem:
+#pragma unroll
+            for (int j = 0; j < kWeightRing; ++j) wr[j] = gload4(next_w + min(j, next_last) * 256);
+            fused_stem<NW>(src, dst, wq, bias, cur.act, tid);
+            break;
+        case kOpC16: fused_conv<16, 16, 32, 1, 3, true, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpT16_32: fused_conv<16, 32, 32, 2, 3, true, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpS16_32: fused_conv<16, 32, 32, 2, 1, false, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpC32: fused_conv<32, 32, 16, 1, 3, true, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpT32_64: fused_conv<32, 64, 16, 2, 3, true, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpS32_64: fused_conv<32, 64, 16, 2, 1, false, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpC64: fused_conv<64, 64, 8, 1, 3, true, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
         case kOpHead: {
             // 64 channels x 8x8 pixels (padded 10x10 planes): pool, classifier, argmax
-            float *scratch = dst;            // [8][64] partial sums, then pooled[64], then z[classes]
-            const int c = tid & 63, part = tid >> 6; // NW parts
+            float *scratch = dst;            // [NW][64] partial sums, then pooled[64], then z[classes]
+            const int c = tid & 63, part = tid >> 6;
             float acc = 0.0f;
             for (int px = part; px < 64; px += NW) {
                 const int y = px >> 3, x = px & 7;
@@ -217,26 +350,26 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
             }
             __syncthreads();
             float *z = pooled + 64;
-            const int lane = tid & 63, wave = tid >> 6;
-            for (int j = wave; j < op.classes; j += NW) {
-                float t = fused_wave_sum(pooled[lane] * wq[j * 64 + lane]);
-                if (lane == 0) z[j] = t + op.bias[j];
+            for (int j = wave; j < cur.classes; j += NW) {
+                float t = fused_wave_sum(pooled[lane] * gload1(wq + j * 64 + lane));
+                if (lane == 0) z[j] = t + gload1(bias + j);
             }
             __syncthreads();
             if (tid == 0) {
                 int best = 0;
-                for (int j = 1; j < op.classes; ++j)
+                for (int j = 1; j < cur.classes; ++j)
                     if (z[j] > z[best]) best = j;
                 if (s < a.S) a.top1[(size_t)s * a.top1_stride + n] = best;
                 else if (a.top1_base) a.top1_base[n] = best;
             }
-            if (a.logits && s < a.S && tid < op.classes)
-                a.logits[((size_t)s * a.logits_n + a.n0 + n) * op.classes + tid] = z[tid];
+            if (a.logits && s < a.S && tid < cur.classes)
+                a.logits[((size_t)s * a.logits_n + a.n0 + n) * cur.classes + tid] = z[tid];
             break;
         }
         default: break;
         }
         __syncthreads();
+        cur = nxt;
     }
 }
 

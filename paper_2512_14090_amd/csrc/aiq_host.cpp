@@ -467,7 +467,8 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
         }
     }
 
-    if (!(flags & AIQ_MODEL_LAYERWISE)) m->fused = plan_fused(m->nodes, m->fused_ops);
+    if (!(flags & AIQ_MODEL_LAYERWISE))
+        m->fused = plan_fused(m->nodes, m->fused_ops) && m->fused_ops.size() <= (size_t)kFusedMaxOps;
     if (m->fused) {
         Node &stem = m->nodes[0];
         stem.layout = kLayoutStem;

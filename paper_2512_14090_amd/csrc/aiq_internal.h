@@ -180,6 +180,7 @@ struct FusedOp {
 };
 
 constexpr int kFusedThreads = 512;
+constexpr int kFusedMaxOps = 128; // rows of the per-workgroup op table in LDS
 constexpr int kFusedRegionFloats = 18560; // 74 240 bytes: a padded 34x34x16 tensor, or 18x18x32 + 16x16x32
 constexpr int kFusedLdsBytes = 2 * kFusedRegionFloats * 4;
 
