@@ -141,6 +141,15 @@ __device__ __forceinline__ void fused_conv(const float *src, float *dst, const f
 #pragma unroll
             for (int i = 0; i < MT; ++i)
                 acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w[j], xb[cur][i][j], acc[i], 0, 0, 0);
+        // issue order inside the step: the weight fetch, then one LDS read per two MFMAs (all
+        // reads of the next step are in flight by mid-step), then the remaining MFMAs
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * MT, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
     // ops with fewer steps than ring slots (1x1 projections) never used the upper slots
