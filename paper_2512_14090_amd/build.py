@@ -36,6 +36,10 @@ def build(force=True, verbose=False):
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+    # stand-alone copy kernel used to calibrate the HBM traffic counters
+    probe = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", os.path.join(CSRC, "copy_probe.hip"), "-o",
+             os.path.join(HERE, "copy_probe")]
+    subprocess.run(probe, check=True)
     return LIB
 
 

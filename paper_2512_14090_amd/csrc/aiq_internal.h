@@ -102,7 +102,8 @@ struct DepthwiseArgs {
     size_t in_scheme_stride, out_scheme_stride;
     int32_t S, L, slot;
     int32_t N, Hin, Win, C, Hout, Wout, stride, act;
-    FastDiv div_c4, div_wout, div_hout;
+    int32_t band_rows, bands; // output rows per thread walk, walks per image
+    FastDiv div_c4;
 };
 
 struct HeadArgs {

@@ -15,6 +15,13 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------ helpers
 
+// 16-byte read through an explicit global address space: global_load (vmcnt only) rather than
+// flat_load, whose LDS-side counter would make waits on LDS reads wait for weights as well.
+__device__ __forceinline__ floatx4 gload4(const float *p)
+{
+    return *(const __attribute__((address_space(1))) floatx4 *)(p);
+}
+
 __device__ inline int scheme_bits_index(const uint8_t *schemes, int s, int S, int L, int slot)
 {
     if (slot < 0 || s >= S) return 0;
@@ -328,49 +335,89 @@ hipError_t conv_set_lds_limits()
 
 // ------------------------------------------------------------------ depthwise 3x3
 //
-// Bandwidth-bound: 18 FLOP per output element.  One thread produces four
-// consecutive channels of one output pixel (16-byte loads and stores along the
-// NHWC channel axis); neighbouring threads share input rows through L1/L2.
+// Bandwidth-bound: 18 FLOP per output element.  One thread owns four consecutive channels
+// (16 bytes along the NHWC channel axis) of one output column and walks down a band of
+// output rows with a sliding 3x3 window in registers: the nine filter taps are loaded once,
+// every step loads only the new input row (three 16-byte loads for stride 1, six for stride
+// 2), so the L1/texture path carries 3x the input instead of 9x plus the weights.  Lanes
+// run along (channel group, column), which is contiguous in memory.
 
+template <int STRIDE>
 __global__ __launch_bounds__(256) void depthwise3x3_kernel(DepthwiseArgs a)
 {
-    const int s = blockIdx.z, img = blockIdx.y;
+    const int s = blockIdx.z;
+    const int img = blockIdx.y / a.bands, band = blockIdx.y - img * a.bands;
     const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
     const int c4n = a.C >> 2;
-    if (idx >= (uint32_t)(a.Hout * a.Wout * c4n)) return;
-    const uint32_t pix = fd_div(idx, a.div_c4);
-    const int c = (idx - pix * c4n) * 4;
-    const uint32_t oy = fd_div(pix, a.div_wout);
-    const int ox = pix - oy * a.Wout;
+    if (idx >= (uint32_t)(a.Wout * c4n)) return;
+    const uint32_t ox = fd_div(idx, a.div_c4);
+    const int c = (idx - ox * c4n) * 4;
+    const int oy0 = band * a.band_rows;
+    const int oy1 = min(oy0 + a.band_rows, a.Hout);
     const float *wq = a.bank[scheme_bits_index(a.schemes, s, a.S, a.L, a.slot)];
-    const float *in = a.in + (size_t)s * a.in_scheme_stride + (size_t)img * a.Hin * a.Win * a.C;
-    floatx4 acc = *reinterpret_cast<const floatx4 *>(a.bias + c);
+    const float *in = a.in + (size_t)s * a.in_scheme_stride + (size_t)img * a.Hin * a.Win * a.C + c;
+    float *out = a.out + (size_t)s * a.out_scheme_stride + ((size_t)img * a.Hout * a.Wout + ox) * a.C + c;
+
+    floatx4 w[9];
 #pragma unroll
-    for (int ky = 0; ky < 3; ++ky) {
-        const int iy = (int)oy * a.stride + ky - 1;
-        if (iy < 0 || iy >= a.Hin) continue;
+    for (int t = 0; t < 9; ++t) w[t] = *reinterpret_cast<const floatx4 *>(wq + (size_t)t * a.C + c);
+    const floatx4 bias = *reinterpret_cast<const floatx4 *>(a.bias + c);
+    const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
+
+    const int ix0 = (int)ox * STRIDE - 1;
+    const bool okx[3] = {ix0 >= 0, true, ix0 + 2 < a.Win};
+    const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};
+    auto load_row = [&](int iy, floatx4 (&r)[3]) {
+        const bool oky = iy >= 0 && iy < a.Hin;
+        const float *row = in + ((size_t)iy * a.Win + ix0) * a.C;
 #pragma unroll
-        for (int kx = 0; kx < 3; ++kx) {
-            const int ix = ox * a.stride + kx - 1;
-            if (ix < 0 || ix >= a.Win) continue;
-            const floatx4 x = *reinterpret_cast<const floatx4 *>(in + ((size_t)iy * a.Win + ix) * a.C + c);
-            const floatx4 w = *reinterpret_cast<const floatx4 *>(wq + (size_t)(ky * 3 + kx) * a.C + c);
-            acc += x * w;
+        for (int k = 0; k < 3; ++k)
+            r[k] = (oky && okx[k]) ? *reinterpret_cast<const floatx4 *>(row + (size_t)k * a.C) : zero;
+    };
+
+    floatx4 r0[3], r1[3], r2[3];
+    load_row(oy0 * STRIDE - 1, r0);
+    if (STRIDE == 1) load_row(oy0, r1);
+    for (int oy = oy0; oy < oy1; ++oy) {
+        if (STRIDE == 1) {
+            load_row(oy + 1, r2);
+        } else {
+            load_row(oy * 2, r1);
+            load_row(oy * 2 + 1, r2);
+        }
+        floatx4 acc = bias;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            acc += r0[k] * w[k];
+            acc += r1[k] * w[3 + k];
+            acc += r2[k] * w[6 + k];
+        }
+        acc.x = fminf(fmaxf(acc.x, lo), hi);
+        acc.y = fminf(fmaxf(acc.y, lo), hi);
+        acc.z = fminf(fmaxf(acc.z, lo), hi);
+        acc.w = fminf(fmaxf(acc.w, lo), hi);
+        *reinterpret_cast<floatx4 *>(out + (size_t)oy * a.Wout * a.C) = acc;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            if (STRIDE == 1) {
+                r0[k] = r1[k];
+                r1[k] = r2[k];
+            } else {
+                r0[k] = r2[k];
+            }
         }
     }
-    acc.x = apply_act(acc.x, a.act);
-    acc.y = apply_act(acc.y, a.act);
-    acc.z = apply_act(acc.z, a.act);
-    acc.w = apply_act(acc.w, a.act);
-    float *out = a.out + (size_t)s * a.out_scheme_stride + (((size_t)img * a.Hout + oy) * a.Wout + ox) * a.C + c;
-    *reinterpret_cast<floatx4 *>(out) = acc;
 }
 
 hipError_t launch_depthwise(const DepthwiseArgs &a, int s_total, hipStream_t st)
 {
-    const int per_img = a.Hout * a.Wout * (a.C >> 2);
-    dim3 grid((per_img + 255) / 256, a.N, s_total);
-    hipLaunchKernelGGL(depthwise3x3_kernel, grid, dim3(256), 0, st, a);
+    if (a.N == 0 || s_total == 0) return hipSuccess;
+    const int per_row = a.Wout * (a.C >> 2);
+    dim3 grid((per_row + 255) / 256, a.N * a.bands, s_total);
+    if (a.stride == 1)
+        hipLaunchKernelGGL(depthwise3x3_kernel<1>, grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL(depthwise3x3_kernel<2>, grid, dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
