@@ -153,6 +153,58 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
                             void *hip_stream);
 
 /*
+ * Search drivers (paper: Approach - Problem Formulation for the loss, Search Over
+ * Mixed-Precision Schemes for the two loops).  Host loops around aiq_eval_schemes: every
+ * iteration scores all its candidate schemes in one scheme-batched call.
+ *   loss(q) = -lambda * AI(q) + (1 - lambda) * AccLoss(q),  AccLoss = 100 * (1 - agree/N)
+ * (percentage points), AI from aiq_layer_ai with params.batch.
+ * greedy: start all-FP32; per iteration score every move "layer i -> lower width b in Q",
+ *   accept the move with the smallest loss change if negative, else stop; at most
+ *   max_iters iterations (0 = L).  only_fp32_layers = 1: a layer is a candidate only while
+ *   it is still at bits[0].
+ * coordinate descent: start all-FP32; for each layer in turn take argmin over Q with the
+ *   other layers fixed (the current width wins ties); repeat sweeps until one changes
+ *   nothing or max_iters sweeps (0 = 50) are done.
+ * Ties between candidates go to the first in (layer ascending, width descending) order.
+ *
+ * params.bits: the alphabet Q, strictly descending, bits[0] = 32.  layers: the same records
+ * the model was built from (for the AI model).  images: device fp32 [N][hin][win][cin].
+ * workspace: device, >= aiq_search_workspace_bytes.  scheme_out: host uint8[L].
+ * trace: host array of trace_cap entries or NULL; entry 0 is the all-FP32 start, then one
+ * per accepted move (layer, bits, loss, AI, agreement after the move); *n_trace receives the
+ * number of entries the search produced (it may exceed trace_cap; only trace_cap are stored).
+ * Synchronous: returns when the search is finished.
+ * Errors: INVALID_ARG, UNSUPPORTED_BITS, SHAPE_MISMATCH, WORKSPACE_TOO_SMALL, DEVICE_ERROR.
+ */
+typedef struct {
+    double lambda;
+    int32_t n_bits;
+    uint8_t bits[8];
+    int32_t batch;
+    int32_t max_iters;
+    int32_t only_fp32_layers;
+} aiq_search_params;
+
+typedef struct {
+    int32_t layer; /* scheme slot changed by this step, -1 for the start entry */
+    int32_t bits;
+    int32_t agree;
+    int32_t sweep; /* coordinate descent: sweep number (1-based), greedy: iteration */
+    double loss, ai;
+} aiq_search_step;
+
+aiq_status aiq_search_workspace_bytes(const aiq_model *m, int32_t N, int32_t chunk, int32_t n_bits, size_t *bytes);
+aiq_status aiq_search_greedy(aiq_model *m, const aiq_layer_desc *layers, int32_t n_layers, const float *images,
+                             int32_t N, int32_t chunk, const aiq_search_params *params, void *workspace,
+                             size_t workspace_bytes, void *hip_stream, uint8_t *scheme_out,
+                             aiq_search_step *trace, int32_t trace_cap, int32_t *n_trace);
+aiq_status aiq_search_coordinate_descent(aiq_model *m, const aiq_layer_desc *layers, int32_t n_layers,
+                                         const float *images, int32_t N, int32_t chunk,
+                                         const aiq_search_params *params, void *workspace, size_t workspace_bytes,
+                                         void *hip_stream, uint8_t *scheme_out, aiq_search_step *trace,
+                                         int32_t trace_cap, int32_t *n_trace);
+
+/*
  * Per-kernel timing for roofline reports.  While enabled, aiq_eval_schemes brackets
  * every launch with HIP events on the launch stream.  aiq_profile_read waits for the
  * recorded events, then returns for kernel class cls the number of launches, their

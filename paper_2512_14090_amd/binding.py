@@ -13,11 +13,22 @@ _lib = None
 EXPORTED_SYMBOLS = (
     "aiq_status_str", "aiq_last_hip_error", "aiq_layer_ai", "aiq_quantize_weights", "aiq_model_create",
     "aiq_model_create_ex", "aiq_model_is_lds_resident", "aiq_model_destroy", "aiq_model_scheme_layers", "aiq_model_classes", "aiq_eval_workspace_bytes",
-    "aiq_eval_schemes", "aiq_profile_enable", "aiq_profile_read",
+    "aiq_eval_schemes", "aiq_profile_enable", "aiq_profile_read", "aiq_search_workspace_bytes",
+    "aiq_search_greedy", "aiq_search_coordinate_descent",
 )
 K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED = range(6)
 MODEL_LAYERWISE = 1
 _DESC_INTS = 13
+
+
+class _SearchParams(C.Structure):
+    _fields_ = [("lam", C.c_double), ("n_bits", C.c_int32), ("bits", C.c_uint8 * 8), ("batch", C.c_int32),
+                ("max_iters", C.c_int32), ("only_fp32_layers", C.c_int32)]
+
+
+class _SearchStep(C.Structure):
+    _fields_ = [("layer", C.c_int32), ("bits", C.c_int32), ("agree", C.c_int32), ("sweep", C.c_int32),
+                ("loss", C.c_double), ("ai", C.c_double)]
 
 
 class AiqError(RuntimeError):
@@ -61,6 +72,11 @@ def load_library():
     lib.aiq_profile_enable.argtypes = [C.c_void_p, C.c_int32]
     lib.aiq_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double),
                                      C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.aiq_search_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+    for fn in (lib.aiq_search_greedy, lib.aiq_search_coordinate_descent):
+        fn.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
+                       C.POINTER(_SearchParams), C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p,
+                       C.POINTER(_SearchStep), C.c_int32, C.POINTER(C.c_int32)]
     for name in EXPORTED_SYMBOLS:
         getattr(lib, name)
     _lib = lib
@@ -210,6 +226,34 @@ class Model:
                                         ws.data_ptr(), ws.numel(), _stream_ptr(stream))
         _check(st, "aiq_eval_schemes")
         return dict(agree=agree[:S], top1_base=top1_base[:N], logits=logits, top1=top1)
+
+    def search(self, desc, images, method="greedy", bits=(32, 8, 4), lam=0.9, batch=1, max_iters=0,
+               only_fp32_layers=False, chunk=1024, stream=None):
+        """aiq_search_greedy / aiq_search_coordinate_descent.  Returns (scheme uint8[L], trace list of dicts)."""
+        import torch
+        d = _desc(desc)
+        p = _SearchParams()
+        p.lam, p.n_bits, p.batch, p.max_iters = float(lam), len(bits), int(batch), int(max_iters)
+        p.only_fp32_layers = 1 if only_fp32_layers else 0
+        for i, b in enumerate(bits):
+            p.bits[i] = int(b)
+        N = images.shape[0]
+        chunk = max(1, min(int(chunk), max(N, 1)))
+        need = C.c_size_t(0)
+        _check(self._lib.aiq_search_workspace_bytes(self._h, N, chunk, len(bits), C.byref(need)),
+               "aiq_search_workspace_bytes")
+        ws = self._get_workspace(need.value, images.device)
+        scheme = np.zeros(self.L, dtype=np.uint8)
+        cap = 4096
+        trace = (_SearchStep * cap)()
+        n = C.c_int32(0)
+        fn = {"greedy": self._lib.aiq_search_greedy, "cd": self._lib.aiq_search_coordinate_descent}[method]
+        st = fn(self._h, d.ctypes.data, d.shape[0], images.data_ptr(), N, chunk, C.byref(p), ws.data_ptr(),
+                ws.numel(), _stream_ptr(stream), scheme.ctypes.data, trace, cap, C.byref(n))
+        _check(st, "aiq_search_" + method)
+        steps = [dict(layer=t.layer, bits=t.bits, agree=t.agree, sweep=t.sweep, loss=t.loss, ai=t.ai)
+                 for t in trace[:min(n.value, cap)]]
+        return scheme, steps
 
     def profile_enable(self, on=True):
         _check(self._lib.aiq_profile_enable(self._h, 1 if on else 0), "aiq_profile_enable")

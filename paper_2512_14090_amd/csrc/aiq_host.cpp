@@ -791,6 +791,240 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
     return AIQ_OK;
 }
 
+namespace {
+
+// Shared state of one search run: device buffers carved out of the workspace and the
+// scoring of a batch of candidate schemes.
+struct SearchCtx {
+    aiq_model *m;
+    const aiq_layer_desc *layers;
+    int32_t n_layers;
+    const float *images;
+    int32_t N, chunk, L;
+    const aiq_search_params *p;
+    hipStream_t st;
+    int32_t *top1_base, *agree_dev;
+    void *eval_ws;
+    size_t eval_ws_bytes;
+    int32_t s_max;
+    bool base_valid = false;
+    std::vector<int32_t> agree_host;
+
+    double ai(const uint8_t *q, aiq_status *err) const
+    {
+        double v = 0.0;
+        aiq_status st_ = aiq_layer_ai(layers, n_layers, q, L, p->batch, nullptr, nullptr, &v);
+        if (st_ != AIQ_OK) *err = st_;
+        return v;
+    }
+    double loss(double ai_v, int32_t agree) const
+    {
+        const double acc_loss = N > 0 ? 100.0 * (1.0 - (double)agree / (double)N) : 0.0;
+        return -p->lambda * ai_v + (1.0 - p->lambda) * acc_loss;
+    }
+    // scores S schemes (host [S][L]); agree_host[0..S) filled on return
+    aiq_status score(const std::vector<uint8_t> &schemes, int32_t S)
+    {
+        if (S > s_max) return AIQ_WORKSPACE_TOO_SMALL;
+        aiq_status rc = aiq_eval_schemes(m, images, N, schemes.data(), S, chunk, top1_base, base_valid ? 1 : 0,
+                                         nullptr, nullptr, agree_dev, eval_ws, eval_ws_bytes, st);
+        if (rc != AIQ_OK) return rc;
+        base_valid = true;
+        agree_host.assign(S, 0);
+        if (S > 0)
+            AIQ_HIP(hipMemcpyAsync(agree_host.data(), agree_dev, sizeof(int32_t) * S, hipMemcpyDeviceToHost, st));
+        AIQ_HIP(hipStreamSynchronize(st));
+        return AIQ_OK;
+    }
+};
+
+struct SearchLayout {
+    size_t top1_off, agree_off, eval_off, total;
+    int32_t s_max;
+};
+
+SearchLayout search_layout(const aiq_model *m, int32_t N, int32_t chunk, int32_t n_bits)
+{
+    SearchLayout l{};
+    l.s_max = std::max(1, m->L * std::max(1, n_bits - 1));
+    size_t off = 0;
+    l.top1_off = off;
+    off = align_up(off + sizeof(int32_t) * (size_t)std::max(N, 1), 256);
+    l.agree_off = off;
+    off = align_up(off + sizeof(int32_t) * (size_t)l.s_max, 256);
+    l.eval_off = off;
+    off += workspace_layout(m, l.s_max, std::min(chunk, std::max(N, 1))).total;
+    l.total = off;
+    return l;
+}
+
+aiq_status search_setup(SearchCtx &c, aiq_model *m, const aiq_layer_desc *layers, int32_t n_layers,
+                        const float *images, int32_t N, int32_t chunk, const aiq_search_params *p, void *workspace,
+                        size_t workspace_bytes, void *hip_stream, uint8_t *scheme_out, int32_t *n_trace)
+{
+    if (!m || !layers || !p || !scheme_out || !n_trace || N < 1 || chunk < 1 || !images || !workspace)
+        return AIQ_INVALID_ARG;
+    if (n_layers != (int32_t)m->nodes.size()) return AIQ_SHAPE_MISMATCH;
+    if (!(p->lambda >= 0.0 && p->lambda <= 1.0) || p->n_bits < 1 || p->n_bits > 8 || p->batch < 1 || p->max_iters < 0)
+        return AIQ_INVALID_ARG;
+    for (int i = 0; i < p->n_bits; ++i) {
+        if (!bits_supported(p->bits[i])) return AIQ_UNSUPPORTED_BITS;
+        if (i > 0 && p->bits[i] >= p->bits[i - 1]) return AIQ_INVALID_ARG;
+    }
+    if (p->bits[0] != 32) return AIQ_INVALID_ARG;
+    for (int l = 0; l < n_layers; ++l)
+        if (std::memcmp(&layers[l], &m->nodes[l].d, sizeof(aiq_layer_desc)) != 0) return AIQ_SHAPE_MISMATCH;
+    const SearchLayout lay = search_layout(m, N, chunk, p->n_bits);
+    if (workspace_bytes < lay.total) return AIQ_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return AIQ_INVALID_ARG;
+    char *ws = static_cast<char *>(workspace);
+    c.m = m;
+    c.layers = layers;
+    c.n_layers = n_layers;
+    c.images = images;
+    c.N = N;
+    c.chunk = chunk;
+    c.L = m->L;
+    c.p = p;
+    c.st = (hipStream_t)hip_stream;
+    c.top1_base = reinterpret_cast<int32_t *>(ws + lay.top1_off);
+    c.agree_dev = reinterpret_cast<int32_t *>(ws + lay.agree_off);
+    c.eval_ws = ws + lay.eval_off;
+    c.eval_ws_bytes = workspace_bytes - lay.eval_off;
+    c.s_max = lay.s_max;
+    return AIQ_OK;
+}
+
+void push_trace(aiq_search_step *trace, int32_t cap, int32_t &n, int32_t layer, int32_t bits, int32_t agree,
+                int32_t sweep, double loss, double ai)
+{
+    if (trace && n < cap) trace[n] = aiq_search_step{layer, bits, agree, sweep, loss, ai};
+    ++n;
+}
+
+} // namespace
+
+aiq_status aiq_search_workspace_bytes(const aiq_model *m, int32_t N, int32_t chunk, int32_t n_bits, size_t *bytes)
+{
+    if (!m || !bytes || N < 1 || chunk < 1 || n_bits < 1 || n_bits > 8) return AIQ_INVALID_ARG;
+    *bytes = search_layout(m, N, chunk, n_bits).total;
+    return AIQ_OK;
+}
+
+aiq_status aiq_search_greedy(aiq_model *m, const aiq_layer_desc *layers, int32_t n_layers, const float *images,
+                             int32_t N, int32_t chunk, const aiq_search_params *params, void *workspace,
+                             size_t workspace_bytes, void *hip_stream, uint8_t *scheme_out, aiq_search_step *trace,
+                             int32_t trace_cap, int32_t *n_trace)
+{
+    SearchCtx c;
+    aiq_status rc = search_setup(c, m, layers, n_layers, images, N, chunk, params, workspace, workspace_bytes,
+                                 hip_stream, scheme_out, n_trace);
+    if (rc != AIQ_OK) return rc;
+    const int L = c.L, nb = params->n_bits;
+    std::vector<uint8_t> q(L, params->bits[0]);
+    aiq_status err = AIQ_OK;
+    // start: the all-FP32 scheme agrees with itself on every image
+    std::vector<uint8_t> batch(q);
+    if ((rc = c.score(batch, 1)) != AIQ_OK) return rc;
+    double cur_ai = c.ai(q.data(), &err);
+    double cur = c.loss(cur_ai, c.agree_host[0]);
+    int32_t nt = 0;
+    push_trace(trace, trace_cap, nt, -1, params->bits[0], c.agree_host[0], 0, cur, cur_ai);
+    const int iters = params->max_iters > 0 ? params->max_iters : L;
+    for (int it = 1; it <= iters; ++it) {
+        std::vector<std::pair<int, int>> moves;
+        batch.clear();
+        for (int i = 0; i < L; ++i) {
+            if (params->only_fp32_layers && q[i] != params->bits[0]) continue;
+            for (int b = 0; b < nb; ++b)
+                if (params->bits[b] < q[i]) {
+                    moves.emplace_back(i, params->bits[b]);
+                    batch.insert(batch.end(), q.begin(), q.end());
+                    batch[batch.size() - L + i] = params->bits[b];
+                }
+        }
+        if (moves.empty()) break;
+        if ((rc = c.score(batch, (int32_t)moves.size())) != AIQ_OK) return rc;
+        int best = -1;
+        double best_delta = 0.0, best_ai = 0.0;
+        for (size_t k = 0; k < moves.size(); ++k) {
+            const double ai_v = c.ai(batch.data() + k * L, &err);
+            const double delta = c.loss(ai_v, c.agree_host[k]) - cur;
+            if (best < 0 || delta < best_delta) {
+                best = (int)k;
+                best_delta = delta;
+                best_ai = ai_v;
+            }
+        }
+        if (err != AIQ_OK) return err;
+        if (!(best_delta < 0.0)) break;
+        q[moves[best].first] = (uint8_t)moves[best].second;
+        cur += best_delta;
+        push_trace(trace, trace_cap, nt, moves[best].first, moves[best].second, c.agree_host[best], it, cur, best_ai);
+    }
+    std::memcpy(scheme_out, q.data(), L);
+    *n_trace = nt;
+    return err;
+}
+
+aiq_status aiq_search_coordinate_descent(aiq_model *m, const aiq_layer_desc *layers, int32_t n_layers,
+                                         const float *images, int32_t N, int32_t chunk,
+                                         const aiq_search_params *params, void *workspace, size_t workspace_bytes,
+                                         void *hip_stream, uint8_t *scheme_out, aiq_search_step *trace,
+                                         int32_t trace_cap, int32_t *n_trace)
+{
+    SearchCtx c;
+    aiq_status rc = search_setup(c, m, layers, n_layers, images, N, chunk, params, workspace, workspace_bytes,
+                                 hip_stream, scheme_out, n_trace);
+    if (rc != AIQ_OK) return rc;
+    const int L = c.L, nb = params->n_bits;
+    std::vector<uint8_t> q(L, params->bits[0]);
+    aiq_status err = AIQ_OK;
+    std::vector<uint8_t> batch(q);
+    if ((rc = c.score(batch, 1)) != AIQ_OK) return rc;
+    double cur_ai = c.ai(q.data(), &err);
+    double cur = c.loss(cur_ai, c.agree_host[0]);
+    int32_t nt = 0;
+    push_trace(trace, trace_cap, nt, -1, params->bits[0], c.agree_host[0], 0, cur, cur_ai);
+    const int sweeps = params->max_iters > 0 ? params->max_iters : 50;
+    for (int sweep = 1; sweep <= sweeps; ++sweep) {
+        bool updated = false;
+        for (int i = 0; i < L && nb > 1; ++i) {
+            std::vector<int> others;
+            batch.clear();
+            for (int b = 0; b < nb; ++b)
+                if (params->bits[b] != q[i]) {
+                    others.push_back(params->bits[b]);
+                    batch.insert(batch.end(), q.begin(), q.end());
+                    batch[batch.size() - L + i] = params->bits[b];
+                }
+            if ((rc = c.score(batch, (int32_t)others.size())) != AIQ_OK) return rc;
+            int best = -1;
+            double best_val = 0.0, best_ai = 0.0;
+            for (size_t k = 0; k < others.size(); ++k) {
+                const double ai_v = c.ai(batch.data() + k * L, &err);
+                const double v = c.loss(ai_v, c.agree_host[k]);
+                if (best < 0 || v < best_val) {
+                    best = (int)k;
+                    best_val = v;
+                    best_ai = ai_v;
+                }
+            }
+            if (err != AIQ_OK) return err;
+            if (best >= 0 && best_val < cur) {
+                q[i] = (uint8_t)others[best];
+                cur = best_val;
+                updated = true;
+                push_trace(trace, trace_cap, nt, i, others[best], c.agree_host[best], sweep, cur, best_ai);
+            }
+        }
+        if (!updated) break;
+    }
+    std::memcpy(scheme_out, q.data(), L);
+    *n_trace = nt;
+    return err;
+}
+
 aiq_status aiq_profile_enable(aiq_model *m, int32_t on)
 {
     if (!m) return AIQ_INVALID_ARG;
