@@ -95,14 +95,25 @@ aiq_status plan_conv(Node &nd)
     ConvPlan p{};
     p.cout_tiles = (d.cout + 15) / 16;
     p.CB = (d.cin + 15) / 16;
-    if (p.cout_tiles % 4 == 0) p.nt = 4;
-    else if (p.cout_tiles % 3 == 0) p.nt = 3;
-    else if (p.cout_tiles % 2 == 0) p.nt = 2;
-    else p.nt = 1;
-    const int groups = (p.cout_tiles + p.nt - 1) / p.nt; // wavefront tiles along output channels
-    p.wave_px_split = groups <= 1 ? 4 : (groups <= 2 ? 2 : 1);
-    const int wco = 4 / p.wave_px_split;
-    p.grid_y = (groups + wco - 1) / wco;
+    // output-channel tiles per wavefront (nt) and wavefronts along output channels (wco): among
+    // the pairs that waste at most 1/8 of the MFMAs on padding or idle wavefronts, take the one
+    // covering the most output channels per workgroup (the staged input is reused most), then
+    // the larger nt (each LDS read feeds more MFMAs)
+    int wco = 1, best_cover = 0;
+    p.nt = 1;
+    for (int nt = 1; nt <= 4; ++nt)
+        for (int w = 1; w <= 4; w *= 2) {
+            const int per_wg = nt * w;
+            const int waste = (p.cout_tiles + per_wg - 1) / per_wg * per_wg - p.cout_tiles;
+            if (waste * 8 > p.cout_tiles) continue;
+            if (per_wg > best_cover || (per_wg == best_cover && nt > p.nt)) {
+                best_cover = per_wg;
+                p.nt = nt;
+                wco = w;
+            }
+        }
+    p.wave_px_split = 4 / wco;
+    p.grid_y = (p.cout_tiles + p.nt * wco - 1) / (p.nt * wco);
     const int region_px = 64 * p.wave_px_split;
     const int px_img = nd.hout * nd.wout;
     if (px_img >= region_px) {
@@ -683,7 +694,36 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
                 in_stride = (size_t)n * nd.in_elems;
             }
             const double work = (double)s_total * n;
-            if (d.kind == 0) {
+            if (d.kind == 0 && d.kh == 1 && d.stride == 1 && d.input >= 0) {
+                // 1x1 stride 1: flat pixel axis
+                const ConvPlan &p = nd.plan;
+                PointwiseArgs a{};
+                a.in = in;
+                a.out = buf_ptr(nd.buf);
+                a.res = d.residual >= 0 ? buf_ptr(m->nodes[d.residual].buf) : nullptr;
+                a.bias = nd.bias;
+                for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+                a.schemes = schemes_dev;
+                a.in_scheme_stride = in_stride;
+                a.out_scheme_stride = (size_t)n * nd.out_elems;
+                a.S = S;
+                a.L = m->L;
+                a.slot = d.scheme_slot;
+                a.P = n * nd.hout * nd.wout;
+                a.Cin = d.cin;
+                a.Cout = d.cout;
+                a.act = d.act;
+                a.CB = p.CB;
+                a.CKC = p.CKC;
+                a.PS = p.PS;
+                a.wave_px_split = p.wave_px_split;
+                a.cout_tiles = p.cout_tiles;
+                const int tile_px = 64 * p.wave_px_split;
+                const size_t lds = sizeof(float) * (size_t)tile_px * p.PS;
+                ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+                AIQ_HIP(launch_pointwise(a, p.nt, lds, dim3((unsigned)((a.P + tile_px - 1) / tile_px), p.grid_y, s_total),
+                                         st));
+            } else if (d.kind == 0) {
                 const ConvPlan &p = nd.plan;
                 ConvArgs a{};
                 a.in = in;

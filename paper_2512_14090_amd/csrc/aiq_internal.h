@@ -93,6 +93,22 @@ struct ConvArgs {
     FastDiv div_lw, div_rin, div_wout, div_rw; // LW, RIN, Wout, R*Wout
 };
 
+// Arguments of the 1x1 stride-1 convolution (pixels form one flat axis).
+struct PointwiseArgs {
+    const float *in;          // [S?][P][Cin]
+    float *out;               // [S][P][Cout]
+    const float *res;         // like out, or nullptr
+    const float *bias;
+    const float *bank[kNumBits];
+    const uint8_t *schemes;
+    size_t in_scheme_stride, out_scheme_stride;
+    int32_t S, L, slot;
+    int32_t P;                // pixels of this chunk: images * H * W
+    int32_t Cin, Cout, act;
+    int32_t CB, CKC, PS;      // ceil(Cin/16), channels staged per pass, LDS pixel stride (floats)
+    int32_t wave_px_split, cout_tiles;
+};
+
 struct DepthwiseArgs {
     const float *in;
     float *out;
@@ -136,6 +152,7 @@ hipError_t launch_quantize_batch(const QuantJob *jobs_dev, const int32_t *block_
                                  const QuantMask &mask, hipStream_t st);
 hipError_t launch_conv(const ConvArgs &a, int ks, int stride, int nt, size_t lds_bytes, dim3 grid,
                        hipStream_t st);
+hipError_t launch_pointwise(const PointwiseArgs &a, int nt, size_t lds_bytes, dim3 grid, hipStream_t st);
 hipError_t launch_depthwise(const DepthwiseArgs &a, int s_total, hipStream_t st);
 hipError_t launch_head(const HeadArgs &a, int s_total, hipStream_t st);
 hipError_t launch_agree(const AgreeArgs &a, hipStream_t st);

@@ -12,6 +12,7 @@
 namespace aiq {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+constexpr int kStageBatch = 8; // 16-byte global reads a thread keeps in flight while staging
 
 // ------------------------------------------------------------------ helpers
 
@@ -162,7 +163,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
     const int ct0 = (blockIdx.y * wco_count + wco) * NT;
     const int p = lane & 15, kq = lane >> 4;
 
-    // per pixel tile: LDS base offset (floats) of the lane's pixel, and its output position
+    floatx4 *lds4 = reinterpret_cast<floatx4 *>(lds); // LDS is addressed in 16-byte units (PS % 4 == 0)
+    const int ps4 = a.PS >> 2;
+    // per pixel tile: LDS base offset (16-byte units) of the lane's pixel, and its output position
     int lds_base[4];
     int out_img[4], out_y[4], out_x[4];
     const int rw = a.R * a.Wout;
@@ -174,7 +177,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
         const uint32_t oy = fd_div(rem, a.div_wout);
         const uint32_t ox = rem - oy * a.Wout;
         const bool in_region = g < (uint32_t)a.G; // lanes past the region's last pixel compute nothing useful
-        lds_base[m] = in_region ? ((g * a.RIN + oy * STRIDE) * a.LW + ox * STRIDE) * a.PS + kq * 4 : kq * 4;
+        lds_base[m] = in_region ? ((g * a.RIN + oy * STRIDE) * a.LW + ox * STRIDE) * ps4 + kq : kq;
         out_img[m] = in_region ? img0 + (int)g : a.N;
         out_y[m] = oy0 + oy;
         out_x[m] = ox;
@@ -198,31 +201,41 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
 
     for (int c0 = 0; c0 < a.CB * 16; c0 += a.CKC) {
         if (c0) __syncthreads();
-        // ---- stage channels [c0, c0+CKC) of the region's input rows, zero outside the image
-        for (int idx = tid; idx < n_chunks; idx += 256) {
-            const int c4 = idx & (c4n - 1);
-            const uint32_t pix = (uint32_t)idx >> c4shift;
-            const uint32_t row = fd_div(pix, a.div_lw); // g*RIN + r
-            const int x = pix - row * a.LW;
-            const uint32_t g = fd_div(row, a.div_rin);
-            const int r = row - g * a.RIN;
-            const int iy = oy0 * STRIDE - PAD + r;
-            const int ix = x - PAD;
-            const int img = img0 + g;
-            const int c = c0 + c4 * 4;
-            floatx4 v = floatx4{0.f, 0.f, 0.f, 0.f};
-            if (iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win && img < a.N && c < a.Cin) {
-                const float *src = in_s + (((size_t)img * a.Hin + iy) * a.Win + ix) * a.Cin + c;
-                if (vec_ok) {
-                    v = *reinterpret_cast<const floatx4 *>(src);
-                } else {
-                    v.x = src[0];
-                    if (c + 1 < a.Cin) v.y = src[1];
-                    if (c + 2 < a.Cin) v.z = src[2];
-                    if (c + 3 < a.Cin) v.w = src[3];
+        // ---- stage channels [c0, c0+CKC) of the region's input rows, zero outside the image;
+        // kStageBatch loads are issued before their LDS stores (several reads in flight per thread)
+        for (int base = tid; base < n_chunks; base += 256 * kStageBatch) {
+            floatx4 v[kStageBatch];
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int idx = base + u * 256;
+                const int c4 = idx & (c4n - 1);
+                const uint32_t pix = (uint32_t)idx >> c4shift;
+                const uint32_t row = fd_div(pix, a.div_lw); // g*RIN + r
+                const int x = pix - row * a.LW;
+                const uint32_t g = fd_div(row, a.div_rin);
+                const int r = row - g * a.RIN;
+                const int iy = oy0 * STRIDE - PAD + r;
+                const int ix = x - PAD;
+                const int img = img0 + g;
+                const int c = c0 + c4 * 4;
+                v[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (idx < n_chunks && iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win && img < a.N && c < a.Cin) {
+                    const float *src = in_s + (((size_t)img * a.Hin + iy) * a.Win + ix) * a.Cin + c;
+                    if (vec_ok) {
+                        v[u] = *reinterpret_cast<const floatx4 *>(src);
+                    } else {
+                        v[u].x = src[0];
+                        if (c + 1 < a.Cin) v[u].y = src[1];
+                        if (c + 2 < a.Cin) v[u].z = src[2];
+                        if (c + 3 < a.Cin) v[u].w = src[3];
+                    }
                 }
             }
-            *reinterpret_cast<floatx4 *>(lds + (size_t)pix * a.PS + c4 * 4) = v;
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int idx = base + u * 256;
+                if (idx < n_chunks) lds4[((uint32_t)idx >> c4shift) * ps4 + (idx & (c4n - 1))] = v[u];
+            }
         }
         __syncthreads();
 
@@ -232,7 +245,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
 #pragma unroll 1
             for (int t = 0; t < T; ++t) {
                 const int ky = t / KS, kx = t - ky * KS;
-                const int tapoff = (ky * a.LW + kx) * a.PS;
+                const int tapoff = (ky * a.LW + kx) * ps4;
 #pragma unroll 1
                 for (int cbl = 0; cbl < ncb; ++cbl) {
                     floatx4 wa[NT], xb[4];
@@ -244,7 +257,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
                     }
 #pragma unroll
                     for (int m = 0; m < 4; ++m)
-                        xb[m] = *reinterpret_cast<const floatx4 *>(lds + lds_base[m] + tapoff + cbl * 16);
+                        xb[m] = lds4[lds_base[m] + tapoff + cbl * 4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -331,6 +344,142 @@ hipError_t conv_set_lds_limits()
     AIQ_SET(1, 2)
 #undef AIQ_SET
     return e;
+}
+
+// ------------------------------------------------------------------ 1x1 stride-1 convolution
+//
+// Same MFMA tiling as conv_mfma_kernel, but a 1x1 stride-1 convolution has no spatial
+// structure: the pixels of all images form one flat axis, so staging is a strided copy and
+// no per-pixel (image, row, column) arithmetic or border handling is needed.  That matters
+// for the narrow layers (16..32 input channels), where a wavefront tile holds only a few
+// dozen MFMAs and index arithmetic would otherwise outweigh them.
+
+template <int NT>
+__global__ __launch_bounds__(256, 2) void pointwise_mfma_kernel(PointwiseArgs a)
+{
+    extern __shared__ float lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int s = blockIdx.z;
+    const int tile_px = 64 * a.wave_px_split;
+    const int P0 = blockIdx.x * tile_px;
+    const int wpx = wave % a.wave_px_split;
+    const int wco = wave / a.wave_px_split;
+    const int ct0 = (blockIdx.y * (4 / a.wave_px_split) + wco) * NT;
+    const int p = lane & 15, kq = lane >> 4;
+    const bool active = ct0 < a.cout_tiles;
+
+    const float *wq = a.bank[scheme_bits_index(a.schemes, s, a.S, a.L, a.slot)];
+    const float *in_s = a.in + (size_t)s * a.in_scheme_stride + (size_t)P0 * a.Cin;
+    const int px_here = min(tile_px, a.P - P0);
+
+    floatx4 acc[4][NT];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int n = 0; n < NT; ++n) acc[m][n] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const int c4n = a.CKC >> 2;
+    const int c4shift = __ffs(c4n) - 1;
+    const int n_chunks = tile_px << c4shift;
+    floatx4 *lds4 = reinterpret_cast<floatx4 *>(lds); // LDS is addressed in 16-byte units (PS % 4 == 0)
+    const int ps4 = a.PS >> 2;
+    const int lds_lane = (wpx * 64 + p) * ps4 + kq;
+
+    for (int c0 = 0; c0 < a.CB * 16; c0 += a.CKC) {
+        if (c0) __syncthreads();
+        // batches of kStageBatch 16-byte loads are issued before their LDS stores, so that a
+        // thread has several global reads in flight instead of one
+        for (int base = tid; base < n_chunks; base += 256 * kStageBatch) {
+            floatx4 v[kStageBatch];
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int idx = base + u * 256;
+                const int c4 = idx & (c4n - 1);
+                const int pix = idx >> c4shift;
+                const int c = c0 + c4 * 4;
+                v[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (idx < n_chunks && pix < px_here && c < a.Cin)
+                    v[u] = *reinterpret_cast<const floatx4 *>(in_s + (size_t)pix * a.Cin + c);
+            }
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int idx = base + u * 256;
+                if (idx < n_chunks) lds4[(idx >> c4shift) * ps4 + (idx & (c4n - 1))] = v[u];
+            }
+        }
+        __syncthreads();
+        if (active) {
+            const int ncb = min(a.CKC, a.CB * 16 - c0) >> 4;
+            const int cb0 = c0 >> 4;
+#pragma unroll 1
+            for (int cbl = 0; cbl < ncb; ++cbl) {
+                floatx4 wa[NT], xb[4];
+#pragma unroll
+                for (int n = 0; n < NT; ++n) {
+                    const int ct = min(ct0 + n, a.cout_tiles - 1);
+                    wa[n] = *reinterpret_cast<const floatx4 *>(wq + (((size_t)ct * a.CB + cb0 + cbl) * 64 + lane) * 4);
+                }
+#pragma unroll
+                for (int m = 0; m < 4; ++m)
+                    xb[m] = lds4[lds_lane + m * 16 * ps4 + cbl * 4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int m = 0; m < 4; ++m)
+#pragma unroll
+                        for (int n = 0; n < NT; ++n)
+                            acc[m][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[n][j], xb[m][j], acc[m][n], 0, 0, 0);
+            }
+        }
+    }
+    if (!active) return;
+
+    const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
+    const size_t obase = (size_t)s * a.out_scheme_stride + (size_t)P0 * a.Cout;
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int co = (ct0 + n) * 16 + kq * 4;
+        if (co >= a.Cout) continue;
+        const floatx4 b = *reinterpret_cast<const floatx4 *>(a.bias + co);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int pl = wpx * 64 + m * 16 + p;
+            if (pl >= px_here) continue;
+            const size_t o = obase + (size_t)pl * a.Cout + co;
+            floatx4 v = acc[m][n] + b;
+            if (a.res) v += *reinterpret_cast<const floatx4 *>(a.res + o);
+            v.x = fminf(fmaxf(v.x, lo), hi);
+            v.y = fminf(fmaxf(v.y, lo), hi);
+            v.z = fminf(fmaxf(v.z, lo), hi);
+            v.w = fminf(fmaxf(v.w, lo), hi);
+            *reinterpret_cast<floatx4 *>(a.out + o) = v;
+        }
+    }
+}
+
+template <int NT>
+static hipError_t launch_pointwise_t(const PointwiseArgs &a, size_t lds_bytes, dim3 grid, hipStream_t st)
+{
+    static bool lds_set = false;
+    if (!lds_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pointwise_mfma_kernel<NT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        lds_set = true;
+    }
+    hipLaunchKernelGGL((pointwise_mfma_kernel<NT>), grid, dim3(256), lds_bytes, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_pointwise(const PointwiseArgs &a, int nt, size_t lds_bytes, dim3 grid, hipStream_t st)
+{
+    switch (nt) {
+    case 1: return launch_pointwise_t<1>(a, lds_bytes, grid, st);
+    case 2: return launch_pointwise_t<2>(a, lds_bytes, grid, st);
+    case 3: return launch_pointwise_t<3>(a, lds_bytes, grid, st);
+    case 4: return launch_pointwise_t<4>(a, lds_bytes, grid, st);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 // ------------------------------------------------------------------ depthwise 3x3
