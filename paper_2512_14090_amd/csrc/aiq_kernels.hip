@@ -109,10 +109,83 @@ __global__ __launch_bounds__(256) void quantize_batch_kernel(const QuantJob *job
     if (c < j.cout) quantize_channel(j, c, threadIdx.x & 63);
 }
 
+// Plain [cout][k] rows with k % 4 == 0 and 16-byte aligned pointers: the wavefront keeps its
+// whole row in registers (NV 16-byte elements per lane), so every weight is read from memory
+// once and written once, 16 bytes per lane per access; a workgroup's four rows are one
+// contiguous stretch of memory.  Same arithmetic, step for step, as quantize_channel.
+template <int NV>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(QuantJob j)
+{
+    const int c = blockIdx.x * kQuantChannelsPerBlock + (threadIdx.x >> 6);
+    if (c >= j.cout) return;
+    const int lane = threadIdx.x & 63;
+    const int k4 = j.k >> 2;
+    const floatx4 *row = reinterpret_cast<const floatx4 *>(j.w + (size_t)c * j.k);
+    floatx4 *out = reinterpret_cast<floatx4 *>(j.out + (size_t)c * j.k);
+    floatx4 v[NV];
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int i = u * 64 + lane;
+        v[u] = i < k4 ? __builtin_nontemporal_load(row + i) : floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    if (j.bits == 32) {
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int i = u * 64 + lane;
+            if (i < k4) __builtin_nontemporal_store(v[u], out + i);
+        }
+        if (lane == 0 && j.scales) j.scales[c] = 1.0f;
+        return;
+    }
+    float amax = 0.0f;
+#pragma unroll
+    for (int u = 0; u < NV; ++u)
+        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v[u].x), fabsf(v[u].y))), fmaxf(fabsf(v[u].z), fabsf(v[u].w)));
+    amax = wave_max(amax);
+    const int qmax = (1 << (j.bits - 1)) - 1;
+    const float s = amax > 0.0f ? __fdiv_rn(amax, (float)qmax) : 1.0f;
+    if (lane == 0 && j.scales) j.scales[c] = s;
+    typedef int intx4 __attribute__((ext_vector_type(4)));
+    intx4 *codes = j.codes ? reinterpret_cast<intx4 *>(j.codes + (size_t)c * j.k) : nullptr;
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int i = u * 64 + lane;
+        if (i >= k4) continue;
+        intx4 q;
+        floatx4 d;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            int qe = (int)rintf(__fdiv_rn(v[u][e], s));
+            qe = min(max(qe, -qmax), qmax);
+            q[e] = qe;
+            d[e] = __fmul_rn((float)qe, s);
+        }
+        __builtin_nontemporal_store(d, out + i);
+        if (codes) codes[i] = q;
+    }
+}
+
+template <int NV>
+static hipError_t launch_quantize_rows(const QuantJob &job, int blocks, hipStream_t st)
+{
+    hipLaunchKernelGGL((quantize_rows_kernel<NV>), dim3(blocks), dim3(256), 0, st, job);
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize_single(const QuantJob &job, hipStream_t st)
 {
     if (job.cout == 0) return hipSuccess; // k == 0 still writes s = 1 for every (empty) row
     const int blocks = (job.cout + kQuantChannelsPerBlock - 1) / kQuantChannelsPerBlock;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(job.w) | reinterpret_cast<uintptr_t>(job.out) |
+                           reinterpret_cast<uintptr_t>(job.codes)) & 15) == 0;
+    if (job.layout == kLayoutPlain && job.k > 0 && (job.k & 3) == 0 && aligned && job.k <= 4 * 64 * 20) {
+        const int nv = (job.k / 4 + 63) / 64;
+        if (nv <= 1) return launch_quantize_rows<1>(job, blocks, st);
+        if (nv <= 2) return launch_quantize_rows<2>(job, blocks, st);
+        if (nv <= 5) return launch_quantize_rows<5>(job, blocks, st);
+        if (nv <= 10) return launch_quantize_rows<10>(job, blocks, st);
+        return launch_quantize_rows<20>(job, blocks, st);
+    }
     hipLaunchKernelGGL(quantize_single_kernel, dim3(blocks), dim3(256), 0, st, job);
     return hipGetLastError();
 }

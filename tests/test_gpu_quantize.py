@@ -8,7 +8,9 @@ BITS = (32, 16, 8, 6, 4, 2)
 # (cout, k): dense 3x3 rows of the ResNet stages, the stem, depthwise, MobileNetV2 1x1 and classifier
 # rows, plus ragged sizes around the 64-lane and 4-channels-per-block tiling
 SHAPES = [(16, 27), (16, 144), (32, 288), (64, 576), (96, 9), (10, 64), (10, 1280), (160, 960),
-          (1, 1), (3, 63), (5, 65), (7, 129), (130, 200)]
+          (1, 1), (3, 63), (5, 65), (7, 129), (130, 200),
+          # row-in-registers path: one 16-byte element per lane exactly, one over, its largest row, one beyond it
+          (9, 256), (6, 260), (5, 1284), (3, 2564), (5, 5120), (2, 5124), (3, 8192)]
 
 
 @pytest.fixture(scope="module")
@@ -81,6 +83,24 @@ def test_stress_shape_sample(aiq):
         qmax = 2 ** (bits - 1) - 1
         ratio = (w_dq / s[:, None]).round().abs().max().item()
         assert ratio == qmax
+
+
+def test_unaligned_rows_take_the_scalar_path(aiq):
+    """A weight matrix that starts 4 bytes into an allocation (rows not 16-byte aligned)."""
+    import torch
+    import oracle
+    w = _w(12, 288, 5)
+    buf = torch.zeros(12 * 288 + 1, dtype=torch.float32, device="cuda")
+    buf[1:] = torch.from_numpy(w).reshape(-1).cuda()
+    wv = buf[1:].view(12, 288)
+    assert wv.data_ptr() % 16 == 4
+    for bits in (8, 2):
+        w_dq, s, q = aiq.quantize_weights(wv, bits)
+        torch.cuda.synchronize()
+        r_dq, r_s, r_q = oracle.quantize_weights(w, bits)
+        assert s.cpu().numpy().tobytes() == r_s.tobytes()
+        assert w_dq.cpu().numpy().tobytes() == r_dq.tobytes()
+        np.testing.assert_array_equal(q.cpu().numpy(), r_q)
 
 
 def test_empty_and_errors(aiq):
