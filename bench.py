@@ -92,7 +92,7 @@ def main():
         step()
     torch.cuda.synchronize()
     model.profile_enable(True)
-    for c in range(6):
+    for c in range(7):
         model.profile_read(c)
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -100,18 +100,20 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     model.profile_enable(False)
-    names = ("quantize", "conv_mfma", "depthwise", "head", "agree", "resnet_fused")
+    names = ("quantize", "conv_mfma", "depthwise", "head", "agree", "resnet_fused", "mbconv")
     prof = {name: model.profile_read(c) for c, name in enumerate(names)}
     agree = r["agree"].cpu().numpy()
 
     ms_per_step = dt / args.steps * 1e3
     value = S * N * args.steps / dt
-    # dominant kernel: the LDS-resident whole-network kernel when the model runs that way,
-    # else the layer-by-layer dense convolution
-    dom = "resnet_fused" if prof["resnet_fused"]["launches"] else "conv_mfma"
+    # dominant kernel: the LDS-resident whole-network kernel when the model runs that way, the
+    # LDS-resident inverted-residual block kernel when the model has such blocks, else the
+    # layer-by-layer dense convolution
+    dom = "resnet_fused" if prof["resnet_fused"]["launches"] else ("mbconv" if prof["mbconv"]["launches"] else "conv_mfma")
     conv = prof[dom]
     achieved = conv["flops"] / (conv["total_ms"] * 1e-3) / 1e12 if conv["total_ms"] > 0 else 0.0
     label = {"resnet_fused": "resnet_fused_kernel (whole network per (scheme, image), activations in LDS, fp32 MFMA)",
+             "mbconv": "mbconv_kernel (1x1 expand, depthwise 3x3, 1x1 project per launch, hidden tensor in LDS, fp32 MFMA)",
              "conv_mfma": "conv_mfma_kernel (3x3/1x1 implicit GEMM, fp32 MFMA)"}[dom]
     roofline = {"bound": "mfma", "kernel": label,
                 "achieved": achieved, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
@@ -128,6 +130,7 @@ def main():
             "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
             "config": {"workload": wl["name"], "schemes": int(S), "images": int(N), "chunk": int(chunk),
                        "scheme_layers": int(L), "base_pass_in_step": True, "lds_resident": bool(model.lds_resident),
+                       "lds_resident_blocks": int(model.lds_resident_blocks),
                        "agree_min_max": [int(agree.min()), int(agree.max())] if S else []},
             "roofline": roofline, "kernels": kernels}
     if not args.no_cpu_baseline:

@@ -118,8 +118,11 @@ aiq_status aiq_model_create(const aiq_layer_desc *layers, int32_t n_layers, cons
 enum { AIQ_MODEL_LAYERWISE = 1 };
 aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, const float *const *w_host,
                                const float *const *bias_host, uint32_t flags, aiq_model **out);
-/* 1 if the model runs LDS-resident (one launch for the whole network), 0 if layer by layer, -1 for NULL. */
+/* 1 if the model runs LDS-resident (one launch for the whole network), 0 if not, -1 for NULL. */
 int32_t aiq_model_is_lds_resident(const aiq_model *m);
+/* Number of inverted-residual blocks (1x1 expand, depthwise 3x3, 1x1 project) that run as one
+   launch with the expanded tensor held in LDS; the other layers run layer by layer.  -1 for NULL. */
+int32_t aiq_model_lds_resident_blocks(const aiq_model *m);
 void aiq_model_destroy(aiq_model *m); /* NULL-safe */
 
 /* L (number of scheme layers) and the classifier width; -1 for a NULL model. */
@@ -210,10 +213,11 @@ aiq_status aiq_search_coordinate_descent(aiq_model *m, const aiq_layer_desc *lay
  * recorded events, then returns for kernel class cls the number of launches, their
  * summed duration and the algorithmic FLOPs and bytes they covered, and clears the
  * record for that class.  Classes: 0 quantize, 1 dense convolution (MFMA),
- * 2 depthwise convolution, 3 classifier head, 4 agreement count, 5 LDS-resident whole network.
+ * 2 depthwise convolution, 3 classifier head, 4 agreement count, 5 LDS-resident whole network,
+ * 6 LDS-resident inverted-residual block.
  */
 enum { AIQ_K_QUANTIZE = 0, AIQ_K_CONV = 1, AIQ_K_DEPTHWISE = 2, AIQ_K_HEAD = 3, AIQ_K_AGREE = 4,
-       AIQ_K_FUSED = 5, AIQ_K_CLASSES = 6 };
+       AIQ_K_FUSED = 5, AIQ_K_MBCONV = 6, AIQ_K_CLASSES = 7 };
 aiq_status aiq_profile_enable(aiq_model *m, int32_t on);
 aiq_status aiq_profile_read(aiq_model *m, int32_t cls, int64_t *launches, double *total_ms, double *flops,
                             double *bytes);

@@ -12,11 +12,11 @@ _lib = None
 
 EXPORTED_SYMBOLS = (
     "aiq_status_str", "aiq_last_hip_error", "aiq_layer_ai", "aiq_quantize_weights", "aiq_model_create",
-    "aiq_model_create_ex", "aiq_model_is_lds_resident", "aiq_model_destroy", "aiq_model_scheme_layers", "aiq_model_classes", "aiq_eval_workspace_bytes",
+    "aiq_model_create_ex", "aiq_model_is_lds_resident", "aiq_model_lds_resident_blocks", "aiq_model_destroy", "aiq_model_scheme_layers", "aiq_model_classes", "aiq_eval_workspace_bytes",
     "aiq_eval_schemes", "aiq_profile_enable", "aiq_profile_read", "aiq_search_workspace_bytes",
     "aiq_search_greedy", "aiq_search_coordinate_descent",
 )
-K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED = range(6)
+K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV = range(7)
 MODEL_LAYERWISE = 1
 _DESC_INTS = 13
 
@@ -61,6 +61,7 @@ def load_library():
     lib.aiq_model_create_ex.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32,
                                         C.POINTER(C.c_void_p)]
     lib.aiq_model_is_lds_resident.argtypes = [C.c_void_p]
+    lib.aiq_model_lds_resident_blocks.argtypes = [C.c_void_p]
     lib.aiq_model_destroy.argtypes = [C.c_void_p]
     lib.aiq_model_destroy.restype = None
     lib.aiq_model_scheme_layers.argtypes = [C.c_void_p]
@@ -154,6 +155,7 @@ class Model:
                                              C.byref(h)), "aiq_model_create_ex")
         self._h = h
         self.lds_resident = bool(self._lib.aiq_model_is_lds_resident(h))
+        self.lds_resident_blocks = int(self._lib.aiq_model_lds_resident_blocks(h))
         self.L = int(self._lib.aiq_model_scheme_layers(h))
         self.classes = int(self._lib.aiq_model_classes(h))
         self._workspace = None

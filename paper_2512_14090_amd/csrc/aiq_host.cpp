@@ -52,6 +52,8 @@ struct Node {
     int buf = -1;       // activation buffer holding this node's output
     int job0 = -1;      // first quantize job (bits index 1) of this node, -1 if not a scheme layer
     ConvPlan plan;
+    int mb_role = 0;    // 1: 1x1 expand heading an LDS-resident inverted-residual block, 2: its depthwise / project
+    MbShape mb_shape{};
     double flops_per_image;      // 2 * multiply-adds
     double act_bytes_per_image;  // algorithmic: input + output (+ residual) activations
 };
@@ -77,6 +79,7 @@ struct aiq_model {
     std::vector<void *> allocations;
     // LDS-resident path (CIFAR-style ResNets)
     bool fused = false;
+    int mb_blocks = 0;  // inverted-residual blocks run by the LDS-resident block kernel
     std::vector<FusedOp> fused_ops;
     FusedOp *fused_ops_dev = nullptr;
     double fused_flops_per_image = 0.0;
@@ -209,6 +212,34 @@ bool plan_fused(const std::vector<Node> &nodes, std::vector<FusedOp> &ops)
     if (fc.kind != 2 || fc.input != cur || fc.cin != 64 || c != 64 || h != 8 || fc.hin != 8 || fc.win != 8) return false;
     mk(kOpHead, i, R[reg], R[1 - reg], -1, 0, 0);
     return true;
+}
+
+// Marks every expand -> depthwise -> project triple whose shape the LDS-resident block kernel
+// covers and whose two hidden tensors have no other reader.  Returns the number of blocks.
+int plan_mbconv(std::vector<Node> &nodes)
+{
+    const int n = (int)nodes.size();
+    std::vector<int> readers(n, 0);
+    for (const Node &nd : nodes) {
+        if (nd.d.input >= 0) ++readers[nd.d.input];
+        if (nd.d.residual >= 0) ++readers[nd.d.residual];
+    }
+    int blocks = 0;
+    for (int i = 0; i + 2 < n; ++i) {
+        const aiq_layer_desc &e = nodes[i].d, &d = nodes[i + 1].d, &p = nodes[i + 2].d;
+        if (e.kind != 0 || e.kh != 1 || e.stride != 1 || e.input < 0 || e.residual >= 0 || e.hin != e.win) continue;
+        if (d.kind != 1 || d.input != i || readers[i] != 1) continue;
+        if (p.kind != 0 || p.kh != 1 || p.stride != 1 || p.input != i + 1 || readers[i + 1] != 1) continue;
+        if (p.residual >= 0 && p.residual != e.input) continue;
+        MbShape sh{e.cin, e.cout, p.cout, e.hin, d.stride, p.residual >= 0 ? 1 : 0};
+        if (!mbconv_supported(sh)) continue;
+        nodes[i].mb_role = 1;
+        nodes[i].mb_shape = sh;
+        nodes[i + 1].mb_role = nodes[i + 2].mb_role = 2;
+        ++blocks;
+        i += 2;
+    }
+    return blocks;
 }
 
 aiq_status validate_graph(const aiq_layer_desc *layers, int n_layers)
@@ -414,6 +445,7 @@ void aiq_model_destroy(aiq_model *m)
 }
 
 int32_t aiq_model_is_lds_resident(const aiq_model *m) { return m ? (m->fused ? 1 : 0) : -1; }
+int32_t aiq_model_lds_resident_blocks(const aiq_model *m) { return m ? m->mb_blocks : -1; }
 
 aiq_status aiq_model_create(const aiq_layer_desc *layers, int32_t n_layers, const float *const *w_host,
                             const float *const *bias_host, aiq_model **out)
@@ -485,6 +517,8 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
         stem.layout = kLayoutStem;
         stem.bank_elems = (size_t)((stem.d.cout + 15) / 16) * 9 * 64;
         for (const Node &nd : m->nodes) m->fused_flops_per_image += nd.flops_per_image;
+    } else if (!(flags & AIQ_MODEL_LAYERWISE)) {
+        m->mb_blocks = plan_mbconv(m->nodes);
     }
 
     // activation buffers: a node's output lives until its last reader has run
@@ -492,9 +526,13 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
     for (int l = 0; l < n_layers; ++l) {
         if (layers[l].input >= 0) last_use[layers[l].input] = l;
         if (layers[l].residual >= 0) last_use[layers[l].residual] = std::max(last_use[layers[l].residual], l);
+        // a block kernel reads the block input while it writes the project output: both stay live
+        if (m->nodes[l].mb_role == 1) last_use[layers[l].input] = std::max(last_use[layers[l].input], l + 2);
     }
     std::vector<int> owner; // owner[b] = node currently held by buffer b, -1 free
     for (int l = 0; l + 1 < n_layers; ++l) {
+        // the hidden tensors of an LDS-resident block (expand and depthwise outputs) never reach memory
+        if (m->nodes[l].mb_role == 1 || (m->nodes[l].mb_role == 2 && m->nodes[l].d.kind == 1)) continue;
         // free buffers whose tenant is no longer needed by node l or later
         for (size_t b = 0; b < owner.size(); ++b)
             if (owner[b] >= 0 && last_use[owner[b]] < l) owner[b] = -1;
@@ -694,6 +732,38 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
                 in_stride = (size_t)n * nd.in_elems;
             }
             const double work = (double)s_total * n;
+            if (nd.mb_role == 2) continue; // computed by the block kernel launched at its expand node
+            if (nd.mb_role == 1) {
+                const Node &dwn = m->nodes[l + 1], &pjn = m->nodes[l + 2];
+                MbArgs a{};
+                a.in = in;
+                a.out = buf_ptr(pjn.buf);
+                for (int b = 0; b < kNumBits; ++b) {
+                    a.bank_e[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+                    a.bank_d[b] = dwn.bank[b] ? dwn.bank[b] : dwn.bank[0];
+                    a.bank_p[b] = pjn.bank[b] ? pjn.bank[b] : pjn.bank[0];
+                }
+                a.bias_e = nd.bias;
+                a.bias_d = dwn.bias;
+                a.bias_p = pjn.bias;
+                a.schemes = schemes_dev;
+                a.in_scheme_stride = in_stride;
+                a.out_scheme_stride = (size_t)n * pjn.out_elems;
+                a.S = S;
+                a.L = m->L;
+                a.slot_e = d.scheme_slot;
+                a.slot_d = dwn.d.scheme_slot;
+                a.slot_p = pjn.d.scheme_slot;
+                a.N = n;
+                a.act_e = d.act;
+                a.act_d = dwn.d.act;
+                a.act_p = pjn.d.act;
+                const double flops = nd.flops_per_image + dwn.flops_per_image + pjn.flops_per_image;
+                const double bytes = 4.0 * (nd.in_elems + pjn.out_elems + (pjn.d.residual >= 0 ? pjn.out_elems : 0));
+                ProfScope ps(m, st, AIQ_K_MBCONV, flops * work, bytes * work);
+                AIQ_HIP(launch_mbconv(nd.mb_shape, a, s_total, st));
+                continue;
+            }
             if (d.kind == 0 && d.kh == 1 && d.stride == 1 && d.input >= 0) {
                 // 1x1 stride 1: flat pixel axis
                 const ConvPlan &p = nd.plan;

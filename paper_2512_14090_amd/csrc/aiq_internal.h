@@ -219,3 +219,33 @@ hipError_t launch_fused(const FusedArgs &a, int s_total, hipStream_t st);
 hipError_t fused_set_lds_limit();
 
 } // namespace aiq
+
+// ---------------------------------------------------------------- inverted-residual blocks
+//
+// 1x1 expand -> depthwise 3x3 -> 1x1 project with the expanded tensor held in LDS
+// (aiq_mbconv.hip).  Only the shapes listed there are covered; everything else runs layer
+// by layer.
+namespace aiq {
+
+constexpr int kMbThreads = 512;
+
+struct MbShape {
+    int32_t cin, hid, cout, h, stride, res;
+};
+
+struct MbArgs {
+    const float *in;  // [S?][N][H][W][CIN]
+    float *out;       // [S][N][HO][WO][COUT]
+    const float *bank_e[kNumBits], *bank_d[kNumBits], *bank_p[kNumBits]; // expand (MFMA layout), depthwise (tap-major), project
+    const float *bias_e, *bias_d, *bias_p;
+    const uint8_t *schemes;
+    size_t in_scheme_stride, out_scheme_stride;
+    int32_t S, L, slot_e, slot_d, slot_p;
+    int32_t N;
+    int32_t act_e, act_d, act_p;
+};
+
+bool mbconv_supported(const MbShape &sh);
+hipError_t launch_mbconv(const MbShape &sh, const MbArgs &a, int s_total, hipStream_t st);
+
+} // namespace aiq

@@ -677,8 +677,8 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
                 for (int g = 1; g < groups; ++g) acc += partial[g * cw + cl];
                 pooled[c] = acc * inv;
             }
-        } else {
-            pooled[c] = acc * inv;
+        } else if (grp == 0) {
+            pooled[c] = acc * inv; // threads past the last whole group (256 % C != 0) hold nothing
         }
     }
     __syncthreads();

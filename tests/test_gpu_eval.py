@@ -88,16 +88,74 @@ def test_resnet20_workload1(env, layerwise):
     print("max logit rel err %.3e" % err, flush=True)
 
 
-def test_mobilenetv2_workload3(env):
-    """Workload 3 (MobileNetV2-32, 10 random layers at 4 bits) on 6 images, 5 of its schemes + extras."""
-    wl = env["synth"].make_workload(3, n_images=6, n_schemes=5)
+@pytest.mark.parametrize("layerwise", [pytest.param(False, id="lds_resident_blocks"), pytest.param(True, id="layerwise")])
+def test_mobilenetv2_workload3(env, layerwise):
+    """Workload 3 (MobileNetV2-32, 10 random layers at 4 bits) on 7 images, 5 of its schemes + extras;
+    chunks of 5 and 2 images (odd counts: the 8x8 blocks take two images per workgroup)."""
+    aiq = env["aiq"]
+    wl = env["synth"].make_workload(3, n_images=7, n_schemes=5)
     schemes = np.concatenate([wl["schemes"], np.full((1, wl["L"]), 32, np.uint8), np.full((1, wl["L"]), 8, np.uint8),
                               np.full((1, wl["L"]), 2, np.uint8)])
-    print("mobilenetv2: S=%d N=6" % schemes.shape[0], flush=True)
+    print("mobilenetv2: S=%d N=7 layerwise=%s" % (schemes.shape[0], layerwise), flush=True)
     ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes)
-    gpu = _run_gpu(env, wl, schemes, chunk=4, expect_resident=False)
-    err = check_eval(gpu, ref, 6)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=layerwise)
+    assert not m.lds_resident
+    # every inverted-residual block with an expand layer (16 of 17) keeps its hidden tensor in LDS
+    assert m.lds_resident_blocks == (0 if layerwise else 16)
+    gpu = _run_gpu(env, wl, schemes, chunk=5, model=m)
+    m.close()
+    err = check_eval(gpu, ref, 7)
     print("max logit rel err %.3e" % err, flush=True)
+
+
+def test_mobilenetv2_full_size_sampled(env):
+    """Workload 3 in the benchmark's launch configuration (16 schemes x 512 images, one chunk); the
+    oracle recomputes every scheme on a sample of images, the agreement identity covers the rest."""
+    wl = env["synth"].make_workload(3)
+    print("mobilenetv2 full size", flush=True)
+    gpu = _run_gpu(env, wl, wl["schemes"], chunk=1024)
+    idx = np.array([0, 1, 255, 256, 510, 511])
+    ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"][idx], wl["schemes"])
+    err = logits_rel_error(gpu["logits"][:, idx], ref["logits"])
+    assert err <= 1e-3, err
+    assert not ((gpu["top1"][:, idx] != ref["top1"]) & ~near_tied(ref["logits"])).any()
+    assert not ((gpu["top1_base"][idx] != ref["top1_base"]) & ~near_tied(ref["logits_base"])).any()
+    np.testing.assert_array_equal(gpu["agree"], (gpu["top1"] == gpu["top1_base"][None]).sum(axis=1))
+    print("sampled max logit rel err %.3e; agree %s" % (err, gpu["agree"]), flush=True)
+
+
+def test_inverted_residual_blocks_one_by_one(env):
+    """Each block shape of MobileNetV2-32 as a tiny network of its own (stem-like 1x1 feeding the
+    block is not needed: the block reads the network input), LDS-resident against layer by layer
+    and against the oracle, with every bit-width on each of the three layers."""
+    synth, oracle, aiq, torch = env["synth"], env["oracle"], env["aiq"], env["torch"]
+    shapes = [(16, 96, 24, 32, 1), (24, 144, 24, 32, 1), (24, 144, 32, 32, 1), (32, 192, 32, 32, 1),
+              (32, 192, 64, 32, 2), (64, 384, 64, 16, 1), (64, 384, 96, 16, 1), (96, 576, 96, 16, 1),
+              (96, 576, 160, 16, 2), (160, 960, 160, 8, 1), (160, 960, 320, 8, 1)]
+    for k, (cin, hid, cout, h, stride) in enumerate(shapes):
+        res = stride == 1 and cin == cout
+        G = synth.graphs
+        nodes = [G._node(G.KIND_CONV, 4, cin, 1, 1, h, -1, act=G.ACT_NONE, slot=0, name="in"),
+                 G._node(G.KIND_CONV, cin, hid, 1, 1, h, 0, act=G.ACT_RELU6, slot=1, name="expand"),
+                 G._node(G.KIND_DEPTHWISE, hid, hid, 3, stride, h, 1, act=G.ACT_RELU6, slot=2, name="dw"),
+                 G._node(G.KIND_CONV, hid, cout, 1, 1, h // stride, 2, residual=0 if res else -1, act=G.ACT_NONE,
+                         slot=3, name="project"),
+                 G._node(G.KIND_FC, cout, 10, 1, 1, h // stride, 3, act=G.ACT_NONE, slot=4, name="fc")]
+        rng = np.random.Generator(np.random.PCG64(300 + k))
+        w, b = synth.make_model(nodes, rng)
+        n = 5
+        images = rng.standard_normal((n, h, h, 4)).astype(np.float32)
+        desc = synth.desc_array(nodes)
+        schemes = np.array([[32, 32, 32, 32, 32], [32, 8, 4, 2, 32], [32, 2, 16, 6, 8], [8, 4, 8, 4, 4]], dtype=np.uint8)
+        print(f"block {cin}->{hid}->{cout} h{h} s{stride} res={res}", flush=True)
+        ref = oracle.eval_schemes(desc, w, b, images, schemes)
+        wl = dict(desc=desc, weights=w, biases=b, images=images)
+        m = aiq.Model(desc, w, b)
+        assert m.lds_resident_blocks == 1
+        gpu = _run_gpu(env, wl, schemes, chunk=3, model=m)
+        m.close()
+        err = check_eval(gpu, ref, n)
+        print("  max logit rel err %.3e" % err, flush=True)
 
 
 def test_variant_models(env):
