@@ -227,7 +227,6 @@ hipError_t fused_set_lds_limit();
 // by layer.
 namespace aiq {
 
-constexpr int kMbThreads = 512;
 
 struct MbShape {
     int32_t cin, hid, cout, h, stride, res;
