@@ -223,7 +223,8 @@ struct OpRT {
     uint32_t w_lo, w_hi;     // weights of the scheme's bit-width, kernel layout
     uint32_t b_lo, b_hi;     // bias
     int32_t type, act, src_off, dst_off;
-    int32_t res_off, flags, classes, pad_;
+    int32_t res_off, flags, classes;
+    int32_t shape;           // dense ops: (reduction steps << 8) | (output-channel tiles - 1); 0 otherwise
 };
 
 __device__ __forceinline__ OpRT uniform_op(const OpRT &v)
@@ -240,7 +241,7 @@ __device__ __forceinline__ OpRT uniform_op(const OpRT &v)
     r.res_off = __builtin_amdgcn_readfirstlane(v.res_off);
     r.flags = __builtin_amdgcn_readfirstlane(v.flags);
     r.classes = __builtin_amdgcn_readfirstlane(v.classes);
-    r.pad_ = 0;
+    r.shape = __builtin_amdgcn_readfirstlane(v.shape);
     return r;
 }
 __device__ __forceinline__ const float *op_ptr(uint32_t lo, uint32_t hi)
@@ -282,7 +283,7 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
         r.res_off = op.res_off;
         r.flags = (op.res_padded ? 1 : 0) | (op.zero_ring ? 2 : 0);
         r.classes = op.classes;
-        r.pad_ = 0;
+        r.shape = kOpSteps[op.type] > 0 ? (kOpSteps[op.type] << 8) | (kOpCoutTiles[op.type] - 1) : 0;
         s_ops[tid] = r;
     }
     // clear both regions (borders must be zero), then store the image as (r, g, b, 0) pixels
@@ -321,9 +322,10 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
         // none the prefetch harmlessly re-reads chunk 0 of this op's own weights
         const float *next_w = wq + lane * 4;
         int next_last = 0;
-        if (o + 1 < a.n_ops && kOpSteps[nxt.type] > 0) {
-            const int ns = kOpSteps[nxt.type];
-            const int nct = wave & (kOpCoutTiles[nxt.type] - 1);
+        if (o + 1 < a.n_ops && nxt.shape != 0) {
+            // the next op's shape comes with its table row: no dependent constant-memory reads here
+            const int ns = nxt.shape >> 8;
+            const int nct = wave & (nxt.shape & 255);
             next_w = op_ptr(nxt.w_lo, nxt.w_hi) + ((size_t)nct * ns * 64 + lane) * 4;
             next_last = ns - 1;
         }
