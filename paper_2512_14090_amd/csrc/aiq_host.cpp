@@ -853,8 +853,6 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
                 a.stride = d.stride;
                 a.act = d.act;
                 a.div_c4 = make_fastdiv(d.cin / 4);
-                a.band_rows = std::min(nd.hout, 8);
-                a.bands = (nd.hout + a.band_rows - 1) / a.band_rows;
                 ProfScope ps(m, st, AIQ_K_DEPTHWISE, nd.flops_per_image * work, nd.act_bytes_per_image * work);
                 AIQ_HIP(launch_depthwise(a, s_total, st));
             } else {

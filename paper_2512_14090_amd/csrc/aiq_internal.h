@@ -118,7 +118,6 @@ struct DepthwiseArgs {
     size_t in_scheme_stride, out_scheme_stride;
     int32_t S, L, slot;
     int32_t N, Hin, Win, C, Hout, Wout, stride, act;
-    int32_t band_rows, bands; // output rows per thread walk, walks per image
     FastDiv div_c4;
 };
 

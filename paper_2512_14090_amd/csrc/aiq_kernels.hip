@@ -558,89 +558,102 @@ hipError_t launch_pointwise(const PointwiseArgs &a, int nt, size_t lds_bytes, di
 // ------------------------------------------------------------------ depthwise 3x3
 //
 // Bandwidth-bound: 18 FLOP per output element.  One thread owns four consecutive channels
-// (16 bytes along the NHWC channel axis) of one output column and walks down a band of
-// output rows with a sliding 3x3 window in registers: the nine filter taps are loaded once,
-// every step loads only the new input row (three 16-byte loads for stride 1, six for stride
-// 2), so the L1/texture path carries 3x the input instead of 9x plus the weights.  Lanes
-// run along (channel group, column), which is contiguous in memory.
+// (16 bytes along the NHWC channel axis) of XG adjacent output columns and walks down the
+// whole image with the 3-row window in registers: the nine filter taps are loaded once, every
+// input row is loaded once per thread ((XG-1)*STRIDE + 3 16-byte loads for XG outputs, the two
+// outer ones shared with the neighbouring threads through L1), rows are requested PF output
+// rows ahead of their use, results leave with nontemporal 16-byte stores.  The (column group,
+// channel group) positions of all images of the chunk form one flat thread axis, so a
+// workgroup's accesses per row are one contiguous stretch of memory.
 
-template <int STRIDE>
+template <int STRIDE, int XG, int PF>
 __global__ __launch_bounds__(256) void depthwise3x3_kernel(DepthwiseArgs a)
 {
+    constexpr int WIN = (XG - 1) * STRIDE + 3; // input columns per window row
+    constexpr int NB = 3 + PF * STRIDE;        // row buffers: the window plus the rows in flight
     const int s = blockIdx.z;
-    const int img = blockIdx.y / a.bands, band = blockIdx.y - img * a.bands;
-    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
     const int c4n = a.C >> 2;
-    if (idx >= (uint32_t)(a.Wout * c4n)) return;
-    const uint32_t ox = fd_div(idx, a.div_c4);
-    const int c = (idx - ox * c4n) * 4;
-    const int oy0 = band * a.band_rows;
-    const int oy1 = min(oy0 + a.band_rows, a.Hout);
+    const uint32_t P = (uint32_t)(a.Wout / XG) * c4n;
+    const uint32_t gidx = blockIdx.x * 256u + threadIdx.x;
+    if (gidx >= (uint32_t)a.N * P) return;
+    const uint32_t img = gidx / P, pos = gidx - img * P;
+    const uint32_t xg = fd_div(pos, a.div_c4);
+    const int c = (pos - xg * c4n) * 4, ox0 = xg * XG;
     const float *wq = a.bank[scheme_bits_index(a.schemes, s, a.S, a.L, a.slot)];
-    const float *in = a.in + (size_t)s * a.in_scheme_stride + (size_t)img * a.Hin * a.Win * a.C + c;
-    float *out = a.out + (size_t)s * a.out_scheme_stride + ((size_t)img * a.Hout * a.Wout + ox) * a.C + c;
+    const float *__restrict__ in = a.in + (size_t)s * a.in_scheme_stride + (size_t)img * a.Hin * a.Win * a.C + c;
+    float *__restrict__ out =
+        a.out + (size_t)s * a.out_scheme_stride + ((size_t)img * a.Hout * a.Wout + ox0) * a.C + c;
 
     floatx4 w[9];
 #pragma unroll
     for (int t = 0; t < 9; ++t) w[t] = *reinterpret_cast<const floatx4 *>(wq + (size_t)t * a.C + c);
     const floatx4 bias = *reinterpret_cast<const floatx4 *>(a.bias + c);
     const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
-
-    const int ix0 = (int)ox * STRIDE - 1;
-    const bool okx[3] = {ix0 >= 0, true, ix0 + 2 < a.Win};
     const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};
-    auto load_row = [&](int iy, floatx4 (&r)[3]) {
-        const bool oky = iy >= 0 && iy < a.Hin;
-        const float *row = in + ((size_t)iy * a.Win + ix0) * a.C;
+    const int ix0 = ox0 * STRIDE - 1;
+    const bool ok_first = ix0 >= 0, ok_last = ix0 + WIN - 1 < a.Win; // only the outer columns can fall outside
+    auto load_row = [&](int iy, floatx4 (&r)[WIN]) {
+        if (iy < 0 || iy >= a.Hin) {
 #pragma unroll
-        for (int k = 0; k < 3; ++k)
-            r[k] = (oky && okx[k]) ? *reinterpret_cast<const floatx4 *>(row + (size_t)k * a.C) : zero;
+            for (int k = 0; k < WIN; ++k) r[k] = zero;
+            return;
+        }
+        const float *row = in + ((size_t)iy * a.Win + ix0) * a.C;
+        r[0] = ok_first ? *reinterpret_cast<const floatx4 *>(row) : zero;
+#pragma unroll
+        for (int k = 1; k < WIN - 1; ++k) r[k] = *reinterpret_cast<const floatx4 *>(row + (size_t)k * a.C);
+        r[WIN - 1] = ok_last ? *reinterpret_cast<const floatx4 *>(row + (size_t)(WIN - 1) * a.C) : zero;
     };
 
-    floatx4 r0[3], r1[3], r2[3];
-    load_row(oy0 * STRIDE - 1, r0);
-    if (STRIDE == 1) load_row(oy0, r1);
-    for (int oy = oy0; oy < oy1; ++oy) {
-        if (STRIDE == 1) {
-            load_row(oy + 1, r2);
-        } else {
-            load_row(oy * 2, r1);
-            load_row(oy * 2 + 1, r2);
-        }
-        floatx4 acc = bias;
+    // r[q] holds input row oy*STRIDE - 1 + q
+    floatx4 r[NB][WIN];
 #pragma unroll
-        for (int k = 0; k < 3; ++k) {
-            acc += r0[k] * w[k];
-            acc += r1[k] * w[3 + k];
-            acc += r2[k] * w[6 + k];
-        }
-        acc.x = fminf(fmaxf(acc.x, lo), hi);
-        acc.y = fminf(fmaxf(acc.y, lo), hi);
-        acc.z = fminf(fmaxf(acc.z, lo), hi);
-        acc.w = fminf(fmaxf(acc.w, lo), hi);
-        *reinterpret_cast<floatx4 *>(out + (size_t)oy * a.Wout * a.C) = acc;
+    for (int q = 0; q < NB; ++q) load_row(q - 1, r[q]);
+    for (int oy = 0; oy < a.Hout; ++oy) {
 #pragma unroll
-        for (int k = 0; k < 3; ++k) {
-            if (STRIDE == 1) {
-                r0[k] = r1[k];
-                r1[k] = r2[k];
-            } else {
-                r0[k] = r2[k];
+        for (int x = 0; x < XG; ++x) {
+            floatx4 acc = bias;
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                acc += r[0][x * STRIDE + k] * w[k];
+                acc += r[1][x * STRIDE + k] * w[3 + k];
+                acc += r[2][x * STRIDE + k] * w[6 + k];
             }
+            acc.x = __builtin_amdgcn_fmed3f(acc.x, lo, hi);
+            acc.y = __builtin_amdgcn_fmed3f(acc.y, lo, hi);
+            acc.z = __builtin_amdgcn_fmed3f(acc.z, lo, hi);
+            acc.w = __builtin_amdgcn_fmed3f(acc.w, lo, hi);
+            __builtin_nontemporal_store(acc, reinterpret_cast<floatx4 *>(out + ((size_t)oy * a.Wout + x) * a.C));
         }
+#pragma unroll
+        for (int q = 0; q + STRIDE < NB; ++q)
+#pragma unroll
+            for (int k = 0; k < WIN; ++k) r[q][k] = r[q + STRIDE][k];
+#pragma unroll
+        for (int i = 0; i < STRIDE; ++i) load_row((oy + 1) * STRIDE - 1 + NB - STRIDE + i, r[NB - STRIDE + i]);
     }
+}
+
+template <int STRIDE, int XG, int PF>
+static hipError_t launch_depthwise_t(const DepthwiseArgs &a, int s_total, hipStream_t st)
+{
+    const size_t threads = (size_t)a.N * (a.Wout / XG) * (a.C >> 2);
+    if (threads > 0xffffffffull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((depthwise3x3_kernel<STRIDE, XG, PF>), dim3((unsigned)((threads + 255) / 256), 1, s_total),
+                       dim3(256), 0, st, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_depthwise(const DepthwiseArgs &a, int s_total, hipStream_t st)
 {
     if (a.N == 0 || s_total == 0) return hipSuccess;
-    const int per_row = a.Wout * (a.C >> 2);
-    dim3 grid((per_row + 255) / 256, a.N * a.bands, s_total);
-    if (a.stride == 1)
-        hipLaunchKernelGGL(depthwise3x3_kernel<1>, grid, dim3(256), 0, st, a);
-    else
-        hipLaunchKernelGGL(depthwise3x3_kernel<2>, grid, dim3(256), 0, st, a);
-    return hipGetLastError();
+    if (a.stride == 1) {
+        if (a.Wout % 4 == 0) return launch_depthwise_t<1, 4, 2>(a, s_total, st);
+        if (a.Wout % 2 == 0) return launch_depthwise_t<1, 2, 2>(a, s_total, st);
+        return launch_depthwise_t<1, 1, 2>(a, s_total, st);
+    }
+    if (a.Wout % 2 == 0) return launch_depthwise_t<2, 2, 1>(a, s_total, st);
+    return launch_depthwise_t<2, 1, 1>(a, s_total, st);
 }
 
 // ------------------------------------------------------------------ classifier head

@@ -158,6 +158,32 @@ def test_inverted_residual_blocks_one_by_one(env):
         print("  max logit rel err %.3e" % err, flush=True)
 
 
+def test_depthwise_layers_outside_blocks(env):
+    """Stand-alone depthwise kernel: widths that are multiples of 4, of 2 only, and odd; both strides;
+    channel counts from 8 to 200; every bit-width on the depthwise layer."""
+    synth, oracle, aiq = env["synth"], env["oracle"], env["aiq"]
+    G = synth.graphs
+    cases = [(32, 32, 1), (12, 24, 1), (10, 8, 1), (7, 200, 1), (5, 16, 1), (32, 48, 2), (12, 16, 2), (14, 40, 2),
+             (9, 8, 2), (6, 96, 2)]
+    for k, (h, c, stride) in enumerate(cases):
+        ho = (h + 2 - 3) // stride + 1
+        nodes = [G._node(G.KIND_CONV, 4, c, 1, 1, h, -1, act=G.ACT_RELU, slot=0, name="in"),
+                 G._node(G.KIND_DEPTHWISE, c, c, 3, stride, h, 0, act=G.ACT_RELU6, slot=1, name="dw"),
+                 G._node(G.KIND_DEPTHWISE, c, c, 3, 1, ho, 1, act=G.ACT_NONE, slot=2, name="dw2"),
+                 G._node(G.KIND_FC, c, 10, 1, 1, ho, 2, act=G.ACT_NONE, slot=3, name="fc")]
+        rng = np.random.Generator(np.random.PCG64(500 + k))
+        w, b = synth.make_model(nodes, rng)
+        n = 6
+        images = rng.standard_normal((n, h, h, 4)).astype(np.float32)
+        desc = synth.desc_array(nodes)
+        schemes = np.array([[32, 32, 32, 32], [32, 8, 4, 32], [8, 2, 16, 6], [4, 6, 2, 8]], dtype=np.uint8)
+        print(f"depthwise h={h} c={c} stride={stride}", flush=True)
+        ref = oracle.eval_schemes(desc, w, b, images, schemes)
+        gpu = _run_gpu(env, dict(desc=desc, weights=w, biases=b, images=images), schemes, chunk=4)
+        err = check_eval(gpu, ref, n)
+        print("  max logit rel err %.3e" % err, flush=True)
+
+
 def test_variant_models(env):
     """PlainConvNet20 and HeavyEarlyResNet20 descriptors (64-channel layers at 32x32, stride-1 projection)."""
     synth, oracle = env["synth"], env["oracle"]
