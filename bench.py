@@ -17,22 +17,37 @@ sys.path.insert(0, ROOT)
 PEAK_MFMA_F32_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE x 2.000 and
+# HBM bytes per launch of a kernel class from rocprofv3 counters (FETCH_SIZE x 2.000 and
 # WRITE_SIZE x 1.000, the factors a plain copy of known size gives; profiles/ has the runs).
 # Valid only for the kernel source it was measured on: keyed by the sha256 of that source.
 TRAFFIC = {
-    "resnet20_greedy_step_n1024_s40": {
+    ("resnet20_greedy_step_n1024_s40", "resnet_fused"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_fused.hip",
-        "sha256": "4184e34478a48ff43e43fb10e682790b5ffb7de5f880b6ec6617354653fe20cf",
-        "bytes_per_launch": 62163763,
+        "sha256": "8a24e122f14b05402ada0e2a99fa2740a4b5228d124e6d17d2247f9423f8ae61",
+        "bytes_per_launch": 62165973,
+    },
+    ("mobilenetv2_32_n512_s16", "mbconv"): {  # average over the 16 block launches of a step
+        "kernel_source": "paper_2512_14090_amd/csrc/aiq_mbconv.hip",
+        "sha256": "35e11f7ba20ff749cd60bae49ab5c1fb72a1116509a9b4e83b45c0495db9c667",
+        "bytes_per_launch": 1905394733,
+    },
+    ("mobilenetv2_32_n512_s16", "depthwise"): {  # layer by layer: average over the 17 depthwise launches
+        "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
+        "sha256": "9605ac8581e4041a75d85d2d805b373e9b79707f88f04226dc43576b02170cd0",
+        "bytes_per_launch": 8289556892,
+    },
+    ("quantize_stress_8192x4608_b8", "quantize"): {
+        "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
+        "sha256": "9605ac8581e4041a75d85d2d805b373e9b79707f88f04226dc43576b02170cd0",
+        "bytes_per_launch": 302275802,
     },
 }
 
 
-def measured_traffic(workload_name, lds_resident):
+def measured_traffic(workload_name, cls):
     import hashlib
-    rec = TRAFFIC.get(workload_name)
-    if not rec or not lds_resident:
+    rec = TRAFFIC.get((workload_name, cls))
+    if not rec:
         return None
     with open(os.path.join(ROOT, rec["kernel_source"]), "rb") as f:
         if hashlib.sha256(f.read()).hexdigest() != rec["sha256"]:
@@ -53,6 +68,68 @@ def cpu_baseline(wl, budget_schemes=8, budget_images=192):
             "sample": f"first {s} schemes x first {n} images of the workload (+ its FP32 base pass), {dt:.1f} s"}
 
 
+def stress_quantize(args, torch, aiq):
+    """aiq_quantize_weights on a matrix far larger than the caches: 8 bytes moved per weight."""
+    import ctypes as C
+    cout, k = (int(v) for v in args.stress_shape.split("x"))
+    lib = aiq.load_library()
+    w = torch.randn(cout, k, device="cuda") * 0.02
+    w_dq = torch.empty_like(w)
+    scales = torch.empty(cout, device="cuda")
+    st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    results = {}
+    for bits in (8, 4, 16, 2):
+        def call():
+            rc = lib.aiq_quantize_weights(w.data_ptr(), cout, k, bits, w_dq.data_ptr(), scales.data_ptr(), None, st)
+            assert rc == 0, rc
+        for _ in range(args.warmup):
+            call()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        results[bits] = e0.elapsed_time(e1) / args.steps
+    ms = results[8]
+    nbytes = 8.0 * cout * k + 4.0 * cout
+    gbs = nbytes / ms / 1e6
+    line = {"metric": "quantize_gbytes_per_sec", "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"quantize_stress_{cout}x{k}_b8", "cout": cout, "k": k,
+                       "ms_by_bits": {str(b): v for b, v in results.items()}},
+            "roofline": {"bound": "hbm", "kernel": "quantize_rows_kernel (row in registers, one read and one write per weight)",
+                         "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                         "traffic": measured_traffic(f"quantize_stress_{cout}x{k}_b8", "quantize"),
+                         "algorithmic_gbytes_per_launch": nbytes / 1e9, "avg_launch_ms": ms}}
+    print(json.dumps(line))
+
+
+def print_hbm_line(args, wl, model, S, N, L, chunk, dt, agree, prof, cls):
+    """Same step, but the roofline block describes a bandwidth-bound kernel class."""
+    k = prof[cls]
+    gbs = k["bytes"] / (k["total_ms"] * 1e-3) / 1e9 if k["total_ms"] > 0 else 0.0
+    label = {"depthwise": "depthwise3x3_kernel (whole-height walk, 3-row window in registers)",
+             "head": "head_kernel (global average pool, classifier, argmax)"}[cls]
+    line = {"metric": "scheme_images_per_sec", "value": S * N * args.steps / dt, "unit": "scheme-images/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": wl["name"], "schemes": int(S), "images": int(N), "chunk": int(chunk),
+                       "scheme_layers": int(L), "base_pass_in_step": True, "lds_resident": bool(model.lds_resident),
+                       "lds_resident_blocks": int(model.lds_resident_blocks)},
+            "roofline": {"bound": "hbm", "kernel": label, "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": gbs / PEAK_HBM_GBS, "traffic": measured_traffic(wl["name"], cls),
+                         "launches": k["launches"],
+                         "avg_launch_ms": k["total_ms"] / max(k["launches"], 1),
+                         "algorithmic_gbytes_per_launch": k["bytes"] / max(k["launches"], 1) / 1e9},
+            "kernels": {n: {"launches": v["launches"], "ms_per_step": v["total_ms"] / args.steps,
+                            "gflop_per_step": v["flops"] / args.steps / 1e9, "gbyte_per_step": v["bytes"] / args.steps / 1e9}
+                        for n, v in prof.items()}}
+    model.close()
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +138,11 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="0..4; 2 = ResNet-20 greedy step (headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layerwise", action="store_true", help="force the layer-by-layer kernels")
+    ap.add_argument("--roofline-class", default="auto",
+                    choices=("auto", "conv_mfma", "depthwise", "head", "resnet_fused", "mbconv"),
+                    help="kernel class whose roofline is reported (auto: the one the step spends most time in)")
+    ap.add_argument("--stress", choices=("quantize",), help="time one kernel on a bandwidth-stress shape instead of a workload")
+    ap.add_argument("--stress-shape", default="8192x4608", help="cout x k of the quantizer stress matrix")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build scores schemes on ONE GPU; --gpus N with N > 1 is not supported "
@@ -75,6 +157,8 @@ def main():
         sys.exit("bench.py: no GPU visible; there is no CPU fallback")
     torch.cuda.set_device(0)
     aiq.load_library()
+    if args.stress == "quantize":
+        return stress_quantize(args, torch, aiq)
     wl = synth.make_workload(args.workload)
     S, L = wl["schemes"].shape
     N = wl["images"].shape[0]
@@ -110,7 +194,11 @@ def main():
     # LDS-resident inverted-residual block kernel when the model has such blocks, else the
     # layer-by-layer dense convolution
     dom = "resnet_fused" if prof["resnet_fused"]["launches"] else ("mbconv" if prof["mbconv"]["launches"] else "conv_mfma")
+    if args.roofline_class != "auto":
+        dom = args.roofline_class
     conv = prof[dom]
+    if dom in ("depthwise", "head"):
+        return print_hbm_line(args, wl, model, S, N, L, chunk, dt, agree, prof, dom)
     achieved = conv["flops"] / (conv["total_ms"] * 1e-3) / 1e12 if conv["total_ms"] > 0 else 0.0
     label = {"resnet_fused": "resnet_fused_kernel (whole network per (scheme, image), activations in LDS, fp32 MFMA)",
              "mbconv": "mbconv_kernel (1x1 expand, depthwise 3x3, 1x1 project per launch, hidden tensor in LDS, fp32 MFMA)",
@@ -118,7 +206,7 @@ def main():
     roofline = {"bound": "mfma", "kernel": label,
                 "achieved": achieved, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_MFMA_F32_TFLOPS,
-                "traffic": measured_traffic(wl["name"], model.lds_resident),
+                "traffic": measured_traffic(wl["name"], dom),
                 "launches": conv["launches"], "avg_launch_ms": conv["total_ms"] / max(conv["launches"], 1),
                 "algorithmic_gflop_per_launch": conv["flops"] / max(conv["launches"], 1) / 1e9,
                 "algorithmic_gbytes_per_launch": conv["bytes"] / max(conv["launches"], 1) / 1e9}
