@@ -15,6 +15,8 @@ FLAGS = [
     # packed-FP32 instruction selection off; IEEE-exact fp32 division for the quantizer
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-fast-math",
+    # the LDS-resident kernels are straight-line code: loops marked for unrolling are unrolled whatever their size
+    "-mllvm", "-pragma-unroll-threshold=1000000",
     "-Wall", "-Wno-unused-function",
 ]
 

@@ -42,7 +42,7 @@ __device__ __forceinline__ float act_hi(int act) { return act == 2 ? 6.0f : __bu
 // first weights of the next op while the current one finishes.
 __device__ constexpr int kOpSteps[9] = {0, 9, 9, 1, 18, 18, 2, 36, 0};
 __device__ constexpr int kOpCoutTiles[9] = {0, 1, 2, 2, 2, 4, 4, 4, 0};
-constexpr int kWeightRing = 4; // weight chunks in flight per wavefront
+constexpr int kWeightRing = 6; // weight chunks in flight per wavefront (two tap columns of a 3x3 layer)
 
 // One dense convolution, LDS -> LDS.  NW wavefronts; wavefront w owns output-channel tile
 // w % CT and MT pixel tiles.  The reduction is a straight line of STEPS = taps x CB steps;
@@ -165,6 +165,119 @@ __device__ __forceinline__ void fused_conv(const float *src, float *dst, const f
 #pragma unroll
         for (int i = 0; i < MT; ++i)
             *reinterpret_cast<floatx4 *>(dst + out_index(i, DST_PADDED)) = clamp4(acc[i] + bv, lo, hi);
+    }
+}
+
+// Stride-1 3x3 convolution with vertical operand reuse.  A wavefront owns output-channel tile
+// w % CT and a strip of MT vertically adjacent pixel tiles.  For one tap column kx and one
+// 16-channel block the strip's inputs are NR = RPT*(MT-1) + 3 window rows (RPT image rows per
+// pixel tile); the row a tile needs for tap row ky is the one its lower neighbour needs for
+// ky-1, so each 16-byte LDS read feeds up to three tiles (12 MFMAs) instead of one (4): 10 reads
+// instead of 24 per 96 MFMAs at 32x32.  Weights come one tap column at a time (three chunks:
+// ky = 0, 1, 2; bank layout [kx][channel block][ky]) through the same register ring as
+// fused_conv, including the hand-over of the next op's first chunks.
+template <int CIN, int COUT, int HIN, int NW>
+__device__ __forceinline__ void fused_conv3s1(const float *src, float *dst, const float *res, bool res_padded,
+                                              const float *__restrict__ wq, const float *__restrict__ bias, int act,
+                                              bool zero_ring, int tid, floatx4 (&wr)[kWeightRing],
+                                              const float *__restrict__ next_w, int next_last)
+{
+    constexpr int CB = CIN / 16, CT = COUT / 16, HO = HIN, PT = HO * HO / 16, STEPS = 9 * CB;
+    constexpr int WPC = NW / CT, MT = PT / WPC;
+    constexpr int RPT = HO >= 16 ? 1 : 16 / HO; // image rows per pixel tile
+    constexpr int TPR = HO >= 16 ? HO / 16 : 1; // pixel tiles per image row
+    constexpr int NR = RPT * (MT - 1) + 3;      // window rows of a strip
+    constexpr int NG = 3 * CB;                  // (tap column, channel block) groups of three weight chunks
+    constexpr int PIN = HIN + 2, PLANE = PIN * PIN * 4;
+    static_assert(NW % CT == 0 && PT % WPC == 0 && WPC % TPR == 0 && STEPS >= kWeightRing, "strips must tile the image");
+    asm volatile("" : "+v"(tid)); // keep the index arithmetic inside the op (see fused_conv)
+    const int lane = tid & 63, wave = tid >> 6, p = lane & 15, kq = lane >> 4;
+    const int ct = wave % CT, pg = wave / CT;
+    const int oy0 = (pg / TPR) * MT * RPT + (RPT > 1 ? p / HO : 0);
+    const int ox = (pg % TPR) * 16 + (RPT > 1 ? p % HO : p);
+    const int src_base = kq * PLANE + (oy0 * PIN + ox) * 4;
+
+    if (zero_ring) {
+        constexpr int RING = 4 * PIN - 4;
+        for (int i = tid; i < (COUT / 4) * RING; i += NW * 64) {
+            const int plane = i / RING, r = i - plane * RING;
+            int y, x;
+            if (r < PIN) { y = 0; x = r; }
+            else if (r < 2 * PIN) { y = PIN - 1; x = r - PIN; }
+            else { const int q = r - 2 * PIN; y = 1 + (q >> 1); x = (q & 1) ? PIN - 1 : 0; }
+            *reinterpret_cast<floatx4 *>(dst + plane * PLANE + (y * PIN + x) * 4) = floatx4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+    auto out_index = [&](int i, bool padded) {
+        const int oy = oy0 + i * RPT, plane = ct * 4 + kq;
+        return padded ? plane * PLANE + ((oy + 1) * PIN + ox + 1) * 4 : plane * (HO * HO * 4) + (oy * HO + ox) * 4;
+    };
+    const float *wbase = wq + ((size_t)ct * STEPS * 64 + lane) * 4;
+    const floatx4 bv = gload4(bias + ct * 16 + kq * 4);
+    const float lo = act_lo(act), hi = act_hi(act);
+
+    floatx4 acc[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // window rows are read two ahead of their use; q = g * NR + r runs over (group, row)
+    constexpr int NQ = NG * NR, DEPTH = 2;
+    auto row_addr = [&](int q) {
+        const int g = q / NR, r = q - g * NR;
+        const int kx = g / CB, cb = g - kx * CB;
+        return src + src_base + (kx + r * PIN) * 4 + cb * 4 * PLANE;
+    };
+    floatx4 xb[DEPTH + 1];
+#pragma unroll
+    for (int q = 0; q < DEPTH; ++q) xb[q] = *reinterpret_cast<const floatx4 *>(row_addr(q));
+    floatx4 rv[MT]; // residual values, fetched during the last group
+    floatx4 w0, w1, w2;
+
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        __builtin_amdgcn_sched_barrier(0);
+        const int g = q / NR, r = q - g * NR;
+        if (q + DEPTH < NQ) xb[(q + DEPTH) % (DEPTH + 1)] = *reinterpret_cast<const floatx4 *>(row_addr(q + DEPTH));
+        if (r == 0) {
+            // this group's three chunks leave the ring; their slots are refilled at once, with this
+            // op's chunks two groups on or, at the end, with the next op's first chunks
+            w0 = wr[(3 * g) % kWeightRing];
+            w1 = wr[(3 * g + 1) % kWeightRing];
+            w2 = wr[(3 * g + 2) % kWeightRing];
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                const int c = 3 * g + j, slot = c % kWeightRing;
+                wr[slot] = c + kWeightRing < STEPS ? gload4(wbase + (c + kWeightRing) * 256)
+                                                   : gload4(next_w + min(slot, next_last) * 256);
+            }
+            if (g == NG - 1 && res) {
+#pragma unroll
+                for (int i = 0; i < MT; ++i) rv[i] = *reinterpret_cast<const floatx4 *>(res + out_index(i, res_padded));
+            }
+        }
+        const floatx4 x = xb[q % (DEPTH + 1)];
+        // the (up to three) tiles this row feeds take turns, so that consecutive MFMAs never
+        // accumulate into the same registers
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky) {
+            const int d = r - ky;
+            if (d < 0 || d % RPT != 0 || d / RPT >= MT) continue;
+            const floatx4 w = ky == 0 ? w0 : (ky == 1 ? w1 : w2);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[d / RPT] = __builtin_amdgcn_mfma_f32_16x16x4f32(w[j], x[j], acc[d / RPT], 0, 0, 0);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    if (res) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+            *reinterpret_cast<floatx4 *>(dst + out_index(i, true)) = clamp4(acc[i] + bv + rv[i], lo, hi);
+    } else {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+            *reinterpret_cast<floatx4 *>(dst + out_index(i, true)) = clamp4(acc[i] + bv, lo, hi);
     }
 }
 
@@ -335,13 +448,13 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
             for (int j = 0; j < kWeightRing; ++j) wr[j] = gload4(next_w + min(j, next_last) * 256);
             fused_stem<NW>(src, dst, wq, bias, cur.act, tid);
             break;
-        case kOpC16: fused_conv<16, 16, 32, 1, 3, true, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpC16: fused_conv3s1<16, 16, 32, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
         case kOpT16_32: fused_conv<16, 32, 32, 2, 3, true, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
         case kOpS16_32: fused_conv<16, 32, 32, 2, 1, false, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
-        case kOpC32: fused_conv<32, 32, 16, 1, 3, true, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpC32: fused_conv3s1<32, 32, 16, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
         case kOpT32_64: fused_conv<32, 64, 16, 2, 3, true, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
         case kOpS32_64: fused_conv<32, 64, 16, 2, 1, false, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
-        case kOpC64: fused_conv<64, 64, 8, 1, 3, true, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpC64: fused_conv3s1<64, 64, 8, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
         case kOpHead: {
             // 64 channels x 8x8 pixels (padded 10x10 planes): pool, classifier, argmax
             float *scratch = dst;            // [NW][64] partial sums, then pooled[64], then z[classes]

@@ -516,6 +516,11 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
         Node &stem = m->nodes[0];
         stem.layout = kLayoutStem;
         stem.bank_elems = (size_t)((stem.d.cout + 15) / 16) * 9 * 64;
+        // stride-1 3x3 layers read their weights one tap column at a time
+        for (size_t o = 0; o < m->fused_ops.size(); ++o) {
+            const int t = m->fused_ops[o].type;
+            if (t == kOpC16 || t == kOpC32 || t == kOpC64) m->nodes[o].layout = kLayoutMfmaKx;
+        }
         for (const Node &nd : m->nodes) m->fused_flops_per_image += nd.flops_per_image;
     } else if (!(flags & AIQ_MODEL_LAYERWISE)) {
         m->mb_blocks = plan_mbconv(m->nodes);

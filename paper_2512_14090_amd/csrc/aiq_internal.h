@@ -29,7 +29,8 @@ enum WeightLayout : int32_t {
     kLayoutPlain = 0,   // [cout][k]
     kLayoutMfma = 1,    // dense convolution: [cout/16][tap][cin/16][64 lanes][4], zero padded
     kLayoutTapMajor = 2, // depthwise: [tap][channels]
-    kLayoutStem = 3      // dense convolution with cin <= 4: [cout/16][tap][64 lanes], lane = ci*16 + co
+    kLayoutStem = 3,     // dense convolution with cin <= 4: [cout/16][tap][64 lanes], lane = ci*16 + co
+    kLayoutMfmaKx = 4    // dense 3x3 convolution: [cout/16][kx][cin/16][ky][64 lanes][4] (column-major taps)
 };
 
 // One (weight matrix, bit-width) quantization job.

@@ -65,6 +65,10 @@ __device__ inline size_t quant_out_index(const QuantJob &j, int c, int i)
     if (j.layout == kLayoutStem) return (((size_t)(c >> 4) * j.taps + t) * 64) + ci * 16 + (c & 15);
     const int ct = c >> 4, co = c & 15;
     const int cb = ci >> 4, kq = (ci & 15) >> 2, jj = ci & 3;
+    if (j.layout == kLayoutMfmaKx) { // taps == 9: t = ky * 3 + kx
+        const int ky = t / 3, kx = t - ky * 3;
+        return (((((size_t)ct * 3 + kx) * j.cblocks + cb) * 3 + ky) * 64 + (kq * 16 + co)) * 4 + jj;
+    }
     return ((((size_t)ct * j.taps + t) * j.cblocks + cb) * 64 + (kq * 16 + co)) * 4 + jj;
 }
 
