@@ -28,10 +28,11 @@ __device__ __forceinline__ float gload1(const float *p) { return *(gfloat_ptr)(p
 // Activation as a clamp to [lo, hi]: none = (-inf, inf), ReLU = (0, inf), ReLU6 = (0, 6).
 __device__ __forceinline__ floatx4 clamp4(floatx4 v, float lo, float hi)
 {
-    v.x = fminf(fmaxf(v.x, lo), hi);
-    v.y = fminf(fmaxf(v.y, lo), hi);
-    v.z = fminf(fmaxf(v.z, lo), hi);
-    v.w = fminf(fmaxf(v.w, lo), hi);
+    // one v_med3_f32 per element: the median of (v, lo, hi) is v clamped to [lo, hi]
+    v.x = __builtin_amdgcn_fmed3f(v.x, lo, hi);
+    v.y = __builtin_amdgcn_fmed3f(v.y, lo, hi);
+    v.z = __builtin_amdgcn_fmed3f(v.z, lo, hi);
+    v.w = __builtin_amdgcn_fmed3f(v.w, lo, hi);
     return v;
 }
 __device__ __forceinline__ float act_lo(int act) { return act >= 1 ? 0.0f : -__builtin_inff(); }
@@ -53,7 +54,7 @@ constexpr int kWeightRing = 6; // weight chunks in flight per wavefront (two tap
 // next op (next_w; next_last = index of its last chunk), so no wavefront waits on L2 right after a barrier.
 template <int CIN, int COUT, int HIN, int STRIDE, int KS, bool DST_PADDED, int NW>
 __device__ __forceinline__ void fused_conv(const float *src, float *dst, const float *res, bool res_padded,
-                                           const float *__restrict__ wq, const float *__restrict__ bias, int act,
+                                           const float *__restrict__ wq, const floatx4 bv, int act,
                                            bool zero_ring, int tid, floatx4 (&wr)[kWeightRing],
                                            const float *__restrict__ next_w, int next_last)
 {
@@ -100,12 +101,11 @@ __device__ __forceinline__ void fused_conv(const float *src, float *dst, const f
                       : plane * (HO * HO * 4) + (oy * HO + ox) * 4;
     };
     const float *wbase = wq + ((size_t)ct * STEPS * 64 + lane) * 4;
-    const floatx4 bv = gload4(bias + ct * 16 + kq * 4);
     const float lo = act_lo(act), hi = act_hi(act);
 
-    floatx4 acc[MT];
+    floatx4 acc[MT]; // start from the bias: nothing to add in the epilogue
 #pragma unroll
-    for (int i = 0; i < MT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < MT; ++i) acc[i] = bv;
 
     floatx4 xb[2][MT];
 #pragma unroll
@@ -160,11 +160,11 @@ __device__ __forceinline__ void fused_conv(const float *src, float *dst, const f
     if (res) {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
-            *reinterpret_cast<floatx4 *>(dst + out_index(i, DST_PADDED)) = clamp4(acc[i] + bv + xb[RB][i], lo, hi);
+            *reinterpret_cast<floatx4 *>(dst + out_index(i, DST_PADDED)) = clamp4(acc[i] + xb[RB][i], lo, hi);
     } else {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
-            *reinterpret_cast<floatx4 *>(dst + out_index(i, DST_PADDED)) = clamp4(acc[i] + bv, lo, hi);
+            *reinterpret_cast<floatx4 *>(dst + out_index(i, DST_PADDED)) = clamp4(acc[i], lo, hi);
     }
 }
 
@@ -178,7 +178,7 @@ __device__ __forceinline__ void fused_conv(const float *src, float *dst, const f
 // fused_conv, including the hand-over of the next op's first chunks.
 template <int CIN, int COUT, int HIN, int NW>
 __device__ __forceinline__ void fused_conv3s1(const float *src, float *dst, const float *res, bool res_padded,
-                                              const float *__restrict__ wq, const float *__restrict__ bias, int act,
+                                              const float *__restrict__ wq, const floatx4 bv, int act,
                                               bool zero_ring, int tid, floatx4 (&wr)[kWeightRing],
                                               const float *__restrict__ next_w, int next_last)
 {
@@ -213,12 +213,11 @@ __device__ __forceinline__ void fused_conv3s1(const float *src, float *dst, cons
         return padded ? plane * PLANE + ((oy + 1) * PIN + ox + 1) * 4 : plane * (HO * HO * 4) + (oy * HO + ox) * 4;
     };
     const float *wbase = wq + ((size_t)ct * STEPS * 64 + lane) * 4;
-    const floatx4 bv = gload4(bias + ct * 16 + kq * 4);
     const float lo = act_lo(act), hi = act_hi(act);
 
-    floatx4 acc[MT];
+    floatx4 acc[MT]; // start from the bias: nothing to add in the epilogue
 #pragma unroll
-    for (int i = 0; i < MT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < MT; ++i) acc[i] = bv;
 
     // window rows are read two ahead of their use; q = g * NR + r runs over (group, row)
     constexpr int NQ = NG * NR, DEPTH = 2;
@@ -273,11 +272,11 @@ __device__ __forceinline__ void fused_conv3s1(const float *src, float *dst, cons
     if (res) {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
-            *reinterpret_cast<floatx4 *>(dst + out_index(i, true)) = clamp4(acc[i] + bv + rv[i], lo, hi);
+            *reinterpret_cast<floatx4 *>(dst + out_index(i, true)) = clamp4(acc[i] + rv[i], lo, hi);
     } else {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
-            *reinterpret_cast<floatx4 *>(dst + out_index(i, true)) = clamp4(acc[i] + bv, lo, hi);
+            *reinterpret_cast<floatx4 *>(dst + out_index(i, true)) = clamp4(acc[i], lo, hi);
     }
 }
 
@@ -421,6 +420,9 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
 #pragma unroll
     for (int j = 0; j < kWeightRing; ++j) wr[j] = floatx4{0.f, 0.f, 0.f, 0.f};
     const int lane = tid & 63, wave = tid >> 6;
+    // bias of the current dense op for this lane's four output channels; like the first weight
+    // chunks it is fetched while the previous op runs (the stem reads its own)
+    floatx4 bcur = floatx4{0.f, 0.f, 0.f, 0.f};
 
     for (int o = 0; o < a.n_ops; ++o) {
         const OpRT nxt = uniform_op(nxt_raw);
@@ -434,27 +436,30 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
         // first weight chunks of the next dense op, fetched while this op runs; when there is
         // none the prefetch harmlessly re-reads chunk 0 of this op's own weights
         const float *next_w = wq + lane * 4;
+        const float *next_b = bias;
         int next_last = 0;
         if (o + 1 < a.n_ops && nxt.shape != 0) {
             // the next op's shape comes with its table row: no dependent constant-memory reads here
             const int ns = nxt.shape >> 8;
             const int nct = wave & (nxt.shape & 255);
             next_w = op_ptr(nxt.w_lo, nxt.w_hi) + ((size_t)nct * ns * 64 + lane) * 4;
+            next_b = op_ptr(nxt.b_lo, nxt.b_hi) + nct * 16 + (lane >> 4) * 4;
             next_last = ns - 1;
         }
+        const floatx4 bnxt = gload4(next_b); // every bias array holds at least four values
         switch (cur.type) {
         case kOpStem:
 #pragma unroll
             for (int j = 0; j < kWeightRing; ++j) wr[j] = gload4(next_w + min(j, next_last) * 256);
             fused_stem<NW>(src, dst, wq, bias, cur.act, tid);
             break;
-        case kOpC16: fused_conv3s1<16, 16, 32, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
-        case kOpT16_32: fused_conv<16, 32, 32, 2, 3, true, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
-        case kOpS16_32: fused_conv<16, 32, 32, 2, 1, false, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
-        case kOpC32: fused_conv3s1<32, 32, 16, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
-        case kOpT32_64: fused_conv<32, 64, 16, 2, 3, true, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
-        case kOpS32_64: fused_conv<32, 64, 16, 2, 1, false, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
-        case kOpC64: fused_conv3s1<64, 64, 8, NW>(src, dst, res, rp, wq, bias, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpC16: fused_conv3s1<16, 16, 32, NW>(src, dst, res, rp, wq, bcur, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpT16_32: fused_conv<16, 32, 32, 2, 3, true, NW>(src, dst, res, rp, wq, bcur, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpS16_32: fused_conv<16, 32, 32, 2, 1, false, NW>(src, dst, res, rp, wq, bcur, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpC32: fused_conv3s1<32, 32, 16, NW>(src, dst, res, rp, wq, bcur, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpT32_64: fused_conv<32, 64, 16, 2, 3, true, NW>(src, dst, res, rp, wq, bcur, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpS32_64: fused_conv<32, 64, 16, 2, 1, false, NW>(src, dst, res, rp, wq, bcur, cur.act, zr, tid, wr, next_w, next_last); break;
+        case kOpC64: fused_conv3s1<64, 64, 8, NW>(src, dst, res, rp, wq, bcur, cur.act, zr, tid, wr, next_w, next_last); break;
         case kOpHead: {
             // 64 channels x 8x8 pixels (padded 10x10 planes): pool, classifier, argmax
             float *scratch = dst;            // [NW][64] partial sums, then pooled[64], then z[classes]
@@ -494,6 +499,7 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
         }
         __syncthreads();
         cur = nxt;
+        bcur = bnxt;
     }
 }
 
