@@ -16,6 +16,8 @@
 //            hidden channels 16*hb + 4*kq .. +3 (nine 16-byte LDS reads, 36 FMAs) - exactly
 //            the B operand of the project MFMAs for that 16-channel block - and accumulates
 //            into the block output tile it owns.  The depthwise output never leaves registers.
+//            A wavefront's tiles are vertically adjacent, so a window row read for one tile
+//            also serves its neighbours (3 * (MT + 2) reads for MT tiles at stride 1).
 // E is double buffered: chunk c+1 is expanded in the same barrier interval in which chunk c
 // is consumed.  With X in registers E alone occupies LDS and two workgroups share a compute
 // unit, so that one's barriers, prologue and epilogue are covered by the other's MFMAs.
@@ -85,11 +87,14 @@ struct MbCfg {
     static constexpr int WPP = PTO >= NW ? 1 : NW / PTO;
     static constexpr int CTW = CT / WPP;
     static constexpr int BANDS = HO / R;
+    static constexpr int TPR = WO >= 16 ? WO / 16 : 1;   // output pixel tiles per image row
+    static constexpr int NRW = (MT - 1) * STRIDE + 3;    // depthwise window rows of a strip of MT tiles
     static_assert(CIN % 4 == 0 && HID % HC == 0 && HC % 16 == 0 && COUT % 4 == 0, "channel counts");
     static_assert(HO % R == 0 && (G == 1 || WHOLE), "bands tile the image; several images only as whole images");
     static_assert((G * XROWS * W) % 16 == 0 && (PTE >= NW || (NW % PTE == 0 && HT % HS == 0)), "expand tiles");
     static_assert((G * R * WO) % 16 == 0 && (PTO >= NW ? PTO % NW == 0 : NW % PTO == 0), "pixel tiles per wavefront");
     static_assert(CT % WPP == 0, "output-channel tiles per wavefront");
+    static_assert(MT == 1 || (WO >= 16 && NW % TPR == 0 && G == 1), "strips of tiles need whole 16-pixel row segments");
     static_assert((W & (W - 1)) == 0 && ((R * WO) & (R * WO - 1)) == 0, "powers of two");
     static_assert(!RES || (CIN == COUT && STRIDE == 1), "residual needs matching shapes");
     static_assert(LDS_BYTES * WGS <= 160 * 1024, "LDS budget");
@@ -193,7 +198,9 @@ void mbconv_kernel(MbArgs a)
     int e_base[C::MT], o_g[C::MT], o_y[C::MT], o_x[C::MT];
 #pragma unroll
     for (int m = 0; m < C::MT; ++m) {
-        const int t = C::WPP > 1 ? wave / C::WPP : wave * C::MT + m;
+        // a wavefront's MT tiles are vertically adjacent (a strip TPR-th of the width wide), so
+        // that the depthwise window rows of one tile are shared with the tiles above and below
+        const int t = C::WPP > 1 ? wave / C::WPP : ((wave / C::TPR) * C::MT + m) * C::TPR + wave % C::TPR;
         const int o = t * 16 + p;
         const int g = o / (C::R * C::WO), rem = o % (C::R * C::WO);
         const int oy = rem / C::WO, ox = rem % C::WO;
@@ -277,21 +284,32 @@ void mbconv_kernel(MbArgs a)
             w.wp[i] = mb_gload4(w_p + (((size_t)(ct0 + i) * C::HB + hb) * 64 + lane) * 4);
     };
     auto dw_project = [&](int sb, int eb, const DwW &w) {
-        const float *Eb = E + eb * C::E_FLOATS + sb * 4 * C::EPL;
+        const float *Eb = E + eb * C::E_FLOATS + sb * 4 * C::EPL + e_base[0];
+        // depthwise: window row r of tap column kx serves tap row ky of tile (r - ky) / STRIDE, so a
+        // strip of MT tiles needs 3 * NRW reads instead of 9 * MT
+        floatx4 d[C::MT];
+#pragma unroll
+        for (int m = 0; m < C::MT; ++m) d[m] = w.bd;
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx)
+#pragma unroll
+            for (int r = 0; r < C::NRW; ++r) {
+                const floatx4 v = *reinterpret_cast<const floatx4 *>(Eb + (r * C::EW + kx) * 4);
+#pragma unroll
+                for (int ky = 0; ky < 3; ++ky) {
+                    const int dd = r - ky;
+                    if (dd < 0 || dd % C::STRIDE != 0 || dd / C::STRIDE >= C::MT) continue;
+                    d[dd / C::STRIDE] += v * w.wd[ky * 3 + kx];
+                }
+            }
 #pragma unroll
         for (int m = 0; m < C::MT; ++m) {
-            floatx4 d = w.bd;
-#pragma unroll
-            for (int t = 0; t < 9; ++t) {
-                const floatx4 v = *reinterpret_cast<const floatx4 *>(Eb + e_base[m] + ((t / 3) * C::EW + (t % 3)) * 4);
-                d += v * w.wd[t];
-            }
-            d = mb_clamp4(d, lo_d, hi_d);
+            d[m] = mb_clamp4(d[m], lo_d, hi_d);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int i = 0; i < C::CTW; ++i)
-                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w.wp[i][j], d[j], acc[m][i], 0, 0, 0);
+                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w.wp[i][j], d[m][j], acc[m][i], 0, 0, 0);
         }
     };
     // consumes chunk c; w0 arrives holding the weights of its first hidden block
@@ -371,9 +389,9 @@ namespace {
 #ifndef AIQ_MB_TABLE
 //                CIN  HID  COUT  H  S  RES    R  G  HC NW XREG WGS EPRE
 typedef MbCfg<16, 96, 24, 32, 1, false, 8, 1, 16, 4, true, 3, true> Mb0;
-typedef MbCfg<24, 144, 24, 32, 1, true, 8, 1, 16, 4, true, 3, false> Mb1;
-typedef MbCfg<24, 144, 32, 32, 1, false, 8, 1, 16, 4, true, 3, false> Mb2;
-typedef MbCfg<32, 192, 32, 32, 1, true, 8, 1, 16, 4, true, 3, false> Mb3;
+typedef MbCfg<24, 144, 24, 32, 1, true, 8, 1, 16, 4, true, 2, false> Mb1;
+typedef MbCfg<24, 144, 32, 32, 1, false, 8, 1, 16, 4, true, 2, false> Mb2;
+typedef MbCfg<32, 192, 32, 32, 1, true, 8, 1, 16, 4, true, 2, false> Mb3;
 typedef MbCfg<32, 192, 64, 32, 2, false, 8, 1, 16, 4, true, 2, true> Mb4;
 typedef MbCfg<64, 384, 64, 16, 1, true, 16, 1, 32, 8, false, 1, false> Mb5;
 typedef MbCfg<64, 384, 96, 16, 1, false, 16, 1, 32, 8, false, 1, false> Mb6;
