@@ -286,40 +286,38 @@ template <int NW>
 __device__ __forceinline__ void fused_stem(const float *src, float *dst, const float *__restrict__ wq,
                                            const float *__restrict__ bias, int act, int tid)
 {
-    constexpr int H = 32, PIN = 34, PT = H * H / 16, MT = PT / NW, DST_PLANE = PIN * PIN * 4, GROUP = 4;
-    static_assert(MT % GROUP == 0, "pixel tiles per wavefront must be a multiple of the group");
+    // A wavefront owns a strip of MT vertically adjacent pixel tiles (half an image row wide), so a
+    // window row read for tap column kx serves tap row ky of tile r - ky: 3 * (MT + 2) four-byte
+    // LDS reads instead of 9 * MT.
+    constexpr int H = 32, PIN = 34, PT = H * H / 16, MT = PT / NW, PLANE = PIN * PIN * 4, NR = MT + 2;
+    static_assert(NW % 2 == 0 && PT % NW == 0, "strips must tile the image");
     asm volatile("" : "+v"(tid)); // keep the index arithmetic inside the op (see fused_conv)
     const int lane = tid & 63, wave = tid >> 6, p = lane & 15, kq = lane >> 4;
+    const int oy0 = (wave >> 1) * MT, ox = (wave & 1) * 16 + p;
+    const float *base = src + (oy0 * PIN + ox) * 4 + kq;
     float w[9];
 #pragma unroll
     for (int t = 0; t < 9; ++t) w[t] = gload1(wq + t * 64 + lane);
     const floatx4 bv = gload4(bias + kq * 4);
-#pragma unroll 1
-    for (int g = 0; g < MT; g += GROUP) {
-        float x[GROUP][9];
+    float x[3][NR];
 #pragma unroll
-        for (int i = 0; i < GROUP; ++i) {
-            const int P = (wave + (g + i) * NW) * 16 + p;
-            const int oy = P / H, ox = P % H;
+    for (int kx = 0; kx < 3; ++kx)
 #pragma unroll
-            for (int t = 0; t < 9; ++t) x[i][t] = src[((oy + t / 3) * PIN + ox + t % 3) * 4 + kq];
-        }
-        floatx4 acc[GROUP];
+        for (int r = 0; r < NR; ++r) x[kx][r] = base[(r * PIN + kx) * 4];
+    floatx4 acc[MT];
 #pragma unroll
-        for (int i = 0; i < GROUP; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < MT; ++i) acc[i] = bv;
 #pragma unroll
-        for (int t = 0; t < 9; ++t)
+    for (int kx = 0; kx < 3; ++kx)
 #pragma unroll
-            for (int i = 0; i < GROUP; ++i)
-                acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w[t], x[i][t], acc[i], 0, 0, 0);
+        for (int ky = 0; ky < 3; ++ky)
 #pragma unroll
-        for (int i = 0; i < GROUP; ++i) {
-            const int P = (wave + (g + i) * NW) * 16 + p;
-            const int oy = P / H, ox = P % H;
-            *reinterpret_cast<floatx4 *>(dst + kq * DST_PLANE + ((oy + 1) * PIN + ox + 1) * 4) =
-                clamp4(acc[i] + bv, act_lo(act), act_hi(act));
-        }
-    }
+            for (int i = 0; i < MT; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w[ky * 3 + kx], x[kx][i + ky], acc[i], 0, 0, 0);
+    const float lo = act_lo(act), hi = act_hi(act);
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+        *reinterpret_cast<floatx4 *>(dst + kq * PLANE + ((oy0 + i + 1) * PIN + ox + 1) * 4) = clamp4(acc[i], lo, hi);
 }
 
 __device__ inline float fused_wave_sum(float v)
@@ -398,11 +396,28 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
         r.shape = kOpSteps[op.type] > 0 ? (kOpSteps[op.type] << 8) | (kOpCoutTiles[op.type] - 1) : 0;
         s_ops[tid] = r;
     }
-    // clear both regions (borders must be zero), then store the image as (r, g, b, 0) pixels
-    for (int i = tid; i < kFusedLdsBytes / 16; i += NW * 64)
-        reinterpret_cast<floatx4 *>(lds)[i] = floatx4{0.f, 0.f, 0.f, 0.f};
     __syncthreads();
     OpRT cur = uniform_op(s_ops[0]);
+    // What has to be zero before the first read: the image plane (border and fourth component)
+    // and the borders of the 34 x 34 planes the first stage writes - four in the stem's
+    // destination region, the other three of the image's region.  Interiors are always written
+    // before they are read; later layouts clear their own borders (zero_ring).
+    {
+        constexpr int PIN = 34, PLANE = PIN * PIN * 4, RING = 4 * PIN - 4;
+        const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};
+        floatx4 *img4 = reinterpret_cast<floatx4 *>(lds + cur.src_off);
+        for (int i = tid; i < PIN * PIN; i += NW * 64) img4[i] = zero;
+        for (int i = tid; i < 7 * RING; i += NW * 64) {
+            const int q = i / RING, r = i - q * RING;
+            float *plane = q < 4 ? lds + cur.dst_off + q * PLANE : lds + cur.src_off + (q - 3) * PLANE;
+            int y, x;
+            if (r < PIN) { y = 0; x = r; }
+            else if (r < 2 * PIN) { y = PIN - 1; x = r - PIN; }
+            else { const int e = r - 2 * PIN; y = 1 + (e >> 1); x = (e & 1) ? PIN - 1 : 0; }
+            *reinterpret_cast<floatx4 *>(plane + (y * PIN + x) * 4) = zero;
+        }
+    }
+    __syncthreads();
     {
         float *plane = lds + cur.src_off;
 #pragma unroll
@@ -461,7 +476,17 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
         case kOpS32_64: fused_conv<32, 64, 16, 2, 1, false, NW>(src, dst, res, rp, wq, bcur, cur.act, zr, tid, wr, next_w, next_last); break;
         case kOpC64: fused_conv3s1<64, 64, 8, NW>(src, dst, res, rp, wq, bcur, cur.act, zr, tid, wr, next_w, next_last); break;
         case kOpHead: {
-            // 64 channels x 8x8 pixels (padded 10x10 planes): pool, classifier, argmax
+            // 64 channels x 8x8 pixels (padded 10x10 planes): pool, classifier, argmax.  The
+            // classifier rows of this wavefront are requested first, so that they arrive while
+            // the pooling runs.
+            constexpr int JW = (16 + NW - 1) / NW; // classes per wavefront (at most 16 classes per round)
+            float wrow[JW], brow[JW];
+#pragma unroll
+            for (int q = 0; q < JW; ++q) {
+                const int j = min(wave + q * NW, cur.classes - 1);
+                wrow[q] = gload1(wq + j * 64 + lane);
+                brow[q] = gload1(bias + j);
+            }
             float *scratch = dst;            // [NW][64] partial sums, then pooled[64], then z[classes]
             const int c = tid & 63, part = tid >> 6;
             float acc = 0.0f;
@@ -479,8 +504,15 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
             }
             __syncthreads();
             float *z = pooled + 64;
-            for (int j = wave; j < cur.classes; j += NW) {
-                float t = fused_wave_sum(pooled[lane] * gload1(wq + j * 64 + lane));
+            const float pl = pooled[lane];
+#pragma unroll
+            for (int q = 0; q < JW; ++q) {
+                const int j = wave + q * NW;
+                const float t = fused_wave_sum(pl * wrow[q]);
+                if (lane == 0 && j < cur.classes) z[j] = t + brow[q];
+            }
+            for (int j = JW * NW + wave; j < cur.classes; j += NW) { // more than 16 classes: the rest, unprefetched
+                const float t = fused_wave_sum(pl * gload1(wq + j * 64 + lane));
                 if (lane == 0) z[j] = t + gload1(bias + j);
             }
             __syncthreads();
