@@ -190,7 +190,8 @@ __device__ __forceinline__ void fused_conv3s1(const float *src, float *dst, cons
     constexpr int NG = 3 * CB;                  // (tap column, channel block) groups of three weight chunks
     constexpr int PIN = HIN + 2, PLANE = PIN * PIN * 4;
     static_assert(NW % CT == 0 && PT % WPC == 0 && WPC % TPR == 0 && STEPS >= kWeightRing, "strips must tile the image");
-    asm volatile("" : "+v"(tid)); // keep the index arithmetic inside the op (see fused_conv)
+    // (no barrier against hoisting here: the three strip geometries' lane offsets are computed
+    // once per kernel and kept in registers, which shortens every op's prologue)
     const int lane = tid & 63, wave = tid >> 6, p = lane & 15, kq = lane >> 4;
     const int ct = wave % CT, pg = wave / CT;
     const int oy0 = (pg / TPR) * MT * RPT + (RPT > 1 ? p / HO : 0);
