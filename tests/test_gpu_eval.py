@@ -222,6 +222,50 @@ def test_greedy_step_full_size_sampled(env, layerwise):
     print("sampled max logit rel err %.3e; agree %s" % (err, gpu["agree"]), flush=True)
 
 
+def test_resnet20_workload1_full_size_sampled(env):
+    """Workload 1 at full size (1 scheme over {32,16,8,4} x 1024 images, one chunk); oracle on a sample."""
+    wl = env["synth"].make_workload(1)
+    print("workload 1 full size", flush=True)
+    gpu = _run_gpu(env, wl, wl["schemes"], chunk=1024)
+    idx = np.array([0, 1, 2, 511, 512, 1000, 1022, 1023])
+    ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"][idx], wl["schemes"])
+    assert logits_rel_error(gpu["logits"][:, idx], ref["logits"]) <= 1e-3
+    assert not ((gpu["top1"][:, idx] != ref["top1"]) & ~near_tied(ref["logits"])).any()
+    assert not ((gpu["top1_base"][idx] != ref["top1_base"]) & ~near_tied(ref["logits_base"])).any()
+    np.testing.assert_array_equal(gpu["agree"], (gpu["top1"] == gpu["top1_base"][None]).sum(axis=1))
+
+
+def test_cd_sweep_full_size_sampled(env):
+    """Workload 4 in the benchmark's launch configuration: 64 schemes over all six widths x 10 000
+    images in chunks of 1024 (9 full chunks and one of 784), agreement counts only - plus one call
+    with logits for the oracle to check on images around every chunk boundary."""
+    torch, aiq = env["torch"], env["aiq"]
+    wl = env["synth"].make_workload(4)
+    print("workload 4 full size", flush=True)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    img = torch.from_numpy(wl["images"]).cuda()
+    r = m.eval_schemes(img, wl["schemes"], chunk=1024)
+    torch.cuda.synchronize()
+    agree = r["agree"].cpu().numpy()
+    assert r["logits"] is None and agree.shape == (64,)
+    full = m.eval_schemes(img, wl["schemes"], chunk=1024, want_logits=True, want_top1=True, top1_base=r["top1_base"])
+    torch.cuda.synchronize()
+    top1, top1_base = full["top1"].cpu().numpy(), full["top1_base"].cpu().numpy()
+    np.testing.assert_array_equal(agree, (top1 == top1_base[None]).sum(axis=1))
+    np.testing.assert_array_equal(agree, full["agree"].cpu().numpy())
+    idx = np.array([0, 1023, 1024, 5119, 5120, 9215, 9216, 9999])
+    ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"][idx], wl["schemes"])
+    logits = full["logits"][:, torch.from_numpy(idx).cuda()].cpu().numpy()
+    assert logits_rel_error(logits, ref["logits"]) <= 1e-3
+    assert not ((top1[:, idx] != ref["top1"]) & ~near_tied(ref["logits"])).any()
+    assert not ((top1_base[idx] != ref["top1_base"]) & ~near_tied(ref["logits_base"])).any()
+    # schemes made only of 32- and 16-bit layers barely change a prediction; 2-bit layers change many
+    sch = wl["schemes"]
+    assert agree.max() <= 10000 and agree.min() >= 0
+    m.close()
+    print("agree min/max", agree.min(), agree.max(), flush=True)
+
+
 def test_cd_sweep_chunk_remainder_sampled(env):
     """Workload 4's chunking (chunks of 1024 with a ragged last chunk) on 2100 images and 6 of its
     schemes; the oracle checks images on both sides of every chunk boundary and in the tail."""
