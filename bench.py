@@ -135,7 +135,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", type=int, default=2, help="0..4; 2 = ResNet-20 greedy step (headline)")
+    ap.add_argument("--workload", type=int, default=2, help="0..4 (benchmark configurations; 2 = ResNet-20 greedy step, the headline), 5 / 6 = variant models")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layerwise", action="store_true", help="force the layer-by-layer kernels")
     ap.add_argument("--roofline-class", default="auto",

@@ -208,6 +208,21 @@ aiq_status aiq_search_coordinate_descent(aiq_model *m, const aiq_layer_desc *lay
                                          int32_t trace_cap, int32_t *n_trace);
 
 /*
+ * Per-layer sensitivity (paper: Analysis of Initial Hypotheses, Table 1 - the accuracy change when a
+ * single layer is quantized to 8 or 4 bits and every other layer stays FP32).  Scores the
+ * L * n_bits single-layer schemes in scheme-batched calls and returns their agreement counts:
+ * agree_out[i * n_bits + k] = #{n : top-1 with only layer i at bits[k] == FP32 top-1}; the
+ * sensitivity in percentage points is 100 * (1 - agree / N).
+ * bits: host uint8[n_bits], each in {16,8,6,4,2}, 1 <= n_bits <= 5.  images: device fp32 [N][hin][win][cin].
+ * workspace: device, >= aiq_sensitivity_workspace_bytes, 256-byte aligned.  agree_out: HOST int32 [L][n_bits].
+ * Synchronous.  Errors: INVALID_ARG, UNSUPPORTED_BITS, WORKSPACE_TOO_SMALL, DEVICE_ERROR.
+ */
+aiq_status aiq_sensitivity_workspace_bytes(const aiq_model *m, int32_t N, int32_t chunk, int32_t n_bits, size_t *bytes);
+aiq_status aiq_layer_sensitivity(aiq_model *m, const float *images, int32_t N, int32_t chunk, const uint8_t *bits,
+                                 int32_t n_bits, void *workspace, size_t workspace_bytes, void *hip_stream,
+                                 int32_t *agree_out);
+
+/*
  * Per-kernel timing for roofline reports.  While enabled, aiq_eval_schemes brackets
  * every launch with HIP events on the launch stream.  aiq_profile_read waits for the
  * recorded events, then returns for kernel class cls the number of launches, their

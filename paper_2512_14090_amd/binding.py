@@ -14,7 +14,7 @@ EXPORTED_SYMBOLS = (
     "aiq_status_str", "aiq_last_hip_error", "aiq_layer_ai", "aiq_quantize_weights", "aiq_model_create",
     "aiq_model_create_ex", "aiq_model_is_lds_resident", "aiq_model_lds_resident_blocks", "aiq_model_destroy", "aiq_model_scheme_layers", "aiq_model_classes", "aiq_eval_workspace_bytes",
     "aiq_eval_schemes", "aiq_profile_enable", "aiq_profile_read", "aiq_search_workspace_bytes",
-    "aiq_search_greedy", "aiq_search_coordinate_descent",
+    "aiq_search_greedy", "aiq_search_coordinate_descent", "aiq_sensitivity_workspace_bytes", "aiq_layer_sensitivity",
 )
 K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV = range(7)
 MODEL_LAYERWISE = 1
@@ -78,6 +78,9 @@ def load_library():
         fn.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
                        C.POINTER(_SearchParams), C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p,
                        C.POINTER(_SearchStep), C.c_int32, C.POINTER(C.c_int32)]
+    lib.aiq_sensitivity_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+    lib.aiq_layer_sensitivity.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
+                                          C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     for name in EXPORTED_SYMBOLS:
         getattr(lib, name)
     _lib = lib
@@ -256,6 +259,21 @@ class Model:
         steps = [dict(layer=t.layer, bits=t.bits, agree=t.agree, sweep=t.sweep, loss=t.loss, ai=t.ai)
                  for t in trace[:min(n.value, cap)]]
         return scheme, steps
+
+    def layer_sensitivity(self, images, bits=(8, 4), chunk=1024, stream=None):
+        """aiq_layer_sensitivity.  Returns int32 [L][len(bits)] agreement counts of the single-layer schemes."""
+        b = np.ascontiguousarray(bits, dtype=np.uint8)
+        N = images.shape[0]
+        chunk = max(1, min(int(chunk), max(N, 1)))
+        need = C.c_size_t(0)
+        _check(self._lib.aiq_sensitivity_workspace_bytes(self._h, N, chunk, len(b), C.byref(need)),
+               "aiq_sensitivity_workspace_bytes")
+        ws = self._get_workspace(need.value, images.device)
+        out = np.zeros((self.L, len(b)), dtype=np.int32)
+        _check(self._lib.aiq_layer_sensitivity(self._h, images.data_ptr(), N, chunk, b.ctypes.data, len(b),
+                                               ws.data_ptr(), ws.numel(), _stream_ptr(stream), out.ctypes.data),
+               "aiq_layer_sensitivity")
+        return out
 
     def profile_enable(self, on=True):
         _check(self._lib.aiq_profile_enable(self._h, 1 if on else 0), "aiq_profile_enable")

@@ -1138,6 +1138,40 @@ aiq_status aiq_search_coordinate_descent(aiq_model *m, const aiq_layer_desc *lay
     return err;
 }
 
+aiq_status aiq_sensitivity_workspace_bytes(const aiq_model *m, int32_t N, int32_t chunk, int32_t n_bits, size_t *bytes)
+{
+    if (!m || !bytes || N < 1 || chunk < 1 || n_bits < 1 || n_bits > 5) return AIQ_INVALID_ARG;
+    *bytes = search_layout(m, N, chunk, n_bits + 1).total; // as a search over {32} + bits: L * n_bits schemes at most
+    return AIQ_OK;
+}
+
+aiq_status aiq_layer_sensitivity(aiq_model *m, const float *images, int32_t N, int32_t chunk, const uint8_t *bits,
+                                 int32_t n_bits, void *workspace, size_t workspace_bytes, void *hip_stream,
+                                 int32_t *agree_out)
+{
+    if (!m || !images || !bits || !workspace || !agree_out || N < 1 || chunk < 1 || n_bits < 1 || n_bits > 5)
+        return AIQ_INVALID_ARG;
+    for (int k = 0; k < n_bits; ++k)
+        if (!bits_supported(bits[k]) || bits[k] == 32) return AIQ_UNSUPPORTED_BITS;
+    const SearchLayout lay = search_layout(m, N, chunk, n_bits + 1);
+    if (workspace_bytes < lay.total) return AIQ_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return AIQ_INVALID_ARG;
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t st = (hipStream_t)hip_stream;
+    int32_t *top1_base = reinterpret_cast<int32_t *>(ws + lay.top1_off);
+    int32_t *agree_dev = reinterpret_cast<int32_t *>(ws + lay.agree_off);
+    const int L = m->L, S = L * n_bits;
+    std::vector<uint8_t> schemes((size_t)S * L, 32);
+    for (int i = 0; i < L; ++i)
+        for (int k = 0; k < n_bits; ++k) schemes[((size_t)i * n_bits + k) * L + i] = bits[k];
+    aiq_status rc = aiq_eval_schemes(m, images, N, schemes.data(), S, chunk, top1_base, 0, nullptr, nullptr, agree_dev,
+                                     ws + lay.eval_off, workspace_bytes - lay.eval_off, st);
+    if (rc != AIQ_OK) return rc;
+    AIQ_HIP(hipMemcpyAsync(agree_out, agree_dev, sizeof(int32_t) * S, hipMemcpyDeviceToHost, st));
+    AIQ_HIP(hipStreamSynchronize(st));
+    return AIQ_OK;
+}
+
 aiq_status aiq_profile_enable(aiq_model *m, int32_t on)
 {
     if (!m) return AIQ_INVALID_ARG;

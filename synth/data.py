@@ -74,6 +74,10 @@ def make_workload(index, n_images=None, n_schemes=None):
     2: ResNet-20 greedy step, 1024 images, 40 single-layer schemes (layer i at 8 or 4)
     3: MobileNetV2-32, 512 images, 16 schemes with 10 random layers at 4 bits
     4: ResNet-20 coordinate-descent sweep, 10000 images, 64 schemes from all six widths
+    5: PlainConvNet20 sensitivity sweep, 256 images, 42 single-layer schemes (layer i at 8 or 4)
+    6: HeavyEarlyResNet20 sensitivity sweep, 256 images, 40 single-layer schemes
+  (5 and 6 are the paper's two variant models with the candidate batch of its per-layer
+  sensitivity table; they are not among the five benchmark configurations.)
     ``n_images`` / ``n_schemes`` shrink a workload for tests; the draw order is
     unchanged so weights do not depend on them.
     """
@@ -87,8 +91,12 @@ def make_workload(index, n_images=None, n_schemes=None):
                 4: "resnet20_cd_sweep_n10000_s64"}[index]
     elif index == 3:
         nodes, n, name = G.mobilenetv2_32(), 512, "mobilenetv2_32_n512_s16"
+    elif index == 5:
+        nodes, n, name = G.plain_convnet20(), 256, "plainconvnet20_sensitivity_n256_s42"
+    elif index == 6:
+        nodes, n, name = G.heavy_early_resnet20(), 256, "heavyearlyresnet20_sensitivity_n256_s40"
     else:
-        raise ValueError("workload index must be 0..4")
+        raise ValueError("workload index must be 0..6")
     L = G.n_scheme_layers(nodes)
     weights, biases = make_model(nodes, rng)
     n = n if n_images is None else n_images
@@ -97,7 +105,7 @@ def make_workload(index, n_images=None, n_schemes=None):
         schemes = _choice_schemes(rng, 1, L, (32, 8, 4))
     elif index == 1:
         schemes = _choice_schemes(rng, 1, L, (32, 16, 8, 4))
-    elif index == 2:
+    elif index in (2, 5, 6):
         schemes = np.full((2 * L, L), 32, dtype=np.uint8)
         for i in range(L):
             schemes[2 * i, i] = 8

@@ -54,6 +54,38 @@ def test_search_matches_oracle_on_resnet8(env, method, kwargs, layerwise):
     m.close()
 
 
+@pytest.mark.parametrize("builder", ["plain", "heavy", "resnet8"])
+def test_layer_sensitivity_table(env, builder):
+    """Single-layer 8-bit / 4-bit agreement counts (the sensitivity columns of the paper's Table 1) for the
+    two variant models and ResNet-8, against the oracle scoring the same single-layer schemes."""
+    torch, aiq, oracle, synth = env["torch"], env["aiq"], env["oracle"], env["synth"]
+    import sys, os
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    from parity import near_tied
+    nodes = {"plain": synth.plain_convnet20, "heavy": synth.heavy_early_resnet20,
+             "resnet8": lambda: synth.resnet_cifar(1)}[builder]()
+    rng = np.random.Generator(np.random.PCG64(41))
+    w, b = synth.make_model(nodes, rng)
+    n = 12 if builder != "resnet8" else 40
+    images = synth.make_images(n, rng)
+    desc = synth.desc_array(nodes)
+    L = synth.n_scheme_layers(nodes)
+    bits = (8, 4)
+    print(f"sensitivity {builder}: L={L} N={n}", flush=True)
+    m = aiq.Model(desc, w, b)
+    got = m.layer_sensitivity(torch.from_numpy(images).cuda(), bits=bits, chunk=7)
+    m.close()
+    schemes = np.full((L * len(bits), L), 32, dtype=np.uint8)
+    for i in range(L):
+        for k, bb in enumerate(bits):
+            schemes[i * len(bits) + k, i] = bb
+    ref = oracle.eval_schemes(desc, w, b, images, schemes)
+    slack = (near_tied(ref["logits"]) | near_tied(ref["logits_base"])[None, :]).sum(axis=1)
+    assert got.shape == (L, len(bits))
+    assert (np.abs(got.reshape(-1).astype(np.int64) - ref["agree"]) <= slack).all(), (got.reshape(-1), ref["agree"])
+    assert (got <= n).all() and (got >= 0).all()
+
+
 def test_search_argument_errors(env):
     torch, aiq = env["torch"], env["aiq"]
     wl = env["synth"].make_workload(0, n_images=8)
