@@ -23,23 +23,23 @@ PEAK_HBM_GBS = 8000.0
 TRAFFIC = {
     ("resnet20_greedy_step_n1024_s40", "resnet_fused"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_fused.hip",
-        "sha256": "8a24e122f14b05402ada0e2a99fa2740a4b5228d124e6d17d2247f9423f8ae61",
-        "bytes_per_launch": 62165973,
+        "sha256": "83b162e477aee2be83b6280e61c609ba3657c79a388c2143e3ecb410b8617a4d",
+        "bytes_per_launch": 62251157,
     },
     ("mobilenetv2_32_n512_s16", "mbconv"): {  # average over the 16 block launches of a step
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_mbconv.hip",
-        "sha256": "35e11f7ba20ff749cd60bae49ab5c1fb72a1116509a9b4e83b45c0495db9c667",
-        "bytes_per_launch": 1905394733,
+        "sha256": "66777d758ea353b9180d24b15e25141120421943d76149893492ee309104d29d",
+        "bytes_per_launch": 1800837096,
     },
     ("mobilenetv2_32_n512_s16", "depthwise"): {  # layer by layer: average over the 17 depthwise launches
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "9605ac8581e4041a75d85d2d805b373e9b79707f88f04226dc43576b02170cd0",
-        "bytes_per_launch": 8289556892,
+        "sha256": "d714d9f8af2944a09315b6ee2ec9f2c194c23815bfe2ecf1b3e73f17c2a9b77f",
+        "bytes_per_launch": 8289545077,
     },
     ("quantize_stress_8192x4608_b8", "quantize"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "9605ac8581e4041a75d85d2d805b373e9b79707f88f04226dc43576b02170cd0",
-        "bytes_per_launch": 302275802,
+        "sha256": "d714d9f8af2944a09315b6ee2ec9f2c194c23815bfe2ecf1b3e73f17c2a9b77f",
+        "bytes_per_launch": 302277254,
     },
 }
 
