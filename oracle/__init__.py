@@ -64,15 +64,17 @@ def _check(rc):
         raise OracleError(rc)
 
 
-def quantize_weights(w, bits, want_codes=True):
-    """w fp32 [cout][k] -> (w_dq fp32 [cout][k], scales fp32 [cout], codes int32 [cout][k] or None)."""
+def quantize_weights(w, bits, want_codes=True, per_tensor=False):
+    """w fp32 [cout][k] -> (w_dq fp32 [cout][k], scales fp32 [cout], codes int32 [cout][k] or None).
+
+    per_tensor: one scale for the whole matrix instead of one per output channel (row)."""
     w = np.ascontiguousarray(w, dtype=np.float32)
     cout, k = w.shape
     w_dq = np.empty_like(w)
     scales = np.empty(cout, dtype=np.float32)
     codes = np.zeros((cout, k), dtype=np.int32) if want_codes else None
-    _check(lib().oracle_quantize_weights(_p(w, C.c_float), cout, k, int(bits), _p(w_dq, C.c_float),
-                                         _p(scales, C.c_float), _p(codes, C.c_int32)))
+    fn = lib().oracle_quantize_weights_per_tensor if per_tensor else lib().oracle_quantize_weights
+    _check(fn(_p(w, C.c_float), cout, k, int(bits), _p(w_dq, C.c_float), _p(scales, C.c_float), _p(codes, C.c_int32)))
     return w_dq, scales, codes
 
 
@@ -122,7 +124,7 @@ def forward(desc, weights, biases, images, want_acts=False):
     return dict(logits=logits, top1=top1, acts=acts, macs_per_image=macs.value)
 
 
-def eval_schemes(desc, weights, biases, images, schemes, want_logits=True):
+def eval_schemes(desc, weights, biases, images, schemes, want_logits=True, per_tensor=False):
     """Score schemes uint8 [S][L].  Returns dict(logits_base, top1_base, logits, top1, agree)."""
     desc = np.ascontiguousarray(desc, dtype=np.int32)
     images = np.ascontiguousarray(images, dtype=np.float32)
@@ -135,10 +137,11 @@ def eval_schemes(desc, weights, biases, images, schemes, want_logits=True):
     logits = np.empty((S, N, ncls), dtype=np.float64) if want_logits else None
     top1 = np.empty((S, N), dtype=np.int32)
     agree = np.empty(S, dtype=np.int32)
-    _check(lib().oracle_eval_schemes(_p(desc, C.c_int32), n_layers, _ptr_array(weights), _ptr_array(biases),
-                                     _p(images, C.c_float), N, _p(schemes, C.c_uint8), S, L,
-                                     _p(logits_base, C.c_double), _p(top1_base, C.c_int32),
-                                     _p(logits, C.c_double), _p(top1, C.c_int32), _p(agree, C.c_int32)))
+    _check(lib().oracle_eval_schemes_ex(_p(desc, C.c_int32), n_layers, _ptr_array(weights), _ptr_array(biases),
+                                        _p(images, C.c_float), N, _p(schemes, C.c_uint8), S, L,
+                                        1 if per_tensor else 0,
+                                        _p(logits_base, C.c_double), _p(top1_base, C.c_int32),
+                                        _p(logits, C.c_double), _p(top1, C.c_int32), _p(agree, C.c_int32)))
     return dict(logits_base=logits_base, top1_base=top1_base, logits=logits, top1=top1, agree=agree)
 
 

@@ -96,6 +96,26 @@ int oracle_quantize_weights(const float *w, int cout, int k, int bits, float *w_
     return 0;
 }
 
+/*
+ * Per-tensor variant: one scale for the whole weight matrix     [Conclusion: per-channel effects are
+ *                                                                named as future work, so the paper's
+ *                                                                own runs most likely used one scale
+ *                                                                per layer]
+ * Definition: the per-output-channel rule above applied to the matrix read as a single row of
+ * cout * k weights; scales[c] receives that one scale for every c.
+ */
+int oracle_quantize_weights_per_tensor(const float *w, int cout, int k, int bits, float *w_dq, float *scales,
+                                       int32_t *codes)
+{
+    if (!bits_supported(bits)) return 2;
+    if (!w || !w_dq || !scales || cout < 0 || k < 0) return 1;
+    float s = 1.0f;
+    int rc = oracle_quantize_weights(w, 1, cout * k, bits, w_dq, &s, codes);
+    if (rc) return rc;
+    for (int c = 0; c < cout; ++c) scales[c] = s;
+    return 0;
+}
+
 static int out_size(int in, int k, int stride, int pad) { return (in + 2 * pad - k) / stride + 1; }
 
 /*
@@ -343,10 +363,25 @@ int oracle_forward(const int32_t *desc, int n_layers, const float *const *w, con
  * w / bias: fp32 per node.  schemes uint8 [S][L].  Outputs (host, caller-allocated):
  * logits_base [N][C], top1_base [N], logits [S][N][C], top1 [S][N], agree [S]; logits, top1 nullable.
  */
+int oracle_eval_schemes_ex(const int32_t *desc, int n_layers, const float *const *w, const float *const *bias,
+                           const float *images, int N, const uint8_t *schemes, int S, int L, int per_tensor,
+                           double *logits_base, int32_t *top1_base, double *logits, int32_t *top1,
+                           int32_t *agree);
+
 int oracle_eval_schemes(const int32_t *desc, int n_layers, const float *const *w, const float *const *bias,
                         const float *images, int N, const uint8_t *schemes, int S, int L,
                         double *logits_base, int32_t *top1_base, double *logits, int32_t *top1,
                         int32_t *agree)
+{
+    return oracle_eval_schemes_ex(desc, n_layers, w, bias, images, N, schemes, S, L, 0, logits_base, top1_base,
+                                  logits, top1, agree);
+}
+
+/* per_tensor != 0: every scheme layer is quantized with one scale per layer instead of one per output channel. */
+int oracle_eval_schemes_ex(const int32_t *desc, int n_layers, const float *const *w, const float *const *bias,
+                           const float *images, int N, const uint8_t *schemes, int S, int L, int per_tensor,
+                           double *logits_base, int32_t *top1_base, double *logits, int32_t *top1,
+                           int32_t *agree)
 {
     if (!desc || !w || !bias || !images || !schemes || !logits_base || !top1_base || !agree) return 1;
     if (N < 0 || S < 0) return 1;
@@ -378,7 +413,10 @@ int oracle_eval_schemes(const int32_t *desc, int n_layers, const float *const *w
             int bits = d[F_SLOT] >= 0 ? schemes[(size_t)s * L + d[F_SLOT]] : 32;
             wq[l] = (float *)malloc(sizeof(float) * (size_t)cout * k);
             float *sc = (float *)malloc(sizeof(float) * cout);
-            oracle_quantize_weights(w[l], cout, k, bits, wq[l], sc, NULL);
+            if (per_tensor)
+                oracle_quantize_weights_per_tensor(w[l], cout, k, bits, wq[l], sc, NULL);
+            else
+                oracle_quantize_weights(w[l], cout, k, bits, wq[l], sc, NULL);
             free(sc);
         }
         int32_t count = 0;

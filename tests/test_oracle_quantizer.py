@@ -169,3 +169,66 @@ def test_matches_vectorised_numpy_float32(bits):
     np.testing.assert_array_equal(s, s_np)
     np.testing.assert_array_equal(q, q_np)
     np.testing.assert_array_equal(w_dq, (q_np.astype(np.float32) * s_np[:, None]).astype(np.float32))
+
+
+# ---------------------------------------------------------------- per-tensor variant
+
+def test_per_tensor_hand_worked(oracle_lib):
+    """Two rows, 4 bits: the tensor's largest magnitude (7) sets the one scale s = 1, so the second row,
+    whose own scale would be 0.25, keeps only coarse codes: 1.75 -> 2, 0.4 -> 0."""
+    w = np.array([[7.0, -3.5], [1.75, 0.4]], dtype=np.float32)
+    dq, s, q = oracle_lib.quantize_weights(w, 4, per_tensor=True)
+    np.testing.assert_array_equal(s, np.array([1.0, 1.0], dtype=np.float32))
+    np.testing.assert_array_equal(q, np.array([[7, -4], [2, 0]], dtype=np.int32))
+    np.testing.assert_array_equal(dq, np.array([[7.0, -4.0], [2.0, 0.0]], dtype=np.float32))
+    _, s_c, q_c = oracle_lib.quantize_weights(w, 4)
+    np.testing.assert_array_equal(s_c, np.array([1.0, 0.25], dtype=np.float32))
+    np.testing.assert_array_equal(q_c[1], np.array([7, 2], dtype=np.int32))
+
+
+@pytest.mark.parametrize("bits", [16, 8, 6, 4, 2])
+def test_per_tensor_properties(oracle_lib, bits):
+    rng = np.random.Generator(np.random.PCG64(900 + bits))
+    w = (rng.standard_normal((24, 50)) * rng.uniform(0.1, 2.0, size=(24, 1))).astype(np.float32)
+    dq, s, q = oracle_lib.quantize_weights(w, bits, per_tensor=True)
+    qmax = 2 ** (bits - 1) - 1
+    # one scale, set by the largest magnitude of the whole tensor, computed in binary32
+    assert (s == s[0]).all()
+    assert s[0] == np.float32(np.abs(w).max()) / np.float32(qmax)
+    assert np.abs(q).max() == qmax and (np.abs(q) <= qmax).all()
+    # the row holding the tensor maximum is quantized exactly as the per-channel rule would
+    r = int(np.abs(w).max(axis=1).argmax())
+    dq_c, s_c, q_c = oracle_lib.quantize_weights(w, bits)
+    assert s_c[r] == s[0]
+    np.testing.assert_array_equal(q[r], q_c[r])
+    assert (s_c <= s[0]).all()
+    # vectorised binary32 second implementation
+    t = (w / s[0]).astype(np.float32)
+    ref_q = np.clip(np.rint(t), -qmax, qmax).astype(np.int32)
+    np.testing.assert_array_equal(q, ref_q)
+    assert dq.tobytes() == (ref_q.astype(np.float32) * s[0]).astype(np.float32).tobytes()
+    # a single row: both granularities coincide
+    a = oracle_lib.quantize_weights(w[:1], bits, per_tensor=True)
+    b = oracle_lib.quantize_weights(w[:1], bits)
+    for x, y in zip(a, b):
+        assert x.tobytes() == y.tobytes()
+    # b = 32 is the identity in both
+    dq32, s32, _ = oracle_lib.quantize_weights(w, 32, per_tensor=True)
+    assert dq32.tobytes() == w.tobytes() and (s32 == 1.0).all()
+
+
+def test_per_tensor_scoring_uses_one_scale_per_layer(oracle_lib):
+    import synth
+    wl = synth.make_workload(0, n_images=6)
+    schemes = np.full((2, wl["L"]), 4, dtype=np.uint8)
+    schemes[1] = 32
+    r_t = oracle_lib.eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes, per_tensor=True)
+    # equals a plain forward pass on weights quantized per tensor by hand
+    wq = []
+    for node, w in zip(wl["nodes"], wl["weights"]):
+        wq.append(oracle_lib.quantize_weights(w, 4, per_tensor=True)[0] if node["scheme_slot"] >= 0 else w)
+    f = oracle_lib.forward(wl["desc"], wq, wl["biases"], wl["images"])
+    np.testing.assert_array_equal(r_t["logits"][0], f["logits"])
+    np.testing.assert_array_equal(r_t["logits"][1], r_t["logits_base"])
+    r_c = oracle_lib.eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes)
+    assert not np.array_equal(r_t["logits"][0], r_c["logits"][0])
