@@ -98,6 +98,17 @@ aiq_status aiq_layer_ai(const aiq_layer_desc *layers, int32_t n_layers, const ui
 aiq_status aiq_quantize_weights(const float *w, int32_t cout, int32_t k, int32_t bits, float *w_dq,
                                 float *scales, int32_t *codes, void *hip_stream);
 
+/*
+ * Same with a choice of granularity (the paper does not say which it used; its Conclusion names
+ * per-channel effects as future work).  per_tensor = 0: one scale per output channel, as above.
+ * per_tensor = 1: one scale for the whole matrix, s = max_{c,k} |w| / qmax, written to every
+ * scales[c].  scratch: device, 4 bytes, 4-byte aligned, required when per_tensor = 1 (the
+ * matrix-wide maximum is formed there by a first launch); may be NULL otherwise.
+ * Errors: INVALID_ARG, UNSUPPORTED_BITS, DEVICE_ERROR.
+ */
+aiq_status aiq_quantize_weights_ex(const float *w, int32_t cout, int32_t k, int32_t bits, int32_t per_tensor,
+                                   float *w_dq, float *scales, int32_t *codes, void *scratch, void *hip_stream);
+
 typedef struct aiq_model aiq_model; /* opaque */
 
 /*
@@ -115,7 +126,7 @@ aiq_status aiq_model_create(const aiq_layer_desc *layers, int32_t n_layers, cons
  * graphs (CIFAR-style ResNets of 16/32/64 channels) whose activations would otherwise stay
  * in LDS for the whole network.  Both strategies compute the same function.
  */
-enum { AIQ_MODEL_LAYERWISE = 1 };
+enum { AIQ_MODEL_LAYERWISE = 1, AIQ_MODEL_PER_TENSOR = 2 };
 aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, const float *const *w_host,
                                const float *const *bias_host, uint32_t flags, aiq_model **out);
 /* 1 if the model runs LDS-resident (one launch for the whole network), 0 if not, -1 for NULL. */

@@ -7,5 +7,5 @@ the built library, or without a GPU, the device entry points raise.
 """
 from .binding import (  # noqa: F401
     AiqError, Model, layer_ai, quantize_weights, library_path, load_library, EXPORTED_SYMBOLS,
-    K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV, MODEL_LAYERWISE,
+    K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV, MODEL_LAYERWISE, MODEL_PER_TENSOR,
 )

@@ -11,13 +11,14 @@ _LIB_PATH = os.path.join(_HERE, "libaiq.so")
 _lib = None
 
 EXPORTED_SYMBOLS = (
-    "aiq_status_str", "aiq_last_hip_error", "aiq_layer_ai", "aiq_quantize_weights", "aiq_model_create",
+    "aiq_status_str", "aiq_last_hip_error", "aiq_layer_ai", "aiq_quantize_weights", "aiq_quantize_weights_ex", "aiq_model_create",
     "aiq_model_create_ex", "aiq_model_is_lds_resident", "aiq_model_lds_resident_blocks", "aiq_model_destroy", "aiq_model_scheme_layers", "aiq_model_classes", "aiq_eval_workspace_bytes",
     "aiq_eval_schemes", "aiq_profile_enable", "aiq_profile_read", "aiq_search_workspace_bytes",
     "aiq_search_greedy", "aiq_search_coordinate_descent", "aiq_sensitivity_workspace_bytes", "aiq_layer_sensitivity",
 )
 K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV = range(7)
 MODEL_LAYERWISE = 1
+MODEL_PER_TENSOR = 2
 _DESC_INTS = 13
 
 
@@ -57,6 +58,8 @@ def load_library():
                                  C.POINTER(C.c_double)]
     lib.aiq_quantize_weights.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_void_p]
+    lib.aiq_quantize_weights_ex.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.aiq_model_create.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
     lib.aiq_model_create_ex.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32,
                                         C.POINTER(C.c_void_p)]
@@ -124,8 +127,8 @@ def layer_ai(desc, scheme, batch=1):
     return flops, byts, ai.value
 
 
-def quantize_weights(w, bits, want_codes=True, stream=None):
-    """aiq_quantize_weights on a CUDA fp32 tensor [cout][k]; returns (w_dq, scales, codes|None) tensors."""
+def quantize_weights(w, bits, want_codes=True, stream=None, per_tensor=False):
+    """aiq_quantize_weights[_ex] on a CUDA fp32 tensor [cout][k]; returns (w_dq, scales, codes|None) tensors."""
     import torch
     if not (w.is_cuda and w.dtype == torch.float32 and w.dim() == 2 and w.is_contiguous()):
         raise ValueError("w must be a contiguous CUDA float32 matrix")
@@ -133,6 +136,13 @@ def quantize_weights(w, bits, want_codes=True, stream=None):
     w_dq = torch.empty_like(w)
     scales = torch.empty(cout, dtype=torch.float32, device=w.device)
     codes = torch.zeros((cout, k), dtype=torch.int32, device=w.device) if want_codes else None
+    if per_tensor:
+        scratch = torch.empty(1, dtype=torch.int32, device=w.device)
+        st = load_library().aiq_quantize_weights_ex(w.data_ptr(), cout, k, int(bits), 1, w_dq.data_ptr(),
+                                                    scales.data_ptr(), None if codes is None else codes.data_ptr(),
+                                                    scratch.data_ptr(), _stream_ptr(stream))
+        _check(st, "aiq_quantize_weights_ex")
+        return w_dq, scales, codes
     st = load_library().aiq_quantize_weights(w.data_ptr(), cout, k, int(bits), w_dq.data_ptr(), scales.data_ptr(),
                                              None if codes is None else codes.data_ptr(), _stream_ptr(stream))
     _check(st, "aiq_quantize_weights")
@@ -142,7 +152,7 @@ def quantize_weights(w, bits, want_codes=True, stream=None):
 class Model:
     """Owns an aiq_model handle.  desc: int32 [n][13]; weights / biases: lists of fp32 numpy arrays."""
 
-    def __init__(self, desc, weights, biases, layerwise=False):
+    def __init__(self, desc, weights, biases, layerwise=False, per_tensor=False):
         self._h = C.c_void_p(None)
         self._lib = load_library()
         d = _desc(desc)
@@ -154,8 +164,8 @@ class Model:
         wp = (C.c_void_p * n)(*[w.ctypes.data for w in ws])
         bp = (C.c_void_p * n)(*[b.ctypes.data for b in bs])
         h = C.c_void_p(None)
-        _check(self._lib.aiq_model_create_ex(d.ctypes.data, n, wp, bp, MODEL_LAYERWISE if layerwise else 0,
-                                             C.byref(h)), "aiq_model_create_ex")
+        flags = (MODEL_LAYERWISE if layerwise else 0) | (MODEL_PER_TENSOR if per_tensor else 0)
+        _check(self._lib.aiq_model_create_ex(d.ctypes.data, n, wp, bp, flags, C.byref(h)), "aiq_model_create_ex")
         self._h = h
         self.lds_resident = bool(self._lib.aiq_model_is_lds_resident(h))
         self.lds_resident_blocks = int(self._lib.aiq_model_lds_resident_blocks(h))

@@ -79,6 +79,8 @@ struct aiq_model {
     std::vector<void *> allocations;
     // LDS-resident path (CIFAR-style ResNets)
     bool fused = false;
+    bool per_tensor = false;       // one quantization scale per layer instead of one per output channel
+    uint32_t *layer_amax = nullptr; // device: bit pattern of max |w| of every layer (per-tensor scales)
     int mb_blocks = 0;  // inverted-residual blocks run by the LDS-resident block kernel
     std::vector<FusedOp> fused_ops;
     FusedOp *fused_ops_dev = nullptr;
@@ -433,6 +435,35 @@ aiq_status aiq_quantize_weights(const float *w, int32_t cout, int32_t k, int32_t
     return AIQ_OK;
 }
 
+aiq_status aiq_quantize_weights_ex(const float *w, int32_t cout, int32_t k, int32_t bits, int32_t per_tensor,
+                                   float *w_dq, float *scales, int32_t *codes, void *scratch, void *hip_stream)
+{
+    if (per_tensor != 0 && per_tensor != 1) return AIQ_INVALID_ARG;
+    if (!per_tensor) return aiq_quantize_weights(w, cout, k, bits, w_dq, scales, codes, hip_stream);
+    if (cout < 0 || k < 0) return AIQ_INVALID_ARG;
+    if (!bits_supported(bits)) return AIQ_UNSUPPORTED_BITS;
+    if (cout == 0) return AIQ_OK;
+    if (!scales || !scratch || (reinterpret_cast<uintptr_t>(scratch) & 3) || (k > 0 && (!w || !w_dq)))
+        return AIQ_INVALID_ARG;
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint32_t *amax = static_cast<uint32_t *>(scratch);
+    if (bits != 32) AIQ_HIP(launch_tensor_absmax(w, (size_t)cout * k, amax, st));
+    QuantJob j{};
+    j.w = w;
+    j.out = w_dq;
+    j.scales = scales;
+    j.codes = bits == 32 ? nullptr : codes;
+    j.cout = cout;
+    j.k = k;
+    j.bits = bits;
+    j.layout = kLayoutPlain;
+    j.taps = 1;
+    j.cblocks = 1;
+    j.tensor_amax = bits == 32 ? nullptr : amax;
+    AIQ_HIP(launch_quantize_single(j, st));
+    return AIQ_OK;
+}
+
 int32_t aiq_model_scheme_layers(const aiq_model *m) { return m ? m->L : -1; }
 int32_t aiq_model_classes(const aiq_model *m) { return m ? m->classes : -1; }
 
@@ -457,7 +488,7 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
                                const float *const *bias_host, uint32_t flags, aiq_model **out)
 {
     if (out) *out = nullptr;
-    if (flags & ~(uint32_t)AIQ_MODEL_LAYERWISE) return AIQ_INVALID_ARG;
+    if (flags & ~(uint32_t)(AIQ_MODEL_LAYERWISE | AIQ_MODEL_PER_TENSOR)) return AIQ_INVALID_ARG;
     if (!layers || n_layers <= 0 || !w_host || !bias_host || !out) return AIQ_INVALID_ARG;
     for (int l = 0; l < n_layers; ++l)
         if (!w_host[l] || !bias_host[l]) return AIQ_INVALID_ARG;
@@ -564,6 +595,8 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
     };
     if (!hip_ok(conv_set_lds_limits()) || !hip_ok(fused_set_lds_limit())) return fail(AIQ_DEVICE_ERROR);
     std::vector<int32_t> block_job;
+    m->per_tensor = (flags & AIQ_MODEL_PER_TENSOR) != 0;
+    if (m->per_tensor && (st = dev_alloc(m, &m->layer_amax, (size_t)n_layers)) != AIQ_OK) return fail(st);
     for (int l = 0; l < n_layers; ++l) {
         Node &nd = m->nodes[l];
         const size_t wn = (size_t)nd.d.cout * nd.k;
@@ -571,6 +604,9 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
         if ((st = dev_alloc(m, &nd.bias, (size_t)nd.d.cout)) != AIQ_OK) return fail(st);
         if (!hip_ok(hipMemcpy(nd.w_plain, w_host[l], wn * sizeof(float), hipMemcpyHostToDevice)) ||
             !hip_ok(hipMemcpy(nd.bias, bias_host[l], nd.d.cout * sizeof(float), hipMemcpyHostToDevice)))
+            return fail(AIQ_DEVICE_ERROR);
+        // the weights never change: the matrix-wide maximum per-tensor scales need is formed once
+        if (m->per_tensor && !hip_ok(launch_tensor_absmax(nd.w_plain, wn, m->layer_amax + l, nullptr)))
             return fail(AIQ_DEVICE_ERROR);
         const int n_slots = nd.d.scheme_slot >= 0 ? kNumBits : 1;
         for (int b = 0; b < n_slots; ++b) {
@@ -585,6 +621,7 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
             j.layout = nd.layout;
             j.taps = nd.d.kind == 2 ? 1 : nd.d.kh * nd.d.kw;
             j.cblocks = (nd.d.cin + 15) / 16;
+            j.tensor_amax = (m->per_tensor && b > 0) ? m->layer_amax + l : nullptr;
             if (b == 0) {
                 // the FP32 copy in kernel layout is written once, here
                 if (!hip_ok(launch_quantize_single(j, nullptr))) return fail(AIQ_DEVICE_ERROR);

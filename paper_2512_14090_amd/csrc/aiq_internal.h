@@ -46,6 +46,7 @@ struct QuantJob {
     int32_t cblocks;  // ceil(cin/16) (mfma layout)
     int32_t first_block; // first grid block of this job in a batched launch
     int32_t pad_;
+    const uint32_t *tensor_amax; // per-tensor scale: bit pattern of the whole matrix's largest |w|; nullptr: per channel
 };
 
 constexpr int kQuantChannelsPerBlock = 4; // one wavefront per output channel
@@ -148,6 +149,8 @@ struct AgreeArgs {
 
 // Launchers (aiq_kernels.hip).  All return the launch's hipError_t.
 hipError_t launch_quantize_single(const QuantJob &job, hipStream_t st);
+// out = bit pattern of max |w[i]| over n elements (out is cleared first); non-negative floats order like integers
+hipError_t launch_tensor_absmax(const float *w, size_t n, uint32_t *out, hipStream_t st);
 hipError_t launch_quantize_batch(const QuantJob *jobs_dev, const int32_t *block_job_dev, int n_blocks,
                                  const QuantMask &mask, hipStream_t st);
 hipError_t launch_conv(const ConvArgs &a, int ks, int stride, int nt, size_t lds_bytes, dim3 grid,

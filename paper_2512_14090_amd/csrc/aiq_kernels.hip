@@ -9,6 +9,8 @@
 // slot of that scheme's bit-width.
 #include "aiq_internal.h"
 
+#include <algorithm>
+
 namespace aiq {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -81,8 +83,12 @@ __device__ inline void quantize_channel(const QuantJob &j, int c, int lane)
         return;
     }
     float amax = 0.0f;
-    for (int i = lane; i < j.k; i += 64) amax = fmaxf(amax, fabsf(row[i]));
-    amax = wave_max(amax);
+    if (j.tensor_amax) {
+        amax = __uint_as_float(*j.tensor_amax);
+    } else {
+        for (int i = lane; i < j.k; i += 64) amax = fmaxf(amax, fabsf(row[i]));
+        amax = wave_max(amax);
+    }
     const int qmax = (1 << (j.bits - 1)) - 1;
     const float s = amax > 0.0f ? __fdiv_rn(amax, (float)qmax) : 1.0f;
     if (lane == 0 && j.scales) j.scales[c] = s;
@@ -142,10 +148,14 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantJob j)
         return;
     }
     float amax = 0.0f;
+    if (j.tensor_amax) {
+        amax = __uint_as_float(*j.tensor_amax);
+    } else {
 #pragma unroll
-    for (int u = 0; u < NV; ++u)
-        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v[u].x), fabsf(v[u].y))), fmaxf(fabsf(v[u].z), fabsf(v[u].w)));
-    amax = wave_max(amax);
+        for (int u = 0; u < NV; ++u)
+            amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v[u].x), fabsf(v[u].y))), fmaxf(fabsf(v[u].z), fabsf(v[u].w)));
+        amax = wave_max(amax);
+    }
     const int qmax = (1 << (j.bits - 1)) - 1;
     const float s = amax > 0.0f ? __fdiv_rn(amax, (float)qmax) : 1.0f;
     if (lane == 0 && j.scales) j.scales[c] = s;
@@ -191,6 +201,27 @@ hipError_t launch_quantize_single(const QuantJob &job, hipStream_t st)
         return launch_quantize_rows<20>(job, blocks, st);
     }
     hipLaunchKernelGGL(quantize_single_kernel, dim3(blocks), dim3(256), 0, st, job);
+    return hipGetLastError();
+}
+
+// Largest magnitude of a whole matrix (per-tensor scales): wavefront butterfly, then one integer
+// atomic per wavefront - the bit patterns of non-negative floats order like unsigned integers,
+// so the result does not depend on the order of arrival.
+__global__ __launch_bounds__(256) void tensor_absmax_kernel(const float *__restrict__ w, size_t n, uint32_t *out)
+{
+    float amax = 0.0f;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
+        amax = fmaxf(amax, fabsf(w[i]));
+    amax = wave_max(amax);
+    if ((threadIdx.x & 63) == 0) atomicMax(out, __float_as_uint(amax));
+}
+
+hipError_t launch_tensor_absmax(const float *w, size_t n, uint32_t *out, hipStream_t st)
+{
+    hipError_t e = launch_fill_i32(reinterpret_cast<int32_t *>(out), 0, 1, st);
+    if (e != hipSuccess || n == 0) return e;
+    const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 2048);
+    hipLaunchKernelGGL(tensor_absmax_kernel, dim3(blocks), dim3(256), 0, st, w, n, out);
     return hipGetLastError();
 }
 

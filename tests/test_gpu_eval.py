@@ -184,6 +184,28 @@ def test_depthwise_layers_outside_blocks(env):
         print("  max logit rel err %.3e" % err, flush=True)
 
 
+@pytest.mark.parametrize("case", ["resnet8", "resnet8_layerwise", "mobilenetv2"])
+def test_per_tensor_scales(env, case):
+    """Scheme scoring with one quantization scale per layer (per-tensor variant) against the oracle's."""
+    aiq = env["aiq"]
+    if case == "mobilenetv2":
+        wl = env["synth"].make_workload(3, n_images=4, n_schemes=3)
+        schemes = np.concatenate([wl["schemes"], np.full((1, wl["L"]), 8, np.uint8), np.full((1, wl["L"]), 4, np.uint8)])
+    else:
+        wl = env["synth"].make_workload(0, n_images=24)
+        schemes = _extra_schemes(wl, 11)
+    n = wl["images"].shape[0]
+    print(f"per-tensor scales: {case}", flush=True)
+    ref = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes, per_tensor=True)
+    ref_c = env["oracle"].eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=case.endswith("layerwise"), per_tensor=True)
+    gpu = _run_gpu(env, wl, schemes, chunk=16, model=m)
+    m.close()
+    check_eval(gpu, ref, n)
+    # and it is not the per-channel result
+    assert logits_rel_error(gpu["logits"], ref_c["logits"]) > 1e-3
+
+
 def test_variant_models(env):
     """PlainConvNet20 and HeavyEarlyResNet20 descriptors (64-channel layers at 32x32, stride-1 projection)."""
     synth, oracle = env["synth"], env["oracle"]

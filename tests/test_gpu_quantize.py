@@ -85,6 +85,28 @@ def test_stress_shape_sample(aiq):
         assert ratio == qmax
 
 
+@pytest.mark.parametrize("bits", BITS)
+def test_per_tensor_bit_exact_against_oracle(aiq, bits):
+    """One scale per matrix: codes, the (replicated) scale and the dequantized values, bit for bit."""
+    import torch
+    import oracle
+    for i, (cout, k) in enumerate(SHAPES):
+        w = _w(cout, k, 2000 + i)
+        print(f"per-tensor quantize bits={bits} cout={cout} k={k}", flush=True)
+        w_dq, s, q = aiq.quantize_weights(torch.from_numpy(w).cuda(), bits, want_codes=True, per_tensor=True)
+        torch.cuda.synchronize()
+        r_dq, r_s, r_q = oracle.quantize_weights(w, bits, per_tensor=True)
+        assert s.cpu().numpy().tobytes() == r_s.tobytes(), (bits, cout, k)
+        assert w_dq.cpu().numpy().tobytes() == r_dq.tobytes(), (bits, cout, k)
+        if bits != 32:
+            np.testing.assert_array_equal(q.cpu().numpy(), r_q)
+    # all-zero matrix: scale 1, codes 0
+    z = torch.zeros((3, 8), dtype=torch.float32, device="cuda")
+    w_dq, s, q = aiq.quantize_weights(z, 8, per_tensor=True)
+    torch.cuda.synchronize()
+    assert s.cpu().tolist() == [1.0] * 3 and not w_dq.any().item()
+
+
 def test_unaligned_rows_take_the_scalar_path(aiq):
     """A weight matrix that starts 4 bytes into an allocation (rows not 16-byte aligned)."""
     import torch
