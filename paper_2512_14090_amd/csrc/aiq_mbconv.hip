@@ -92,6 +92,7 @@ struct MbCfg {
     static_assert(CIN % 4 == 0 && HID % HC == 0 && HC % 16 == 0 && COUT % 4 == 0, "channel counts");
     static_assert(HO % R == 0 && (G == 1 || WHOLE), "bands tile the image; several images only as whole images");
     static_assert((G * XROWS * W) % 16 == 0 && (PTE >= NW || (NW % PTE == 0 && HT % HS == 0)), "expand tiles");
+    static_assert(!WHOLE || PTE < NW || PTE % NW == 0, "whole images: every wavefront has all its expand tiles");
     static_assert((G * R * WO) % 16 == 0 && (PTO >= NW ? PTO % NW == 0 : NW % PTO == 0), "pixel tiles per wavefront");
     static_assert(CT % WPP == 0, "output-channel tiles per wavefront");
     static_assert(MT == 1 || (WO >= 16 && NW % TPR == 0 && G == 1), "strips of tiles need whole 16-pixel row segments");
@@ -217,8 +218,9 @@ void mbconv_kernel(MbArgs a)
         for (int i = 0; i < C::CTW; ++i) acc[m][i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     // Weights of one expand step of this wavefront: bias and the A operands of its hidden tiles.
-    // Blocks with few input channels can keep them in registers and fetch them one step ahead
-    // (EPRE); the others read them where they are used.
+    // Where the registers allow it they are fetched one step ahead (EPRE), which hides their
+    // L2 latency behind the consumption of the previous chunk (measured: 6-25 % per block);
+    // otherwise they are read where they are used.
     constexpr bool EPRE = C::EPRE;
     struct ExpW {
         floatx4 be[C::HTW], wa[EPRE ? C::HTW : 1][EPRE ? C::CB : 1];
@@ -241,7 +243,7 @@ void mbconv_kernel(MbArgs a)
         const float *wc = w_e + ((size_t)(c * C::HT + h0) * C::CB * 64 + lane) * 4;
 #pragma unroll
         for (int k = 0; k < C::XT; ++k) {
-            if (!x_ok[k]) continue; // uniform per wavefront
+            if (!C::WHOLE && !x_ok[k]) continue; // uniform per wavefront; whole images have every tile
             floatx4 ea[C::HTW];
 #pragma unroll
             for (int h = 0; h < C::HTW; ++h) ea[h] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -382,7 +384,8 @@ void mbconv_kernel(MbArgs a)
 // 32x32 pixels small workgroups (4 wavefronts, X in registers, 2-3 workgroups per compute
 // unit) beat one large one by 20-40 % - independent barrier domains keep the matrix pipe fed;
 // at 16x16 and 8x8 the input has too many channels for registers and one workgroup of 8
-// wavefronts with X in LDS does best.
+// wavefronts with X in LDS does best.  The hidden chunk HC is the largest whose expand weights
+// still fit in registers one step ahead (the last block's do not at any chunk size).
 
 namespace {
 
@@ -391,13 +394,13 @@ namespace {
 typedef MbCfg<16, 96, 24, 32, 1, false, 8, 1, 16, 4, true, 3, true> Mb0;
 typedef MbCfg<24, 144, 24, 32, 1, true, 8, 1, 16, 4, true, 2, false> Mb1;
 typedef MbCfg<24, 144, 32, 32, 1, false, 8, 1, 16, 4, true, 2, false> Mb2;
-typedef MbCfg<32, 192, 32, 32, 1, true, 8, 1, 16, 4, true, 2, false> Mb3;
+typedef MbCfg<32, 192, 32, 32, 1, true, 8, 1, 16, 4, true, 2, true> Mb3;
 typedef MbCfg<32, 192, 64, 32, 2, false, 8, 1, 16, 4, true, 2, true> Mb4;
-typedef MbCfg<64, 384, 64, 16, 1, true, 16, 1, 32, 8, false, 1, false> Mb5;
-typedef MbCfg<64, 384, 96, 16, 1, false, 16, 1, 32, 8, false, 1, false> Mb6;
-typedef MbCfg<96, 576, 96, 16, 1, true, 16, 1, 16, 8, false, 1, false> Mb7;
-typedef MbCfg<96, 576, 160, 16, 2, false, 8, 1, 16, 8, false, 1, false> Mb8;
-typedef MbCfg<160, 960, 160, 8, 1, true, 8, 2, 32, 8, false, 1, false> Mb9;
+typedef MbCfg<64, 384, 64, 16, 1, true, 16, 1, 32, 8, false, 1, true> Mb5;
+typedef MbCfg<64, 384, 96, 16, 1, false, 16, 1, 32, 8, false, 1, true> Mb6;
+typedef MbCfg<96, 576, 96, 16, 1, true, 16, 1, 16, 8, false, 1, true> Mb7;
+typedef MbCfg<96, 576, 160, 16, 2, false, 8, 1, 16, 8, false, 1, true> Mb8;
+typedef MbCfg<160, 960, 160, 8, 1, true, 8, 2, 16, 8, false, 1, true> Mb9;
 typedef MbCfg<160, 960, 320, 8, 1, false, 8, 1, 64, 8, false, 1, false> Mb10;
 #else
 AIQ_MB_TABLE
