@@ -141,6 +141,8 @@ def main():
     ap.add_argument("--roofline-class", default="auto",
                     choices=("auto", "conv_mfma", "depthwise", "head", "resnet_fused", "mbconv"),
                     help="kernel class whose roofline is reported (auto: the one the step spends most time in)")
+    ap.add_argument("--no-prefix-shared", action="store_true",
+                    help="skip the second timing (same step with the forward prefix shared)")
     ap.add_argument("--stress", choices=("quantize",), help="time one kernel on a bandwidth-stress shape instead of a workload")
     ap.add_argument("--stress-shape", default="8192x4608", help="cout x k of the quantizer stress matrix")
     args = ap.parse_args()
@@ -221,6 +223,40 @@ def main():
                        "lds_resident_blocks": int(model.lds_resident_blocks),
                        "agree_min_max": [int(agree.min()), int(agree.max())] if S else []},
             "roofline": roofline, "kernels": kernels}
+    # Second throughput: the same step with the forward prefix shared (every candidate differs
+    # from the all-FP32 scheme in one layer and resumes from that scheme's pass).  Same outputs,
+    # fewer layers executed - an algorithmic saving, so it is not the value above and has no
+    # roofline of its own.
+    sch = wl["schemes"]
+    single_moves = S > 0 and bool(((sch != 32).sum(axis=1) <= 1).all())
+    if model.shares_prefix and single_moves and not args.no_prefix_shared:
+        ref = np.full(L, 32, dtype=np.uint8)
+        out2 = {"top1_base": torch.empty(N, dtype=torch.int32, device="cuda"),
+                "agree": torch.empty(S, dtype=torch.int32, device="cuda")}
+
+        def step_shared():
+            return model.eval_schemes(images, sch, chunk=chunk, out=out2, stream=stream, ref_scheme=ref)
+
+        for _ in range(args.warmup):
+            step_shared()
+        torch.cuda.synchronize()
+        model.profile_enable(True)
+        for c in range(7):
+            model.profile_read(c)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            r2 = step_shared()
+        torch.cuda.synchronize()
+        dt2 = time.perf_counter() - t0
+        model.profile_enable(False)
+        fz = model.profile_read(5)
+        line["prefix_shared"] = {
+            "value": S * N * args.steps / dt2, "unit": "scheme-images/s", "ms_per_step": dt2 / args.steps * 1e3,
+            "reference_scheme": "all-fp32", "executed_gflop_per_step": fz["flops"] / args.steps / 1e9,
+            "kernel_ms_per_step": fz["total_ms"] / args.steps,
+            "kernel_tflops": fz["flops"] / (fz["total_ms"] * 1e-3) / 1e12 if fz["total_ms"] > 0 else 0.0,
+            "outputs_identical": bool((r2["agree"].cpu().numpy() == agree).all()
+                                      and (out2["top1_base"] == out["top1_base"]).all().item())}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl)
     model.close()

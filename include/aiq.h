@@ -167,6 +167,26 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
                             void *hip_stream);
 
 /*
+ * aiq_eval_schemes with a shared forward prefix.  The schemes of one search step are all
+ * derived from one scheme by changing a single layer (paper: Search Over Mixed-Precision
+ * Schemes - greedy lowers one layer of the current scheme, coordinate descent varies one
+ * layer with the others fixed), so up to that layer their forward passes equal the
+ * current scheme's.  ref_scheme (HOST uint8 [L], read before the call returns) is that
+ * scheme: it is run once per image, and scheme s resumes at its first layer whose width
+ * differs from ref_scheme's.  Every output is bit for bit what aiq_eval_schemes returns
+ * for the same arguments; schemes need not be related to ref_scheme (a scheme that differs
+ * in its first layer simply runs whole).  Models for which aiq_model_shares_prefix is 0 run
+ * every scheme whole.  workspace >= aiq_eval_shared_workspace_bytes(m, S, chunk); other
+ * arguments, ownership and errors as for aiq_eval_schemes (ref_scheme NULL: INVALID_ARG).
+ */
+int32_t aiq_model_shares_prefix(const aiq_model *m); /* 1, 0, or -1 for a NULL model */
+aiq_status aiq_eval_shared_workspace_bytes(const aiq_model *m, int32_t S, int32_t chunk, size_t *bytes);
+aiq_status aiq_eval_schemes_shared(aiq_model *m, const float *images, int32_t N, const uint8_t *schemes, int32_t S,
+                                   const uint8_t *ref_scheme, int32_t chunk, int32_t *top1_base,
+                                   int32_t base_valid, float *logits, int32_t *top1, int32_t *agree,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Search drivers (paper: Approach - Problem Formulation for the loss, Search Over
  * Mixed-Precision Schemes for the two loops).  Host loops around aiq_eval_schemes: every
  * iteration scores all its candidate schemes in one scheme-batched call.
@@ -180,6 +200,8 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
  *   other layers fixed (the current width wins ties); repeat sweeps until one changes
  *   nothing or max_iters sweeps (0 = 50) are done.
  * Ties between candidates go to the first in (layer ascending, width descending) order.
+ * share_prefix = 1 scores each step through aiq_eval_schemes_shared with the current scheme
+ * as the reference: same result, less work.
  *
  * params.bits: the alphabet Q, strictly descending, bits[0] = 32.  layers: the same records
  * the model was built from (for the AI model).  images: device fp32 [N][hin][win][cin].
@@ -197,6 +219,7 @@ typedef struct {
     int32_t batch;
     int32_t max_iters;
     int32_t only_fp32_layers;
+    int32_t share_prefix; /* 1: the candidates of a step share the forward prefix of the current scheme */
 } aiq_search_params;
 
 typedef struct {

@@ -13,7 +13,8 @@ _lib = None
 EXPORTED_SYMBOLS = (
     "aiq_status_str", "aiq_last_hip_error", "aiq_layer_ai", "aiq_quantize_weights", "aiq_quantize_weights_ex", "aiq_model_create",
     "aiq_model_create_ex", "aiq_model_is_lds_resident", "aiq_model_lds_resident_blocks", "aiq_model_destroy", "aiq_model_scheme_layers", "aiq_model_classes", "aiq_eval_workspace_bytes",
-    "aiq_eval_schemes", "aiq_profile_enable", "aiq_profile_read", "aiq_search_workspace_bytes",
+    "aiq_eval_schemes", "aiq_model_shares_prefix", "aiq_eval_shared_workspace_bytes", "aiq_eval_schemes_shared",
+    "aiq_profile_enable", "aiq_profile_read", "aiq_search_workspace_bytes",
     "aiq_search_greedy", "aiq_search_coordinate_descent", "aiq_sensitivity_workspace_bytes", "aiq_layer_sensitivity",
 )
 K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV = range(7)
@@ -24,7 +25,7 @@ _DESC_INTS = 13
 
 class _SearchParams(C.Structure):
     _fields_ = [("lam", C.c_double), ("n_bits", C.c_int32), ("bits", C.c_uint8 * 8), ("batch", C.c_int32),
-                ("max_iters", C.c_int32), ("only_fp32_layers", C.c_int32)]
+                ("max_iters", C.c_int32), ("only_fp32_layers", C.c_int32), ("share_prefix", C.c_int32)]
 
 
 class _SearchStep(C.Structure):
@@ -73,6 +74,11 @@ def load_library():
     lib.aiq_eval_schemes.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
                                      C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_size_t, C.c_void_p]
+    lib.aiq_model_shares_prefix.argtypes = [C.c_void_p]
+    lib.aiq_eval_shared_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+    lib.aiq_eval_schemes_shared.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
+                                            C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_size_t, C.c_void_p]
     lib.aiq_profile_enable.argtypes = [C.c_void_p, C.c_int32]
     lib.aiq_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double),
                                      C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -169,6 +175,7 @@ class Model:
         self._h = h
         self.lds_resident = bool(self._lib.aiq_model_is_lds_resident(h))
         self.lds_resident_blocks = int(self._lib.aiq_model_lds_resident_blocks(h))
+        self.shares_prefix = bool(self._lib.aiq_model_shares_prefix(h))
         self.L = int(self._lib.aiq_model_scheme_layers(h))
         self.classes = int(self._lib.aiq_model_classes(h))
         self._workspace = None
@@ -184,10 +191,14 @@ class Model:
         except Exception:
             pass
 
-    def workspace_bytes(self, S, chunk):
+    def workspace_bytes(self, S, chunk, shared=False):
         out = C.c_size_t(0)
-        _check(self._lib.aiq_eval_workspace_bytes(self._h, int(S), int(chunk), C.byref(out)),
-               "aiq_eval_workspace_bytes")
+        if shared:
+            _check(self._lib.aiq_eval_shared_workspace_bytes(self._h, int(S), int(chunk), C.byref(out)),
+                   "aiq_eval_shared_workspace_bytes")
+        else:
+            _check(self._lib.aiq_eval_workspace_bytes(self._h, int(S), int(chunk), C.byref(out)),
+                   "aiq_eval_workspace_bytes")
         return out.value
 
     def _get_workspace(self, nbytes, device):
@@ -198,9 +209,10 @@ class Model:
         return self._workspace
 
     def eval_schemes(self, images, schemes, chunk=1024, top1_base=None, want_logits=False, want_top1=False,
-                     out=None, stream=None):
-        """aiq_eval_schemes.  images: CUDA fp32 [N][H][W][C]; schemes: uint8 [S][L] (host).
+                     out=None, stream=None, ref_scheme=None):
+        """aiq_eval_schemes, or aiq_eval_schemes_shared when ref_scheme (uint8 [L], host) is given.
 
+        images: CUDA fp32 [N][H][W][C]; schemes: uint8 [S][L] (host).
         top1_base: CUDA int32 [N] from an earlier call (then the FP32 pass is skipped), or None.
         out: optional dict of preallocated CUDA tensors (top1_base, logits, top1, agree) to reuse.
         Returns dict(agree, top1_base, logits|None, top1|None); all CUDA tensors, not synchronised.
@@ -232,24 +244,34 @@ class Model:
             if top1 is None:
                 top1 = torch.empty((S, N), dtype=torch.int32, device=dev)
         chunk = max(1, min(int(chunk), max(N, 1)))
-        nbytes = self.workspace_bytes(S, chunk)
+        nbytes = self.workspace_bytes(S, chunk, shared=ref_scheme is not None)
         ws = self._get_workspace(nbytes, dev)
-        st = self._lib.aiq_eval_schemes(self._h, images.data_ptr(), N, sch.ctypes.data, S, chunk,
-                                        top1_base.data_ptr(), base_valid,
-                                        None if logits is None else logits.data_ptr(),
-                                        None if top1 is None else top1.data_ptr(), agree.data_ptr(),
-                                        ws.data_ptr(), ws.numel(), _stream_ptr(stream))
-        _check(st, "aiq_eval_schemes")
+        lg = None if logits is None else logits.data_ptr()
+        t1 = None if top1 is None else top1.data_ptr()
+        if ref_scheme is None:
+            st = self._lib.aiq_eval_schemes(self._h, images.data_ptr(), N, sch.ctypes.data, S, chunk,
+                                            top1_base.data_ptr(), base_valid, lg, t1, agree.data_ptr(),
+                                            ws.data_ptr(), ws.numel(), _stream_ptr(stream))
+            _check(st, "aiq_eval_schemes")
+        else:
+            ref = np.ascontiguousarray(ref_scheme, dtype=np.uint8)
+            if ref.shape != (self.L,):
+                raise AiqError(3, "aiq_eval_schemes_shared: reference scheme length differs from the model's L")
+            st = self._lib.aiq_eval_schemes_shared(self._h, images.data_ptr(), N, sch.ctypes.data, S,
+                                                   ref.ctypes.data, chunk, top1_base.data_ptr(), base_valid, lg, t1,
+                                                   agree.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(stream))
+            _check(st, "aiq_eval_schemes_shared")
         return dict(agree=agree[:S], top1_base=top1_base[:N], logits=logits, top1=top1)
 
     def search(self, desc, images, method="greedy", bits=(32, 8, 4), lam=0.9, batch=1, max_iters=0,
-               only_fp32_layers=False, chunk=1024, stream=None):
+               only_fp32_layers=False, chunk=1024, stream=None, share_prefix=True):
         """aiq_search_greedy / aiq_search_coordinate_descent.  Returns (scheme uint8[L], trace list of dicts)."""
         import torch
         d = _desc(desc)
         p = _SearchParams()
         p.lam, p.n_bits, p.batch, p.max_iters = float(lam), len(bits), int(batch), int(max_iters)
         p.only_fp32_layers = 1 if only_fp32_layers else 0
+        p.share_prefix = 1 if share_prefix else 0
         for i, b in enumerate(bits):
             p.bits[i] = int(b)
         N = images.shape[0]

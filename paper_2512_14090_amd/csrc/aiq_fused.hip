@@ -360,19 +360,57 @@ __device__ __forceinline__ const float *op_ptr(uint32_t lo, uint32_t hi)
     return reinterpret_cast<const float *>(((uint64_t)hi << 32) | lo);
 }
 
-template <int NW>
+// Copies between the two LDS regions and an image's checkpoint record: the first e0 floats of
+// region 0 and the first e1 of region 1, back to back in global memory (all multiples of 4).
+// kBatch 16-byte transfers are in flight per thread.  The caller synchronises.
+template <int NW, bool RESTORE>
+__device__ __forceinline__ void fused_checkpoint_copy(float *lds, float *g, int e0, int e1, int tid)
+{
+    constexpr int kBatch = 8;
+    floatx4 *lds4 = reinterpret_cast<floatx4 *>(lds);
+    floatx4 *g4 = reinterpret_cast<floatx4 *>(g);
+    const int n0 = e0 >> 2, n4 = (e0 + e1) >> 2;
+    for (int base = tid; base < n4; base += NW * 64 * kBatch) {
+        floatx4 v[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int i = base + u * NW * 64;
+            const int l = i < n0 ? i : i - n0 + kFusedRegionFloats / 4;
+            if (i < n4) v[u] = RESTORE ? gload4(g + (size_t)i * 4) : lds4[l];
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int i = base + u * NW * 64;
+            const int l = i < n0 ? i : i - n0 + kFusedRegionFloats / 4;
+            if (i < n4) {
+                if (RESTORE) lds4[l] = v[u];
+                else g4[i] = v[u];
+            }
+        }
+    }
+}
+
+// MODE (FusedMode): the plain kernel runs every op; the reference pass also writes the LDS
+// state out before each op that has a checkpoint; a resumed pass starts scheme s at op
+// first_op[s] from that state.  Ops before first_op[s] carry the same bit-widths in scheme s
+// and in the reference scheme, so the restored state is bit for bit what the full run of
+// scheme s would hold there and the result does not depend on the mode.
+template <int NW, int MODE>
 __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
 {
     extern __shared__ float lds[];
     __shared__ OpRT s_ops[kFusedMaxOps];
     const int tid = threadIdx.x;
     const int n = blockIdx.x, s = blockIdx.y;
+    int o0 = 0;
+    if (MODE == kFusedResume && s < a.S) o0 = __builtin_amdgcn_readfirstlane(a.first_op[s]);
+    const bool from_image = MODE != kFusedResume || o0 == 0;
 
     // the image goes to registers first so that its HBM latency overlaps the LDS clear
     constexpr int IMG_PER_THREAD = 3072 / (NW * 64);
     static_assert(3072 % (NW * 64) == 0, "image elements must divide among the threads");
     float img_r[IMG_PER_THREAD];
-    {
+    if (from_image) {
         const float *img = a.images + (size_t)n * 3072;
 #pragma unroll
         for (int q = 0; q < IMG_PER_THREAD; ++q) img_r[q] = img[tid + q * NW * 64];
@@ -398,12 +436,12 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
         s_ops[tid] = r;
     }
     __syncthreads();
-    OpRT cur = uniform_op(s_ops[0]);
+    OpRT cur = uniform_op(s_ops[o0]);
     // What has to be zero before the first read: the image plane (border and fourth component)
     // and the borders of the 34 x 34 planes the first stage writes - four in the stem's
     // destination region, the other three of the image's region.  Interiors are always written
     // before they are read; later layouts clear their own borders (zero_ring).
-    {
+    if (from_image) {
         constexpr int PIN = 34, PLANE = PIN * PIN * 4, RING = 4 * PIN - 4;
         const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};
         floatx4 *img4 = reinterpret_cast<floatx4 *>(lds + cur.src_off);
@@ -419,7 +457,7 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
         }
     }
     __syncthreads();
-    {
+    if (from_image) {
         float *plane = lds + cur.src_off;
 #pragma unroll
         for (int q = 0; q < IMG_PER_THREAD; ++q) {
@@ -428,8 +466,12 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
             const int y = pix >> 5, x = pix & 31;
             plane[((y + 1) * 34 + x + 1) * 4 + c] = img_r[q];
         }
+    } else {
+        const FusedOp &op = a.ops[o0];
+        fused_checkpoint_copy<NW, true>(lds, a.ckpt + (size_t)n * a.ckpt_stride + op.ck_off, op.ck_ext[0],
+                                        op.ck_ext[1], tid);
     }
-    OpRT nxt_raw = s_ops[a.n_ops > 1 ? 1 : 0]; // stays in flight until the next iteration needs it
+    OpRT nxt_raw = s_ops[o0 + 1 < a.n_ops ? o0 + 1 : o0]; // stays in flight until the next iteration needs it
     __syncthreads();
 
     floatx4 wr[kWeightRing];
@@ -439,8 +481,25 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
     // bias of the current dense op for this lane's four output channels; like the first weight
     // chunks it is fetched while the previous op runs (the stem reads its own)
     floatx4 bcur = floatx4{0.f, 0.f, 0.f, 0.f};
+    if (!from_image && cur.shape != 0) {
+        // no previous op has fetched the first weights and the bias of the op resumed at
+        const int ns = cur.shape >> 8;
+        const int nct = wave & (cur.shape & 255);
+        const float *w0 = op_ptr(cur.w_lo, cur.w_hi) + ((size_t)nct * ns * 64 + lane) * 4;
+#pragma unroll
+        for (int j = 0; j < kWeightRing; ++j) wr[j] = gload4(w0 + min(j, ns - 1) * 256);
+        bcur = gload4(op_ptr(cur.b_lo, cur.b_hi) + nct * 16 + (lane >> 4) * 4);
+    }
 
-    for (int o = 0; o < a.n_ops; ++o) {
+    for (int o = o0; o < a.n_ops; ++o) {
+        if (MODE == kFusedReference && o > 0) {
+            const FusedOp &op = a.ops[o];
+            if ((a.ck_mask[o >> 6] >> (o & 63)) & 1ull) {
+                fused_checkpoint_copy<NW, false>(lds, a.ckpt + (size_t)n * a.ckpt_stride + op.ck_off, op.ck_ext[0],
+                                                 op.ck_ext[1], tid);
+                __syncthreads(); // the op below overwrites what other wavefronts may still be copying
+            }
+        }
         const OpRT nxt = uniform_op(nxt_raw);
         nxt_raw = s_ops[o + 2 < a.n_ops ? o + 2 : a.n_ops - 1];
         const float *wq = op_ptr(cur.w_lo, cur.w_hi);
@@ -538,15 +597,37 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
 
 hipError_t fused_set_lds_limit()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&resnet_fused_kernel<kFusedThreads / 64>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLdsBytes);
+    constexpr int NW = kFusedThreads / 64;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&resnet_fused_kernel<NW, kFusedPlain>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLdsBytes);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&resnet_fused_kernel<NW, kFusedReference>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLdsBytes);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&resnet_fused_kernel<NW, kFusedResume>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLdsBytes);
+    return e;
 }
 
-hipError_t launch_fused(const FusedArgs &a, int s_total, hipStream_t st)
+hipError_t launch_fused(const FusedArgs &a, int s_total, FusedMode mode, hipStream_t st)
 {
+    constexpr int NW = kFusedThreads / 64;
     if (a.N == 0 || s_total == 0) return hipSuccess;
-    hipLaunchKernelGGL((resnet_fused_kernel<kFusedThreads / 64>), dim3(a.N, s_total), dim3(kFusedThreads),
-                       kFusedLdsBytes, st, a);
+    if (mode != kFusedPlain && !a.ckpt) return hipErrorInvalidValue;
+    if (mode == kFusedResume && !a.first_op) return hipErrorInvalidValue;
+    const dim3 grid(a.N, s_total), block(kFusedThreads);
+    switch (mode) {
+    case kFusedPlain:
+        hipLaunchKernelGGL((resnet_fused_kernel<NW, kFusedPlain>), grid, block, kFusedLdsBytes, st, a);
+        break;
+    case kFusedReference:
+        hipLaunchKernelGGL((resnet_fused_kernel<NW, kFusedReference>), grid, block, kFusedLdsBytes, st, a);
+        break;
+    case kFusedResume:
+        hipLaunchKernelGGL((resnet_fused_kernel<NW, kFusedResume>), grid, block, kFusedLdsBytes, st, a);
+        break;
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

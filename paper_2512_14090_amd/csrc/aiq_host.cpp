@@ -85,6 +85,8 @@ struct aiq_model {
     std::vector<FusedOp> fused_ops;
     FusedOp *fused_ops_dev = nullptr;
     double fused_flops_per_image = 0.0;
+    size_t fused_ckpt_floats = 0;     // checkpoint record of one image (0: prefix sharing not available)
+    std::vector<int> slot_op;         // scheme slot -> op that carries it
     // profiling
     bool prof_on = false;
     std::vector<hipEvent_t> ev_pool;
@@ -216,6 +218,54 @@ bool plan_fused(const std::vector<Node> &nodes, std::vector<FusedOp> &ops)
     return true;
 }
 
+// Checkpoints for prefix sharing.  A pass that resumes at op o needs every LDS float that op o
+// or a later op reads before writing it - tensors still live and the zero borders of the
+// regions later ops write into.  Per region that is covered by the prefix that reaches the
+// furthest read of any op >= o, which is what the reference pass stores before op o.  Only
+// ops that carry a scheme layer can be the first difference between two schemes.  Returns
+// the floats of one image's record, 0 if the scheme slots do not follow the op order.
+size_t plan_fused_checkpoints(std::vector<FusedOp> &ops, int L, std::vector<int> &slot_op)
+{
+    static const int in_floats[9] = {34 * 34 * 4, 18496, 18496, 18496, 10368, 10368, 10368, 6400, 6400};
+    static const int res_unpadded[9] = {0, 0, 0, 0, 32 * 16 * 16, 0, 0, 64 * 8 * 8, 0};
+    const int n = (int)ops.size();
+    slot_op.assign(L, -1);
+    int last = -1;
+    for (int o = 0; o < n; ++o) {
+        if (ops[o].slot < 0) continue;
+        if (ops[o].slot <= last || ops[o].slot >= L) return 0;
+        last = ops[o].slot;
+        slot_op[last] = o;
+    }
+    for (int v : slot_op)
+        if (v < 0) return 0;
+    int ext[2] = {0, 0};
+    std::vector<int> e0(n), e1(n);
+    for (int o = n - 1; o >= 0; --o) {
+        auto cover = [&](int off, int len) {
+            const int r = off >= kFusedRegionFloats ? 1 : 0;
+            ext[r] = std::max(ext[r], off + len - r * kFusedRegionFloats);
+        };
+        cover(ops[o].src_off, in_floats[ops[o].type]);
+        if (ops[o].res_off >= 0)
+            cover(ops[o].res_off, ops[o].res_padded ? in_floats[ops[o].type] : res_unpadded[ops[o].type]);
+        e0[o] = (ext[0] + 3) & ~3;
+        e1[o] = (ext[1] + 3) & ~3;
+    }
+    size_t total = 0;
+    for (int o = 0; o < n; ++o) {
+        ops[o].ck_off = 0;
+        ops[o].ck_ext[0] = ops[o].ck_ext[1] = 0;
+        if (o == 0 || ops[o].slot < 0) continue;
+        if (e0[o] > kFusedRegionFloats || e1[o] > kFusedRegionFloats) return 0;
+        ops[o].ck_off = (int32_t)total;
+        ops[o].ck_ext[0] = e0[o];
+        ops[o].ck_ext[1] = e1[o];
+        total += (size_t)e0[o] + e1[o];
+    }
+    return total;
+}
+
 // Marks every expand -> depthwise -> project triple whose shape the LDS-resident block kernel
 // covers and whose two hidden tensors have no other reader.  Returns the number of blocks.
 int plan_mbconv(std::vector<Node> &nodes)
@@ -312,9 +362,12 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct WorkspaceLayout {
     size_t schemes_off, top1_off, act_off, total;
     size_t buf_stride; // bytes of one activation buffer
+    // prefix sharing only (0 otherwise): reference scheme, first op per scheme, the reference
+    // pass's top-1, the checkpoint records of one chunk
+    size_t ref_off, first_op_off, ref_top1_off, ckpt_off;
 };
 
-WorkspaceLayout workspace_layout(const aiq_model *m, int S, int chunk)
+WorkspaceLayout workspace_layout(const aiq_model *m, int S, int chunk, bool shared = false)
 {
     WorkspaceLayout w{};
     size_t off = 0;
@@ -325,6 +378,17 @@ WorkspaceLayout workspace_layout(const aiq_model *m, int S, int chunk)
     w.act_off = off;
     w.buf_stride = align_up(sizeof(float) * m->buf_elems * (size_t)(S + 1) * chunk, 256);
     off += w.buf_stride * m->n_bufs;
+    if (shared && m->fused_ckpt_floats > 0) {
+        off = align_up(off, 256);
+        w.ref_off = off;
+        off = align_up(off + (size_t)std::max(m->L, 1), 256);
+        w.first_op_off = off;
+        off = align_up(off + sizeof(int32_t) * (size_t)(S + 1), 256);
+        w.ref_top1_off = off;
+        off = align_up(off + sizeof(int32_t) * (size_t)chunk, 256);
+        w.ckpt_off = off;
+        off += align_up(sizeof(float) * m->fused_ckpt_floats * (size_t)chunk, 256);
+    }
     w.total = off;
     return w;
 }
@@ -553,6 +617,7 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
             if (t == kOpC16 || t == kOpC32 || t == kOpC64) m->nodes[o].layout = kLayoutMfmaKx;
         }
         for (const Node &nd : m->nodes) m->fused_flops_per_image += nd.flops_per_image;
+        m->fused_ckpt_floats = plan_fused_checkpoints(m->fused_ops, m->L, m->slot_op);
     } else if (!(flags & AIQ_MODEL_LAYERWISE)) {
         m->mb_blocks = plan_mbconv(m->nodes);
     }
@@ -670,9 +735,16 @@ aiq_status aiq_eval_workspace_bytes(const aiq_model *m, int32_t S, int32_t chunk
     return AIQ_OK;
 }
 
-aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const uint8_t *schemes, int32_t S,
-                            int32_t chunk, int32_t *top1_base, int32_t base_valid, float *logits, int32_t *top1,
-                            int32_t *agree, void *workspace, size_t workspace_bytes, void *hip_stream)
+} // extern "C"
+
+namespace {
+
+// Scores S schemes.  ref = NULL: every scheme runs the whole network.  ref = host uint8[L]:
+// where the model supports it, the reference scheme is run once per image and scheme s
+// resumes at its first layer whose width differs from ref's; the results are the same.
+aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t *schemes, int32_t S,
+                     const uint8_t *ref, int32_t chunk, int32_t *top1_base, int32_t base_valid, float *logits,
+                     int32_t *top1, int32_t *agree, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!m || N < 0 || S < 0 || chunk < 1) return AIQ_INVALID_ARG;
     if (S > 0 && (!schemes || !agree)) return AIQ_INVALID_ARG;
@@ -680,8 +752,14 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
     if (base_valid != 0 && base_valid != 1) return AIQ_INVALID_ARG;
     for (size_t i = 0; i < (size_t)S * m->L; ++i)
         if (!bits_supported(schemes[i])) return AIQ_UNSUPPORTED_BITS;
+    if (ref)
+        for (int i = 0; i < m->L; ++i)
+            if (!bits_supported(ref[i])) return AIQ_UNSUPPORTED_BITS;
     chunk = std::min(chunk, std::max(N, 1));
-    const WorkspaceLayout wl = workspace_layout(m, S, chunk);
+    const bool shared = ref != nullptr;
+    const WorkspaceLayout wl = workspace_layout(m, S, chunk, shared);
+    // sharing needs a reference pass that can hand over its state, and something to share it with
+    const bool resume = shared && m->fused && m->fused_ckpt_floats > 0 && S > 0;
     if (N > 0 && workspace_bytes < wl.total) return AIQ_WORKSPACE_TOO_SMALL;
     if (N > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255)) return AIQ_INVALID_ARG;
 
@@ -712,6 +790,45 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
     }
     if (S > 0)
         AIQ_HIP(hipMemcpyAsync(schemes_dev, schemes, (size_t)S * m->L, hipMemcpyHostToDevice, st));
+
+    // prefix sharing: op at which every scheme leaves the reference scheme, and what the
+    // passes that start there execute
+    uint8_t *ref_dev = nullptr;
+    int32_t *first_op_dev = nullptr, *ref_top1 = nullptr;
+    float *ckpt = nullptr;
+    bool ref_is_base = false;
+    double resumed_flops_per_image = 0.0; // summed over the S schemes
+    std::vector<int32_t> first_op;
+    if (resume) {
+        ref_dev = reinterpret_cast<uint8_t *>(ws + wl.ref_off);
+        first_op_dev = reinterpret_cast<int32_t *>(ws + wl.first_op_off);
+        ref_top1 = reinterpret_cast<int32_t *>(ws + wl.ref_top1_off);
+        ckpt = reinterpret_cast<float *>(ws + wl.ckpt_off);
+        ref_is_base = true;
+        for (int i = 0; i < m->L; ++i) {
+            ref_is_base = ref_is_base && ref[i] == 32;
+            const int bi = bits_index(ref[i]);
+            if (bi > 0) {
+                const int ji = m->nodes[m->slot_op[i]].job0 + bi - 1;
+                mask.word[ji >> 6] |= 1ull << (ji & 63);
+                any = true;
+            }
+        }
+        const int n_ops = (int)m->fused_ops.size();
+        std::vector<double> suffix(n_ops + 1, 0.0);
+        for (int o = n_ops - 1; o >= 0; --o) suffix[o] = suffix[o + 1] + m->nodes[o].flops_per_image;
+        first_op.assign(S + 1, 0);
+        for (int s_ = 0; s_ < S; ++s_) {
+            int d = 0;
+            while (d < m->L && schemes[(size_t)s_ * m->L + d] == ref[d]) ++d;
+            first_op[s_] = d < m->L ? m->slot_op[d] : n_ops - 1; // identical to ref: only the last op runs again
+            resumed_flops_per_image += suffix[first_op[s_]];
+        }
+        // first_op lives on the host stack of this call: the copy below must not outlive it
+        AIQ_HIP(hipMemcpyAsync(ref_dev, ref, (size_t)m->L, hipMemcpyHostToDevice, st));
+        AIQ_HIP(hipMemcpyAsync(first_op_dev, first_op.data(), sizeof(int32_t) * (S + 1), hipMemcpyHostToDevice, st));
+        AIQ_HIP(hipStreamSynchronize(st));
+    }
     if (any) {
         double qbytes = 0.0;
         for (int ji = 0; ji < m->n_jobs; ++ji)
@@ -745,10 +862,49 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
             }
             a.top1_base = run_base ? top1_base + n0 : nullptr;
             const double work = (double)s_total * n;
-            {
+            if (resume) {
+                // reference pass: one scheme (the FP32 pass itself when ref is all-FP32)
+                FusedArgs r = a;
+                r.schemes = ref_dev;
+                r.S = ref_is_base ? 0 : 1;
+                r.logits = nullptr;
+                r.top1 = ref_top1;
+                r.top1_stride = chunk;
+                r.top1_base = ref_is_base && run_base ? top1_base + n0 : nullptr;
+                r.ckpt = ckpt;
+                r.ckpt_stride = (int64_t)m->fused_ckpt_floats;
+                double ck_floats = 0.0; // only the checkpoints some scheme resumes from are written
+                for (int s_ = 0; s_ < S; ++s_) {
+                    const int o = first_op[s_];
+                    if (o > 0 && !((r.ck_mask[o >> 6] >> (o & 63)) & 1ull)) {
+                        r.ck_mask[o >> 6] |= 1ull << (o & 63);
+                        ck_floats += m->fused_ops[o].ck_ext[0] + m->fused_ops[o].ck_ext[1];
+                    }
+                }
+                const double ck_bytes = 4.0 * ck_floats;
+                {
+                    ProfScope ps(m, st, AIQ_K_FUSED, m->fused_flops_per_image * n,
+                                 n * (4.0 * (m->nodes[0].in_elems + m->classes) + ck_bytes));
+                    AIQ_HIP(launch_fused(r, 1, kFusedReference, st));
+                }
+                a.ckpt = ckpt;
+                a.ckpt_stride = r.ckpt_stride;
+                a.first_op = first_op_dev;
+                if (ref_is_base) a.top1_base = nullptr; // written by the reference pass
+                const bool extra_base = run_base && !ref_is_base;
+                double rd_bytes = 0.0;
+                for (int s_ = 0; s_ < S; ++s_) {
+                    const FusedOp &op = m->fused_ops[first_op[s_]];
+                    rd_bytes += first_op[s_] > 0 ? 4.0 * (op.ck_ext[0] + op.ck_ext[1]) : 4.0 * m->nodes[0].in_elems;
+                }
+                ProfScope ps(m, st, AIQ_K_FUSED,
+                             (resumed_flops_per_image + (extra_base ? m->fused_flops_per_image : 0.0)) * n,
+                             n * (rd_bytes + 4.0 * m->classes * S));
+                AIQ_HIP(launch_fused(a, S + (extra_base ? 1 : 0), kFusedResume, st));
+            } else {
                 ProfScope ps(m, st, AIQ_K_FUSED, m->fused_flops_per_image * work,
                              work * 4.0 * (m->nodes[0].in_elems + m->classes));
-                AIQ_HIP(launch_fused(a, s_total, st));
+                AIQ_HIP(launch_fused(a, s_total, kFusedPlain, st));
             }
             AgreeArgs g{};
             g.top1 = a.top1;
@@ -941,6 +1097,37 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
     return AIQ_OK;
 }
 
+} // namespace
+
+extern "C" {
+
+aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const uint8_t *schemes, int32_t S,
+                            int32_t chunk, int32_t *top1_base, int32_t base_valid, float *logits, int32_t *top1,
+                            int32_t *agree, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return eval_impl(m, images, N, schemes, S, nullptr, chunk, top1_base, base_valid, logits, top1, agree, workspace,
+                     workspace_bytes, hip_stream);
+}
+
+int32_t aiq_model_shares_prefix(const aiq_model *m) { return m ? (m->fused && m->fused_ckpt_floats > 0 ? 1 : 0) : -1; }
+
+aiq_status aiq_eval_shared_workspace_bytes(const aiq_model *m, int32_t S, int32_t chunk, size_t *bytes)
+{
+    if (!m || !bytes || S < 0 || chunk < 1) return AIQ_INVALID_ARG;
+    *bytes = workspace_layout(m, S, chunk, true).total;
+    return AIQ_OK;
+}
+
+aiq_status aiq_eval_schemes_shared(aiq_model *m, const float *images, int32_t N, const uint8_t *schemes, int32_t S,
+                                   const uint8_t *ref_scheme, int32_t chunk, int32_t *top1_base, int32_t base_valid,
+                                   float *logits, int32_t *top1, int32_t *agree, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream)
+{
+    if (!m || !ref_scheme) return AIQ_INVALID_ARG;
+    return eval_impl(m, images, N, schemes, S, ref_scheme, chunk, top1_base, base_valid, logits, top1, agree,
+                     workspace, workspace_bytes, hip_stream);
+}
+
 namespace {
 
 // Shared state of one search run: device buffers carved out of the workspace and the
@@ -972,12 +1159,14 @@ struct SearchCtx {
         const double acc_loss = N > 0 ? 100.0 * (1.0 - (double)agree / (double)N) : 0.0;
         return -p->lambda * ai_v + (1.0 - p->lambda) * acc_loss;
     }
-    // scores S schemes (host [S][L]); agree_host[0..S) filled on return
-    aiq_status score(const std::vector<uint8_t> &schemes, int32_t S)
+    // scores S schemes (host [S][L]); agree_host[0..S) filled on return.  With prefix sharing the
+    // schemes of one batch resume from the forward pass of ref (host [L]), the scheme they all
+    // were derived from by changing one layer.
+    aiq_status score(const std::vector<uint8_t> &schemes, int32_t S, const uint8_t *ref)
     {
         if (S > s_max) return AIQ_WORKSPACE_TOO_SMALL;
-        aiq_status rc = aiq_eval_schemes(m, images, N, schemes.data(), S, chunk, top1_base, base_valid ? 1 : 0,
-                                         nullptr, nullptr, agree_dev, eval_ws, eval_ws_bytes, st);
+        aiq_status rc = eval_impl(m, images, N, schemes.data(), S, p->share_prefix ? ref : nullptr, chunk, top1_base,
+                                  base_valid ? 1 : 0, nullptr, nullptr, agree_dev, eval_ws, eval_ws_bytes, st);
         if (rc != AIQ_OK) return rc;
         base_valid = true;
         agree_host.assign(S, 0);
@@ -1003,7 +1192,7 @@ SearchLayout search_layout(const aiq_model *m, int32_t N, int32_t chunk, int32_t
     l.agree_off = off;
     off = align_up(off + sizeof(int32_t) * (size_t)l.s_max, 256);
     l.eval_off = off;
-    off += workspace_layout(m, l.s_max, std::min(chunk, std::max(N, 1))).total;
+    off += workspace_layout(m, l.s_max, std::min(chunk, std::max(N, 1)), true).total;
     l.total = off;
     return l;
 }
@@ -1075,7 +1264,7 @@ aiq_status aiq_search_greedy(aiq_model *m, const aiq_layer_desc *layers, int32_t
     aiq_status err = AIQ_OK;
     // start: the all-FP32 scheme agrees with itself on every image
     std::vector<uint8_t> batch(q);
-    if ((rc = c.score(batch, 1)) != AIQ_OK) return rc;
+    if ((rc = c.score(batch, 1, nullptr)) != AIQ_OK) return rc;
     double cur_ai = c.ai(q.data(), &err);
     double cur = c.loss(cur_ai, c.agree_host[0]);
     int32_t nt = 0;
@@ -1094,7 +1283,7 @@ aiq_status aiq_search_greedy(aiq_model *m, const aiq_layer_desc *layers, int32_t
                 }
         }
         if (moves.empty()) break;
-        if ((rc = c.score(batch, (int32_t)moves.size())) != AIQ_OK) return rc;
+        if ((rc = c.score(batch, (int32_t)moves.size(), q.data())) != AIQ_OK) return rc;
         int best = -1;
         double best_delta = 0.0, best_ai = 0.0;
         for (size_t k = 0; k < moves.size(); ++k) {
@@ -1131,7 +1320,7 @@ aiq_status aiq_search_coordinate_descent(aiq_model *m, const aiq_layer_desc *lay
     std::vector<uint8_t> q(L, params->bits[0]);
     aiq_status err = AIQ_OK;
     std::vector<uint8_t> batch(q);
-    if ((rc = c.score(batch, 1)) != AIQ_OK) return rc;
+    if ((rc = c.score(batch, 1, nullptr)) != AIQ_OK) return rc;
     double cur_ai = c.ai(q.data(), &err);
     double cur = c.loss(cur_ai, c.agree_host[0]);
     int32_t nt = 0;
@@ -1148,7 +1337,7 @@ aiq_status aiq_search_coordinate_descent(aiq_model *m, const aiq_layer_desc *lay
                     batch.insert(batch.end(), q.begin(), q.end());
                     batch[batch.size() - L + i] = params->bits[b];
                 }
-            if ((rc = c.score(batch, (int32_t)others.size())) != AIQ_OK) return rc;
+            if ((rc = c.score(batch, (int32_t)others.size(), q.data())) != AIQ_OK) return rc;
             int best = -1;
             double best_val = 0.0, best_ai = 0.0;
             for (size_t k = 0; k < others.size(); ++k) {
@@ -1201,8 +1390,10 @@ aiq_status aiq_layer_sensitivity(aiq_model *m, const float *images, int32_t N, i
     std::vector<uint8_t> schemes((size_t)S * L, 32);
     for (int i = 0; i < L; ++i)
         for (int k = 0; k < n_bits; ++k) schemes[((size_t)i * n_bits + k) * L + i] = bits[k];
-    aiq_status rc = aiq_eval_schemes(m, images, N, schemes.data(), S, chunk, top1_base, 0, nullptr, nullptr, agree_dev,
-                                     ws + lay.eval_off, workspace_bytes - lay.eval_off, st);
+    // every candidate differs from the all-FP32 scheme in one layer: share its forward prefix
+    const std::vector<uint8_t> ref(L, 32);
+    aiq_status rc = eval_impl(m, images, N, schemes.data(), S, ref.data(), chunk, top1_base, 0, nullptr, nullptr,
+                              agree_dev, ws + lay.eval_off, workspace_bytes - lay.eval_off, st);
     if (rc != AIQ_OK) return rc;
     AIQ_HIP(hipMemcpyAsync(agree_out, agree_dev, sizeof(int32_t) * S, hipMemcpyDeviceToHost, st));
     AIQ_HIP(hipStreamSynchronize(st));

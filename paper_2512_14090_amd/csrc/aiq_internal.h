@@ -197,7 +197,11 @@ struct FusedOp {
     int32_t res_padded; // residual region has the padded layout of the destination
     int32_t zero_ring; // destination gets a new layout: clear its border first
     int32_t classes;   // head only
-    int32_t pad_[3];
+    // Checkpoint taken before this op in a reference pass and restored by a pass that starts
+    // here: the first ck_ext[r] floats of LDS region r, stored back to back at float offset
+    // ck_off of the image's checkpoint record.  ck_ext = {0, 0}: no checkpoint for this op.
+    int32_t ck_off;
+    int32_t ck_ext[2];
 };
 
 constexpr int kFusedThreads = 512;
@@ -216,9 +220,20 @@ struct FusedArgs {
     int32_t *top1;
     int64_t top1_stride;
     int32_t *top1_base;
+    float *ckpt;               // checkpoint records [N][ckpt_stride] (reference and resumed passes)
+    int64_t ckpt_stride;       // floats per image
+    const int32_t *first_op;   // resumed pass: [S] op at which scheme s starts (0 = from the image)
+    uint64_t ck_mask[2];       // reference pass: bit o set = write the checkpoint of op o
 };
 
-hipError_t launch_fused(const FusedArgs &a, int s_total, hipStream_t st);
+// How a launch of the LDS-resident kernel treats the checkpoints.
+enum FusedMode : int32_t {
+    kFusedPlain = 0,     // every (scheme, image) runs the whole network
+    kFusedReference = 1, // whole network, LDS state written out before every op that has a checkpoint
+    kFusedResume = 2     // scheme s starts at op first_op[s] from the reference pass's checkpoint
+};
+
+hipError_t launch_fused(const FusedArgs &a, int s_total, FusedMode mode, hipStream_t st);
 hipError_t fused_set_lds_limit();
 
 } // namespace aiq

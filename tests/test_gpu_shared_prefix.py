@@ -1,0 +1,173 @@
+"""GPU: scoring with a shared forward prefix (aiq_eval_schemes_shared).
+
+The contract is exact: every output equals, bit for bit, what aiq_eval_schemes returns for
+the same schemes.  The tests therefore compare the two entry points element by element,
+on candidate batches with the structure of the search steps (one layer changed against a
+reference scheme) and on batches that have nothing to do with the reference; one case is
+also checked against the oracle so that the pair cannot be wrong together.
+"""
+import numpy as np
+import pytest
+
+from parity import check_eval
+
+pytestmark = pytest.mark.gpu
+
+ALPHABET = np.array([32, 16, 8, 6, 4, 2], dtype=np.uint8)
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2512_14090_amd as aiq
+    import oracle
+    import synth
+    aiq.load_library()
+    return dict(torch=torch, aiq=aiq, oracle=oracle, synth=synth)
+
+
+def _single_layer_moves(ref, widths):
+    """Every scheme that differs from ref in exactly one layer, taking the given widths."""
+    rows = []
+    for i in range(ref.shape[0]):
+        for b in widths:
+            if b != ref[i]:
+                q = ref.copy()
+                q[i] = b
+                rows.append(q)
+    return np.ascontiguousarray(np.stack(rows))
+
+
+def _both(env, m, img, schemes, ref, chunk, top1_base=None):
+    torch = env["torch"]
+    outs = []
+    for r in (None, ref):
+        tb = None if top1_base is None else top1_base.clone()
+        o = m.eval_schemes(img, schemes, chunk=chunk, want_logits=True, want_top1=True, top1_base=tb, ref_scheme=r)
+        torch.cuda.synchronize()
+        outs.append({k: v.cpu().numpy() for k, v in o.items()})
+    return outs
+
+
+def _assert_identical(plain, shared):
+    for k in ("agree", "top1_base", "top1"):
+        np.testing.assert_array_equal(plain[k], shared[k], err_msg=k)
+    # logits compared as bit patterns: equal floats, and no NaN slipping through
+    np.testing.assert_array_equal(plain["logits"].view(np.uint32), shared["logits"].view(np.uint32))
+
+
+@pytest.mark.parametrize("blocks,n,chunk", [(1, 70, 32), (3, 150, 64), (3, 33, 1024)])
+def test_single_layer_moves_from_fp32(env, blocks, n, chunk):
+    """The first greedy step / the sensitivity sweep: reference all-FP32, the FP32 pass requested."""
+    torch, aiq, synth = env["torch"], env["aiq"], env["synth"]
+    wl = synth.make_workload(0 if blocks == 1 else 2, n_images=n)
+    L = wl["L"]
+    ref = np.full(L, 32, dtype=np.uint8)
+    schemes = _single_layer_moves(ref, (8, 4))
+    print(f"shared prefix, fp32 reference: blocks={blocks} S={schemes.shape[0]} N={n} chunk={chunk}", flush=True)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    assert m.lds_resident and m.shares_prefix
+    img = torch.from_numpy(wl["images"]).cuda()
+    plain, shared = _both(env, m, img, schemes, ref, chunk)
+    m.close()
+    _assert_identical(plain, shared)
+
+
+@pytest.mark.parametrize("base_valid", [False, True])
+def test_moves_from_a_mixed_reference(env, base_valid):
+    """A later search step: the reference is a mixed scheme; the batch also holds the reference itself,
+    schemes unrelated to it and one that differs in the first layer only."""
+    torch, aiq, synth = env["torch"], env["aiq"], env["synth"]
+    wl = synth.make_workload(1, n_images=97)
+    L = wl["L"]
+    rng = np.random.Generator(np.random.PCG64(77))
+    ref = rng.choice(ALPHABET, size=L).astype(np.uint8)
+    first = ref.copy()
+    first[0] = 2 if ref[0] != 2 else 4
+    schemes = np.concatenate([_single_layer_moves(ref, (16, 4)), ref[None, :], first[None, :],
+                              rng.choice(ALPHABET, size=(3, L)).astype(np.uint8)])
+    schemes = np.ascontiguousarray(schemes[rng.permutation(schemes.shape[0])])
+    print(f"shared prefix, mixed reference {ref.tolist()}: S={schemes.shape[0]} base_valid={base_valid}", flush=True)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    img = torch.from_numpy(wl["images"]).cuda()
+    tb = None
+    if base_valid:
+        r0 = m.eval_schemes(img, schemes[:0], chunk=40)
+        torch.cuda.synchronize()
+        tb = r0["top1_base"]
+    plain, shared = _both(env, m, img, schemes, ref, 40, top1_base=tb)
+    m.close()
+    _assert_identical(plain, shared)
+
+
+def test_shared_against_oracle(env):
+    """The shared path on its own against the oracle, to the bars of the plain path."""
+    torch, aiq, oracle, synth = env["torch"], env["aiq"], env["oracle"], env["synth"]
+    wl = synth.make_workload(0, n_images=48)
+    L = wl["L"]
+    ref = np.full(L, 32, dtype=np.uint8)
+    ref[2] = 8
+    schemes = _single_layer_moves(ref, (32, 4))
+    print(f"shared prefix vs oracle: S={schemes.shape[0]}", flush=True)
+    want = oracle.eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    img = torch.from_numpy(wl["images"]).cuda()
+    o = m.eval_schemes(img, schemes, chunk=20, want_logits=True, want_top1=True, ref_scheme=ref)
+    torch.cuda.synchronize()
+    m.close()
+    check_eval({k: v.cpu().numpy() for k, v in o.items()}, want, 48)
+
+
+def test_empty_batches_and_errors(env):
+    torch, aiq, synth = env["torch"], env["aiq"], env["synth"]
+    wl = synth.make_workload(0, n_images=9)
+    L = wl["L"]
+    ref = np.full(L, 32, dtype=np.uint8)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    img = torch.from_numpy(wl["images"]).cuda()
+    # no schemes: only the FP32 pass runs
+    a = m.eval_schemes(img, np.zeros((0, L), dtype=np.uint8), chunk=4)
+    b = m.eval_schemes(img, np.zeros((0, L), dtype=np.uint8), chunk=4, ref_scheme=ref)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(a["top1_base"].cpu().numpy(), b["top1_base"].cpu().numpy())
+    # no images
+    c = m.eval_schemes(img[:0], _single_layer_moves(ref, (4,)), ref_scheme=ref)
+    torch.cuda.synchronize()
+    assert int(c["agree"].sum()) == 0
+    bad = ref.copy()
+    bad[1] = 7
+    with pytest.raises(aiq.AiqError) as e:
+        m.eval_schemes(img, ref[None, :], ref_scheme=bad)
+    assert e.value.code == 2
+    m.close()
+
+
+def test_models_without_sharing_give_the_plain_result(env):
+    """A model the LDS-resident kernel does not cover scores every scheme whole; the entry point still works."""
+    torch, aiq, synth = env["torch"], env["aiq"], env["synth"]
+    wl = synth.make_workload(0, n_images=21)
+    L = wl["L"]
+    ref = np.full(L, 32, dtype=np.uint8)
+    ref[1] = 4
+    schemes = _single_layer_moves(ref, (8,))
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=True)
+    assert not m.shares_prefix
+    img = torch.from_numpy(wl["images"]).cuda()
+    plain, shared = _both(env, m, img, schemes, ref, 8)
+    m.close()
+    _assert_identical(plain, shared)
+
+
+@pytest.mark.parametrize("method", ["greedy", "cd"])
+def test_search_is_unchanged_by_sharing(env, method):
+    torch, aiq, synth = env["torch"], env["aiq"], env["synth"]
+    wl = synth.make_workload(0, n_images=64)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    img = torch.from_numpy(wl["images"]).cuda()
+    print(f"search {method} with and without prefix sharing", flush=True)
+    q0, t0 = m.search(wl["desc"], img, method=method, bits=(32, 8, 4), chunk=48, share_prefix=False)
+    q1, t1 = m.search(wl["desc"], img, method=method, bits=(32, 8, 4), chunk=48, share_prefix=True)
+    m.close()
+    np.testing.assert_array_equal(q0, q1)
+    assert t0 == t1
