@@ -175,8 +175,11 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
  * scheme: it is run once per image, and scheme s resumes at its first layer whose width
  * differs from ref_scheme's.  Every output is bit for bit what aiq_eval_schemes returns
  * for the same arguments; schemes need not be related to ref_scheme (a scheme that differs
- * in its first layer simply runs whole).  Models for which aiq_model_shares_prefix is 0 run
- * every scheme whole.  workspace >= aiq_eval_shared_workspace_bytes(m, S, chunk); other
+ * in its first layer simply runs whole).  The LDS-resident ResNet kernel hands its state over
+ * through per-layer checkpoints of one workgroup's LDS; the layer-by-layer kernels keep the
+ * reference pass's activations per layer and launch each layer only for the schemes that
+ * have left the reference by then.  Models for which aiq_model_shares_prefix is 0 (none at
+ * present) run every scheme whole.  workspace >= aiq_eval_shared_workspace_bytes(m, S, chunk); other
  * arguments, ownership and errors as for aiq_eval_schemes (ref_scheme NULL: INVALID_ARG).
  */
 int32_t aiq_model_shares_prefix(const aiq_model *m); /* 1, 0, or -1 for a NULL model */

@@ -87,6 +87,10 @@ struct aiq_model {
     double fused_flops_per_image = 0.0;
     size_t fused_ckpt_floats = 0;     // checkpoint record of one image (0: prefix sharing not available)
     std::vector<int> slot_op;         // scheme slot -> op that carries it
+    // layer-by-layer path: outputs of a reference pass kept per node (prefix sharing)
+    std::vector<int> slot_node;       // scheme slot -> node that carries it
+    std::vector<size_t> ref_node_off; // element offset of a node's output in one image's record
+    size_t ref_act_elems = 0;         // elements of one image's record
     // profiling
     bool prof_on = false;
     std::vector<hipEvent_t> ev_pool;
@@ -364,7 +368,7 @@ struct WorkspaceLayout {
     size_t buf_stride; // bytes of one activation buffer
     // prefix sharing only (0 otherwise): reference scheme, first op per scheme, the reference
     // pass's top-1, the checkpoint records of one chunk
-    size_t ref_off, first_op_off, ref_top1_off, ckpt_off;
+    size_t ref_off, first_op_off, ref_top1_off, sorted_off, ckpt_off;
 };
 
 WorkspaceLayout workspace_layout(const aiq_model *m, int S, int chunk, bool shared = false)
@@ -378,16 +382,18 @@ WorkspaceLayout workspace_layout(const aiq_model *m, int S, int chunk, bool shar
     w.act_off = off;
     w.buf_stride = align_up(sizeof(float) * m->buf_elems * (size_t)(S + 1) * chunk, 256);
     off += w.buf_stride * m->n_bufs;
-    if (shared && m->fused_ckpt_floats > 0) {
+    if (shared && (m->fused_ckpt_floats > 0 || !m->fused)) {
         off = align_up(off, 256);
         w.ref_off = off;
         off = align_up(off + (size_t)std::max(m->L, 1), 256);
-        w.first_op_off = off;
-        off = align_up(off + sizeof(int32_t) * (size_t)(S + 1), 256);
+        w.first_op_off = off; // layer-by-layer path: the row map, S + 2 entries
+        off = align_up(off + sizeof(int32_t) * (size_t)(S + 2), 256);
         w.ref_top1_off = off;
         off = align_up(off + sizeof(int32_t) * (size_t)chunk, 256);
-        w.ckpt_off = off;
-        off += align_up(sizeof(float) * m->fused_ckpt_floats * (size_t)chunk, 256);
+        w.sorted_off = off;
+        if (!m->fused) off = align_up(off + (size_t)(S + 1) * std::max(m->L, 1), 256);
+        w.ckpt_off = off; // layer-by-layer path: the reference pass's activations
+        off += align_up(sizeof(float) * (m->fused ? m->fused_ckpt_floats : m->ref_act_elems) * (size_t)chunk, 256);
     }
     w.total = off;
     return w;
@@ -652,6 +658,15 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
         m->buf_elems = std::max(m->buf_elems, m->nodes[l].out_elems);
     }
     m->n_bufs = m->fused ? 0 : (int)owner.size();
+    m->slot_node.assign(m->L, -1);
+    m->ref_node_off.assign(n_layers, 0);
+    for (int l = 0; l < n_layers; ++l) {
+        if (layers[l].scheme_slot >= 0) m->slot_node[layers[l].scheme_slot] = l;
+        if (!m->fused && m->nodes[l].buf >= 0) {
+            m->ref_node_off[l] = m->ref_act_elems;
+            m->ref_act_elems += (m->nodes[l].out_elems + 63) / 64 * 64; // 256-byte aligned records
+        }
+    }
 
     // device copies, bank slots, quantize job table
     auto fail = [&](aiq_status code) {
@@ -738,6 +753,22 @@ aiq_status aiq_eval_workspace_bytes(const aiq_model *m, int32_t S, int32_t chunk
 } // extern "C"
 
 namespace {
+
+// What one launch of a node reads and writes: pointers for its first scheme and the distance
+// (in elements) between consecutive schemes; distance 0 = all schemes share one copy.
+struct NodeIO {
+    const float *in;
+    size_t in_stride;
+    float *out;
+    size_t out_stride;
+    const float *res;
+    size_t res_stride;
+    const uint8_t *schemes;  // device [S][L], first scheme of the launch
+    int S;                   // scheme rows; launch indices >= S run all-FP32 (the base pass)
+    int s_total;             // launch extent along the scheme axis
+    const int32_t *row_map;  // classifier: output row of launch index i (-1: the FP32 pass), or nullptr = i
+    int32_t *top1_base_out;  // classifier: where the FP32 pass writes its top-1, or nullptr
+};
 
 // Scores S schemes.  ref = NULL: every scheme runs the whole network.  ref = host uint8[L]:
 // where the model supports it, the reference scheme is run once per image and scheme s
@@ -829,6 +860,59 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
         AIQ_HIP(hipMemcpyAsync(first_op_dev, first_op.data(), sizeof(int32_t) * (S + 1), hipMemcpyHostToDevice, st));
         AIQ_HIP(hipStreamSynchronize(st));
     }
+    // The same on the layer-by-layer path: the rows (schemes, plus the FP32 pass when it has to
+    // run and is not the reference itself) are sorted by the node at which they leave the
+    // reference, so that the rows a node has to compute are always a prefix of the sorted order.
+    const bool share_nodes = shared && !m->fused && S > 0;
+    uint8_t *sorted_dev = nullptr;
+    int32_t *row_map_dev = nullptr;
+    float *ref_act = nullptr;
+    int S_rows = 0;
+    std::vector<int> active;
+    const std::vector<size_t> &ref_node_off = m->ref_node_off;
+    if (share_nodes) {
+        ref_dev = reinterpret_cast<uint8_t *>(ws + wl.ref_off);
+        row_map_dev = reinterpret_cast<int32_t *>(ws + wl.first_op_off);
+        sorted_dev = reinterpret_cast<uint8_t *>(ws + wl.sorted_off);
+        ref_act = reinterpret_cast<float *>(ws + wl.ckpt_off);
+        const int n_nodes = (int)m->nodes.size();
+        ref_is_base = true;
+        for (int i = 0; i < m->L; ++i) {
+            ref_is_base = ref_is_base && ref[i] == 32;
+            const int bi = bits_index(ref[i]);
+            if (bi > 0) {
+                const int ji = m->nodes[m->slot_node[i]].job0 + bi - 1;
+                mask.word[ji >> 6] |= 1ull << (ji & 63);
+                any = true;
+            }
+        }
+        std::vector<std::pair<int, int>> rows; // (first node, original row; -1 = the FP32 pass)
+        if (run_base && !ref_is_base) rows.emplace_back(0, -1);
+        for (int s_ = 0; s_ < S; ++s_) {
+            int d = 0;
+            while (d < m->L && schemes[(size_t)s_ * m->L + d] == ref[d]) ++d;
+            int f = d < m->L ? m->slot_node[d] : n_nodes - 1; // identical to ref: only the classifier runs again
+            while (m->nodes[f].mb_role == 2) --f;             // a block runs from its expand node
+            rows.emplace_back(f, s_);
+        }
+        std::stable_sort(rows.begin(), rows.end(),
+                         [](const std::pair<int, int> &x, const std::pair<int, int> &y) { return x.first < y.first; });
+        S_rows = (int)rows.size();
+        std::vector<uint8_t> sorted((size_t)S_rows * m->L, 32);
+        std::vector<int32_t> row_map(S_rows + 1, -1);
+        active.assign(n_nodes, 0);
+        for (int i = 0; i < S_rows; ++i) {
+            row_map[i] = rows[i].second;
+            if (rows[i].second >= 0)
+                std::memcpy(&sorted[(size_t)i * m->L], schemes + (size_t)rows[i].second * m->L, m->L);
+            ++active[rows[i].first];
+        }
+        for (int l = 1; l < n_nodes; ++l) active[l] += active[l - 1];
+        AIQ_HIP(hipMemcpyAsync(ref_dev, ref, (size_t)m->L, hipMemcpyHostToDevice, st));
+        AIQ_HIP(hipMemcpyAsync(sorted_dev, sorted.data(), sorted.size(), hipMemcpyHostToDevice, st));
+        AIQ_HIP(hipMemcpyAsync(row_map_dev, row_map.data(), sizeof(int32_t) * row_map.size(), hipMemcpyHostToDevice, st));
+        AIQ_HIP(hipStreamSynchronize(st)); // the host vectors above end with this call
+    }
     if (any) {
         double qbytes = 0.0;
         for (int ji = 0; ji < m->n_jobs; ++ji)
@@ -837,6 +921,166 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
         ProfScope ps(m, st, AIQ_K_QUANTIZE, 0.0, qbytes);
         AIQ_HIP(launch_quantize_batch(m->jobs_dev, m->block_job_dev, m->n_quant_blocks, mask, st));
     }
+
+    // One node (or one LDS-resident block, at its expand node) for the schemes the launch covers.
+    auto launch_node = [&](size_t l, const NodeIO &io, int n, int n0) -> aiq_status {
+        const Node &nd = m->nodes[l];
+        const aiq_layer_desc &d = nd.d;
+        const double work = (double)io.s_total * n;
+        if (nd.mb_role == 2) return AIQ_OK; // computed by the block kernel launched at its expand node
+        if (nd.mb_role == 1) {
+            const Node &dwn = m->nodes[l + 1], &pjn = m->nodes[l + 2];
+            MbArgs a{};
+            a.in = io.in;
+            a.out = io.out;
+            for (int b = 0; b < kNumBits; ++b) {
+                a.bank_e[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+                a.bank_d[b] = dwn.bank[b] ? dwn.bank[b] : dwn.bank[0];
+                a.bank_p[b] = pjn.bank[b] ? pjn.bank[b] : pjn.bank[0];
+            }
+            a.bias_e = nd.bias;
+            a.bias_d = dwn.bias;
+            a.bias_p = pjn.bias;
+            a.schemes = io.schemes;
+            a.in_scheme_stride = io.in_stride;
+            a.out_scheme_stride = io.out_stride;
+            a.S = io.S;
+            a.L = m->L;
+            a.slot_e = d.scheme_slot;
+            a.slot_d = dwn.d.scheme_slot;
+            a.slot_p = pjn.d.scheme_slot;
+            a.N = n;
+            a.act_e = d.act;
+            a.act_d = dwn.d.act;
+            a.act_p = pjn.d.act;
+            const double flops = nd.flops_per_image + dwn.flops_per_image + pjn.flops_per_image;
+            const double bytes = 4.0 * (nd.in_elems + pjn.out_elems + (pjn.d.residual >= 0 ? pjn.out_elems : 0));
+            ProfScope ps(m, st, AIQ_K_MBCONV, flops * work, bytes * work);
+            AIQ_HIP(launch_mbconv(nd.mb_shape, a, io.s_total, st));
+        } else if (d.kind == 0 && d.kh == 1 && d.stride == 1 && d.input >= 0) {
+            // 1x1 stride 1: flat pixel axis
+            const ConvPlan &p = nd.plan;
+            PointwiseArgs a{};
+            a.in = io.in;
+            a.out = io.out;
+            a.res = io.res;
+            a.bias = nd.bias;
+            for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+            a.schemes = io.schemes;
+            a.in_scheme_stride = io.in_stride;
+            a.out_scheme_stride = io.out_stride;
+            a.res_scheme_stride = io.res_stride;
+            a.S = io.S;
+            a.L = m->L;
+            a.slot = d.scheme_slot;
+            a.P = n * nd.hout * nd.wout;
+            a.Cin = d.cin;
+            a.Cout = d.cout;
+            a.act = d.act;
+            a.CB = p.CB;
+            a.CKC = p.CKC;
+            a.PS = p.PS;
+            a.wave_px_split = p.wave_px_split;
+            a.cout_tiles = p.cout_tiles;
+            const int tile_px = 64 * p.wave_px_split;
+            const size_t lds = sizeof(float) * (size_t)tile_px * p.PS;
+            ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+            AIQ_HIP(launch_pointwise(a, p.nt, lds,
+                                     dim3((unsigned)((a.P + tile_px - 1) / tile_px), p.grid_y, io.s_total), st));
+        } else if (d.kind == 0) {
+            const ConvPlan &p = nd.plan;
+            ConvArgs a{};
+            a.in = io.in;
+            a.out = io.out;
+            a.res = io.res;
+            a.bias = nd.bias;
+            for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+            a.schemes = io.schemes;
+            a.in_scheme_stride = io.in_stride;
+            a.out_scheme_stride = io.out_stride;
+            a.res_scheme_stride = io.res_stride;
+            a.S = io.S;
+            a.L = m->L;
+            a.slot = d.scheme_slot;
+            a.N = n;
+            a.Hin = d.hin;
+            a.Win = d.win;
+            a.Cin = d.cin;
+            a.Hout = nd.hout;
+            a.Wout = nd.wout;
+            a.Cout = d.cout;
+            a.act = d.act;
+            a.R = p.R;
+            a.G = p.G;
+            a.regions_per_image = p.regions_per_image;
+            a.CB = p.CB;
+            a.CKC = p.CKC;
+            a.RIN = p.RIN;
+            a.LW = p.LW;
+            a.PS = p.PS;
+            a.wave_px_split = p.wave_px_split;
+            a.cout_tiles = p.cout_tiles;
+            a.div_lw = make_fastdiv(p.LW);
+            a.div_rin = make_fastdiv(p.RIN);
+            a.div_wout = make_fastdiv(nd.wout);
+            a.div_rw = make_fastdiv(p.R * nd.wout);
+            const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
+            ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+            AIQ_HIP(launch_conv(a, d.kh, d.stride, p.nt, p.lds_bytes, dim3(gx, p.grid_y, io.s_total), st));
+        } else if (d.kind == 1) {
+            DepthwiseArgs a{};
+            a.in = io.in;
+            a.out = io.out;
+            a.bias = nd.bias;
+            for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+            a.schemes = io.schemes;
+            a.in_scheme_stride = io.in_stride;
+            a.out_scheme_stride = io.out_stride;
+            a.S = io.S;
+            a.L = m->L;
+            a.slot = d.scheme_slot;
+            a.N = n;
+            a.Hin = d.hin;
+            a.Win = d.win;
+            a.C = d.cin;
+            a.Hout = nd.hout;
+            a.Wout = nd.wout;
+            a.stride = d.stride;
+            a.act = d.act;
+            a.div_c4 = make_fastdiv(d.cin / 4);
+            ProfScope ps(m, st, AIQ_K_DEPTHWISE, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+            AIQ_HIP(launch_depthwise(a, io.s_total, st));
+        } else {
+            HeadArgs a{};
+            a.in = io.in;
+            a.bias = nd.bias;
+            for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+            a.schemes = io.schemes;
+            a.in_scheme_stride = io.in_stride;
+            a.S = io.S;
+            a.L = m->L;
+            a.slot = d.scheme_slot;
+            a.N = n;
+            a.HW = d.hin * d.win;
+            a.C = d.cin;
+            a.classes = d.cout;
+            a.logits = logits;
+            a.logits_n = N;
+            a.n0 = n0;
+            if (top1) {
+                a.top1 = top1 + n0;
+                a.top1_stride = N;
+            } else {
+                a.top1 = top1_tmp;
+                a.top1_stride = chunk;
+            }
+            a.top1_base = io.top1_base_out;
+            a.row_map = io.row_map;
+            ProfScope ps(m, st, AIQ_K_HEAD, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+            AIQ_HIP(launch_head(a, io.s_total, st));
+        }
+        return AIQ_OK;
+    };
 
     for (int n0 = 0; n0 < N; n0 += chunk) {
         const int n = std::min(chunk, N - n0);
@@ -917,181 +1161,100 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
             AIQ_HIP(launch_agree(g, st));
             continue;
         }
-        for (size_t l = 0; l < m->nodes.size(); ++l) {
-            const Node &nd = m->nodes[l];
-            const aiq_layer_desc &d = nd.d;
-            const float *in;
-            size_t in_stride;
-            if (d.input < 0) {
-                in = images + (size_t)n0 * nd.in_elems;
-                in_stride = 0;
-            } else {
-                in = buf_ptr(m->nodes[d.input].buf);
-                in_stride = (size_t)n * nd.in_elems;
+        if (!share_nodes) {
+            NodeIO io{};
+            io.schemes = schemes_dev;
+            io.S = S;
+            io.s_total = s_total;
+            io.top1_base_out = run_base ? top1_base + n0 : nullptr;
+            for (size_t l = 0; l < m->nodes.size(); ++l) {
+                const Node &nd = m->nodes[l];
+                io.in = nd.d.input < 0 ? images + (size_t)n0 * nd.in_elems : buf_ptr(m->nodes[nd.d.input].buf);
+                io.in_stride = nd.d.input < 0 ? 0 : (size_t)n * nd.in_elems;
+                const Node &on = nd.mb_role == 1 ? m->nodes[l + 2] : nd; // a block writes its project node's output
+                io.out = on.buf >= 0 ? buf_ptr(on.buf) : nullptr;
+                io.out_stride = (size_t)n * on.out_elems;
+                io.res = nd.d.residual >= 0 ? buf_ptr(m->nodes[nd.d.residual].buf) : nullptr;
+                io.res_stride = io.out_stride;
+                aiq_status rc = launch_node(l, io, n, n0);
+                if (rc != AIQ_OK) return rc;
             }
-            const double work = (double)s_total * n;
-            if (nd.mb_role == 2) continue; // computed by the block kernel launched at its expand node
-            if (nd.mb_role == 1) {
-                const Node &dwn = m->nodes[l + 1], &pjn = m->nodes[l + 2];
-                MbArgs a{};
-                a.in = in;
-                a.out = buf_ptr(pjn.buf);
-                for (int b = 0; b < kNumBits; ++b) {
-                    a.bank_e[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
-                    a.bank_d[b] = dwn.bank[b] ? dwn.bank[b] : dwn.bank[0];
-                    a.bank_p[b] = pjn.bank[b] ? pjn.bank[b] : pjn.bank[0];
-                }
-                a.bias_e = nd.bias;
-                a.bias_d = dwn.bias;
-                a.bias_p = pjn.bias;
-                a.schemes = schemes_dev;
-                a.in_scheme_stride = in_stride;
-                a.out_scheme_stride = (size_t)n * pjn.out_elems;
-                a.S = S;
-                a.L = m->L;
-                a.slot_e = d.scheme_slot;
-                a.slot_d = dwn.d.scheme_slot;
-                a.slot_p = pjn.d.scheme_slot;
-                a.N = n;
-                a.act_e = d.act;
-                a.act_d = dwn.d.act;
-                a.act_p = pjn.d.act;
-                const double flops = nd.flops_per_image + dwn.flops_per_image + pjn.flops_per_image;
-                const double bytes = 4.0 * (nd.in_elems + pjn.out_elems + (pjn.d.residual >= 0 ? pjn.out_elems : 0));
-                ProfScope ps(m, st, AIQ_K_MBCONV, flops * work, bytes * work);
-                AIQ_HIP(launch_mbconv(nd.mb_shape, a, s_total, st));
-                continue;
+        } else {
+            // ---- reference pass: every node once, outputs kept per node
+            auto ref_ptr = [&](int node) { return ref_act + ref_node_off[node] * (size_t)chunk; };
+            const bool ref_head = ref_is_base && run_base; // its top-1 is the FP32 pass's
+            NodeIO io{};
+            io.schemes = ref_dev;
+            io.S = 1;
+            io.s_total = 1;
+            io.row_map = row_map_dev + S_rows; // a single -1: the row of the FP32 pass
+            io.top1_base_out = ref_head ? top1_base + n0 : nullptr;
+            for (size_t l = 0; l < m->nodes.size(); ++l) {
+                const Node &nd = m->nodes[l];
+                if (nd.d.kind == 2 && !ref_head) continue;
+                io.in = nd.d.input < 0 ? images + (size_t)n0 * nd.in_elems : ref_ptr(nd.d.input);
+                io.in_stride = 0;
+                const int on = nd.mb_role == 1 ? (int)l + 2 : (int)l;
+                io.out = m->nodes[on].buf >= 0 ? ref_ptr(on) : nullptr;
+                io.out_stride = 0;
+                io.res = nd.d.residual >= 0 ? ref_ptr(nd.d.residual) : nullptr;
+                io.res_stride = 0;
+                aiq_status rc = launch_node(l, io, n, n0);
+                if (rc != AIQ_OK) return rc;
             }
-            if (d.kind == 0 && d.kh == 1 && d.stride == 1 && d.input >= 0) {
-                // 1x1 stride 1: flat pixel axis
-                const ConvPlan &p = nd.plan;
-                PointwiseArgs a{};
-                a.in = in;
-                a.out = buf_ptr(nd.buf);
-                a.res = d.residual >= 0 ? buf_ptr(m->nodes[d.residual].buf) : nullptr;
-                a.bias = nd.bias;
-                for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
-                a.schemes = schemes_dev;
-                a.in_scheme_stride = in_stride;
-                a.out_scheme_stride = (size_t)n * nd.out_elems;
-                a.S = S;
-                a.L = m->L;
-                a.slot = d.scheme_slot;
-                a.P = n * nd.hout * nd.wout;
-                a.Cin = d.cin;
-                a.Cout = d.cout;
-                a.act = d.act;
-                a.CB = p.CB;
-                a.CKC = p.CKC;
-                a.PS = p.PS;
-                a.wave_px_split = p.wave_px_split;
-                a.cout_tiles = p.cout_tiles;
-                const int tile_px = 64 * p.wave_px_split;
-                const size_t lds = sizeof(float) * (size_t)tile_px * p.PS;
-                ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);
-                AIQ_HIP(launch_pointwise(a, p.nt, lds, dim3((unsigned)((a.P + tile_px - 1) / tile_px), p.grid_y, s_total),
-                                         st));
-            } else if (d.kind == 0) {
-                const ConvPlan &p = nd.plan;
-                ConvArgs a{};
-                a.in = in;
-                a.out = buf_ptr(nd.buf);
-                a.res = d.residual >= 0 ? buf_ptr(m->nodes[d.residual].buf) : nullptr;
-                a.bias = nd.bias;
-                for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
-                a.schemes = schemes_dev;
-                a.in_scheme_stride = in_stride;
-                a.out_scheme_stride = (size_t)n * nd.out_elems;
-                a.S = S;
-                a.L = m->L;
-                a.slot = d.scheme_slot;
-                a.N = n;
-                a.Hin = d.hin;
-                a.Win = d.win;
-                a.Cin = d.cin;
-                a.Hout = nd.hout;
-                a.Wout = nd.wout;
-                a.Cout = d.cout;
-                a.act = d.act;
-                a.R = p.R;
-                a.G = p.G;
-                a.regions_per_image = p.regions_per_image;
-                a.CB = p.CB;
-                a.CKC = p.CKC;
-                a.RIN = p.RIN;
-                a.LW = p.LW;
-                a.PS = p.PS;
-                a.wave_px_split = p.wave_px_split;
-                a.cout_tiles = p.cout_tiles;
-                a.div_lw = make_fastdiv(p.LW);
-                a.div_rin = make_fastdiv(p.RIN);
-                a.div_wout = make_fastdiv(nd.wout);
-                a.div_rw = make_fastdiv(p.R * nd.wout);
-                const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
-                ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);
-                AIQ_HIP(launch_conv(a, d.kh, d.stride, p.nt, p.lds_bytes, dim3(gx, p.grid_y, s_total), st));
-            } else if (d.kind == 1) {
-                DepthwiseArgs a{};
-                a.in = in;
-                a.out = buf_ptr(nd.buf);
-                a.bias = nd.bias;
-                for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
-                a.schemes = schemes_dev;
-                a.in_scheme_stride = in_stride;
-                a.out_scheme_stride = (size_t)n * nd.out_elems;
-                a.S = S;
-                a.L = m->L;
-                a.slot = d.scheme_slot;
-                a.N = n;
-                a.Hin = d.hin;
-                a.Win = d.win;
-                a.C = d.cin;
-                a.Hout = nd.hout;
-                a.Wout = nd.wout;
-                a.stride = d.stride;
-                a.act = d.act;
-                a.div_c4 = make_fastdiv(d.cin / 4);
-                ProfScope ps(m, st, AIQ_K_DEPTHWISE, nd.flops_per_image * work, nd.act_bytes_per_image * work);
-                AIQ_HIP(launch_depthwise(a, s_total, st));
-            } else {
-                HeadArgs a{};
-                a.in = in;
-                a.bias = nd.bias;
-                for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
-                a.schemes = schemes_dev;
-                a.in_scheme_stride = in_stride;
-                a.S = S;
-                a.L = m->L;
-                a.slot = d.scheme_slot;
-                a.N = n;
-                a.HW = d.hin * d.win;
-                a.C = d.cin;
-                a.classes = d.cout;
-                a.logits = logits;
-                a.logits_n = N;
-                a.n0 = n0;
-                if (top1) {
-                    a.top1 = top1 + n0;
-                    a.top1_stride = N;
-                } else {
-                    a.top1 = top1_tmp;
-                    a.top1_stride = chunk;
+            // ---- candidates, sorted by the node they leave the reference at: node l runs rows
+            // [0, active[l]); a row reads its own copy of an input it has computed itself and the
+            // reference pass's copy otherwise
+            for (size_t l = 0; l < m->nodes.size(); ++l) {
+                const Node &nd = m->nodes[l];
+                if (nd.mb_role == 2) continue;
+                const int na = active[l];
+                const int own_in = nd.d.input < 0 ? na : std::min(na, active[nd.d.input]);
+                const int own_res = nd.d.residual < 0 ? na : std::min(na, active[nd.d.residual]);
+                const int cuts[4] = {0, std::min(own_in, own_res), std::max(own_in, own_res), na};
+                const int on = nd.mb_role == 1 ? (int)l + 2 : (int)l;
+                for (int c = 0; c < 3; ++c) {
+                    const int b0 = cuts[c], b1 = cuts[c + 1];
+                    if (b1 <= b0) continue;
+                    io = NodeIO{};
+                    io.schemes = sorted_dev + (size_t)b0 * m->L;
+                    io.S = b1 - b0;
+                    io.s_total = b1 - b0;
+                    io.row_map = row_map_dev + b0;
+                    io.top1_base_out = top1_base + n0; // only the FP32 row (row_map < 0) writes it
+                    if (nd.d.input < 0) {
+                        io.in = images + (size_t)n0 * nd.in_elems;
+                    } else if (b0 < own_in) {
+                        io.in_stride = (size_t)n * nd.in_elems;
+                        io.in = buf_ptr(m->nodes[nd.d.input].buf) + (size_t)b0 * io.in_stride;
+                    } else {
+                        io.in = ref_ptr(nd.d.input);
+                    }
+                    io.out_stride = (size_t)n * m->nodes[on].out_elems;
+                    io.out = m->nodes[on].buf >= 0 ? buf_ptr(m->nodes[on].buf) + (size_t)b0 * io.out_stride : nullptr;
+                    if (nd.d.residual >= 0) {
+                        if (b0 < own_res) {
+                            io.res_stride = io.out_stride;
+                            io.res = buf_ptr(m->nodes[nd.d.residual].buf) + (size_t)b0 * io.res_stride;
+                        } else {
+                            io.res = ref_ptr(nd.d.residual);
+                        }
+                    }
+                    aiq_status rc = launch_node(l, io, n, n0);
+                    if (rc != AIQ_OK) return rc;
                 }
-                a.top1_base = run_base ? top1_base + n0 : nullptr;
-                {
-                    ProfScope ps(m, st, AIQ_K_HEAD, nd.flops_per_image * work, nd.act_bytes_per_image * work);
-                    AIQ_HIP(launch_head(a, s_total, st));
-                }
-                AgreeArgs g{};
-                g.top1 = a.top1;
-                g.top1_stride = a.top1_stride;
-                g.top1_base = top1_base + n0;
-                g.agree = agree;
-                g.N = n;
-                g.S = S;
-                ProfScope ps(m, st, AIQ_K_AGREE, 0.0, 8.0 * S * n);
-                AIQ_HIP(launch_agree(g, st));
             }
+        }
+        if (S > 0) {
+            AgreeArgs g{};
+            g.top1 = top1 ? top1 + n0 : top1_tmp;
+            g.top1_stride = top1 ? N : chunk;
+            g.top1_base = top1_base + n0;
+            g.agree = agree;
+            g.N = n;
+            g.S = S;
+            ProfScope ps(m, st, AIQ_K_AGREE, 0.0, 8.0 * S * n);
+            AIQ_HIP(launch_agree(g, st));
         }
     }
     return AIQ_OK;
@@ -1109,7 +1272,11 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
                      workspace_bytes, hip_stream);
 }
 
-int32_t aiq_model_shares_prefix(const aiq_model *m) { return m ? (m->fused && m->fused_ckpt_floats > 0 ? 1 : 0) : -1; }
+int32_t aiq_model_shares_prefix(const aiq_model *m)
+{
+    if (!m) return -1;
+    return !m->fused || m->fused_ckpt_floats > 0 ? 1 : 0;
+}
 
 aiq_status aiq_eval_shared_workspace_bytes(const aiq_model *m, int32_t S, int32_t chunk, size_t *bytes)
 {

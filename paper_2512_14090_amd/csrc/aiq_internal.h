@@ -79,7 +79,8 @@ struct ConvArgs {
     const float *bank[kNumBits];
     const uint8_t *schemes;   // device [S][L]
     size_t in_scheme_stride;  // elements between schemes of `in` (0: shared network input)
-    size_t out_scheme_stride; // elements between schemes of out / res
+    size_t out_scheme_stride; // elements between schemes of out
+    size_t res_scheme_stride; // elements between schemes of res (0: one copy for all schemes)
     int32_t S, L, slot;       // schemes with index >= S (the base pass) and slot < 0 use FP32
     int32_t N;                // images in this chunk
     int32_t Hin, Win, Cin, Hout, Wout, Cout;
@@ -103,7 +104,7 @@ struct PointwiseArgs {
     const float *bias;
     const float *bank[kNumBits];
     const uint8_t *schemes;
-    size_t in_scheme_stride, out_scheme_stride;
+    size_t in_scheme_stride, out_scheme_stride, res_scheme_stride;
     int32_t S, L, slot;
     int32_t P;                // pixels of this chunk: images * H * W
     int32_t Cin, Cout, act;
@@ -136,7 +137,9 @@ struct HeadArgs {
     int64_t logits_n, n0;
     int32_t *top1;             // (s, n) at top1 + s*top1_stride + n
     int64_t top1_stride;
-    int32_t *top1_base;        // base pass (s == S) writes top1_base[n]; may be nullptr when no base pass
+    int32_t *top1_base;        // the FP32 pass writes top1_base[n]; may be nullptr when there is none
+    const int32_t *row_map;    // device: output row of launch index s, < 0 = the FP32 pass; nullptr: row s, and
+                               // indices >= S are the FP32 pass
 };
 
 struct AgreeArgs {

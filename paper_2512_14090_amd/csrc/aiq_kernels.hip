@@ -392,7 +392,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
             const size_t o = (size_t)s * a.out_scheme_stride +
                              (((size_t)out_img[m] * a.Hout + out_y[m]) * a.Wout + out_x[m]) * a.Cout + co;
             floatx4 v = acc[m][n] + b;
-            if (a.res) v += *reinterpret_cast<const floatx4 *>(a.res + o);
+            if (a.res)
+                v += *reinterpret_cast<const floatx4 *>(a.res + (o - (size_t)s * a.out_scheme_stride) +
+                                                        (size_t)s * a.res_scheme_stride);
             v.x = apply_act(v.x, a.act);
             v.y = apply_act(v.y, a.act);
             v.z = apply_act(v.z, a.act);
@@ -555,7 +557,9 @@ __global__ __launch_bounds__(256, 2) void pointwise_mfma_kernel(PointwiseArgs a)
             if (pl >= px_here) continue;
             const size_t o = obase + (size_t)pl * a.Cout + co;
             floatx4 v = acc[m][n] + b;
-            if (a.res) v += *reinterpret_cast<const floatx4 *>(a.res + o);
+            if (a.res)
+                v += *reinterpret_cast<const floatx4 *>(a.res + (o - (size_t)s * a.out_scheme_stride) +
+                                                        (size_t)s * a.res_scheme_stride);
             v.x = fminf(fmaxf(v.x, lo), hi);
             v.y = fminf(fmaxf(v.y, lo), hi);
             v.z = fminf(fmaxf(v.z, lo), hi);
@@ -731,6 +735,8 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
     }
     __syncthreads();
 
+    // output row of this launch index: itself, unless the caller maps it; < 0 = the FP32 pass
+    const int row = a.row_map ? a.row_map[s] : (s < a.S ? s : -1);
     const float *w = a.bank[scheme_bits_index(a.schemes, s, a.S, a.L, a.slot)];
     for (int j = wave; j < a.classes; j += 4) {
         float acc = 0.0f;
@@ -743,14 +749,14 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
         int best = 0;
         for (int j = 1; j < a.classes; ++j)
             if (z[j] > z[best]) best = j;
-        if (s < a.S) {
-            a.top1[(size_t)s * a.top1_stride + n] = best;
+        if (row >= 0) {
+            a.top1[(size_t)row * a.top1_stride + n] = best;
         } else if (a.top1_base) {
             a.top1_base[n] = best;
         }
     }
-    if (a.logits && s < a.S && tid < a.classes)
-        a.logits[((size_t)s * a.logits_n + a.n0 + n) * a.classes + tid] = z[tid];
+    if (a.logits && row >= 0 && tid < a.classes)
+        a.logits[((size_t)row * a.logits_n + a.n0 + n) * a.classes + tid] = z[tid];
 }
 
 hipError_t launch_head(const HeadArgs &a, int s_total, hipStream_t st)

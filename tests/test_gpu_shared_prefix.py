@@ -143,18 +143,43 @@ def test_empty_batches_and_errors(env):
     m.close()
 
 
-def test_models_without_sharing_give_the_plain_result(env):
-    """A model the LDS-resident kernel does not cover scores every scheme whole; the entry point still works."""
+def _variant_workload(synth, builder, n):
+    nodes = {"plain": synth.plain_convnet20, "heavy": synth.heavy_early_resnet20,
+             "mobilenet": synth.mobilenetv2_32}[builder]()
+    rng = np.random.Generator(np.random.PCG64(53))
+    w, b = synth.make_model(nodes, rng)
+    return dict(desc=synth.desc_array(nodes), weights=w, biases=b, images=synth.make_images(n, rng),
+                L=synth.n_scheme_layers(nodes))
+
+
+@pytest.mark.parametrize("builder,n,chunk,layerwise", [
+    ("resnet8", 21, 8, True), ("plain", 10, 4, False), ("heavy", 11, 16, False), ("heavy", 11, 16, True),
+    ("mobilenet", 9, 4, False), ("mobilenet", 9, 4, True)])
+def test_layer_by_layer_models(env, builder, n, chunk, layerwise):
+    """Models that run layer by layer or through the inverted-residual block kernel: rows sorted by
+    the node they leave the reference at, each node launched for the rows that have left it."""
     torch, aiq, synth = env["torch"], env["aiq"], env["synth"]
-    wl = synth.make_workload(0, n_images=21)
+    if builder == "resnet8":
+        wl = synth.make_workload(0, n_images=n)
+    else:
+        wl = _variant_workload(synth, builder, n)
     L = wl["L"]
+    rng = np.random.Generator(np.random.PCG64(91))
     ref = np.full(L, 32, dtype=np.uint8)
-    ref[1] = 4
-    schemes = _single_layer_moves(ref, (8,))
-    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=True)
-    assert not m.shares_prefix
+    ref[rng.choice(L, 3, replace=False)] = (8, 4, 16)
+    moves = _single_layer_moves(ref, (32, 4))
+    moves = moves[rng.choice(moves.shape[0], min(12, moves.shape[0]), replace=False)]
+    schemes = np.ascontiguousarray(np.concatenate([moves, ref[None, :],
+                                                   rng.choice(ALPHABET, size=(2, L)).astype(np.uint8)]))
+    print(f"shared prefix, {builder} layerwise={layerwise}: S={schemes.shape[0]} N={n} chunk={chunk}", flush=True)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=layerwise)
+    assert m.shares_prefix and not m.lds_resident
     img = torch.from_numpy(wl["images"]).cuda()
-    plain, shared = _both(env, m, img, schemes, ref, 8)
+    plain, shared = _both(env, m, img, schemes, ref, chunk)
+    _assert_identical(plain, shared)
+    # and with the FP32 pass as the reference
+    ref32 = np.full(L, 32, dtype=np.uint8)
+    plain, shared = _both(env, m, img, schemes, ref32, chunk)
     m.close()
     _assert_identical(plain, shared)
 
