@@ -142,11 +142,18 @@ aiq_status plan_conv(Node &nd)
     p.CKC = cp >= 64 ? 64 : (cp >= 32 ? 32 : 16);
     p.RIN = (p.R - 1) * d.stride + d.kh;
     p.LW = d.win + 2 * d.pad;
+    // Channels staged per pass: as many as leave room for two workgroups per compute unit
+    // (with one, its four wavefronts sit alone on their SIMDs and every staging phase and every
+    // load latency idles the matrix pipe); a single workgroup only when even 16 channels need
+    // more than half of the LDS.
     for (;;) {
         p.PS = p.CKC + 4;
         p.lds_bytes = sizeof(float) * (size_t)p.G * p.RIN * p.LW * p.PS;
-        if (p.lds_bytes <= 152 * 1024) break;
-        if (p.CKC == 16) return AIQ_UNSUPPORTED_LAYER;
+        if (p.lds_bytes <= 76 * 1024) break;
+        if (p.CKC == 16) {
+            if (p.lds_bytes <= 152 * 1024) break;
+            return AIQ_UNSUPPORTED_LAYER;
+        }
         p.CKC /= 2;
     }
     nd.plan = p;
@@ -599,6 +606,11 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
                 nd.k = d.cin * d.kh * d.kw;
                 nd.layout = kLayoutMfma;
                 nd.bank_elems = (size_t)((d.cout + 15) / 16) * 16 * d.kh * d.kw * ((d.cin + 15) / 16) * 16;
+                if (d.cin <= 4 && d.kh == 3 && d.kw == 3 && d.stride == 1 && d.pad == 1 && d.residual < 0) {
+                    // network stem: the input channel is the MFMA's k index (conv_stem_kernel)
+                    nd.layout = kLayoutStem;
+                    nd.bank_elems = (size_t)((d.cout + 15) / 16) * 9 * 64;
+                }
                 st = plan_conv(nd);
                 if (st != AIQ_OK) {
                     delete m;
@@ -1026,7 +1038,10 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
             a.div_rw = make_fastdiv(p.R * nd.wout);
             const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
             ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);
-            AIQ_HIP(launch_conv(a, d.kh, d.stride, p.nt, p.lds_bytes, dim3(gx, p.grid_y, io.s_total), st));
+            if (nd.layout == kLayoutStem)
+                AIQ_HIP(launch_conv_stem(a, p.nt, dim3(gx, p.grid_y, io.s_total), st));
+            else
+                AIQ_HIP(launch_conv(a, d.kh, d.stride, p.nt, p.lds_bytes, dim3(gx, p.grid_y, io.s_total), st));
         } else if (d.kind == 1) {
             DepthwiseArgs a{};
             a.in = io.in;

@@ -158,6 +158,8 @@ hipError_t launch_quantize_batch(const QuantJob *jobs_dev, const int32_t *block_
                                  const QuantMask &mask, hipStream_t st);
 hipError_t launch_conv(const ConvArgs &a, int ks, int stride, int nt, size_t lds_bytes, dim3 grid,
                        hipStream_t st);
+// 3x3 stride-1 convolution with at most four input channels and no residual (bank layout kLayoutStem)
+hipError_t launch_conv_stem(const ConvArgs &a, int nt, dim3 grid, hipStream_t st);
 hipError_t launch_pointwise(const PointwiseArgs &a, int nt, size_t lds_bytes, dim3 grid, hipStream_t st);
 hipError_t launch_depthwise(const DepthwiseArgs &a, int s_total, hipStream_t st);
 hipError_t launch_head(const HeadArgs &a, int s_total, hipStream_t st);

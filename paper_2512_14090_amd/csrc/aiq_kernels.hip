@@ -247,6 +247,66 @@ hipError_t launch_quantize_batch(const QuantJob *jobs_dev, const int32_t *block_
 // zero border) in LDS, CKC channels at a time; every wavefront owns a tile of 64
 // pixels x 16*NT output channels and keeps its accumulators across channel passes.
 
+// Stages channels [c0, c0 + 4*c4n) of the region's input rows into LDS, zero outside the
+// image.  One wavefront takes NR rows at a time (rows wave, wave+4, ...): a row's image,
+// position and validity are uniform, so per element only the column and the channel chunk
+// are lane arithmetic.  All B*NR 16-byte loads of a round are issued before the first LDS
+// store, so a lane has that many reads in flight.
+template <int STRIDE, int PAD, int B, int NR>
+__device__ __forceinline__ void conv_stage_rows(const ConvArgs &a, const float *in_s, floatx4 *lds4, int ps4, int c0,
+                                                int c4n, int c4shift, int img0, int oy0, int wave_u, int lane)
+{
+    const int stage_rows = a.G * a.RIN;
+    const int per_row = a.LW << c4shift; // 16-byte chunks of one staged row
+    const bool vec_ok = (a.Cin & 3) == 0;
+    for (int row0 = wave_u; row0 < stage_rows; row0 += 4 * NR) {
+        for (int base = lane; base < per_row; base += 64 * B) {
+            floatx4 v[NR][B];
+#pragma unroll
+            for (int rr = 0; rr < NR; ++rr) {
+                const int row = row0 + 4 * rr;
+                const int g = (int)fd_div((uint32_t)row, a.div_rin);
+                const int r = row - g * a.RIN;
+                const int iy = oy0 * STRIDE - PAD + r;
+                const int img = img0 + g;
+                const bool row_ok = row < stage_rows && iy >= 0 && iy < a.Hin && img < a.N;
+                // dereferenced only when row_ok
+                const float *src_row =
+                    in_s + (((size_t)(row_ok ? img : 0) * a.Hin + (row_ok ? iy : 0)) * a.Win) * a.Cin + c0;
+#pragma unroll
+                for (int u = 0; u < B; ++u) {
+                    const int e = base + u * 64;
+                    const int c = (e & (c4n - 1)) * 4;
+                    const int ix = (e >> c4shift) - PAD;
+                    v[rr][u] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    if (row_ok && e < per_row && ix >= 0 && ix < a.Win && c0 + c < a.Cin) {
+                        const float *src = src_row + ix * a.Cin + c;
+                        if (vec_ok) {
+                            v[rr][u] = *reinterpret_cast<const floatx4 *>(src);
+                        } else {
+                            v[rr][u].x = src[0];
+                            if (c0 + c + 1 < a.Cin) v[rr][u].y = src[1];
+                            if (c0 + c + 2 < a.Cin) v[rr][u].z = src[2];
+                            if (c0 + c + 3 < a.Cin) v[rr][u].w = src[3];
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int rr = 0; rr < NR; ++rr) {
+                const int row = row0 + 4 * rr;
+                if (row >= stage_rows) continue;
+                floatx4 *dst_row = lds4 + row * a.LW * ps4;
+#pragma unroll
+                for (int u = 0; u < B; ++u) {
+                    const int e = base + u * 64;
+                    if (e < per_row) dst_row[(e >> c4shift) * ps4 + (e & (c4n - 1))] = v[rr][u];
+                }
+            }
+        }
+    }
+}
+
 template <int KS, int STRIDE, int NT>
 __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
 {
@@ -302,106 +362,229 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
 
     const int c4n = a.CKC >> 2;            // 16-byte chunks per staged pixel
     const int c4shift = __ffs(c4n) - 1;    // CKC is 16, 32 or 64
-    const int n_pix = a.G * a.RIN * a.LW;
-    const int n_chunks = n_pix << c4shift;
-    const bool vec_ok = (a.Cin & 3) == 0;
     const bool active = ct0 < a.cout_tiles; // wavefronts past the last output-channel tile only help staging
+
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int per_row = a.LW << c4shift; // 16-byte chunks of one staged row
 
     for (int c0 = 0; c0 < a.CB * 16; c0 += a.CKC) {
         if (c0) __syncthreads();
-        // ---- stage channels [c0, c0+CKC) of the region's input rows, zero outside the image;
-        // kStageBatch loads are issued before their LDS stores (several reads in flight per thread)
-        for (int base = tid; base < n_chunks; base += 256 * kStageBatch) {
-            floatx4 v[kStageBatch];
-#pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int idx = base + u * 256;
-                const int c4 = idx & (c4n - 1);
-                const uint32_t pix = (uint32_t)idx >> c4shift;
-                const uint32_t row = fd_div(pix, a.div_lw); // g*RIN + r
-                const int x = pix - row * a.LW;
-                const uint32_t g = fd_div(row, a.div_rin);
-                const int r = row - g * a.RIN;
-                const int iy = oy0 * STRIDE - PAD + r;
-                const int ix = x - PAD;
-                const int img = img0 + g;
-                const int c = c0 + c4 * 4;
-                v[u] = floatx4{0.f, 0.f, 0.f, 0.f};
-                if (idx < n_chunks && iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win && img < a.N && c < a.Cin) {
-                    const float *src = in_s + (((size_t)img * a.Hin + iy) * a.Win + ix) * a.Cin + c;
-                    if (vec_ok) {
-                        v[u] = *reinterpret_cast<const floatx4 *>(src);
-                    } else {
-                        v[u].x = src[0];
-                        if (c + 1 < a.Cin) v[u].y = src[1];
-                        if (c + 2 < a.Cin) v[u].z = src[2];
-                        if (c + 3 < a.Cin) v[u].w = src[3];
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int idx = base + u * 256;
-                if (idx < n_chunks) lds4[((uint32_t)idx >> c4shift) * ps4 + (idx & (c4n - 1))] = v[u];
-            }
-        }
+        // ---- stage channels [c0, c0+CKC) of the region's input rows: about nine 16-byte reads in
+        // flight per lane whatever the row length
+        if (per_row <= 64)
+            conv_stage_rows<STRIDE, PAD, 1, 8>(a, in_s, lds4, ps4, c0, c4n, c4shift, img0, oy0, wave_u, lane);
+        else if (per_row <= 128)
+            conv_stage_rows<STRIDE, PAD, 2, 4>(a, in_s, lds4, ps4, c0, c4n, c4shift, img0, oy0, wave_u, lane);
+        else if (per_row <= 192)
+            conv_stage_rows<STRIDE, PAD, 3, 3>(a, in_s, lds4, ps4, c0, c4n, c4shift, img0, oy0, wave_u, lane);
+        else if (per_row <= 320)
+            conv_stage_rows<STRIDE, PAD, 5, 2>(a, in_s, lds4, ps4, c0, c4n, c4shift, img0, oy0, wave_u, lane);
+        else
+            conv_stage_rows<STRIDE, PAD, 9, 1>(a, in_s, lds4, ps4, c0, c4n, c4shift, img0, oy0, wave_u, lane);
         __syncthreads();
 
         if (active) {
+            // The reduction over (tap, channel block) is one flat sequence of steps; step k+1's
+            // weights (16-byte global reads, L2-resident) and activations (16-byte LDS reads) are
+            // requested before step k's MFMAs, alternating between two register sets.
             const int ncb = min(a.CKC, a.CB * 16 - c0) >> 4;
             const int cb0 = c0 >> 4;
-#pragma unroll 1
-            for (int t = 0; t < T; ++t) {
+            const int steps = T * ncb;
+            int lt = 0, lc = 0; // (tap, channel block) of the next step to load
+            auto load_step = [&](floatx4 (&wa)[NT], floatx4 (&xb)[4]) {
+                const int t = lt, cbl = lc;
+                if (++lc == ncb) {
+                    lc = 0;
+                    ++lt;
+                }
                 const int ky = t / KS, kx = t - ky * KS;
-                const int tapoff = (ky * a.LW + kx) * ps4;
-#pragma unroll 1
-                for (int cbl = 0; cbl < ncb; ++cbl) {
-                    floatx4 wa[NT], xb[4];
+                const int tapoff = (ky * a.LW + kx) * ps4 + cbl * 4;
 #pragma unroll
-                    for (int n = 0; n < NT; ++n) {
-                        const int ct = min(ct0 + n, a.cout_tiles - 1);
-                        wa[n] = *reinterpret_cast<const floatx4 *>(
-                            wq + ((((size_t)ct * T + t) * a.CB + cb0 + cbl) * 64 + lane) * 4);
-                    }
+                for (int n = 0; n < NT; ++n) {
+                    const int ct = min(ct0 + n, a.cout_tiles - 1);
+                    wa[n] = *reinterpret_cast<const floatx4 *>(
+                        wq + ((((size_t)ct * T + t) * a.CB + cb0 + cbl) * 64 + lane) * 4);
+                }
+#pragma unroll
+                for (int m = 0; m < 4; ++m) xb[m] = lds4[lds_base[m] + tapoff];
+            };
+            auto mma_step = [&](const floatx4 (&wa)[NT], const floatx4 (&xb)[4]) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int m = 0; m < 4; ++m)
-                        xb[m] = lds4[lds_base[m] + tapoff + cbl * 4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-#pragma unroll
-                        for (int m = 0; m < 4; ++m)
-#pragma unroll
-                            for (int n = 0; n < NT; ++n)
-                                acc[m][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[n][j], xb[m][j], acc[m][n],
-                                                                                 0, 0, 0);
-                }
+                        for (int n = 0; n < NT; ++n)
+                            acc[m][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[n][j], xb[m][j], acc[m][n], 0, 0, 0);
+            };
+            floatx4 wa0[NT], xb0[4], wa1[NT], xb1[4];
+            load_step(wa0, xb0);
+            int k = 0;
+#pragma unroll 1
+            for (; k + 2 <= steps; k += 2) {
+                load_step(wa1, xb1);
+                mma_step(wa0, xb0);
+                if (k + 2 < steps) load_step(wa0, xb0);
+                mma_step(wa1, xb1);
             }
+            if (k < steps) mma_step(wa0, xb0); // odd number of steps: the last one is already loaded
         }
     }
 
     if (!active) return;
     // ---- epilogue: bias, residual, activation, 16-byte NHWC stores
+    const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
 #pragma unroll
-    for (int n = 0; n < NT; ++n) {
-        const int co = (ct0 + n) * 16 + kq * 4;
-        if (co >= a.Cout) continue;
-        const floatx4 b = *reinterpret_cast<const floatx4 *>(a.bias + co);
+    for (int m = 0; m < 4; ++m) {
+        if (out_img[m] >= a.N || out_y[m] >= a.Hout) continue;
+        const size_t pix = (((size_t)out_img[m] * a.Hout + out_y[m]) * a.Wout + out_x[m]) * a.Cout;
+        float *out_p = a.out + (size_t)s * a.out_scheme_stride + pix;
+        const float *res_p = a.res ? a.res + (size_t)s * a.res_scheme_stride + pix : nullptr;
 #pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            if (out_img[m] >= a.N || out_y[m] >= a.Hout) continue;
-            const size_t o = (size_t)s * a.out_scheme_stride +
-                             (((size_t)out_img[m] * a.Hout + out_y[m]) * a.Wout + out_x[m]) * a.Cout + co;
-            floatx4 v = acc[m][n] + b;
-            if (a.res)
-                v += *reinterpret_cast<const floatx4 *>(a.res + (o - (size_t)s * a.out_scheme_stride) +
-                                                        (size_t)s * a.res_scheme_stride);
-            v.x = apply_act(v.x, a.act);
-            v.y = apply_act(v.y, a.act);
-            v.z = apply_act(v.z, a.act);
-            v.w = apply_act(v.w, a.act);
-            *reinterpret_cast<floatx4 *>(a.out + o) = v;
+        for (int n = 0; n < NT; ++n) {
+            const int co = (ct0 + n) * 16 + kq * 4;
+            if (co >= a.Cout) continue;
+            floatx4 v = acc[m][n] + *reinterpret_cast<const floatx4 *>(a.bias + co);
+            if (res_p) v += *reinterpret_cast<const floatx4 *>(res_p + co);
+            v.x = __builtin_amdgcn_fmed3f(v.x, lo, hi);
+            v.y = __builtin_amdgcn_fmed3f(v.y, lo, hi);
+            v.z = __builtin_amdgcn_fmed3f(v.z, lo, hi);
+            v.w = __builtin_amdgcn_fmed3f(v.w, lo, hi);
+            *reinterpret_cast<floatx4 *>(out_p + co) = v;
         }
     }
+}
+
+// ------------------------------------------------------------------ network stems
+//
+// 3x3 stride-1 convolution of an input with at most four channels.  In the general kernel a
+// block of 16 input channels is the unit of the reduction, so three channels would waste
+// 13/16 of the MFMAs; here the MFMA's k index is the input channel itself (lane (p, kq)
+// supplies channel kq of its pixel, one 4-byte LDS read, and the weight of (output channel,
+// tap, channel kq), one register), one MFMA per tap.  Same output tiling and epilogue as
+// conv_mfma_kernel; the weights of the wavefront's NT tiles stay in registers.
+
+template <int NT>
+__global__ __launch_bounds__(256, 2) void conv_stem_kernel(ConvArgs a)
+{
+    extern __shared__ float lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int s = blockIdx.z;
+    int img0, oy0;
+    if (a.G > 1) {
+        img0 = blockIdx.x * a.G;
+        oy0 = 0;
+    } else {
+        img0 = blockIdx.x / a.regions_per_image;
+        oy0 = (blockIdx.x - img0 * a.regions_per_image) * a.R;
+    }
+    const int wpx = wave % a.wave_px_split;
+    const int wco = wave / a.wave_px_split;
+    const int ct0 = (blockIdx.y * (4 / a.wave_px_split) + wco) * NT;
+    const int p = lane & 15, kq = lane >> 4;
+    const bool active = ct0 < a.cout_tiles;
+
+    // weights first: their latency overlaps the staging
+    const float *wq = a.bank[scheme_bits_index(a.schemes, s, a.S, a.L, a.slot)];
+    float w[NT][9];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int ct = min(ct0 + n, a.cout_tiles - 1);
+#pragma unroll
+        for (int t = 0; t < 9; ++t) w[n][t] = wq[((size_t)ct * 9 + t) * 64 + lane];
+    }
+
+    // stage the region's input rows as one 16-byte element per pixel (channels past Cin and
+    // pixels outside the image are zero)
+    const float *in_s = a.in + (size_t)s * a.in_scheme_stride;
+    floatx4 *lds4 = reinterpret_cast<floatx4 *>(lds);
+    const int n_pix = a.G * a.RIN * a.LW;
+    for (int pix = tid; pix < n_pix; pix += 256) {
+        const uint32_t row = fd_div((uint32_t)pix, a.div_lw);
+        const int x = pix - row * a.LW;
+        const uint32_t g = fd_div(row, a.div_rin);
+        const int r = row - g * a.RIN;
+        const int iy = oy0 - 1 + r, ix = x - 1, img = img0 + g;
+        floatx4 v = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win && img < a.N) {
+            const float *src = in_s + (((size_t)img * a.Hin + iy) * a.Win + ix) * a.Cin;
+            v.x = src[0];
+            if (a.Cin > 1) v.y = src[1];
+            if (a.Cin > 2) v.z = src[2];
+            if (a.Cin > 3) v.w = src[3];
+        }
+        lds4[pix] = v;
+    }
+
+    int lds_base[4], out_img[4], out_y[4], out_x[4];
+    const int rw = a.R * a.Wout;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const uint32_t P = (uint32_t)(wpx * 64 + m * 16 + p);
+        const uint32_t g = fd_div(P, a.div_rw);
+        const uint32_t rem = P - g * rw;
+        const uint32_t oy = fd_div(rem, a.div_wout);
+        const uint32_t ox = rem - oy * a.Wout;
+        const bool in_region = g < (uint32_t)a.G;
+        lds_base[m] = in_region ? ((g * a.RIN + oy) * a.LW + ox) * 4 + kq : kq;
+        out_img[m] = in_region ? img0 + (int)g : a.N;
+        out_y[m] = oy0 + oy;
+        out_x[m] = ox;
+    }
+    __syncthreads();
+    if (!active) return;
+
+    floatx4 acc[4][NT];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int n = 0; n < NT; ++n) acc[m][n] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        const int tapoff = ((t / 3) * a.LW + (t % 3)) * 4;
+        float xb[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) xb[m] = lds[lds_base[m] + tapoff];
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+            for (int n = 0; n < NT; ++n)
+                acc[m][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(w[n][t], xb[m], acc[m][n], 0, 0, 0);
+    }
+
+    const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        if (out_img[m] >= a.N || out_y[m] >= a.Hout) continue;
+        const size_t pix = (((size_t)out_img[m] * a.Hout + out_y[m]) * a.Wout + out_x[m]) * a.Cout;
+        float *out_p = a.out + (size_t)s * a.out_scheme_stride + pix;
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+            const int co = (ct0 + n) * 16 + kq * 4;
+            if (co >= a.Cout) continue;
+            floatx4 v = acc[m][n] + *reinterpret_cast<const floatx4 *>(a.bias + co);
+            v.x = __builtin_amdgcn_fmed3f(v.x, lo, hi);
+            v.y = __builtin_amdgcn_fmed3f(v.y, lo, hi);
+            v.z = __builtin_amdgcn_fmed3f(v.z, lo, hi);
+            v.w = __builtin_amdgcn_fmed3f(v.w, lo, hi);
+            __builtin_nontemporal_store(v, reinterpret_cast<floatx4 *>(out_p + co));
+        }
+    }
+}
+
+hipError_t launch_conv_stem(const ConvArgs &a, int nt, dim3 grid, hipStream_t st)
+{
+    if (a.Cin > 4 || a.res) return hipErrorInvalidValue;
+    const size_t lds_bytes = sizeof(float) * 4 * (size_t)a.G * a.RIN * a.LW;
+    if (lds_bytes > 64 * 1024) return hipErrorInvalidValue;
+    switch (nt) {
+    case 1: hipLaunchKernelGGL((conv_stem_kernel<1>), grid, dim3(256), lds_bytes, st, a); break;
+    case 2: hipLaunchKernelGGL((conv_stem_kernel<2>), grid, dim3(256), lds_bytes, st, a); break;
+    case 3: hipLaunchKernelGGL((conv_stem_kernel<3>), grid, dim3(256), lds_bytes, st, a); break;
+    case 4: hipLaunchKernelGGL((conv_stem_kernel<4>), grid, dim3(256), lds_bytes, st, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
 }
 
 template <int KS, int STRIDE, int NT>
