@@ -56,6 +56,7 @@ struct Node {
     MbShape mb_shape{};
     double flops_per_image;      // 2 * multiply-adds
     double act_bytes_per_image;  // algorithmic: input + output (+ residual) activations
+    bool pooled = false; // 1x1 layer feeding only the classifier: writes the per-image mean of its output instead
 };
 
 struct ProfRec {
@@ -638,6 +639,24 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
         m->fused_ckpt_floats = plan_fused_checkpoints(m->fused_ops, m->L, m->slot_op);
     } else if (!(flags & AIQ_MODEL_LAYERWISE)) {
         m->mb_blocks = plan_mbconv(m->nodes);
+        // A 1x1 layer whose only reader is the classifier, on 8x8 pixels: the classifier starts
+        // with the mean over those pixels, which the layer's own epilogue can form (a wavefront
+        // holds one whole image), so the full-resolution output never reaches memory.
+        if (n_layers >= 2) {
+            Node &pc = m->nodes[n_layers - 2];
+            const aiq_layer_desc &d = pc.d, &fc = layers[n_layers - 1];
+            int readers = 0;
+            for (int l = 0; l < n_layers; ++l)
+                readers += (layers[l].input == n_layers - 2) + (layers[l].residual == n_layers - 2);
+            if (fc.kind == 2 && fc.input == n_layers - 2 && readers == 1 && d.kind == 0 && d.kh == 1 && d.stride == 1 &&
+                d.input >= 0 && d.residual < 0 && pc.mb_role == 0 && pc.hout * pc.wout == 64 && (d.cout & 3) == 0) {
+                pc.pooled = true;
+                pc.out_elems = (size_t)d.cout;
+                pc.act_bytes_per_image = 4.0 * ((double)pc.in_elems + d.cout);
+                m->nodes[n_layers - 1].in_elems = (size_t)d.cout; // what the classifier reads per image
+                m->nodes[n_layers - 1].act_bytes_per_image = 4.0 * d.cout;
+            }
+        }
     }
 
     // activation buffers: a node's output lives until its last reader has run
@@ -994,6 +1013,7 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
             a.PS = p.PS;
             a.wave_px_split = p.wave_px_split;
             a.cout_tiles = p.cout_tiles;
+            a.pool = nd.pooled ? 1 : 0;
             const int tile_px = 64 * p.wave_px_split;
             const size_t lds = sizeof(float) * (size_t)tile_px * p.PS;
             ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);
@@ -1076,7 +1096,7 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
             a.L = m->L;
             a.slot = d.scheme_slot;
             a.N = n;
-            a.HW = d.hin * d.win;
+            a.HW = m->nodes[d.input].pooled ? 1 : d.hin * d.win; // a pooled producer has already taken the mean
             a.C = d.cin;
             a.classes = d.cout;
             a.logits = logits;

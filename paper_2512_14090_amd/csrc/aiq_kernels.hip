@@ -728,6 +728,39 @@ __global__ __launch_bounds__(256, 2) void pointwise_mfma_kernel(PointwiseArgs a)
     if (!active) return;
 
     const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
+    if (a.pool) {
+        // Global average pooling fused into the layer: the 64 pixels of this wavefront are one
+        // whole image, so the mean over them is the sum of the lane's four tiles followed by a
+        // butterfly over the 16 lanes that share kq - a fixed order, hence run-to-run identical.
+        // Only the [image][Cout] means reach memory.
+        const int img = (P0 >> 6) + wpx;
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+            const int co = (ct0 + n) * 16 + kq * 4;
+            const floatx4 b = co < a.Cout ? *reinterpret_cast<const floatx4 *>(a.bias + co) : floatx4{0.f, 0.f, 0.f, 0.f};
+            floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                floatx4 v = acc[m][n] + b;
+                v.x = fminf(fmaxf(v.x, lo), hi);
+                v.y = fminf(fmaxf(v.y, lo), hi);
+                v.z = fminf(fmaxf(v.z, lo), hi);
+                v.w = fminf(fmaxf(v.w, lo), hi);
+                sum += v;
+            }
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) {
+                sum.x += __shfl_xor(sum.x, off);
+                sum.y += __shfl_xor(sum.y, off);
+                sum.z += __shfl_xor(sum.z, off);
+                sum.w += __shfl_xor(sum.w, off);
+            }
+            if (p == 0 && co < a.Cout && img * 64 < a.P)
+                *reinterpret_cast<floatx4 *>(a.out + (size_t)s * a.out_scheme_stride + (size_t)img * a.Cout + co) =
+                    sum * (1.0f / 64.0f);
+        }
+        return;
+    }
     const size_t obase = (size_t)s * a.out_scheme_stride + (size_t)P0 * a.Cout;
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
