@@ -23,23 +23,28 @@ PEAK_HBM_GBS = 8000.0
 TRAFFIC = {
     ("resnet20_greedy_step_n1024_s40", "resnet_fused"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_fused.hip",
-        "sha256": "83b162e477aee2be83b6280e61c609ba3657c79a388c2143e3ecb410b8617a4d",
-        "bytes_per_launch": 62251157,
+        "sha256": "0343a680097f7a82345a3662d5ff49b0c29bb8e74a965efe17a95001a50d329e",
+        "bytes_per_launch": 48630571,
     },
     ("mobilenetv2_32_n512_s16", "mbconv"): {  # average over the 16 block launches of a step
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_mbconv.hip",
-        "sha256": "66777d758ea353b9180d24b15e25141120421943d76149893492ee309104d29d",
-        "bytes_per_launch": 1800837096,
+        "sha256": "e02a1f9407b013c8cf925ecbd3f4b3a8ad76bfb5683fbc093d4c6f4f10930233",
+        "bytes_per_launch": 1788954568,
     },
     ("mobilenetv2_32_n512_s16", "depthwise"): {  # layer by layer: average over the 17 depthwise launches
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "d714d9f8af2944a09315b6ee2ec9f2c194c23815bfe2ecf1b3e73f17c2a9b77f",
-        "bytes_per_launch": 8289545077,
+        "sha256": "f0e500c02e63a532b2235d973872561abf87fc04235b018a1c3743fdcfb24319",
+        "bytes_per_launch": 8289530808,
+    },
+    ("plainconvnet20_sensitivity_n256_s42", "conv_mfma"): {  # average over the 20 convolution launches of a step
+        "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
+        "sha256": "f0e500c02e63a532b2235d973872561abf87fc04235b018a1c3743fdcfb24319",
+        "bytes_per_launch": 2901517701,
     },
     ("quantize_stress_8192x4608_b8", "quantize"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "d714d9f8af2944a09315b6ee2ec9f2c194c23815bfe2ecf1b3e73f17c2a9b77f",
-        "bytes_per_launch": 302277254,
+        "sha256": "f0e500c02e63a532b2235d973872561abf87fc04235b018a1c3743fdcfb24319",
+        "bytes_per_launch": 302314178,
     },
 }
 
