@@ -153,7 +153,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build scores schemes on ONE GPU; --gpus N with N > 1 is not supported "
-                 "(the (scheme, image) grid would shard across GPUs, see DESIGN.md)")
+                 "(the (scheme, image) pairs are independent and would shard across GPUs by scheme or by image)")
 
     import numpy as np
     import torch

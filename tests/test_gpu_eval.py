@@ -184,6 +184,39 @@ def test_depthwise_layers_outside_blocks(env):
         print("  max logit rel err %.3e" % err, flush=True)
 
 
+def test_stem_dense_and_pooled_layers_on_odd_shapes(env):
+    """Layer-by-layer kernels on shapes the workloads do not have: stems with 1, 2, 3 and 4 input channels
+    and 16 to 72 output channels on images of 5 to 32 pixels (several images per workgroup, ragged last
+    group, widths that are not a multiple of 16); dense 3x3 layers with 20 to 112 input channels (one, two and
+    three staging passes, a last pass of three channel blocks), both strides, with a residual; and an 8x8
+    1x1 layer read only by the classifier, whose average pool is formed inside that layer."""
+    synth, oracle, aiq = env["synth"], env["oracle"], env["aiq"]
+    G = synth.graphs
+    cases = [  # image channels, image size, stem width, mid width, stride of the second conv, last 1x1 width
+        (3, 32, 64, 64, 1, 0), (1, 16, 16, 20, 2, 0), (2, 5, 24, 24, 1, 0), (4, 9, 72, 112, 2, 0),
+        (3, 16, 40, 48, 2, 96), (4, 8, 112, 64, 1, 1280), (3, 8, 16, 16, 1, 44)]
+    for k, (ci, h, c1, c2, stride, cl) in enumerate(cases):
+        ho = (h + 2 - 3) // stride + 1
+        nodes = [G._node(G.KIND_CONV, ci, c1, 3, 1, h, -1, act=G.ACT_RELU, slot=0, name="stem"),
+                 G._node(G.KIND_CONV, c1, c2, 3, stride, h, 0, act=G.ACT_RELU6, slot=1, name="c2"),
+                 G._node(G.KIND_CONV, c2, c2, 3, 1, ho, 1, residual=1, act=G.ACT_RELU, slot=2, name="c3")]
+        if cl:
+            nodes.append(G._node(G.KIND_CONV, c2, cl, 1, 1, ho, 2, act=G.ACT_RELU6, slot=3, name="last"))
+        nodes.append(G._node(G.KIND_FC, cl or c2, 10, 1, 1, ho, len(nodes) - 1, act=G.ACT_NONE, slot=len(nodes), name="fc"))
+        L = len(nodes)
+        rng = np.random.Generator(np.random.PCG64(700 + k))
+        w, b = synth.make_model(nodes, rng)
+        n = 7
+        images = rng.standard_normal((n, h, h, ci)).astype(np.float32)
+        desc = synth.desc_array(nodes)
+        schemes = np.concatenate([np.full((1, L), 32), rng.choice([32, 16, 8, 6, 4, 2], size=(3, L))]).astype(np.uint8)
+        print(f"odd shapes: {ci}x{h}x{h} -> {c1} -> {c2} (stride {stride}) -> {cl or '-'}", flush=True)
+        ref = oracle.eval_schemes(desc, w, b, images, schemes)
+        gpu = _run_gpu(env, dict(desc=desc, weights=w, biases=b, images=images), schemes, chunk=3)
+        err = check_eval(gpu, ref, n)
+        print("  max logit rel err %.3e" % err, flush=True)
+
+
 @pytest.mark.parametrize("case", ["resnet8", "resnet8_layerwise", "mobilenetv2"])
 def test_per_tensor_scales(env, case):
     """Scheme scoring with one quantization scale per layer (per-tensor variant) against the oracle's."""
