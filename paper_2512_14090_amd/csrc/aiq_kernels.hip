@@ -313,7 +313,10 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
     extern __shared__ float lds[];
     constexpr int T = KS * KS;
     constexpr int PAD = KS == 3 ? 1 : 0;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wavefront index is uniform; saying so keeps everything derived from it (output-channel
+    // tile, weight addresses) in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int s = blockIdx.z;
 
     int img0, oy0;
@@ -364,7 +367,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
     const int c4shift = __ffs(c4n) - 1;    // CKC is 16, 32 or 64
     const bool active = ct0 < a.cout_tiles; // wavefronts past the last output-channel tile only help staging
 
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int wave_u = wave;
     const int per_row = a.LW << c4shift; // 16-byte chunks of one staged row
 
     for (int c0 = 0; c0 < a.CB * 16; c0 += a.CKC) {
@@ -402,8 +405,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
 #pragma unroll
                 for (int n = 0; n < NT; ++n) {
                     const int ct = min(ct0 + n, a.cout_tiles - 1);
-                    wa[n] = *reinterpret_cast<const floatx4 *>(
-                        wq + ((((size_t)ct * T + t) * a.CB + cb0 + cbl) * 64 + lane) * 4);
+                    const float *wrow = wq + (((size_t)ct * T + t) * a.CB + cb0 + cbl) * 256; // uniform
+                    wa[n] = *reinterpret_cast<const floatx4 *>(wrow + lane * 4);
                 }
 #pragma unroll
                 for (int m = 0; m < 4; ++m) xb[m] = lds4[lds_base[m] + tapoff];
@@ -468,7 +471,8 @@ template <int NT>
 __global__ __launch_bounds__(256, 2) void conv_stem_kernel(ConvArgs a)
 {
     extern __shared__ float lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // uniform: keeps the tile indices scalar
     const int s = blockIdx.z;
     int img0, oy0;
     if (a.G > 1) {
@@ -651,7 +655,8 @@ template <int NT>
 __global__ __launch_bounds__(256, 2) void pointwise_mfma_kernel(PointwiseArgs a)
 {
     extern __shared__ float lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // uniform: keeps the tile indices scalar
     const int s = blockIdx.z;
     const int tile_px = 64 * a.wave_px_split;
     const int P0 = blockIdx.x * tile_px;
@@ -710,7 +715,8 @@ __global__ __launch_bounds__(256, 2) void pointwise_mfma_kernel(PointwiseArgs a)
 #pragma unroll
                 for (int n = 0; n < NT; ++n) {
                     const int ct = min(ct0 + n, a.cout_tiles - 1);
-                    wa[n] = *reinterpret_cast<const floatx4 *>(wq + (((size_t)ct * a.CB + cb0 + cbl) * 64 + lane) * 4);
+                    const float *wrow = wq + ((size_t)ct * a.CB + cb0 + cbl) * 256; // uniform
+                    wa[n] = *reinterpret_cast<const floatx4 *>(wrow + lane * 4);
                 }
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
