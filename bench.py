@@ -111,6 +111,37 @@ def stress_quantize(args, torch, aiq):
     print(json.dumps(line))
 
 
+def search_mode(args, torch, aiq, synth):
+    """Whole searches (the paper's greedy and coordinate-descent loops) on a workload's model and images:
+    wall time of one search with and without the shared forward prefix, and the scheme it returns."""
+    wl = synth.make_workload(args.workload)
+    model = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=args.layerwise)
+    images = torch.from_numpy(wl["images"]).cuda()
+    bits = tuple(int(b) for b in args.search_bits.split(","))
+    res = {}
+    for share in (False, True):
+        for _ in range(max(args.warmup, 1)):
+            model.search(wl["desc"], images, method=args.search, bits=bits, lam=0.9, chunk=wl["chunk"], share_prefix=share)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            q, trace = model.search(wl["desc"], images, method=args.search, bits=bits, lam=0.9, chunk=wl["chunk"],
+                                    share_prefix=share)
+        torch.cuda.synchronize()
+        res[share] = ((time.perf_counter() - t0) / args.steps, q, trace)
+    (t_plain, q0, tr0), (t_shared, q1, tr1) = res[False], res[True]
+    line = {"metric": "search_seconds", "value": t_shared, "unit": "s", "n_gpus": 1, "steps": args.steps,
+            "warmup": max(args.warmup, 1), "ms_per_step": t_shared * 1e3, "higher_is_better": False, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": wl["name"] + "_search_" + args.search, "images": int(images.shape[0]),
+                       "alphabet": list(bits), "lambda": 0.9, "accepted_moves": len(tr1) - 1,
+                       "scheme": [int(v) for v in q1], "final_agree": int(tr1[-1]["agree"]),
+                       "lds_resident": bool(model.lds_resident)},
+            "without_prefix_sharing": {"value": t_plain, "unit": "s", "same_result": bool((q0 == q1).all() and tr0 == tr1)}}
+    model.close()
+    print(json.dumps(line))
+
+
 def print_hbm_line(args, wl, model, S, N, L, chunk, dt, agree, prof, cls):
     """Same step, but the roofline block describes a bandwidth-bound kernel class."""
     k = prof[cls]
@@ -148,6 +179,9 @@ def main():
                     help="kernel class whose roofline is reported (auto: the one the step spends most time in)")
     ap.add_argument("--no-prefix-shared", action="store_true",
                     help="skip the second timing (same step with the forward prefix shared)")
+    ap.add_argument("--search", choices=("greedy", "cd"),
+                    help="time a whole search (greedy or coordinate descent) on the workload's model and images")
+    ap.add_argument("--search-bits", default="32,8,4", help="alphabet of --search, descending, first 32")
     ap.add_argument("--stress", choices=("quantize",), help="time one kernel on a bandwidth-stress shape instead of a workload")
     ap.add_argument("--stress-shape", default="8192x4608", help="cout x k of the quantizer stress matrix")
     args = ap.parse_args()
@@ -166,6 +200,8 @@ def main():
     aiq.load_library()
     if args.stress == "quantize":
         return stress_quantize(args, torch, aiq)
+    if args.search:
+        return search_mode(args, torch, aiq, synth)
     wl = synth.make_workload(args.workload)
     S, L = wl["schemes"].shape
     N = wl["images"].shape[0]

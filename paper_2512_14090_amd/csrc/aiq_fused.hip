@@ -391,8 +391,9 @@ __device__ __forceinline__ void fused_checkpoint_copy(float *lds, float *g, int 
 }
 
 // MODE (FusedMode): the plain kernel runs every op; the reference pass also writes the LDS
-// state out before each op that has a checkpoint; a resumed pass starts scheme s at op
-// first_op[s] from that state.  Ops before first_op[s] carry the same bit-widths in scheme s
+// state out before each op whose checkpoint is asked for (and may itself continue from one of
+// its earlier checkpoints and stop once the last one asked for is written); a resumed pass
+// starts scheme s at op first_op[s] from that state.  Ops before first_op[s] carry the same bit-widths in scheme s
 // and in the reference scheme, so the restored state is bit for bit what the full run of
 // scheme s would hold there and the result does not depend on the mode.
 template <int NW, int MODE>
@@ -404,7 +405,8 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
     const int n = blockIdx.x, s = blockIdx.y;
     int o0 = 0;
     if (MODE == kFusedResume && s < a.S) o0 = __builtin_amdgcn_readfirstlane(a.first_op[s]);
-    const bool from_image = MODE != kFusedResume || o0 == 0;
+    if (MODE == kFusedReference) o0 = a.ref_first_op; // a reference pass may continue from its own checkpoint
+    const bool from_image = o0 == 0;
 
     // the image goes to registers first so that its HBM latency overlaps the LDS clear
     constexpr int IMG_PER_THREAD = 3072 / (NW * 64);
@@ -494,11 +496,12 @@ __global__ __launch_bounds__(NW * 64) void resnet_fused_kernel(FusedArgs a)
     for (int o = o0; o < a.n_ops; ++o) {
         if (MODE == kFusedReference && o > 0) {
             const FusedOp &op = a.ops[o];
-            if ((a.ck_mask[o >> 6] >> (o & 63)) & 1ull) {
+            if (o > o0 && ((a.ck_mask[o >> 6] >> (o & 63)) & 1ull)) {
                 fused_checkpoint_copy<NW, false>(lds, a.ckpt + (size_t)n * a.ckpt_stride + op.ck_off, op.ck_ext[0],
                                                  op.ck_ext[1], tid);
                 __syncthreads(); // the op below overwrites what other wavefronts may still be copying
             }
+            if (o >= a.ref_stop_op) break; // only the checkpoints were wanted
         }
         const OpRT nxt = uniform_op(nxt_raw);
         nxt_raw = s_ops[o + 2 < a.n_ops ? o + 2 : a.n_ops - 1];

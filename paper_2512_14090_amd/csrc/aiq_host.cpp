@@ -785,6 +785,19 @@ aiq_status aiq_eval_workspace_bytes(const aiq_model *m, int32_t S, int32_t chunk
 
 namespace {
 
+// Checkpoints a reference pass has left in a workspace, remembered across the scoring calls of
+// one search run (which owns the workspace for its duration and never changes images or
+// chunking): the reference scheme they were taken under and which ops have one.  A later
+// reference scheme that agrees with it on the layers before an op can reuse that op's
+// checkpoint, so the reference pass of the next step continues from the deepest such
+// checkpoint instead of from the image, and stops after the last checkpoint the step needs.
+struct CkptCache {
+    int s_layout = 0;            // scheme count the workspace is laid out for (offsets must not move between steps)
+    const void *workspace = nullptr;
+    std::vector<uint8_t> scheme; // empty: nothing cached
+    uint64_t valid[2] = {0, 0};
+};
+
 // What one launch of a node reads and writes: pointers for its first scheme and the distance
 // (in elements) between consecutive schemes; distance 0 = all schemes share one copy.
 struct NodeIO {
@@ -806,7 +819,8 @@ struct NodeIO {
 // resumes at its first layer whose width differs from ref's; the results are the same.
 aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t *schemes, int32_t S,
                      const uint8_t *ref, int32_t chunk, int32_t *top1_base, int32_t base_valid, float *logits,
-                     int32_t *top1, int32_t *agree, void *workspace, size_t workspace_bytes, void *hip_stream)
+                     int32_t *top1, int32_t *agree, void *workspace, size_t workspace_bytes, void *hip_stream,
+                     CkptCache *cache = nullptr)
 {
     if (!m || N < 0 || S < 0 || chunk < 1) return AIQ_INVALID_ARG;
     if (S > 0 && (!schemes || !agree)) return AIQ_INVALID_ARG;
@@ -819,7 +833,7 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
             if (!bits_supported(ref[i])) return AIQ_UNSUPPORTED_BITS;
     chunk = std::min(chunk, std::max(N, 1));
     const bool shared = ref != nullptr;
-    const WorkspaceLayout wl = workspace_layout(m, S, chunk, shared);
+    const WorkspaceLayout wl = workspace_layout(m, cache ? std::max(cache->s_layout, S) : S, chunk, shared);
     // sharing needs a reference pass that can hand over its state, and something to share it with
     const bool resume = shared && m->fused && m->fused_ckpt_floats > 0 && S > 0;
     if (N > 0 && workspace_bytes < wl.total) return AIQ_WORKSPACE_TOO_SMALL;
@@ -1152,19 +1166,57 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
                 r.top1_base = ref_is_base && run_base ? top1_base + n0 : nullptr;
                 r.ckpt = ckpt;
                 r.ckpt_stride = (int64_t)m->fused_ckpt_floats;
-                double ck_floats = 0.0; // only the checkpoints some scheme resumes from are written
-                for (int s_ = 0; s_ < S; ++s_) {
-                    const int o = first_op[s_];
-                    if (o > 0 && !((r.ck_mask[o >> 6] >> (o & 63)) & 1ull)) {
+                const int n_ops = (int)m->fused_ops.size();
+                const bool ref_head = ref_is_base && run_base; // the pass's own top-1 is wanted
+                // checkpoints the candidates resume from
+                uint64_t need[2] = {0, 0};
+                for (int s_ = 0; s_ < S; ++s_)
+                    if (first_op[s_] > 0) need[first_op[s_] >> 6] |= 1ull << (first_op[s_] & 63);
+                // those a previous step of the same search has left behind and that are still good:
+                // taken under a reference that agrees with this one on every layer before the op
+                const bool cached = cache && N <= chunk && cache->workspace == workspace &&
+                                    cache->scheme.size() == (size_t)m->L;
+                int same_upto = 0; // ops [0, same_upto) carry the same widths in both references
+                if (cached) {
+                    int d = 0;
+                    while (d < m->L && cache->scheme[d] == ref[d]) ++d;
+                    same_upto = d < m->L ? m->slot_op[d] + 1 : n_ops; // a checkpoint precedes its op
+                }
+                auto have = [&](int o) { return cached && o < same_upto && ((cache->valid[o >> 6] >> (o & 63)) & 1ull); };
+                r.ref_first_op = 0;
+                r.ref_stop_op = ref_head ? n_ops : 0;
+                double ck_floats = 0.0;
+                int first_missing = n_ops;
+                for (int o = 1; o < n_ops; ++o)
+                    if (((need[o >> 6] >> (o & 63)) & 1ull) && !have(o)) {
                         r.ck_mask[o >> 6] |= 1ull << (o & 63);
                         ck_floats += m->fused_ops[o].ck_ext[0] + m->fused_ops[o].ck_ext[1];
+                        first_missing = std::min(first_missing, o);
+                        r.ref_stop_op = std::max(r.ref_stop_op, o);
                     }
-                }
-                const double ck_bytes = 4.0 * ck_floats;
-                {
-                    ProfScope ps(m, st, AIQ_K_FUSED, m->fused_flops_per_image * n,
-                                 n * (4.0 * (m->nodes[0].in_elems + m->classes) + ck_bytes));
+                const bool run_ref = ref_head || first_missing < n_ops;
+                if (run_ref && !ref_head)
+                    for (int o = first_missing - 1; o > 0; --o) // deepest reusable checkpoint before the first missing one
+                        if (have(o)) {
+                            r.ref_first_op = o;
+                            break;
+                        }
+                if (run_ref) {
+                    double fl = 0.0;
+                    for (int o = r.ref_first_op; o < std::min(r.ref_stop_op, n_ops); ++o) fl += m->nodes[o].flops_per_image;
+                    ProfScope ps(m, st, AIQ_K_FUSED, fl * n,
+                                 n * (4.0 * (m->nodes[0].in_elems + m->classes) + 4.0 * ck_floats));
                     AIQ_HIP(launch_fused(r, 1, kFusedReference, st));
+                }
+                if (cache && N <= chunk) {
+                    // what the workspace now holds: the reusable part of the old set plus what this pass wrote
+                    uint64_t v[2] = {0, 0};
+                    for (int o = 1; o < n_ops; ++o)
+                        if (have(o) || ((r.ck_mask[o >> 6] >> (o & 63)) & 1ull)) v[o >> 6] |= 1ull << (o & 63);
+                    cache->workspace = workspace;
+                    cache->scheme.assign(ref, ref + m->L);
+                    cache->valid[0] = v[0];
+                    cache->valid[1] = v[1];
                 }
                 a.ckpt = ckpt;
                 a.ckpt_stride = r.ckpt_stride;
@@ -1348,6 +1400,7 @@ struct SearchCtx {
     int32_t s_max;
     bool base_valid = false;
     std::vector<int32_t> agree_host;
+    CkptCache ckpt_cache; // the workspace is this run's alone: checkpoints stay good from step to step
 
     double ai(const uint8_t *q, aiq_status *err) const
     {
@@ -1368,7 +1421,8 @@ struct SearchCtx {
     {
         if (S > s_max) return AIQ_WORKSPACE_TOO_SMALL;
         aiq_status rc = eval_impl(m, images, N, schemes.data(), S, p->share_prefix ? ref : nullptr, chunk, top1_base,
-                                  base_valid ? 1 : 0, nullptr, nullptr, agree_dev, eval_ws, eval_ws_bytes, st);
+                                  base_valid ? 1 : 0, nullptr, nullptr, agree_dev, eval_ws, eval_ws_bytes, st,
+                                  &ckpt_cache);
         if (rc != AIQ_OK) return rc;
         base_valid = true;
         agree_host.assign(S, 0);
@@ -1433,6 +1487,7 @@ aiq_status search_setup(SearchCtx &c, aiq_model *m, const aiq_layer_desc *layers
     c.eval_ws = ws + lay.eval_off;
     c.eval_ws_bytes = workspace_bytes - lay.eval_off;
     c.s_max = lay.s_max;
+    c.ckpt_cache.s_layout = lay.s_max;
     return AIQ_OK;
 }
 

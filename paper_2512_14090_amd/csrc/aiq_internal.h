@@ -231,6 +231,8 @@ struct FusedArgs {
     int64_t ckpt_stride;       // floats per image
     const int32_t *first_op;   // resumed pass: [S] op at which scheme s starts (0 = from the image)
     uint64_t ck_mask[2];       // reference pass: bit o set = write the checkpoint of op o
+    int32_t ref_first_op;      // reference pass: op to start at, from its own checkpoint (0 = from the image)
+    int32_t ref_stop_op;       // reference pass: stop before this op, after its checkpoint (n_ops = run to the end)
 };
 
 // How a launch of the LDS-resident kernel treats the checkpoints.

@@ -184,15 +184,26 @@ def test_layer_by_layer_models(env, builder, n, chunk, layerwise):
     _assert_identical(plain, shared)
 
 
-@pytest.mark.parametrize("method", ["greedy", "cd"])
-def test_search_is_unchanged_by_sharing(env, method):
+SEARCHES = [("greedy", (32, 8, 4)), ("cd", (32, 8, 4)), ("cd", (32, 16, 8, 6, 4, 2)), ("greedy", (32, 16, 4))]
+SEARCH_CASES = [(mth, b, 1, 64, 48, False) for mth, b in SEARCHES] + [(mth, b, 1, 64, 64, False) for mth, b in SEARCHES] + \
+               [(mth, b, 1, 30, 30, True) for mth, b in SEARCHES] + [(mth, b, 3, 40, 1024, False) for mth, b in SEARCHES[:2]]
+
+
+@pytest.mark.parametrize("method,bits,blocks,n,chunk,layerwise", SEARCH_CASES)
+def test_search_is_unchanged_by_sharing(env, method, bits, blocks, n, chunk, layerwise):
+    """Whole searches with and without the shared prefix: same scheme, same trace.  When all images fit in one
+    chunk the reference pass of a step continues from the checkpoints the previous steps left in the workspace
+    (the LDS-resident path), so consecutive steps with changing and unchanged references are covered."""
     torch, aiq, synth = env["torch"], env["aiq"], env["synth"]
-    wl = synth.make_workload(0, n_images=64)
-    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    wl = synth.make_workload(0 if blocks == 1 else 1, n_images=n)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=layerwise)
     img = torch.from_numpy(wl["images"]).cuda()
-    print(f"search {method} with and without prefix sharing", flush=True)
-    q0, t0 = m.search(wl["desc"], img, method=method, bits=(32, 8, 4), chunk=48, share_prefix=False)
-    q1, t1 = m.search(wl["desc"], img, method=method, bits=(32, 8, 4), chunk=48, share_prefix=True)
+    print(f"search {method} {bits} blocks={blocks} n={n} chunk={chunk} layerwise={layerwise}", flush=True)
+    q0, t0 = m.search(wl["desc"], img, method=method, bits=bits, chunk=chunk, share_prefix=False)
+    q1, t1 = m.search(wl["desc"], img, method=method, bits=bits, chunk=chunk, share_prefix=True)
+    # a second shared search on the same model and workspace starts from a clean cache
+    q2, t2 = m.search(wl["desc"], img, method=method, bits=bits, chunk=chunk, share_prefix=True)
     m.close()
     np.testing.assert_array_equal(q0, q1)
-    assert t0 == t1
+    np.testing.assert_array_equal(q0, q2)
+    assert t0 == t1 == t2
