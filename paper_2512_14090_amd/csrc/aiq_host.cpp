@@ -796,6 +796,7 @@ struct CkptCache {
     const void *workspace = nullptr;
     std::vector<uint8_t> scheme; // empty: nothing cached
     uint64_t valid[2] = {0, 0};
+    int valid_nodes = 0;         // layer-by-layer path: the reference outputs of nodes [0, valid_nodes) are good
 };
 
 // What one launch of a node reads and writes: pointers for its first scheme and the distance
@@ -912,7 +913,7 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
     uint8_t *sorted_dev = nullptr;
     int32_t *row_map_dev = nullptr;
     float *ref_act = nullptr;
-    int S_rows = 0;
+    int S_rows = 0, first_node_max = 0;
     std::vector<int> active;
     const std::vector<size_t> &ref_node_off = m->ref_node_off;
     if (share_nodes) {
@@ -943,6 +944,7 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
         std::stable_sort(rows.begin(), rows.end(),
                          [](const std::pair<int, int> &x, const std::pair<int, int> &y) { return x.first < y.first; });
         S_rows = (int)rows.size();
+        first_node_max = rows.back().first; // rows are sorted by their first node
         std::vector<uint8_t> sorted((size_t)S_rows * m->L, 32);
         std::vector<int32_t> row_map(S_rows + 1, -1);
         active.assign(n_nodes, 0);
@@ -1276,7 +1278,26 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
             io.s_total = 1;
             io.row_map = row_map_dev + S_rows; // a single -1: the row of the FP32 pass
             io.top1_base_out = ref_head ? top1_base + n0 : nullptr;
-            for (size_t l = 0; l < m->nodes.size(); ++l) {
+            // Rows only read reference outputs of nodes before the node they start at, so the pass
+            // ends at the last row's first node (unless its own top-1 is wanted); and it begins
+            // where the outputs a previous step of the same search left behind stop being good:
+            // at the first node whose layer differs between the two references.
+            const int n_nodes = (int)m->nodes.size();
+            int ref_lo = 0, ref_hi = ref_head ? n_nodes : first_node_max;
+            const bool caching = cache && N <= chunk;
+            if (caching && cache->workspace == workspace && cache->scheme.size() == (size_t)m->L) {
+                int d = 0;
+                while (d < m->L && cache->scheme[d] == ref[d]) ++d;
+                int changed = d < m->L ? m->slot_node[d] : n_nodes;
+                while (changed < n_nodes && m->nodes[changed].mb_role == 2) --changed; // a block is recomputed whole
+                ref_lo = std::min(cache->valid_nodes, changed);
+            }
+            if (caching) {
+                cache->workspace = workspace;
+                cache->scheme.assign(ref, ref + m->L);
+                cache->valid_nodes = std::max(ref_lo, ref_hi);
+            }
+            for (int l = ref_lo; l < ref_hi; ++l) {
                 const Node &nd = m->nodes[l];
                 if (nd.d.kind == 2 && !ref_head) continue;
                 io.in = nd.d.input < 0 ? images + (size_t)n0 * nd.in_elems : ref_ptr(nd.d.input);

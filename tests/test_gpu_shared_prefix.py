@@ -207,3 +207,20 @@ def test_search_is_unchanged_by_sharing(env, method, bits, blocks, n, chunk, lay
     np.testing.assert_array_equal(q0, q1)
     np.testing.assert_array_equal(q0, q2)
     assert t0 == t1 == t2
+
+
+@pytest.mark.parametrize("method,layerwise", [("cd", False), ("greedy", True)])
+def test_search_on_mobilenet_is_unchanged_by_sharing(env, method, layerwise):
+    """The same on a model of inverted-residual blocks (block kernel and layer by layer): the reference pass of a
+    step recomputes only the nodes between the previous step's layer and this one's."""
+    torch, aiq, synth = env["torch"], env["aiq"], env["synth"]
+    wl = _variant_workload(synth, "mobilenet", 6)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=layerwise)
+    img = torch.from_numpy(wl["images"]).cuda()
+    kw = dict(method=method, bits=(32, 8, 2), chunk=8, max_iters=3 if method == "greedy" else 1)
+    print(f"mobilenet search {method} layerwise={layerwise}", flush=True)
+    q0, t0 = m.search(wl["desc"], img, share_prefix=False, **kw)
+    q1, t1 = m.search(wl["desc"], img, share_prefix=True, **kw)
+    m.close()
+    np.testing.assert_array_equal(q0, q1)
+    assert t0 == t1
