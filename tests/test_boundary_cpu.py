@@ -100,6 +100,14 @@ def test_host_validation_precedes_device_work(aiq):
     assert lib.aiq_eval_workspace_bytes(None, 1, 1, None) == 1
     assert lib.aiq_eval_schemes(None, None, 1, None, 1, 1, None, 0, None, None, None, None, 0, None) == 1
     assert lib.aiq_model_scheme_layers(None) == -1 and lib.aiq_model_classes(None) == -1
+    # the shared-prefix entry points validate the same way
+    assert lib.aiq_model_shares_prefix(None) == -1
+    assert lib.aiq_eval_shared_workspace_bytes(None, 1, 1, None) == 1
+    ref = np.full(8, 32, dtype=np.uint8)
+    assert lib.aiq_eval_schemes_shared(None, None, 1, None, 1, ref.ctypes.data, 1, None, 0, None, None, None, None, 0,
+                                       None) == 1
+    assert lib.aiq_search_workspace_bytes(None, 1, 1, 3, None) == 1
+    assert lib.aiq_sensitivity_workspace_bytes(None, 1, 1, 2, None) == 1
     lib.aiq_model_destroy(None)
 
 
