@@ -217,6 +217,76 @@ def test_stem_dense_and_pooled_layers_on_odd_shapes(env):
         print("  max logit rel err %.3e" % err, flush=True)
 
 
+def _random_graph(G, rng):
+    """A seeded chain of 4 to 7 layers with optional residual links: 3x3 / 1x1 convolutions and depthwise
+    layers of both strides on square maps of 6 to 20 pixels, channel counts that are multiples of 4."""
+    ci = int(rng.choice([1, 3, 4]))
+    h = int(rng.integers(6, 21))
+    widths = [8, 12, 16, 24, 40, 64, 100]
+    c = int(rng.choice(widths))
+    nodes = [G._node(G.KIND_CONV, ci, c, 3, 1, h, -1, act=int(rng.integers(0, 3)), slot=0, name="stem")]
+    shapes = [(c, h)]  # output (channels, size) of every node
+    for i in range(int(rng.integers(3, 7))):
+        c_in, h_in = shapes[-1]
+        kind = str(rng.choice(["c3", "c3", "c1", "dw", "c3s2", "dws2", "c1s2"]))
+        stride = 2 if kind.endswith("s2") and h_in >= 4 else 1
+        k = 1 if kind.startswith("c1") else 3
+        h_out = (h_in + 2 * (k // 2) - k) // stride + 1
+        if kind.startswith("dw"):
+            nodes.append(G._node(G.KIND_DEPTHWISE, c_in, c_in, 3, stride, h_in, len(nodes) - 1, act=int(rng.integers(0, 3)),
+                                 slot=len(nodes), name=f"dw{i}"))
+            shapes.append((c_in, h_out))
+            continue
+        c_out = int(rng.choice(widths))
+        # a residual link to any earlier output of the same shape (choose the width to match one half of the time)
+        cands = [j for j, (cj, hj) in enumerate(shapes) if hj == h_out]
+        res = -1
+        if cands and rng.random() < 0.5:
+            res = int(rng.choice(cands))
+            c_out = shapes[res][0]
+        nodes.append(G._node(G.KIND_CONV, c_in, c_out, k, stride, h_in, len(nodes) - 1, residual=res,
+                             act=int(rng.integers(0, 3)), slot=len(nodes), name=f"c{i}"))
+        shapes.append((c_out, h_out))
+    c_last, h_last = shapes[-1]
+    nodes.append(G._node(G.KIND_FC, c_last, int(rng.choice([2, 10, 37])), 1, 1, h_last, len(nodes) - 1, act=G.ACT_NONE,
+                         slot=len(nodes), name="fc"))
+    return nodes, ci, h
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_random_graphs(env, seed):
+    """Seeded random layer graphs against the oracle, in the default mode and with the layer-by-layer kernels
+    forced, and the shared-prefix entry point against the plain one on the same graph."""
+    synth, oracle, aiq, torch = env["synth"], env["oracle"], env["aiq"], env["torch"]
+    rng = np.random.Generator(np.random.PCG64(9000 + seed))
+    nodes, ci, h = _random_graph(synth.graphs, rng)
+    L = len(nodes)
+    w, b = synth.make_model(nodes, rng)
+    n = 5
+    images = rng.standard_normal((n, h, h, ci)).astype(np.float32)
+    desc = synth.desc_array(nodes)
+    schemes = np.concatenate([np.full((1, L), 32), rng.choice([32, 16, 8, 6, 4, 2], size=(4, L))]).astype(np.uint8)
+    print("random graph %d: %s" % (seed, " ".join(
+        "%s%d>%d/%d@%d%s" % ("cdf"[nd["kind"]], nd["cin"], nd["cout"], nd["stride"], nd["hin"],
+                              "+r%d" % nd["residual"] if nd["residual"] >= 0 else "") for nd in nodes)), flush=True)
+    ref = oracle.eval_schemes(desc, w, b, images, schemes)
+    wl = dict(desc=desc, weights=w, biases=b, images=images)
+    for layerwise in (False, True):
+        gpu = _run_gpu(env, wl, schemes, chunk=2, layerwise=layerwise)
+        check_eval(gpu, ref, n)
+    m = aiq.Model(desc, w, b)
+    img = torch.from_numpy(images).cuda()
+    outs = []
+    for r in (None, schemes[1]):
+        o = m.eval_schemes(img, schemes, chunk=3, want_logits=True, want_top1=True, ref_scheme=r)
+        torch.cuda.synchronize()
+        outs.append({k: v.cpu().numpy() for k, v in o.items()})
+    m.close()
+    for k in ("agree", "top1_base", "top1"):
+        np.testing.assert_array_equal(outs[0][k], outs[1][k], err_msg=k)
+    np.testing.assert_array_equal(outs[0]["logits"].view(np.uint32), outs[1]["logits"].view(np.uint32))
+
+
 @pytest.mark.parametrize("case", ["resnet8", "resnet8_layerwise", "mobilenetv2"])
 def test_per_tensor_scales(env, case):
     """Scheme scoring with one quantization scale per layer (per-tensor variant) against the oracle's."""
