@@ -926,33 +926,47 @@ constexpr int kMaxClasses = 64;
 
 __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
 {
-    extern __shared__ float sm[]; // pooled[C] then partial[groups][C] scratch, then z[classes]
+    extern __shared__ float sm[]; // pooled[C], then partial sums [256] x 16 bytes, then z[classes]
     const int s = blockIdx.y, n = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *x = a.in + (size_t)s * a.in_scheme_stride + (size_t)n * a.HW * a.C;
     float *pooled = sm;
     float *partial = sm + a.C;
-    float *z = partial + 256;
+    float *z = partial + 1024;
 
-    // threads are laid out [group][channel lane]; groups split the positions when C < 256
-    const int cw = a.C < 256 ? a.C : 256;
+    // Pooling with 16-byte loads (C is a multiple of 4 for every producer): threads are laid out
+    // [pixel group][4-channel lane]; the pixel groups split the positions when C / 4 < 256, four
+    // independent partial sums per thread keep several loads in flight.
+    const floatx4 *x4 = reinterpret_cast<const floatx4 *>(x);
+    floatx4 *partial4 = reinterpret_cast<floatx4 *>(partial);
+    const int c4n = a.C >> 2;
+    const int cw = c4n < 256 ? c4n : 256;
     const int groups = 256 / cw;
     const int grp = tid / cw, cl = tid - grp * cw;
     const float inv = 1.0f / (float)a.HW;
-    for (int c = cl; c < a.C; c += cw) {
-        float acc = 0.0f;
-        if (grp < groups)
-            for (int i = grp; i < a.HW; i += groups) acc += x[(size_t)i * a.C + c];
+    for (int c4 = cl; c4 < c4n; c4 += cw) {
+        floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = acc0, acc2 = acc0, acc3 = acc0;
+        if (grp < groups) {
+            int i = grp;
+            for (; i + 3 * groups < a.HW; i += 4 * groups) {
+                acc0 += x4[(size_t)i * c4n + c4];
+                acc1 += x4[(size_t)(i + groups) * c4n + c4];
+                acc2 += x4[(size_t)(i + 2 * groups) * c4n + c4];
+                acc3 += x4[(size_t)(i + 3 * groups) * c4n + c4];
+            }
+            for (; i < a.HW; i += groups) acc0 += x4[(size_t)i * c4n + c4];
+        }
+        floatx4 acc = (acc0 + acc1) + (acc2 + acc3);
         if (groups > 1) {
             __syncthreads();
-            partial[tid] = acc;
+            partial4[tid] = acc;
             __syncthreads();
             if (grp == 0) {
-                for (int g = 1; g < groups; ++g) acc += partial[g * cw + cl];
-                pooled[c] = acc * inv;
+                for (int g = 1; g < groups; ++g) acc += partial4[g * cw + cl];
+                *reinterpret_cast<floatx4 *>(pooled + c4 * 4) = acc * inv;
             }
         } else if (grp == 0) {
-            pooled[c] = acc * inv; // threads past the last whole group (256 % C != 0) hold nothing
+            *reinterpret_cast<floatx4 *>(pooled + c4 * 4) = acc * inv; // threads past the last whole group hold nothing
         }
     }
     __syncthreads();
@@ -984,7 +998,8 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
 hipError_t launch_head(const HeadArgs &a, int s_total, hipStream_t st)
 {
     if (a.N == 0 || s_total == 0) return hipSuccess;
-    const size_t sm = sizeof(float) * ((size_t)a.C + 256 + kMaxClasses);
+    if (a.C & 3) return hipErrorInvalidValue;
+    const size_t sm = sizeof(float) * ((size_t)a.C + 1024 + kMaxClasses);
     hipLaunchKernelGGL(head_kernel, dim3(a.N, s_total), dim3(256), sm, st, a);
     return hipGetLastError();
 }
