@@ -23,28 +23,28 @@ PEAK_HBM_GBS = 8000.0
 TRAFFIC = {
     ("resnet20_greedy_step_n1024_s40", "resnet_fused"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_fused.hip",
-        "sha256": "0343a680097f7a82345a3662d5ff49b0c29bb8e74a965efe17a95001a50d329e",
-        "bytes_per_launch": 48630571,
+        "sha256": "56d1c2d483b20bd9b6d21cb09afec8e50edc7f4cc62b2032687c978bf27bee5e",
+        "bytes_per_launch": 62087680,
     },
     ("mobilenetv2_32_n512_s16", "mbconv"): {  # average over the 16 block launches of a step
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_mbconv.hip",
         "sha256": "e02a1f9407b013c8cf925ecbd3f4b3a8ad76bfb5683fbc093d4c6f4f10930233",
-        "bytes_per_launch": 1788954568,
+        "bytes_per_launch": 1789082922,
     },
     ("mobilenetv2_32_n512_s16", "depthwise"): {  # layer by layer: average over the 17 depthwise launches
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "f0e500c02e63a532b2235d973872561abf87fc04235b018a1c3743fdcfb24319",
-        "bytes_per_launch": 8289530808,
+        "sha256": "21d5ab04e49a794611bd002c8629cfcebc2214c8efefa2fc4bb8f23d738269d5",
+        "bytes_per_launch": 8289526795,
     },
     ("plainconvnet20_sensitivity_n256_s42", "conv_mfma"): {  # average over the 20 convolution launches of a step
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "f0e500c02e63a532b2235d973872561abf87fc04235b018a1c3743fdcfb24319",
-        "bytes_per_launch": 2901517701,
+        "sha256": "21d5ab04e49a794611bd002c8629cfcebc2214c8efefa2fc4bb8f23d738269d5",
+        "bytes_per_launch": 2898891225,
     },
     ("quantize_stress_8192x4608_b8", "quantize"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "f0e500c02e63a532b2235d973872561abf87fc04235b018a1c3743fdcfb24319",
-        "bytes_per_launch": 302314178,
+        "sha256": "21d5ab04e49a794611bd002c8629cfcebc2214c8efefa2fc4bb8f23d738269d5",
+        "bytes_per_launch": 302320344,
     },
 }
 
