@@ -136,6 +136,11 @@ def search_mode(args, torch, aiq, synth):
             "config": {"workload": wl["name"] + "_search_" + args.search, "images": int(images.shape[0]),
                        "alphabet": list(bits), "lambda": 0.9, "accepted_moves": len(tr1) - 1,
                        "scheme": [int(v) for v in q1], "final_agree": int(tr1[-1]["agree"]),
+                       # the paper's report columns: arithmetic intensity before / after, its gain, and the
+                       # combined score AI x accuracy (accuracy = agreement with the FP32 model here)
+                       "ai_fp32": tr1[0]["ai"], "ai_final": tr1[-1]["ai"],
+                       "ai_gain": tr1[-1]["ai"] / tr1[0]["ai"] - 1.0,
+                       "combined_score": tr1[-1]["ai"] * tr1[-1]["agree"] / float(images.shape[0]),
                        "lds_resident": bool(model.lds_resident)},
             "without_prefix_sharing": {"value": t_plain, "unit": "s", "same_result": bool((q0 == q1).all() and tr0 == tr1)}}
     model.close()
