@@ -233,6 +233,15 @@ hipError_t launch_quantize_batch(const QuantJob *jobs_dev, const int32_t *block_
     return hipGetLastError();
 }
 
+// Logical block index for launches whose neighbouring blocks share data: hardware block b runs
+// on XCD b % 8; XCD k is given the k-th contiguous stretch of n / 8 (one more for the first
+// n % 8) logical blocks.  A permutation of [0, n), whatever the dispatch order really is.
+__device__ inline uint32_t xcd_contiguous_block(uint32_t b, uint32_t n)
+{
+    const uint32_t per = n >> 3, rem = n & 7u, xcd = b & 7u, idx = b >> 3;
+    return xcd * per + (xcd < rem ? xcd : rem) + idx;
+}
+
 // ------------------------------------------------------------------ dense convolution
 //
 // Implicit GEMM on v_mfma_f32_16x16x4_f32 with the weights as the A operand
@@ -319,13 +328,15 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int s = blockIdx.z;
 
+    // neighbouring regions share halo rows: keep them on one XCD
+    const int bx = (int)xcd_contiguous_block(blockIdx.x, gridDim.x);
     int img0, oy0;
     if (a.G > 1) {
-        img0 = blockIdx.x * a.G;
+        img0 = bx * a.G;
         oy0 = 0;
     } else {
-        img0 = blockIdx.x / a.regions_per_image;
-        oy0 = (blockIdx.x - img0 * a.regions_per_image) * a.R;
+        img0 = bx / a.regions_per_image;
+        oy0 = (bx - img0 * a.regions_per_image) * a.R;
     }
 
     const int wpx = wave % a.wave_px_split;
@@ -474,13 +485,14 @@ __global__ __launch_bounds__(256, 2) void conv_stem_kernel(ConvArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // uniform: keeps the tile indices scalar
     const int s = blockIdx.z;
+    const int bx = (int)xcd_contiguous_block(blockIdx.x, gridDim.x); // halo rows meet in one XCD's L2
     int img0, oy0;
     if (a.G > 1) {
-        img0 = blockIdx.x * a.G;
+        img0 = bx * a.G;
         oy0 = 0;
     } else {
-        img0 = blockIdx.x / a.regions_per_image;
-        oy0 = (blockIdx.x - img0 * a.regions_per_image) * a.R;
+        img0 = bx / a.regions_per_image;
+        oy0 = (bx - img0 * a.regions_per_image) * a.R;
     }
     const int wpx = wave % a.wave_px_split;
     const int wco = wave / a.wave_px_split;
@@ -835,7 +847,10 @@ __global__ __launch_bounds__(256) void depthwise3x3_kernel(DepthwiseArgs a)
     const int s = blockIdx.z;
     const int c4n = a.C >> 2;
     const uint32_t P = (uint32_t)(a.Wout / XG) * c4n;
-    const uint32_t gidx = blockIdx.x * 256u + threadIdx.x;
+    // Workgroups are handed to the eight XCDs in turn, each with its own L2.  Neighbouring
+    // workgroups share halo columns, so each XCD gets one contiguous eighth of the flat axis
+    // instead of every eighth workgroup: the shared columns then meet in one L2.
+    const uint32_t gidx = xcd_contiguous_block(blockIdx.x, gridDim.x) * 256u + threadIdx.x;
     if (gidx >= (uint32_t)a.N * P) return;
     const uint32_t img = gidx / P, pos = gidx - img * P;
     const uint32_t xg = fd_div(pos, a.div_c4);
