@@ -33,18 +33,18 @@ TRAFFIC = {
     },
     ("mobilenetv2_32_n512_s16", "depthwise"): {  # layer by layer: average over the 17 depthwise launches
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "21d5ab04e49a794611bd002c8629cfcebc2214c8efefa2fc4bb8f23d738269d5",
-        "bytes_per_launch": 8289526795,
+        "sha256": "81f7b392c07c2bdb10f15761e6421f0aabb47f64c91d23cddeba500019a77987",
+        "bytes_per_launch": 7834003484,
     },
     ("plainconvnet20_sensitivity_n256_s42", "conv_mfma"): {  # average over the 20 convolution launches of a step
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "21d5ab04e49a794611bd002c8629cfcebc2214c8efefa2fc4bb8f23d738269d5",
-        "bytes_per_launch": 2898891225,
+        "sha256": "81f7b392c07c2bdb10f15761e6421f0aabb47f64c91d23cddeba500019a77987",
+        "bytes_per_launch": 2694684770,
     },
     ("quantize_stress_8192x4608_b8", "quantize"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "21d5ab04e49a794611bd002c8629cfcebc2214c8efefa2fc4bb8f23d738269d5",
-        "bytes_per_launch": 302320344,
+        "sha256": "81f7b392c07c2bdb10f15761e6421f0aabb47f64c91d23cddeba500019a77987",
+        "bytes_per_launch": 302327530,
     },
 }
 
