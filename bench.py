@@ -19,7 +19,8 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch of a kernel class from rocprofv3 counters (FETCH_SIZE x 2.000 and
 # WRITE_SIZE x 1.000, the factors a plain copy of known size gives; profiles/ has the runs).
-# Valid only for the kernel source it was measured on: keyed by the sha256 of that source.
+# Valid only for the kernel source it was measured on: keyed by the sha256 of that source (of the
+# sections of it that hold the kernel, where the file holds several).
 TRAFFIC = {
     ("resnet20_greedy_step_n1024_s40", "resnet_fused"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_fused.hip",
@@ -33,30 +34,48 @@ TRAFFIC = {
     },
     ("mobilenetv2_32_n512_s16", "depthwise"): {  # layer by layer: average over the 17 depthwise launches
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "81f7b392c07c2bdb10f15761e6421f0aabb47f64c91d23cddeba500019a77987",
+        "sections": ["helpers", "depthwise 3x3"],
+        "sha256": "040711c3eb32c64180a31d22474f57a158017a5ae53563812ff47f6dd63a8e60",
         "bytes_per_launch": 7834003484,
     },
     ("plainconvnet20_sensitivity_n256_s42", "conv_mfma"): {  # average over the 20 convolution launches of a step
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "81f7b392c07c2bdb10f15761e6421f0aabb47f64c91d23cddeba500019a77987",
+        "sections": ["helpers", "dense convolution", "network stems"],
+        "sha256": "a7526213d5d9f3f925369b0a6a961a1088b8de29e471f53501d974fe8ecafab6",
         "bytes_per_launch": 2694684770,
     },
     ("quantize_stress_8192x4608_b8", "quantize"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
-        "sha256": "81f7b392c07c2bdb10f15761e6421f0aabb47f64c91d23cddeba500019a77987",
+        "sections": ["helpers", "quantizer"],
+        "sha256": "6f555449544557c2da2d7e546baf7f5ac38bafb9683b015970fcafded6b2df5c",
         "bytes_per_launch": 302327530,
     },
 }
 
 
-def measured_traffic(workload_name, cls):
+def source_hash(path, sections=None):
+    """sha256 of a kernel source, or of the named sections of it (a section runs from its
+    '// ---...--- title' line to the next such line), so that a change elsewhere in the file does
+    not look like a change of the kernel the counters were taken on."""
     import hashlib
+    with open(os.path.join(ROOT, path), "rb") as f:
+        text = f.read().decode()
+    if sections:
+        marker = "// " + "-" * 66 + " "
+        parts = text.split(marker)
+        picked = [p for p in parts[1:] if p.split("\n", 1)[0].strip() in sections]
+        if len(picked) != len(sections):
+            return None
+        text = marker.join(picked)
+    return hashlib.sha256(text.encode()).hexdigest()
+
+
+def measured_traffic(workload_name, cls):
     rec = TRAFFIC.get((workload_name, cls))
     if not rec:
         return None
-    with open(os.path.join(ROOT, rec["kernel_source"]), "rb") as f:
-        if hashlib.sha256(f.read()).hexdigest() != rec["sha256"]:
-            return None  # the kernel changed since the counters were taken
+    if source_hash(rec["kernel_source"], rec.get("sections")) != rec["sha256"]:
+        return None  # the kernel changed since the counters were taken
     return rec["bytes_per_launch"]
 
 

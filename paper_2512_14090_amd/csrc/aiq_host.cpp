@@ -1030,6 +1030,7 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
             a.wave_px_split = p.wave_px_split;
             a.cout_tiles = p.cout_tiles;
             a.pool = nd.pooled ? 1 : 0;
+            a.grid_y = p.grid_y;
             const int tile_px = 64 * p.wave_px_split;
             const size_t lds = sizeof(float) * (size_t)tile_px * p.PS;
             ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);

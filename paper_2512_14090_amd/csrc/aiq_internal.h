@@ -110,6 +110,7 @@ struct PointwiseArgs {
     int32_t Cin, Cout, act;
     int32_t CB, CKC, PS;      // ceil(Cin/16), channels staged per pass, LDS pixel stride (floats)
     int32_t wave_px_split, cout_tiles;
+    int32_t grid_y;           // output-channel blocks (the launcher folds them into the block axis)
     int32_t pool;             // 1: images of 64 pixels (one per wavefront), no residual; out = [S][images][Cout],
                               // the mean of the activated outputs over each image's pixels
 };

@@ -52,6 +52,15 @@ __device__ inline float wave_sum(float v)
     return v;
 }
 
+// Logical block index for launches whose neighbouring blocks share data: hardware block b runs
+// on XCD b % 8; XCD k is given the k-th contiguous stretch of n / 8 (one more for the first
+// n % 8) logical blocks.  A permutation of [0, n), whatever the dispatch order really is.
+__device__ inline uint32_t xcd_contiguous_block(uint32_t b, uint32_t n)
+{
+    const uint32_t per = n >> 3, rem = n & 7u, xcd = b & 7u, idx = b >> 3;
+    return xcd * per + (xcd < rem ? xcd : rem) + idx;
+}
+
 // ------------------------------------------------------------------ quantizer
 //
 // One wavefront per output channel.  Pass 1: absmax of the row by a cross-lane
@@ -231,15 +240,6 @@ hipError_t launch_quantize_batch(const QuantJob *jobs_dev, const int32_t *block_
     if (n_blocks == 0) return hipSuccess;
     hipLaunchKernelGGL(quantize_batch_kernel, dim3(n_blocks), dim3(256), 0, st, jobs_dev, block_job_dev, mask);
     return hipGetLastError();
-}
-
-// Logical block index for launches whose neighbouring blocks share data: hardware block b runs
-// on XCD b % 8; XCD k is given the k-th contiguous stretch of n / 8 (one more for the first
-// n % 8) logical blocks.  A permutation of [0, n), whatever the dispatch order really is.
-__device__ inline uint32_t xcd_contiguous_block(uint32_t b, uint32_t n)
-{
-    const uint32_t per = n >> 3, rem = n & 7u, xcd = b & 7u, idx = b >> 3;
-    return xcd * per + (xcd < rem ? xcd : rem) + idx;
 }
 
 // ------------------------------------------------------------------ dense convolution
@@ -671,10 +671,15 @@ __global__ __launch_bounds__(256, 2) void pointwise_mfma_kernel(PointwiseArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // uniform: keeps the tile indices scalar
     const int s = blockIdx.z;
     const int tile_px = 64 * a.wave_px_split;
-    const int P0 = blockIdx.x * tile_px;
+    // One flat block axis, output-channel block fastest: the blocks that read the same pixel tile
+    // follow each other, and the XCD-contiguous order puts them behind one L2 (with the
+    // output-channel blocks on a second grid axis every one of them fetched the tile from HBM).
+    const uint32_t lb = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    const int bx = (int)(lb / (uint32_t)a.grid_y), by = (int)(lb - (uint32_t)bx * a.grid_y);
+    const int P0 = bx * tile_px;
     const int wpx = wave % a.wave_px_split;
     const int wco = wave / a.wave_px_split;
-    const int ct0 = (blockIdx.y * (4 / a.wave_px_split) + wco) * NT;
+    const int ct0 = (by * (4 / a.wave_px_split) + wco) * NT;
     const int p = lane & 15, kq = lane >> 4;
     const bool active = ct0 < a.cout_tiles;
 
@@ -813,7 +818,8 @@ static hipError_t launch_pointwise_t(const PointwiseArgs &a, size_t lds_bytes, d
         if (e != hipSuccess) return e;
         lds_set = true;
     }
-    hipLaunchKernelGGL((pointwise_mfma_kernel<NT>), grid, dim3(256), lds_bytes, st, a);
+    if (a.grid_y < 1 || (int)grid.y != a.grid_y) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((pointwise_mfma_kernel<NT>), dim3(grid.x * grid.y, 1, grid.z), dim3(256), lds_bytes, st, a);
     return hipGetLastError();
 }
 
