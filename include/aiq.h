@@ -260,16 +260,52 @@ aiq_status aiq_layer_sensitivity(aiq_model *m, const float *images, int32_t N, i
                                  int32_t *agree_out);
 
 /*
- * Per-kernel timing for roofline reports.  While enabled, aiq_eval_schemes brackets
+ * Deployed inference of one scheme (paper: Implementation, experiment (3); Results, Analysis of
+ * AIQ Throughput Effects - the model with the searched layers at low precision is run end to end
+ * and its images/s compared with the FP32 model's).  The function computed is the scored one:
+ * the forward pass with every layer's weights quantized to scheme[i] bits.  What changes is the
+ * arithmetic of dense convolutions (groups = 1, not the network's first layer) of at most 8 bits:
+ * their weights are integer codes times a per-channel scale, the codes are exact in bf16, and an
+ * fp32 activation is exactly the sum of three bf16 terms, so the layer runs as three
+ * v_mfma_f32_32x32x16_bf16 products with exact terms in place of one fp32 MFMA product, sixteen
+ * times slower.  Results agree with aiq_eval_schemes to fp32 rounding (the accumulation order
+ * differs and the scale multiplies the finished sum).  All other layers run on the fp32 kernels.
+ *
+ * aiq_deploy_create: m must have been created with AIQ_MODEL_LAYERWISE (else UNSUPPORTED_LAYER)
+ * and must outlive the deployment; scheme: host uint8[L].  flags: AIQ_DEPLOY_FP32_MATRIX keeps
+ * every layer on the fp32 kernels (the same model without the bf16 path, for comparison).
+ * Quantizes and packs the weights; allocates device memory (codes and scales), freed by
+ * aiq_deploy_destroy.  Synchronous.  It fills weight-bank slots of m: do not overlap it with
+ * other calls on m.  Errors: INVALID_ARG, UNSUPPORTED_BITS, UNSUPPORTED_LAYER, DEVICE_ERROR.
+ *
+ * aiq_deploy_forward: images: device fp32 [N][hin][win][cin].  logits: device fp32 [N][classes]
+ * or NULL.  top1: device int32 [N], required.  workspace: device, 256-byte aligned, at least
+ * aiq_deploy_workspace_bytes(d, chunk) bytes (activation buffers for `chunk` images at a time).
+ * Asynchronous on hip_stream.  N = 0 is a valid no-op.
+ * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, DEVICE_ERROR.
+ */
+typedef struct aiq_deployed aiq_deployed; /* opaque */
+enum { AIQ_DEPLOY_FP32_MATRIX = 1 };
+aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags, aiq_deployed **out);
+void aiq_deploy_destroy(aiq_deployed *d); /* NULL-safe */
+/* Number of layers that run from their integer codes on the bf16 matrix pipe; -1 for NULL. */
+int32_t aiq_deploy_code_layers(const aiq_deployed *d);
+aiq_status aiq_deploy_workspace_bytes(const aiq_deployed *d, int32_t chunk, size_t *bytes);
+aiq_status aiq_deploy_forward(aiq_deployed *d, const float *images, int32_t N, int32_t chunk, float *logits,
+                              int32_t *top1, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Per-kernel timing for roofline reports.  While enabled, aiq_eval_schemes and aiq_deploy_forward bracket
  * every launch with HIP events on the launch stream.  aiq_profile_read waits for the
  * recorded events, then returns for kernel class cls the number of launches, their
  * summed duration and the algorithmic FLOPs and bytes they covered, and clears the
  * record for that class.  Classes: 0 quantize, 1 dense convolution (MFMA),
  * 2 depthwise convolution, 3 classifier head, 4 agreement count, 5 LDS-resident whole network,
- * 6 LDS-resident inverted-residual block.
+ * 6 LDS-resident inverted-residual block, 7 dense convolution on integer codes (bf16 MFMA,
+ * deployed inference).
  */
 enum { AIQ_K_QUANTIZE = 0, AIQ_K_CONV = 1, AIQ_K_DEPTHWISE = 2, AIQ_K_HEAD = 3, AIQ_K_AGREE = 4,
-       AIQ_K_FUSED = 5, AIQ_K_MBCONV = 6, AIQ_K_CLASSES = 7 };
+       AIQ_K_FUSED = 5, AIQ_K_MBCONV = 6, AIQ_K_CONV_CODES = 7, AIQ_K_CLASSES = 8 };
 aiq_status aiq_profile_enable(aiq_model *m, int32_t on);
 aiq_status aiq_profile_read(aiq_model *m, int32_t cls, int64_t *launches, double *total_ms, double *flops,
                             double *bytes);

@@ -6,6 +6,7 @@ PyTorch supplies device memory and streams.  There is no CPU fallback: without
 the built library, or without a GPU, the device entry points raise.
 """
 from .binding import (  # noqa: F401
-    AiqError, Model, layer_ai, quantize_weights, library_path, load_library, EXPORTED_SYMBOLS,
-    K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV, MODEL_LAYERWISE, MODEL_PER_TENSOR,
+    AiqError, Model, Deployed, layer_ai, quantize_weights, library_path, load_library, EXPORTED_SYMBOLS,
+    K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV, K_CONV_CODES, MODEL_LAYERWISE, MODEL_PER_TENSOR,
+    DEPLOY_FP32_MATRIX,
 )

@@ -16,10 +16,13 @@ EXPORTED_SYMBOLS = (
     "aiq_eval_schemes", "aiq_model_shares_prefix", "aiq_eval_shared_workspace_bytes", "aiq_eval_schemes_shared",
     "aiq_profile_enable", "aiq_profile_read", "aiq_search_workspace_bytes",
     "aiq_search_greedy", "aiq_search_coordinate_descent", "aiq_sensitivity_workspace_bytes", "aiq_layer_sensitivity",
+    "aiq_deploy_create", "aiq_deploy_destroy", "aiq_deploy_code_layers", "aiq_deploy_workspace_bytes",
+    "aiq_deploy_forward",
 )
-K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV = range(7)
+K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV, K_CONV_CODES = range(8)
 MODEL_LAYERWISE = 1
 MODEL_PER_TENSOR = 2
+DEPLOY_FP32_MATRIX = 1
 _DESC_INTS = 13
 
 
@@ -90,6 +93,13 @@ def load_library():
     lib.aiq_sensitivity_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
     lib.aiq_layer_sensitivity.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
                                           C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.aiq_deploy_create.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p)]
+    lib.aiq_deploy_destroy.argtypes = [C.c_void_p]
+    lib.aiq_deploy_destroy.restype = None
+    lib.aiq_deploy_code_layers.argtypes = [C.c_void_p]
+    lib.aiq_deploy_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]
+    lib.aiq_deploy_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_size_t, C.c_void_p]
     for name in EXPORTED_SYMBOLS:
         getattr(lib, name)
     _lib = lib
@@ -315,3 +325,63 @@ class Model:
         _check(self._lib.aiq_profile_read(self._h, int(cls), C.byref(n), C.byref(ms), C.byref(fl), C.byref(by)),
                "aiq_profile_read")
         return dict(launches=n.value, total_ms=ms.value, flops=fl.value, bytes=by.value)
+
+
+class Deployed:
+    """Owns an aiq_deployed handle: one scheme of a layer-by-layer Model, ready for inference."""
+
+    def __init__(self, model, scheme, fp32_matrix=False):
+        self._h = C.c_void_p(None)
+        self._lib = load_library()
+        self._model = model  # the deployment reads the model's weights and banks: keep it alive
+        sch = np.ascontiguousarray(scheme, dtype=np.uint8)
+        if sch.shape != (model.L,):
+            raise AiqError(3, "aiq_deploy_create: scheme length differs from the model's L")
+        h = C.c_void_p(None)
+        _check(self._lib.aiq_deploy_create(model._h, sch.ctypes.data, DEPLOY_FP32_MATRIX if fp32_matrix else 0,
+                                           C.byref(h)), "aiq_deploy_create")
+        self._h = h
+        self.code_layers = int(self._lib.aiq_deploy_code_layers(h))
+        self._workspace = None
+
+    def close(self):
+        if self._h:
+            self._lib.aiq_deploy_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace_bytes(self, chunk):
+        out = C.c_size_t(0)
+        _check(self._lib.aiq_deploy_workspace_bytes(self._h, int(chunk), C.byref(out)), "aiq_deploy_workspace_bytes")
+        return out.value
+
+    def forward(self, images, chunk=1024, want_logits=False, out=None, stream=None):
+        """aiq_deploy_forward.  images: CUDA fp32 [N][H][W][C].  Returns dict(top1, logits|None), not synchronised."""
+        import torch
+        if not (images.is_cuda and images.dtype == torch.float32 and images.is_contiguous()):
+            raise ValueError("images must be a contiguous CUDA float32 tensor")
+        N, dev = images.shape[0], images.device
+        out = out or {}
+        top1 = out.get("top1")
+        if top1 is None:
+            top1 = torch.empty(max(N, 1), dtype=torch.int32, device=dev)
+        logits = None
+        if want_logits:
+            logits = out.get("logits")
+            if logits is None:
+                logits = torch.empty((N, self._model.classes), dtype=torch.float32, device=dev)
+        chunk = max(1, min(int(chunk), max(N, 1)))
+        nbytes = self.workspace_bytes(chunk)
+        if self._workspace is None or self._workspace.numel() < nbytes or self._workspace.device != dev:
+            self._workspace = None
+            self._workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+        ws = self._workspace
+        _check(self._lib.aiq_deploy_forward(self._h, images.data_ptr(), N, chunk,
+                                            None if logits is None else logits.data_ptr(), top1.data_ptr(),
+                                            ws.data_ptr(), ws.numel(), _stream_ptr(stream)), "aiq_deploy_forward")
+        return dict(top1=top1[:N], logits=logits)

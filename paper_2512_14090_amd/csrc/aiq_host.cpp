@@ -161,6 +161,65 @@ aiq_status plan_conv(Node &nd)
     return AIQ_OK;
 }
 
+// Tiling of the integer-code convolution (conv_codes_kernel): output-channel tiles are 32 wide,
+// a wavefront holds one or two of them for 64 pixels, and a staged pixel takes three bf16 planes
+// of CKC channels, each padded by 16 bytes.  False if even 16 channels do not fit the LDS.
+struct CodePlan {
+    int nt, wave_px_split, R, G, regions_per_image, CB, CKC, RIN, LW, PSU, cout_tiles, grid_y;
+    size_t lds_bytes;
+};
+
+bool plan_code_conv(const Node &nd, CodePlan &p)
+{
+    const aiq_layer_desc &d = nd.d;
+    // Preferred split of the four wavefronts as for the fp32 kernel (most output channels per
+    // workgroup at no more than 1/8 of the MFMAs wasted); if the region that goes with it does
+    // not fit the LDS, more wavefronts go along the output channels and the region shrinks.
+    for (int wco_min = 1; wco_min <= 4; wco_min *= 2) {
+        p = CodePlan{};
+        p.cout_tiles = (d.cout + 31) / 32;
+        p.CB = (d.cin + 15) / 16;
+        int wco = 0, best_cover = 0;
+        for (int nt = 1; nt <= 2; ++nt)
+            for (int w = wco_min; w <= 4; w *= 2) {
+                const int per_wg = nt * w;
+                const int waste = (p.cout_tiles + per_wg - 1) / per_wg * per_wg - p.cout_tiles;
+                if (waste * 8 > p.cout_tiles && !(nt == 1 && w == wco_min)) continue;
+                if (per_wg > best_cover || (per_wg == best_cover && nt > p.nt)) {
+                    best_cover = per_wg;
+                    p.nt = nt;
+                    wco = w;
+                }
+            }
+        p.wave_px_split = 4 / wco;
+        p.grid_y = (p.cout_tiles + p.nt * wco - 1) / (p.nt * wco);
+        const int region_px = 64 * p.wave_px_split;
+        const int px_img = nd.hout * nd.wout;
+        if (px_img >= region_px) {
+            p.G = 1;
+            p.R = std::min(region_px / nd.wout, nd.hout);
+            if (p.R < 1) continue;
+            p.regions_per_image = (nd.hout + p.R - 1) / p.R;
+        } else {
+            p.G = region_px / px_img;
+            p.R = nd.hout;
+            p.regions_per_image = 1;
+        }
+        const int cp = p.CB * 16;
+        p.CKC = cp >= 64 ? 64 : (cp >= 32 ? 32 : 16);
+        p.RIN = (p.R - 1) * d.stride + d.kh;
+        p.LW = d.win + 2 * d.pad;
+        for (;;) { // two workgroups per compute unit where the region allows it, as for the fp32 kernel
+            p.PSU = p.CKC / 8 + 1;
+            p.lds_bytes = (size_t)16 * p.G * p.RIN * p.LW * 3 * p.PSU;
+            if (p.lds_bytes <= 80 * 1024 || p.CKC == 16) break;
+            p.CKC /= 2;
+        }
+        if (p.lds_bytes <= 160 * 1024) return true;
+    }
+    return false;
+}
+
 // Recognises stem -> basic blocks (identity, or stride-2 with a 1x1 projection) -> classifier
 // with 16/32/64 channels at 32/16/8 pixels, and lays the tensors out in two LDS regions:
 // a block reads its input from one region, writes the intermediate to the other and the
@@ -704,7 +763,8 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
         aiq_model_destroy(m);
         return code;
     };
-    if (!hip_ok(conv_set_lds_limits()) || !hip_ok(fused_set_lds_limit())) return fail(AIQ_DEVICE_ERROR);
+    if (!hip_ok(conv_set_lds_limits()) || !hip_ok(fused_set_lds_limit()) || !hip_ok(conv_codes_set_lds_limits()))
+        return fail(AIQ_DEVICE_ERROR);
     std::vector<int32_t> block_job;
     m->per_tensor = (flags & AIQ_MODEL_PER_TENSOR) != 0;
     if (m->per_tensor && (st = dev_alloc(m, &m->layer_amax, (size_t)n_layers)) != AIQ_OK) return fail(st);
@@ -814,6 +874,181 @@ struct NodeIO {
     const int32_t *row_map;  // classifier: output row of launch index i (-1: the FP32 pass), or nullptr = i
     int32_t *top1_base_out;  // classifier: where the FP32 pass writes its top-1, or nullptr
 };
+
+// Where the classifier of a call puts its results.
+struct HeadOut {
+    float *logits;     // nullable; [rows][N][classes]
+    int32_t N;         // images of the whole call
+    int32_t *top1;     // nullable: [rows][N]; else top1_tmp [rows][chunk]
+    int32_t *top1_tmp;
+    int32_t chunk;
+};
+
+// One node (or one LDS-resident block, at its expand node) for the schemes the launch covers.
+aiq_status launch_node(aiq_model *m, hipStream_t st, const HeadOut &ho, size_t l, const NodeIO &io, int n, int n0)
+{
+    const Node &nd = m->nodes[l];
+    const aiq_layer_desc &d = nd.d;
+    const double work = (double)io.s_total * n;
+    if (nd.mb_role == 2) return AIQ_OK; // computed by the block kernel launched at its expand node
+    if (nd.mb_role == 1) {
+        const Node &dwn = m->nodes[l + 1], &pjn = m->nodes[l + 2];
+        MbArgs a{};
+        a.in = io.in;
+        a.out = io.out;
+        for (int b = 0; b < kNumBits; ++b) {
+            a.bank_e[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+            a.bank_d[b] = dwn.bank[b] ? dwn.bank[b] : dwn.bank[0];
+            a.bank_p[b] = pjn.bank[b] ? pjn.bank[b] : pjn.bank[0];
+        }
+        a.bias_e = nd.bias;
+        a.bias_d = dwn.bias;
+        a.bias_p = pjn.bias;
+        a.schemes = io.schemes;
+        a.in_scheme_stride = io.in_stride;
+        a.out_scheme_stride = io.out_stride;
+        a.S = io.S;
+        a.L = m->L;
+        a.slot_e = d.scheme_slot;
+        a.slot_d = dwn.d.scheme_slot;
+        a.slot_p = pjn.d.scheme_slot;
+        a.N = n;
+        a.act_e = d.act;
+        a.act_d = dwn.d.act;
+        a.act_p = pjn.d.act;
+        const double flops = nd.flops_per_image + dwn.flops_per_image + pjn.flops_per_image;
+        const double bytes = 4.0 * (nd.in_elems + pjn.out_elems + (pjn.d.residual >= 0 ? pjn.out_elems : 0));
+        ProfScope ps(m, st, AIQ_K_MBCONV, flops * work, bytes * work);
+        AIQ_HIP(launch_mbconv(nd.mb_shape, a, io.s_total, st));
+    } else if (d.kind == 0 && d.kh == 1 && d.stride == 1 && d.input >= 0) {
+        // 1x1 stride 1: flat pixel axis
+        const ConvPlan &p = nd.plan;
+        PointwiseArgs a{};
+        a.in = io.in;
+        a.out = io.out;
+        a.res = io.res;
+        a.bias = nd.bias;
+        for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+        a.schemes = io.schemes;
+        a.in_scheme_stride = io.in_stride;
+        a.out_scheme_stride = io.out_stride;
+        a.res_scheme_stride = io.res_stride;
+        a.S = io.S;
+        a.L = m->L;
+        a.slot = d.scheme_slot;
+        a.P = n * nd.hout * nd.wout;
+        a.Cin = d.cin;
+        a.Cout = d.cout;
+        a.act = d.act;
+        a.CB = p.CB;
+        a.CKC = p.CKC;
+        a.PS = p.PS;
+        a.wave_px_split = p.wave_px_split;
+        a.cout_tiles = p.cout_tiles;
+        a.pool = nd.pooled ? 1 : 0;
+        a.grid_y = p.grid_y;
+        const int tile_px = 64 * p.wave_px_split;
+        const size_t lds = sizeof(float) * (size_t)tile_px * p.PS;
+        ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+        AIQ_HIP(launch_pointwise(a, p.nt, lds,
+                                 dim3((unsigned)((a.P + tile_px - 1) / tile_px), p.grid_y, io.s_total), st));
+    } else if (d.kind == 0) {
+        const ConvPlan &p = nd.plan;
+        ConvArgs a{};
+        a.in = io.in;
+        a.out = io.out;
+        a.res = io.res;
+        a.bias = nd.bias;
+        for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+        a.schemes = io.schemes;
+        a.in_scheme_stride = io.in_stride;
+        a.out_scheme_stride = io.out_stride;
+        a.res_scheme_stride = io.res_stride;
+        a.S = io.S;
+        a.L = m->L;
+        a.slot = d.scheme_slot;
+        a.N = n;
+        a.Hin = d.hin;
+        a.Win = d.win;
+        a.Cin = d.cin;
+        a.Hout = nd.hout;
+        a.Wout = nd.wout;
+        a.Cout = d.cout;
+        a.act = d.act;
+        a.R = p.R;
+        a.G = p.G;
+        a.regions_per_image = p.regions_per_image;
+        a.CB = p.CB;
+        a.CKC = p.CKC;
+        a.RIN = p.RIN;
+        a.LW = p.LW;
+        a.PS = p.PS;
+        a.wave_px_split = p.wave_px_split;
+        a.cout_tiles = p.cout_tiles;
+        a.div_lw = make_fastdiv(p.LW);
+        a.div_rin = make_fastdiv(p.RIN);
+        a.div_wout = make_fastdiv(nd.wout);
+        a.div_rw = make_fastdiv(p.R * nd.wout);
+        const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
+        ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+        if (nd.layout == kLayoutStem)
+            AIQ_HIP(launch_conv_stem(a, p.nt, dim3(gx, p.grid_y, io.s_total), st));
+        else
+            AIQ_HIP(launch_conv(a, d.kh, d.stride, p.nt, p.lds_bytes, dim3(gx, p.grid_y, io.s_total), st));
+    } else if (d.kind == 1) {
+        DepthwiseArgs a{};
+        a.in = io.in;
+        a.out = io.out;
+        a.bias = nd.bias;
+        for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+        a.schemes = io.schemes;
+        a.in_scheme_stride = io.in_stride;
+        a.out_scheme_stride = io.out_stride;
+        a.S = io.S;
+        a.L = m->L;
+        a.slot = d.scheme_slot;
+        a.N = n;
+        a.Hin = d.hin;
+        a.Win = d.win;
+        a.C = d.cin;
+        a.Hout = nd.hout;
+        a.Wout = nd.wout;
+        a.stride = d.stride;
+        a.act = d.act;
+        a.div_c4 = make_fastdiv(d.cin / 4);
+        ProfScope ps(m, st, AIQ_K_DEPTHWISE, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+        AIQ_HIP(launch_depthwise(a, io.s_total, st));
+    } else {
+        HeadArgs a{};
+        a.in = io.in;
+        a.bias = nd.bias;
+        for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
+        a.schemes = io.schemes;
+        a.in_scheme_stride = io.in_stride;
+        a.S = io.S;
+        a.L = m->L;
+        a.slot = d.scheme_slot;
+        a.N = n;
+        a.HW = m->nodes[d.input].pooled ? 1 : d.hin * d.win; // a pooled producer has already taken the mean
+        a.C = d.cin;
+        a.classes = d.cout;
+        a.logits = ho.logits;
+        a.logits_n = ho.N;
+        a.n0 = n0;
+        if (ho.top1) {
+            a.top1 = ho.top1 + n0;
+            a.top1_stride = ho.N;
+        } else {
+            a.top1 = ho.top1_tmp;
+            a.top1_stride = ho.chunk;
+        }
+        a.top1_base = io.top1_base_out;
+        a.row_map = io.row_map;
+        ProfScope ps(m, st, AIQ_K_HEAD, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+        AIQ_HIP(launch_head(a, io.s_total, st));
+    }
+    return AIQ_OK;
+}
 
 // Scores S schemes.  ref = NULL: every scheme runs the whole network.  ref = host uint8[L]:
 // where the model supports it, the reference scheme is run once per image and scheme s
@@ -969,169 +1204,9 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
         AIQ_HIP(launch_quantize_batch(m->jobs_dev, m->block_job_dev, m->n_quant_blocks, mask, st));
     }
 
-    // One node (or one LDS-resident block, at its expand node) for the schemes the launch covers.
+    const HeadOut ho{logits, N, top1, top1_tmp, chunk};
     auto launch_node = [&](size_t l, const NodeIO &io, int n, int n0) -> aiq_status {
-        const Node &nd = m->nodes[l];
-        const aiq_layer_desc &d = nd.d;
-        const double work = (double)io.s_total * n;
-        if (nd.mb_role == 2) return AIQ_OK; // computed by the block kernel launched at its expand node
-        if (nd.mb_role == 1) {
-            const Node &dwn = m->nodes[l + 1], &pjn = m->nodes[l + 2];
-            MbArgs a{};
-            a.in = io.in;
-            a.out = io.out;
-            for (int b = 0; b < kNumBits; ++b) {
-                a.bank_e[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
-                a.bank_d[b] = dwn.bank[b] ? dwn.bank[b] : dwn.bank[0];
-                a.bank_p[b] = pjn.bank[b] ? pjn.bank[b] : pjn.bank[0];
-            }
-            a.bias_e = nd.bias;
-            a.bias_d = dwn.bias;
-            a.bias_p = pjn.bias;
-            a.schemes = io.schemes;
-            a.in_scheme_stride = io.in_stride;
-            a.out_scheme_stride = io.out_stride;
-            a.S = io.S;
-            a.L = m->L;
-            a.slot_e = d.scheme_slot;
-            a.slot_d = dwn.d.scheme_slot;
-            a.slot_p = pjn.d.scheme_slot;
-            a.N = n;
-            a.act_e = d.act;
-            a.act_d = dwn.d.act;
-            a.act_p = pjn.d.act;
-            const double flops = nd.flops_per_image + dwn.flops_per_image + pjn.flops_per_image;
-            const double bytes = 4.0 * (nd.in_elems + pjn.out_elems + (pjn.d.residual >= 0 ? pjn.out_elems : 0));
-            ProfScope ps(m, st, AIQ_K_MBCONV, flops * work, bytes * work);
-            AIQ_HIP(launch_mbconv(nd.mb_shape, a, io.s_total, st));
-        } else if (d.kind == 0 && d.kh == 1 && d.stride == 1 && d.input >= 0) {
-            // 1x1 stride 1: flat pixel axis
-            const ConvPlan &p = nd.plan;
-            PointwiseArgs a{};
-            a.in = io.in;
-            a.out = io.out;
-            a.res = io.res;
-            a.bias = nd.bias;
-            for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
-            a.schemes = io.schemes;
-            a.in_scheme_stride = io.in_stride;
-            a.out_scheme_stride = io.out_stride;
-            a.res_scheme_stride = io.res_stride;
-            a.S = io.S;
-            a.L = m->L;
-            a.slot = d.scheme_slot;
-            a.P = n * nd.hout * nd.wout;
-            a.Cin = d.cin;
-            a.Cout = d.cout;
-            a.act = d.act;
-            a.CB = p.CB;
-            a.CKC = p.CKC;
-            a.PS = p.PS;
-            a.wave_px_split = p.wave_px_split;
-            a.cout_tiles = p.cout_tiles;
-            a.pool = nd.pooled ? 1 : 0;
-            a.grid_y = p.grid_y;
-            const int tile_px = 64 * p.wave_px_split;
-            const size_t lds = sizeof(float) * (size_t)tile_px * p.PS;
-            ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);
-            AIQ_HIP(launch_pointwise(a, p.nt, lds,
-                                     dim3((unsigned)((a.P + tile_px - 1) / tile_px), p.grid_y, io.s_total), st));
-        } else if (d.kind == 0) {
-            const ConvPlan &p = nd.plan;
-            ConvArgs a{};
-            a.in = io.in;
-            a.out = io.out;
-            a.res = io.res;
-            a.bias = nd.bias;
-            for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
-            a.schemes = io.schemes;
-            a.in_scheme_stride = io.in_stride;
-            a.out_scheme_stride = io.out_stride;
-            a.res_scheme_stride = io.res_stride;
-            a.S = io.S;
-            a.L = m->L;
-            a.slot = d.scheme_slot;
-            a.N = n;
-            a.Hin = d.hin;
-            a.Win = d.win;
-            a.Cin = d.cin;
-            a.Hout = nd.hout;
-            a.Wout = nd.wout;
-            a.Cout = d.cout;
-            a.act = d.act;
-            a.R = p.R;
-            a.G = p.G;
-            a.regions_per_image = p.regions_per_image;
-            a.CB = p.CB;
-            a.CKC = p.CKC;
-            a.RIN = p.RIN;
-            a.LW = p.LW;
-            a.PS = p.PS;
-            a.wave_px_split = p.wave_px_split;
-            a.cout_tiles = p.cout_tiles;
-            a.div_lw = make_fastdiv(p.LW);
-            a.div_rin = make_fastdiv(p.RIN);
-            a.div_wout = make_fastdiv(nd.wout);
-            a.div_rw = make_fastdiv(p.R * nd.wout);
-            const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
-            ProfScope ps(m, st, AIQ_K_CONV, nd.flops_per_image * work, nd.act_bytes_per_image * work);
-            if (nd.layout == kLayoutStem)
-                AIQ_HIP(launch_conv_stem(a, p.nt, dim3(gx, p.grid_y, io.s_total), st));
-            else
-                AIQ_HIP(launch_conv(a, d.kh, d.stride, p.nt, p.lds_bytes, dim3(gx, p.grid_y, io.s_total), st));
-        } else if (d.kind == 1) {
-            DepthwiseArgs a{};
-            a.in = io.in;
-            a.out = io.out;
-            a.bias = nd.bias;
-            for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
-            a.schemes = io.schemes;
-            a.in_scheme_stride = io.in_stride;
-            a.out_scheme_stride = io.out_stride;
-            a.S = io.S;
-            a.L = m->L;
-            a.slot = d.scheme_slot;
-            a.N = n;
-            a.Hin = d.hin;
-            a.Win = d.win;
-            a.C = d.cin;
-            a.Hout = nd.hout;
-            a.Wout = nd.wout;
-            a.stride = d.stride;
-            a.act = d.act;
-            a.div_c4 = make_fastdiv(d.cin / 4);
-            ProfScope ps(m, st, AIQ_K_DEPTHWISE, nd.flops_per_image * work, nd.act_bytes_per_image * work);
-            AIQ_HIP(launch_depthwise(a, io.s_total, st));
-        } else {
-            HeadArgs a{};
-            a.in = io.in;
-            a.bias = nd.bias;
-            for (int b = 0; b < kNumBits; ++b) a.bank[b] = nd.bank[b] ? nd.bank[b] : nd.bank[0];
-            a.schemes = io.schemes;
-            a.in_scheme_stride = io.in_stride;
-            a.S = io.S;
-            a.L = m->L;
-            a.slot = d.scheme_slot;
-            a.N = n;
-            a.HW = m->nodes[d.input].pooled ? 1 : d.hin * d.win; // a pooled producer has already taken the mean
-            a.C = d.cin;
-            a.classes = d.cout;
-            a.logits = logits;
-            a.logits_n = N;
-            a.n0 = n0;
-            if (top1) {
-                a.top1 = top1 + n0;
-                a.top1_stride = N;
-            } else {
-                a.top1 = top1_tmp;
-                a.top1_stride = chunk;
-            }
-            a.top1_base = io.top1_base_out;
-            a.row_map = io.row_map;
-            ProfScope ps(m, st, AIQ_K_HEAD, nd.flops_per_image * work, nd.act_bytes_per_image * work);
-            AIQ_HIP(launch_head(a, io.s_total, st));
-        }
-        return AIQ_OK;
+        return ::launch_node(m, st, ho, l, io, n, n0);
     };
 
     for (int n0 = 0; n0 < N; n0 += chunk) {
@@ -1402,6 +1477,193 @@ aiq_status aiq_eval_schemes_shared(aiq_model *m, const float *images, int32_t N,
     if (!m || !ref_scheme) return AIQ_INVALID_ARG;
     return eval_impl(m, images, N, schemes, S, ref_scheme, chunk, top1_base, base_valid, logits, top1, agree,
                      workspace, workspace_bytes, hip_stream);
+}
+
+// ---------------------------------------------------------------- deployed inference
+
+struct aiq_deployed {
+    aiq_model *m = nullptr;
+    std::vector<uint8_t> scheme;
+    uint8_t *scheme_dev = nullptr;
+    struct Layer {
+        uint16_t *codes = nullptr; // non-null: this node runs from its integer codes
+        float *scales = nullptr;
+        CodePlan plan{};
+    };
+    std::vector<Layer> layer; // per node
+    std::vector<void *> allocations;
+    int n_code_layers = 0;
+};
+
+void aiq_deploy_destroy(aiq_deployed *d)
+{
+    if (!d) return;
+    for (void *p : d->allocations) (void)hipFree(p);
+    delete d;
+}
+
+int32_t aiq_deploy_code_layers(const aiq_deployed *d) { return d ? d->n_code_layers : -1; }
+
+aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags, aiq_deployed **out)
+{
+    if (out) *out = nullptr;
+    if (!m || !out || (m->L > 0 && !scheme) || (flags & ~(uint32_t)AIQ_DEPLOY_FP32_MATRIX)) return AIQ_INVALID_ARG;
+    for (int i = 0; i < m->L; ++i)
+        if (!bits_supported(scheme[i])) return AIQ_UNSUPPORTED_BITS;
+    if (m->fused || m->mb_blocks > 0) return AIQ_UNSUPPORTED_LAYER;
+    for (const Node &nd : m->nodes)
+        if (nd.pooled) return AIQ_UNSUPPORTED_LAYER;
+
+    aiq_deployed *d = new (std::nothrow) aiq_deployed();
+    if (!d) return AIQ_INVALID_ARG;
+    d->m = m;
+    d->scheme.assign(scheme, scheme + m->L);
+    d->layer.resize(m->nodes.size());
+    auto fail = [&](aiq_status code) {
+        aiq_deploy_destroy(d);
+        return code;
+    };
+    auto alloc = [&](void **p, size_t bytes) {
+        if (!hip_ok(hipMalloc(p, std::max<size_t>(bytes, 256)))) return false;
+        d->allocations.push_back(*p);
+        return true;
+    };
+    if (!alloc(reinterpret_cast<void **>(&d->scheme_dev), (size_t)std::max(m->L, 1))) return fail(AIQ_DEVICE_ERROR);
+    if (m->L && !hip_ok(hipMemcpy(d->scheme_dev, scheme, (size_t)m->L, hipMemcpyHostToDevice)))
+        return fail(AIQ_DEVICE_ERROR);
+
+    // fp32-path layers read the weight bank: fill the slots this scheme uses (their content
+    // depends on nothing but the weights, so other calls on the model rewrite the same values)
+    QuantMask mask{};
+    bool any = false;
+    size_t tmp_elems = 0;
+    for (size_t l = 0; l < m->nodes.size(); ++l) {
+        const Node &nd = m->nodes[l];
+        if (nd.d.scheme_slot < 0) continue;
+        const int bits = scheme[nd.d.scheme_slot], bi = bits_index(bits);
+        if (bi == 0) continue;
+        const bool on_codes = !(flags & AIQ_DEPLOY_FP32_MATRIX) && bits <= 8 && nd.d.kind == 0 && nd.d.input >= 0 &&
+                              nd.layout == kLayoutMfma && plan_code_conv(nd, d->layer[l].plan);
+        if (on_codes) {
+            const CodePlan &p = d->layer[l].plan;
+            const size_t code_elems = (size_t)p.cout_tiles * nd.d.kh * nd.d.kw * p.CB * 512;
+            if (!alloc(reinterpret_cast<void **>(&d->layer[l].codes), code_elems * sizeof(uint16_t)) ||
+                !alloc(reinterpret_cast<void **>(&d->layer[l].scales), (size_t)nd.d.cout * sizeof(float)) ||
+                !hip_ok(hipMemset(d->layer[l].codes, 0, code_elems * sizeof(uint16_t))))
+                return fail(AIQ_DEVICE_ERROR);
+            tmp_elems = std::max(tmp_elems, (size_t)nd.d.cout * nd.k);
+            ++d->n_code_layers;
+        } else {
+            const int ji = nd.job0 + bi - 1;
+            mask.word[ji >> 6] |= 1ull << (ji & 63);
+            any = true;
+        }
+    }
+    if (any && !hip_ok(launch_quantize_batch(m->jobs_dev, m->block_job_dev, m->n_quant_blocks, mask, nullptr)))
+        return fail(AIQ_DEVICE_ERROR);
+    if (d->n_code_layers) {
+        // quantizer -> integer codes and scales -> codes in the matrix pipe's operand order
+        void *tmp_codes = nullptr, *tmp_out = nullptr;
+        bool ok = hip_ok(hipMalloc(&tmp_codes, tmp_elems * sizeof(int32_t))) &&
+                  hip_ok(hipMalloc(&tmp_out, tmp_elems * sizeof(float)));
+        for (size_t l = 0; ok && l < m->nodes.size(); ++l) {
+            const Node &nd = m->nodes[l];
+            if (!d->layer[l].codes) continue;
+            QuantJob j = m->jobs_host[nd.job0 + bits_index(scheme[nd.d.scheme_slot]) - 1];
+            j.out = static_cast<float *>(tmp_out);
+            j.layout = kLayoutPlain;
+            j.scales = d->layer[l].scales;
+            j.codes = static_cast<int32_t *>(tmp_codes);
+            ok = hip_ok(launch_quantize_single(j, nullptr)) &&
+                 hip_ok(launch_pack_codes(j.codes, d->layer[l].codes, nd.d.cout, nd.d.cin, nd.d.kh * nd.d.kw, nullptr));
+        }
+        ok = hip_ok(hipDeviceSynchronize()) && ok;
+        if (tmp_codes) (void)hipFree(tmp_codes);
+        if (tmp_out) (void)hipFree(tmp_out);
+        if (!ok) return fail(AIQ_DEVICE_ERROR);
+    } else if (!hip_ok(hipDeviceSynchronize())) {
+        return fail(AIQ_DEVICE_ERROR);
+    }
+    *out = d;
+    return AIQ_OK;
+}
+
+aiq_status aiq_deploy_workspace_bytes(const aiq_deployed *d, int32_t chunk, size_t *bytes)
+{
+    if (!d || !bytes || chunk < 1) return AIQ_INVALID_ARG;
+    *bytes = workspace_layout(d->m, 0, chunk).total;
+    return AIQ_OK;
+}
+
+aiq_status aiq_deploy_forward(aiq_deployed *d, const float *images, int32_t N, int32_t chunk, float *logits,
+                              int32_t *top1, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!d || N < 0 || chunk < 1) return AIQ_INVALID_ARG;
+    if (N > 0 && (!images || !top1 || !workspace)) return AIQ_INVALID_ARG;
+    if (N == 0) return AIQ_OK;
+    aiq_model *m = d->m;
+    chunk = std::min(chunk, N);
+    const WorkspaceLayout wl = workspace_layout(m, 0, chunk);
+    if (workspace_bytes < wl.total) return AIQ_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return AIQ_INVALID_ARG;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char *ws = static_cast<char *>(workspace);
+    auto buf_ptr = [&](int b) { return reinterpret_cast<float *>(ws + wl.act_off + wl.buf_stride * b); };
+    const HeadOut ho{logits, N, top1, nullptr, chunk};
+    for (int n0 = 0; n0 < N; n0 += chunk) {
+        const int n = std::min(chunk, N - n0);
+        for (size_t l = 0; l < m->nodes.size(); ++l) {
+            const Node &nd = m->nodes[l];
+            NodeIO io{};
+            io.schemes = d->scheme_dev;
+            io.S = 1;
+            io.s_total = 1;
+            io.in = nd.d.input < 0 ? images + (size_t)n0 * nd.in_elems : buf_ptr(m->nodes[nd.d.input].buf);
+            io.out = nd.buf >= 0 ? buf_ptr(nd.buf) : nullptr;
+            io.res = nd.d.residual >= 0 ? buf_ptr(m->nodes[nd.d.residual].buf) : nullptr;
+            const aiq_deployed::Layer &cl = d->layer[l];
+            if (!cl.codes) {
+                aiq_status rc = launch_node(m, st, ho, l, io, n, n0);
+                if (rc != AIQ_OK) return rc;
+                continue;
+            }
+            const aiq_layer_desc &ld = nd.d;
+            const CodePlan &p = cl.plan;
+            CodeConvArgs a{};
+            a.in = io.in;
+            a.out = io.out;
+            a.res = io.res;
+            a.bias = nd.bias;
+            a.codes = cl.codes;
+            a.scales = cl.scales;
+            a.N = n;
+            a.Hin = ld.hin;
+            a.Win = ld.win;
+            a.Cin = ld.cin;
+            a.Hout = nd.hout;
+            a.Wout = nd.wout;
+            a.Cout = ld.cout;
+            a.act = ld.act;
+            a.R = p.R;
+            a.G = p.G;
+            a.regions_per_image = p.regions_per_image;
+            a.CB = p.CB;
+            a.CKC = p.CKC;
+            a.RIN = p.RIN;
+            a.LW = p.LW;
+            a.PSU = p.PSU;
+            a.wave_px_split = p.wave_px_split;
+            a.cout_tiles = p.cout_tiles;
+            a.div_rin = make_fastdiv(p.RIN);
+            a.div_wout = make_fastdiv(nd.wout);
+            a.div_rw = make_fastdiv(p.R * nd.wout);
+            a.div_per_row = make_fastdiv(p.LW * (p.CKC / 8));
+            const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
+            ProfScope ps(m, st, AIQ_K_CONV_CODES, nd.flops_per_image * n, nd.act_bytes_per_image * n);
+            AIQ_HIP(launch_conv_codes(a, ld.kh, ld.stride, p.nt, p.lds_bytes, dim3(gx, p.grid_y, 1), st));
+        }
+    }
+    return AIQ_OK;
 }
 
 namespace {

@@ -276,3 +276,39 @@ bool mbconv_supported(const MbShape &sh);
 hipError_t launch_mbconv(const MbShape &sh, const MbArgs &a, int s_total, hipStream_t st);
 
 } // namespace aiq
+
+// ---------------------------------------------------------------- deployed inference
+//
+// Dense convolution of a layer of at most eight bits from its integer codes on the bf16
+// matrix pipe (aiq_deploy.hip).  One scheme, so there is no scheme axis.
+namespace aiq {
+
+struct CodeConvArgs {
+    const float *in;       // [N][Hin][Win][Cin]
+    float *out;            // [N][Hout][Wout][Cout]
+    const float *res;      // like out, or nullptr
+    const float *bias;     // [Cout]
+    const uint16_t *codes; // bf16 bit patterns, [ceil(Cout/32)][tap][ceil(Cin/16)][64 lanes][8], zero padded
+    const float *scales;   // [Cout]
+    int32_t N;
+    int32_t Hin, Win, Cin, Hout, Wout, Cout;
+    int32_t act;
+    int32_t R;             // output rows per workgroup region
+    int32_t G;             // images per workgroup (R == Hout when G > 1)
+    int32_t regions_per_image;
+    int32_t CB;            // ceil(Cin/16)
+    int32_t CKC;           // channels staged per pass (16, 32 or 64)
+    int32_t RIN, LW;       // LDS tile: rows, row width (pixels)
+    int32_t PSU;           // 16-byte units of one pixel's plane: CKC / 8 + 1 (odd: conflict-free 16-byte reads)
+    int32_t wave_px_split; // waves along pixels (4, 2 or 1); 4/wave_px_split along output channels
+    int32_t cout_tiles;    // ceil(Cout/32)
+    FastDiv div_rin, div_wout, div_rw, div_per_row; // RIN, Wout, R*Wout, LW * CKC / 8
+};
+
+// codes: int32 [cout][cin][taps]; out: cleared buffer in the layout above
+hipError_t launch_pack_codes(const int32_t *codes, uint16_t *out, int cout, int cin, int taps, hipStream_t st);
+hipError_t launch_conv_codes(const CodeConvArgs &a, int ks, int stride, int nt, size_t lds_bytes, dim3 grid,
+                             hipStream_t st);
+hipError_t conv_codes_set_lds_limits();
+
+} // namespace aiq
