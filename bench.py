@@ -16,6 +16,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_MFMA_F32_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_BF16_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 
 # HBM bytes per launch of a kernel class from rocprofv3 counters (FETCH_SIZE x 2.000 and
 # WRITE_SIZE x 1.000, the factors a plain copy of known size gives; profiles/ has the runs).
@@ -166,6 +167,106 @@ def search_mode(args, torch, aiq, synth):
     print(json.dumps(line))
 
 
+def deploy_mode(args, torch, aiq, synth):
+    """Deployed inference (the paper's throughput experiment, on this machine): images/s of one scheme of the
+    workload's model, FP32 against schemes whose low-bit layers run from integer codes on the bf16 matrix pipe.
+
+    One step = one aiq_deploy_forward over all images (resident in HBM).  Schemes: the one a greedy search with
+    the paper's alphabet and lambda returns on this synthetic model, every layer at 8 bits, and twelve layers at
+    4 bits (the count the paper's search reached on its trained models).
+    """
+    import numpy as np
+    n_img = args.deploy_images
+    wl = synth.make_workload(args.workload, n_images=n_img)
+    L = wl["L"]
+    images = torch.from_numpy(wl["images"]).cuda()
+    chunk = min(n_img, args.deploy_chunk)
+    model = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=True)
+    best = aiq.Model(wl["desc"], wl["weights"], wl["biases"])  # LDS-resident kernels where the graph allows
+    q_search, trace = best.search(wl["desc"], images[:256], method="greedy", bits=(32, 8, 4), lam=0.9, chunk=256)
+    twelve = np.full(L, 32, np.uint8)
+    convs = [nd["scheme_slot"] for nd in wl["nodes"] if nd["kind"] == 0 and nd["input"] >= 0 and nd["scheme_slot"] >= 0]
+    twelve[convs[-12:]] = 4
+    schemes = {"fp32": np.full(L, 32, np.uint8), "greedy_search": q_search, "all_int8": np.full(L, 8, np.uint8),
+               "twelve_layers_int4": twelve}
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            r = fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.steps, r
+
+    stream = torch.cuda.current_stream()
+    out = {"top1": torch.empty(n_img, dtype=torch.int32, device="cuda")}
+    res = {}
+    top1_fp32 = None
+    for name, q in schemes.items():
+        row = {"scheme": [int(v) for v in q]}
+        for variant in (("bf16_codes", False), ("fp32_matrix", True)):
+            if name == "fp32" and not variant[1]:
+                continue
+            d = aiq.Deployed(model, q, fp32_matrix=variant[1])
+            model.profile_enable(True)
+            for c in range(8):
+                model.profile_read(c)
+            model.profile_enable(False)
+            dt, r = timed(lambda: d.forward(images, chunk=chunk, out=out, stream=stream))
+            top1 = r["top1"].clone()
+            if name == "fp32":
+                top1_fp32 = top1
+            row[variant[0]] = {"images_per_s": n_img / dt, "ms_per_step": dt * 1e3, "code_layers": d.code_layers,
+                               "agree_with_fp32": int((top1 == top1_fp32).sum())}
+            if not variant[1]:
+                model.profile_enable(True)
+                d.forward(images, chunk=chunk, out=out, stream=stream)
+                torch.cuda.synchronize()
+                model.profile_enable(False)
+                k = model.profile_read(aiq.K_CONV_CODES)
+                if k["launches"]:
+                    tf = k["flops"] / k["total_ms"] / 1e9
+                    row["conv_codes_kernel"] = {
+                        "launches": k["launches"], "avg_launch_ms": k["total_ms"] / k["launches"],
+                        "fp32_equivalent_tflops": tf, "executed_bf16_tflops": 3.0 * tf,
+                        "frac_of_bf16_peak": 3.0 * tf / PEAK_MFMA_BF16_TFLOPS,
+                        "algorithmic_gbytes_per_s": k["bytes"] / k["total_ms"] / 1e6,
+                        "frac_of_hbm_peak": k["bytes"] / k["total_ms"] / 1e6 / PEAK_HBM_GBS}
+            d.close()
+        res[name] = row
+    # the FP32 model on its fastest path (whole network or blocks LDS-resident where the graph allows)
+    o = {"top1_base": torch.empty(n_img, dtype=torch.int32, device="cuda"), "agree": torch.empty(1, dtype=torch.int32, device="cuda")}
+    dt_best, _ = timed(lambda: best.eval_schemes(images, np.zeros((0, L), np.uint8), chunk=chunk, out=o, stream=stream))
+    fp32_ips = max(res["fp32"]["fp32_matrix"]["images_per_s"], n_img / dt_best)
+    head = res["greedy_search"]["bf16_codes"]
+    kc = res["greedy_search"].get("conv_codes_kernel") or res["all_int8"].get("conv_codes_kernel")
+    line = {"metric": "deployed_images_per_sec", "value": head["images_per_s"], "unit": "images/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32 activations; bf16 x bf16 -> f32 MFMA on integer codes",
+            "data": "synthetic",
+            "config": {"workload": wl["name"].split("_")[0] + f"_deploy_n{n_img}", "images": n_img, "chunk": chunk,
+                       "scheme": "greedy_search", "search_alphabet": [32, 8, 4], "lambda": 0.9,
+                       "search_final_agree_of_256": int(trace[-1]["agree"])},
+            "fp32_model": {"images_per_s_layer_by_layer": res["fp32"]["fp32_matrix"]["images_per_s"],
+                           "images_per_s_fastest_path": n_img / dt_best, "lds_resident": bool(best.lds_resident),
+                           "lds_resident_blocks": int(best.lds_resident_blocks)},
+            "speedup_over_fp32_model": {k: v["bf16_codes"]["images_per_s"] / fp32_ips for k, v in res.items() if "bf16_codes" in v},
+            "speedup_over_same_scheme_on_fp32_matrix": {k: v["bf16_codes"]["images_per_s"] / v["fp32_matrix"]["images_per_s"]
+                                                        for k, v in res.items() if "bf16_codes" in v},
+            "schemes": res}
+    if kc:
+        line["roofline"] = {"bound": "mfma", "kernel": "conv_codes_kernel (3 bf16 MFMA products per fp32-equivalent product)",
+                            "achieved": kc["executed_bf16_tflops"], "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
+                            "frac": kc["frac_of_bf16_peak"], "traffic": None,
+                            "hbm": {"achieved": kc["algorithmic_gbytes_per_s"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                    "frac": kc["frac_of_hbm_peak"]}}
+    model.close()
+    best.close()
+    print(json.dumps(line))
+
+
 def print_hbm_line(args, wl, model, S, N, L, chunk, dt, agree, prof, cls):
     """Same step, but the roofline block describes a bandwidth-bound kernel class."""
     k = prof[cls]
@@ -206,6 +307,11 @@ def main():
     ap.add_argument("--search", choices=("greedy", "cd"),
                     help="time a whole search (greedy or coordinate descent) on the workload's model and images")
     ap.add_argument("--search-bits", default="32,8,4", help="alphabet of --search, descending, first 32")
+    ap.add_argument("--deploy", action="store_true",
+                    help="deployed inference of one scheme: images/s, FP32 against low-bit layers on the bf16 matrix pipe "
+                         "(default workload 5, PlainConvNet20)")
+    ap.add_argument("--deploy-images", type=int, default=2048)
+    ap.add_argument("--deploy-chunk", type=int, default=2048)
     ap.add_argument("--stress", choices=("quantize",), help="time one kernel on a bandwidth-stress shape instead of a workload")
     ap.add_argument("--stress-shape", default="8192x4608", help="cout x k of the quantizer stress matrix")
     args = ap.parse_args()
@@ -226,6 +332,10 @@ def main():
         return stress_quantize(args, torch, aiq)
     if args.search:
         return search_mode(args, torch, aiq, synth)
+    if args.deploy:
+        if "--workload" not in " ".join(sys.argv):
+            args.workload = 5
+        return deploy_mode(args, torch, aiq, synth)
     wl = synth.make_workload(args.workload)
     S, L = wl["schemes"].shape
     N = wl["images"].shape[0]

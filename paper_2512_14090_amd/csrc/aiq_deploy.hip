@@ -51,8 +51,8 @@ __device__ __forceinline__ void split3(float x, uint32_t &hi, uint32_t &mid, uin
     lo = __float_as_uint(r1 - __uint_as_float(mid));
 }
 
-// two bf16 values (upper halves of a and b) as one dword, a first
-__device__ __forceinline__ uint32_t pack2(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+// two bf16 values (upper halves of a and b) as one dword, a first: bytes {a2, a3, b2, b3}
+__device__ __forceinline__ uint32_t pack2(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 
 } // namespace
 
@@ -92,60 +92,82 @@ hipError_t launch_pack_codes(const int32_t *codes, uint16_t *out, int cout, int 
 // four groups of four consecutive output channels of one pixel: four 16-byte NHWC stores.
 //
 // Workgroup = 4 wavefronts; it stages the input rows of its region in LDS already split: per
-// pixel three planes (hi, mid, lo) of CKC bf16 channels.  A wavefront owns 64 pixels x 32*NT
+// pixel three planes (hi, mid, lo) of CKC bf16 channels, CKC channels per pass.  A wavefront owns 64 pixels x 32*NT
 // output channels and issues, per tap and block of 16 channels, 2 * NT * 3 MFMAs from NT
 // 16-byte global reads (codes, L2-resident) and six 16-byte LDS reads.
 
-// Stages channels [c0, c0 + CKC) of the region's input rows, zero outside the image and past
-// Cin.  One item = eight channels of one pixel: two 16-byte global reads, three 16-byte LDS
-// writes.  Three items per thread are in flight before the first is split.
+// Staging.  One item = eight channels of one staged pixel: two 16-byte global reads, three 16-byte
+// LDS writes (the hi, mid and lo planes).  Item tid + 256 * i belongs to thread tid; which pixel
+// and which eight channels of the pass it is does not change from pass to pass, so its LDS unit
+// and its element offset from the workgroup's first image are formed once (kStageItems of them
+// per thread; the host keeps a region's item count within that).  Per pass the reads of all items
+// are issued first (stage_fetch), then split and written to LDS (stage_store).
+constexpr int kStageItems = kCodeStageItems;
+
+struct StageItems {
+    int dst[kStageItems]; // LDS unit of the hi plane, -1: no such item
+    int src[kStageItems]; // element offset of channel c0 + 8 * c8 at the pixel, -1: outside the image
+};
+
 template <int STRIDE, int PAD>
-__device__ __forceinline__ void stage_split_rows(const CodeConvArgs &a, uintx4 *lds4, int c0, int c8shift, int img0,
-                                                 int oy0, int tid)
+__device__ __forceinline__ void stage_plan(const CodeConvArgs &a, StageItems &it, int c8shift, int img0, int oy0, int tid)
 {
-    constexpr int UB = 3;
     const int c8n = 1 << c8shift;
     const int per_row = a.LW << c8shift;
     const int total = a.G * a.RIN * per_row;
-    for (int base = tid; base < total; base += 256 * UB) {
-        floatx4 v[UB][2];
-        int dst[UB];
+    const int g_lim = min(a.G, a.N - img0); // images of the group that exist
+    const int iy0 = oy0 * STRIDE - PAD;
 #pragma unroll
-        for (int u = 0; u < UB; ++u) {
-            const int it = base + u * 256;
-            v[u][0] = v[u][1] = floatx4{0.f, 0.f, 0.f, 0.f};
-            dst[u] = -1;
-            if (it < total) {
-                const int row = (int)fd_div((uint32_t)it, a.div_per_row);
-                const int rem = it - row * per_row;
-                const int col = rem >> c8shift, c8 = rem & (c8n - 1);
-                const int g = (int)fd_div((uint32_t)row, a.div_rin);
-                const int r = row - g * a.RIN;
-                const int iy = oy0 * STRIDE - PAD + r, ix = col - PAD, img = img0 + g;
-                const int c = c0 + c8 * 8;
-                dst[u] = (row * a.LW + col) * 3 * a.PSU + c8;
-                if (iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win && img < a.N && c < a.Cin) { // Cin % 4 == 0
-                    const float *src = a.in + (((size_t)img * a.Hin + iy) * a.Win + ix) * a.Cin + c;
-                    v[u][0] = global_load4(src);
-                    if (c + 4 < a.Cin) v[u][1] = global_load4(src + 4);
-                }
-            }
+    for (int i = 0; i < kStageItems; ++i) {
+        const int e = tid + i * 256;
+        it.dst[i] = it.src[i] = -1;
+        if (e < total) {
+            const int row = (int)fd_div((uint32_t)e, a.div_per_row);
+            const int rem = e - row * per_row;
+            const int col = rem >> c8shift, c8 = rem & (c8n - 1);
+            const int g = (int)fd_div((uint32_t)row, a.div_rin);
+            const int iy = iy0 + row - g * a.RIN, ix = col - PAD;
+            it.dst[i] = (row * a.LW + col) * 3 * a.PSU + c8;
+            if ((unsigned)iy < (unsigned)a.Hin && (unsigned)ix < (unsigned)a.Win && g < g_lim)
+                it.src[i] = ((g * a.Hin + iy) * a.Win + ix) * a.Cin + c8 * 8;
         }
+    }
+}
+
+// in0: the workgroup's first image; offsets within its own images fit 32 bits whatever the batch
+__device__ __forceinline__ void stage_fetch(const CodeConvArgs &a, const StageItems &it, floatx4 (&v)[kStageItems][2],
+                                            const float *in0, int c0, int c8shift, int n_items, int tid)
+{
+    const int c = c0 + (tid & ((1 << c8shift) - 1)) * 8; // 256 is a multiple of the items per pixel: one c8 per thread
+    const bool ok0 = c < a.Cin, ok1 = c + 4 < a.Cin;     // Cin % 4 == 0
 #pragma unroll
-        for (int u = 0; u < UB; ++u) {
-            if (dst[u] < 0) continue;
-            uint32_t hi[8], mid[8], lo[8];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                split3(v[u][0][e], hi[e], mid[e], lo[e]);
-                split3(v[u][1][e], hi[4 + e], mid[4 + e], lo[4 + e]);
-            }
-            lds4[dst[u]] = uintx4{pack2(hi[0], hi[1]), pack2(hi[2], hi[3]), pack2(hi[4], hi[5]), pack2(hi[6], hi[7])};
-            lds4[dst[u] + a.PSU] =
-                uintx4{pack2(mid[0], mid[1]), pack2(mid[2], mid[3]), pack2(mid[4], mid[5]), pack2(mid[6], mid[7])};
-            lds4[dst[u] + 2 * a.PSU] =
-                uintx4{pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(lo[4], lo[5]), pack2(lo[6], lo[7])};
+    for (int i = 0; i < kStageItems; ++i) {
+        v[i][0] = v[i][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (i < n_items && it.src[i] >= 0) {
+            const float *src = in0 + it.src[i] + c0;
+            if (ok0) v[i][0] = global_load4(src);
+            if (ok1) v[i][1] = global_load4(src + 4);
         }
+    }
+}
+
+__device__ __forceinline__ void stage_store(const CodeConvArgs &a, const StageItems &it, const floatx4 (&v)[kStageItems][2],
+                                            uintx4 *lds4, int n_items)
+{
+#pragma unroll
+    for (int i = 0; i < kStageItems; ++i) {
+        if (i >= n_items || it.dst[i] < 0) continue;
+        uint32_t hi[8], mid[8], lo[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            split3(v[i][0][e], hi[e], mid[e], lo[e]);
+            split3(v[i][1][e], hi[4 + e], mid[4 + e], lo[4 + e]);
+        }
+        uintx4 *d = lds4 + it.dst[i];
+        d[0] = uintx4{pack2(hi[0], hi[1]), pack2(hi[2], hi[3]), pack2(hi[4], hi[5]), pack2(hi[6], hi[7])};
+        d[a.PSU] = uintx4{pack2(mid[0], mid[1]), pack2(mid[2], mid[3]), pack2(mid[4], mid[5]), pack2(mid[6], mid[7])};
+        d[2 * a.PSU] = uintx4{pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(lo[4], lo[5]), pack2(lo[6], lo[7])};
+        __builtin_amdgcn_sched_barrier(0); // one item's 24 temporaries at a time: the accumulators are live here
     }
 }
 
@@ -203,89 +225,147 @@ __global__ __launch_bounds__(256, 2) void conv_codes_kernel(CodeConvArgs a)
 
     const int c8shift = __ffs(a.CKC >> 3) - 1; // CKC is 16, 32 or 64
     const bool active = ct0 < a.cout_tiles;    // wavefronts past the last output-channel tile only help staging
+    const uint16_t *wbase[NT];                 // the wavefront's code tiles (uniform)
+#pragma unroll
+    for (int n = 0; n < NT; ++n) wbase[n] = a.codes + (size_t)min(ct0 + n, a.cout_tiles - 1) * T * a.CB * 512;
+
+    StageItems items;
+    stage_plan<STRIDE, PAD>(a, items, c8shift, img0, oy0, tid);
+    const int n_items = (a.G * a.RIN * (a.LW << c8shift) + 255) >> 8; // <= kStageItems (host)
+    const float *in0 = a.in + (size_t)img0 * a.Hin * a.Win * a.Cin;
 
     for (int c0 = 0; c0 < a.CB * 16; c0 += a.CKC) {
-        if (c0) __syncthreads();
-        stage_split_rows<STRIDE, PAD>(a, lds4, c0, c8shift, img0, oy0, tid);
+        {
+            // The pass's activations: all reads first, then split and written.  (Holding the next
+            // pass's reads in registers across the MFMA loop does not pay: memory reads return in
+            // order, so the loop's code reads would wait behind them.)  The other workgroup of the
+            // compute unit computes meanwhile.
+            floatx4 staged[kStageItems][2];
+            stage_fetch(a, items, staged, in0, c0, c8shift, n_items, tid);
+            if (c0) __syncthreads(); // the previous pass's LDS reads are done
+            stage_store(a, items, staged, lds4, n_items);
+        }
         __syncthreads();
 
         if (active) {
-            // one flat sequence of (tap, channel block) steps; step k+1's codes and activations are
-            // requested before step k's MFMAs, alternating between two register sets
+            // One flat sequence of (tap, channel block) steps, channel block fastest.  The codes of
+            // step k+2 are requested during step k (three register sets in rotation: they come from
+            // L2, about two steps away); the activations of step k+1 replace those of step k plane by
+            // plane, each plane as soon as the MFMAs that read it have been issued.  Both addresses
+            // advance by increments.
             const int ncb = min(a.CKC, a.CB * 16 - c0) >> 4;
-            const int cb0 = c0 >> 4;
             const int steps = T * ncb;
-            int lt = 0, lc = 0;
-            auto load_step = [&](uintx4 (&wa)[NT], uintx4 (&xb)[2][3]) {
-                const int t = lt, cbl = lc;
-                if (++lc == ncb) {
-                    lc = 0;
-                    ++lt;
-                }
-                const int ky = t / KS, kx = t - ky * KS;
-                const int tapoff = (ky * a.LW + kx) * pix_units + cbl * 2;
+            const int w_tap_step = (a.CB - ncb + 1) * 512; // last block of a tap -> first block of the next
+            int woff = (c0 >> 4) * 512, wc = 0;            // codes: element offset in the tile, block within the pass
+            auto load_codes = [&](uintx4 (&wa)[NT]) {
 #pragma unroll
-                for (int n = 0; n < NT; ++n) {
-                    const int ct = min(ct0 + n, a.cout_tiles - 1);
-                    const uint16_t *wrow = a.codes + (((size_t)ct * T + t) * a.CB + cb0 + cbl) * 512; // uniform
-                    wa[n] = *reinterpret_cast<const uintx4 *>(wrow + lane * 8);
+                for (int n = 0; n < NT; ++n) wa[n] = *reinterpret_cast<const uintx4 *>(wbase[n] + woff + lane * 8);
+                if (++wc == ncb) {
+                    wc = 0;
+                    woff += w_tap_step;
+                } else {
+                    woff += 512;
                 }
+            };
+            const int a_tap_step = pix_units - (ncb - 1) * 2, a_row_step = (a.LW - KS) * pix_units;
+            int tapoff = 0, ac = 0, akx = 0; // activations: LDS offset of the step's tap and block
+            uintx4 xb[2][3];
+            auto load_plane = [&](int pc) {
+#pragma unroll
+                for (int m = 0; m < 2; ++m) xb[m][pc] = lds4[lds_base[m] + tapoff + pc * a.PSU];
+            };
+            auto next_acts = [&]() {
+                if (++ac == ncb) {
+                    ac = 0;
+                    tapoff += a_tap_step;
+                    if (++akx == KS) {
+                        akx = 0;
+                        tapoff += a_row_step;
+                    }
+                } else {
+                    tapoff += 2;
+                }
+            };
+            auto mma_plane = [&](const uintx4 (&wa)[NT], int pc) {
 #pragma unroll
                 for (int m = 0; m < 2; ++m)
 #pragma unroll
-                    for (int pc = 0; pc < 3; ++pc) xb[m][pc] = lds4[lds_base[m] + tapoff + pc * a.PSU];
+                    for (int n = 0; n < NT; ++n)
+                        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, wa[n]), __builtin_bit_cast(bf16x8, xb[m][pc]), acc[m][n], 0, 0, 0);
             };
-            auto mma_step = [&](const uintx4 (&wa)[NT], const uintx4 (&xb)[2][3]) {
+            // step k: wa holds its codes, xb its activations; wa_later receives the codes of step k+2
+            auto step = [&](int k, const uintx4 (&wa)[NT], uintx4 (&wa_later)[NT]) {
+                if (k + 2 < steps) load_codes(wa_later);
+                __builtin_amdgcn_sched_barrier(0); // the request stays ahead of the step's MFMAs
+                const bool more = k + 1 < steps;
+                if (more) next_acts();
 #pragma unroll
-                for (int pc = 2; pc >= 0; --pc) // smallest terms first
-#pragma unroll
-                    for (int m = 0; m < 2; ++m)
-#pragma unroll
-                        for (int n = 0; n < NT; ++n)
-                            acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                __builtin_bit_cast(bf16x8, wa[n]), __builtin_bit_cast(bf16x8, xb[m][pc]), acc[m][n], 0, 0, 0);
+                for (int pc = 2; pc >= 0; --pc) { // smallest terms first
+                    mma_plane(wa, pc);
+                    if (more) load_plane(pc);
+                }
             };
-            uintx4 wa0[NT], xb0[2][3], wa1[NT], xb1[2][3];
-            load_step(wa0, xb0);
+            uintx4 w0[NT], w1[NT], w2[NT];
+            load_codes(w0);
+            if (steps > 1) load_codes(w1);
+#pragma unroll
+            for (int pc = 0; pc < 3; ++pc) load_plane(pc);
             int k = 0;
 #pragma unroll 1
-            for (; k + 2 <= steps; k += 2) {
-                load_step(wa1, xb1);
-                mma_step(wa0, xb0);
-                if (k + 2 < steps) load_step(wa0, xb0);
-                mma_step(wa1, xb1);
+            for (; k + 3 <= steps; k += 3) {
+                step(k, w0, w2);
+                step(k + 1, w1, w0);
+                step(k + 2, w2, w1);
             }
-            if (k < steps) mma_step(wa0, xb0); // odd number of steps: the last one is already loaded
+            if (k < steps) step(k, w0, w2);
+            if (k + 1 < steps) step(k + 1, w1, w0);
         }
     }
 
     if (!active) return;
     // ---- epilogue: scale, bias, residual, activation.  Accumulator e of a lane is output channel
-    // 8 * (e / 4) + 4 * kh + e % 4 of its tile
+    // 8 * (e / 4) + 4 * kh + e % 4 of its tile.  Everything a pixel's stores need is read before its
+    // first store, so the reads are in flight together instead of one round trip per store.
     const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
+    floatx4 sc[NT][4], bi[NT][4];
+#pragma unroll
+    for (int n = 0; n < NT; ++n)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const int co = (ct0 + n) * 32 + g4 * 8 + kh * 4;
+            sc[n][g4] = bi[n][g4] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (co < a.Cout) { // Cout % 4 == 0
+                sc[n][g4] = *reinterpret_cast<const floatx4 *>(a.scales + co);
+                bi[n][g4] = *reinterpret_cast<const floatx4 *>(a.bias + co);
+            }
+        }
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
         if (out_img[m] >= a.N || out_y[m] >= a.Hout) continue;
         const size_t pix = (((size_t)out_img[m] * a.Hout + out_y[m]) * a.Wout + out_x[m]) * a.Cout;
         float *out_p = a.out + pix;
-        const float *res_p = a.res ? a.res + pix : nullptr;
+        floatx4 rv[NT][4];
 #pragma unroll
-        for (int n = 0; n < NT; ++n) {
+        for (int n = 0; n < NT; ++n)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
                 const int co = (ct0 + n) * 32 + g4 * 8 + kh * 4;
-                if (co >= a.Cout) continue; // Cout % 4 == 0
-                const floatx4 sc = *reinterpret_cast<const floatx4 *>(a.scales + co);
-                const floatx4 bi = *reinterpret_cast<const floatx4 *>(a.bias + co);
+                rv[n][g4] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (a.res && co < a.Cout) rv[n][g4] = global_load4(a.res + pix + co);
+            }
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int co = (ct0 + n) * 32 + g4 * 8 + kh * 4;
+                if (co >= a.Cout) continue;
                 floatx4 v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = __fmaf_rn(acc[m][n][g4 * 4 + e], sc[e], bi[e]);
-                if (res_p) v += *reinterpret_cast<const floatx4 *>(res_p + co);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = __builtin_amdgcn_fmed3f(v[e], lo, hi);
+                for (int e = 0; e < 4; ++e)
+                    v[e] = __builtin_amdgcn_fmed3f(__fmaf_rn(acc[m][n][g4 * 4 + e], sc[n][g4][e], bi[n][g4][e]) + rv[n][g4][e], lo, hi);
                 *reinterpret_cast<floatx4 *>(out_p + co) = v;
             }
-        }
     }
 }
 

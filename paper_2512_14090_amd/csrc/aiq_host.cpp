@@ -209,13 +209,17 @@ bool plan_code_conv(const Node &nd, CodePlan &p)
         p.CKC = cp >= 64 ? 64 : (cp >= 32 ? 32 : 16);
         p.RIN = (p.R - 1) * d.stride + d.kh;
         p.LW = d.win + 2 * d.pad;
-        for (;;) { // two workgroups per compute unit where the region allows it, as for the fp32 kernel
+        // two workgroups per compute unit where the region allows it, as for the fp32 kernel; a thread
+        // stages at most kCodeStageItems items (eight channels of one pixel) per pass
+        int items;
+        for (;;) {
             p.PSU = p.CKC / 8 + 1;
             p.lds_bytes = (size_t)16 * p.G * p.RIN * p.LW * 3 * p.PSU;
-            if (p.lds_bytes <= 80 * 1024 || p.CKC == 16) break;
+            items = p.G * p.RIN * p.LW * (p.CKC / 8);
+            if ((p.lds_bytes <= 80 * 1024 && items <= kCodeStageItems * 256) || p.CKC == 16) break;
             p.CKC /= 2;
         }
-        if (p.lds_bytes <= 160 * 1024) return true;
+        if (p.lds_bytes <= 160 * 1024 && items <= kCodeStageItems * 256) return true;
     }
     return false;
 }

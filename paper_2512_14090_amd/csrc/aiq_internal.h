@@ -283,6 +283,8 @@ hipError_t launch_mbconv(const MbShape &sh, const MbArgs &a, int s_total, hipStr
 // matrix pipe (aiq_deploy.hip).  One scheme, so there is no scheme axis.
 namespace aiq {
 
+constexpr int kCodeStageItems = 6; // items (eight channels of one pixel) a thread stages per pass, at most
+
 struct CodeConvArgs {
     const float *in;       // [N][Hin][Win][Cin]
     float *out;            // [N][Hout][Wout][Cout]
