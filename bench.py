@@ -45,6 +45,11 @@ TRAFFIC = {
         "sha256": "a7526213d5d9f3f925369b0a6a961a1088b8de29e471f53501d974fe8ecafab6",
         "bytes_per_launch": 2694684770,
     },
+    ("plainconvnet20_deploy_n2048", "conv_codes"): {  # average over the 19 launches of one deployed forward pass
+        "kernel_source": "paper_2512_14090_amd/csrc/aiq_deploy.hip",
+        "sha256": "1a2a761d78004617a214fbbcc4d88f6784e31f8f1c1213d149478b8744623047",
+        "bytes_per_launch": 560913570,
+    },
     ("quantize_stress_8192x4608_b8", "quantize"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
         "sections": ["helpers", "quantizer"],
@@ -259,7 +264,10 @@ def deploy_mode(args, torch, aiq, synth):
     if kc:
         line["roofline"] = {"bound": "mfma", "kernel": "conv_codes_kernel (3 bf16 MFMA products per fp32-equivalent product)",
                             "achieved": kc["executed_bf16_tflops"], "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
-                            "frac": kc["frac_of_bf16_peak"], "traffic": None,
+                            "frac": kc["frac_of_bf16_peak"],
+                            "traffic": measured_traffic(line["config"]["workload"], "conv_codes"),
+                            "algorithmic_gbytes_per_launch": kc["algorithmic_gbytes_per_s"] * kc["avg_launch_ms"] / 1e3,
+                            "avg_launch_ms": kc["avg_launch_ms"],
                             "hbm": {"achieved": kc["algorithmic_gbytes_per_s"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                     "frac": kc["frac_of_hbm_peak"]}}
     model.close()

@@ -109,6 +109,13 @@ def test_host_validation_precedes_device_work(aiq):
     assert lib.aiq_search_workspace_bytes(None, 1, 1, 3, None) == 1
     assert lib.aiq_sensitivity_workspace_bytes(None, 1, 1, 2, None) == 1
     lib.aiq_model_destroy(None)
+    # deployment: the same for its entry points
+    d = C.c_void_p(None)
+    assert lib.aiq_deploy_create(None, ref.ctypes.data, 0, C.byref(d)) == 1 and not d
+    assert lib.aiq_deploy_workspace_bytes(None, 1, None) == 1
+    assert lib.aiq_deploy_forward(None, None, 1, 1, None, None, None, 0, None) == 1
+    assert lib.aiq_deploy_code_layers(None) == -1
+    lib.aiq_deploy_destroy(None)
 
 
 def test_descriptor_layout_matches_the_header():
