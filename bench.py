@@ -47,7 +47,7 @@ TRAFFIC = {
     },
     ("plainconvnet20_deploy_n2048", "conv_codes"): {  # average over the 19 launches of one deployed forward pass
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_deploy.hip",
-        "sha256": "1a2a761d78004617a214fbbcc4d88f6784e31f8f1c1213d149478b8744623047",
+        "sha256": "7ef684095cbf506a43e56848a5717b7ed517a0e21ccb857e1f61386ff5547d3d",
         "bytes_per_launch": 560913570,
     },
     ("quantize_stress_8192x4608_b8", "quantize"): {

@@ -92,9 +92,9 @@ hipError_t launch_pack_codes(const int32_t *codes, uint16_t *out, int cout, int 
 // four groups of four consecutive output channels of one pixel: four 16-byte NHWC stores.
 //
 // Workgroup = 4 wavefronts; it stages the input rows of its region in LDS already split: per
-// pixel three planes (hi, mid, lo) of CKC bf16 channels, CKC channels per pass.  A wavefront owns 64 pixels x 32*NT
-// output channels and issues, per tap and block of 16 channels, 2 * NT * 3 MFMAs from NT
-// 16-byte global reads (codes, L2-resident) and six 16-byte LDS reads.
+// pixel three planes (hi, mid, lo) of CKC bf16 channels, CKC channels per pass.  A wavefront
+// owns 64 pixels x 32*NT output channels and issues, per tap and block of 16 channels,
+// 2 * NT * 3 MFMAs from NT 16-byte global reads (codes, L2-resident) and six 16-byte LDS reads.
 
 // Staging.  One item = eight channels of one staged pixel: two 16-byte global reads, three 16-byte
 // LDS writes (the hi, mid and lo planes).  Item tid + 256 * i belongs to thread tid; which pixel
