@@ -91,10 +91,11 @@ hipError_t launch_pack_codes(const int32_t *codes, uint16_t *out, int cout, int 
 // output pixels, k = 16 input channels of one tap.  A lane's sixteen accumulator values are
 // four groups of four consecutive output channels of one pixel: four 16-byte NHWC stores.
 //
-// Workgroup = 4 wavefronts; it stages the input rows of its region in LDS already split: per
-// pixel three planes (hi, mid, lo) of CKC bf16 channels, CKC channels per pass.  A wavefront
-// owns 64 pixels x 32*NT output channels and issues, per tap and block of 16 channels,
-// 2 * NT * 3 MFMAs from NT 16-byte global reads (codes, L2-resident) and six 16-byte LDS reads.
+// Workgroup = 4 wavefronts; per pass of CKC channels it stages in LDS the input rows of its
+// region, already split (per pixel three planes - hi, mid, lo - of CKC bf16 channels), and the
+// codes of its output-channel tiles for those channels.  A wavefront owns 64 pixels x 32*NT
+// output channels and issues, per tap and block of 16 channels, 2 * NT * 3 MFMAs from six + NT
+// 16-byte LDS reads.
 
 // Staging.  One item = eight channels of one staged pixel: two 16-byte global reads, three 16-byte
 // LDS writes (the hi, mid and lo planes).  Item tid + 256 * i belongs to thread tid; which pixel
@@ -102,16 +103,38 @@ hipError_t launch_pack_codes(const int32_t *codes, uint16_t *out, int cout, int 
 // and its element offset from the workgroup's first image are formed once (kStageItems of them
 // per thread; the host keeps a region's item count within that).  Per pass the reads of all items
 // are issued first (stage_fetch), then split and written to LDS (stage_store).
-constexpr int kStageItems = kCodeStageItems;
+constexpr int kChunks = kCodeStageChunks;
 
+template <int kStageItems> // activation items per thread: kCodeStageItems, or twice that for long regions
 struct StageItems {
     int dst[kStageItems]; // LDS unit of the hi plane, -1: no such item
     int src[kStageItems]; // element offset of channel c0 + 8 * c8 at the pixel, -1: outside the image
+    // The pass's codes, 16 bytes per chunk: chunk tid + 256 * i goes to LDS unit code_off + tid + 256 * i;
+    // the units are ordered [tile of the workgroup][tap][block of the pass][lane].
+    int csrc[kChunks];    // element offset of the chunk in the codes for the pass that starts at block 0,
+                          // plus the chunk's block within the pass in the low three bits; -1: no such chunk
 };
 
-template <int STRIDE, int PAD>
-__device__ __forceinline__ void stage_plan(const CodeConvArgs &a, StageItems &it, int c8shift, int img0, int oy0, int tid)
+template <int STRIDE, int PAD, int T, int kStageItems>
+__device__ __forceinline__ void stage_plan(const CodeConvArgs &a, StageItems<kStageItems> &it, int c8shift, int img0, int oy0, int tid,
+                                           int first_tile)
 {
+    {
+        const int bshift = c8shift - 1;            // blocks of 16 channels per full pass: CKC / 16
+        const int run = 64 << bshift;              // chunks of one (tile, tap)
+        const int total = a.tiles_per_wg * T * run;
+#pragma unroll
+        for (int i = 0; i < kChunks; ++i) {
+            const int j = tid + i * 256;
+            it.csrc[i] = -1;
+            if (j < total) {
+                const int r = j >> (6 + bshift), q = j & (run - 1);
+                const int ctl = r / T, t = r - ctl * T;
+                const int ct = min(first_tile + ctl, a.cout_tiles - 1);
+                it.csrc[i] = ((ct * T + t) * a.CB) * 512 + q * 8 + (q >> 6);
+            }
+        }
+    }
     const int c8n = 1 << c8shift;
     const int per_row = a.LW << c8shift;
     const int total = a.G * a.RIN * per_row;
@@ -135,7 +158,8 @@ __device__ __forceinline__ void stage_plan(const CodeConvArgs &a, StageItems &it
 }
 
 // in0: the workgroup's first image; offsets within its own images fit 32 bits whatever the batch
-__device__ __forceinline__ void stage_fetch(const CodeConvArgs &a, const StageItems &it, floatx4 (&v)[kStageItems][2],
+template <int kStageItems>
+__device__ __forceinline__ void stage_fetch(const CodeConvArgs &a, const StageItems<kStageItems> &it, floatx4 (&v)[kStageItems][2],
                                             const float *in0, int c0, int c8shift, int n_items, int tid)
 {
     const int c = c0 + (tid & ((1 << c8shift) - 1)) * 8; // 256 is a multiple of the items per pixel: one c8 per thread
@@ -151,7 +175,30 @@ __device__ __forceinline__ void stage_fetch(const CodeConvArgs &a, const StageIt
     }
 }
 
-__device__ __forceinline__ void stage_store(const CodeConvArgs &a, const StageItems &it, const floatx4 (&v)[kStageItems][2],
+// chunk i of the pass that starts at channel block cb0 and has ncb blocks
+template <int kStageItems>
+__device__ __forceinline__ void code_fetch(const CodeConvArgs &a, const StageItems<kStageItems> &it, uintx4 (&cv)[kChunks], int cb0,
+                                           int ncb)
+{
+#pragma unroll
+    for (int i = 0; i < kChunks; ++i) {
+        cv[i] = uintx4{0u, 0u, 0u, 0u};
+        if (it.csrc[i] >= 0 && (it.csrc[i] & 7) < ncb)
+            cv[i] = *(const __attribute__((address_space(1))) uintx4 *)(a.codes + (it.csrc[i] & ~7) + cb0 * 512);
+    }
+}
+
+template <int kStageItems>
+__device__ __forceinline__ void code_store(const CodeConvArgs &a, const StageItems<kStageItems> &it, const uintx4 (&cv)[kChunks],
+                                           uintx4 *lds4, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < kChunks; ++i)
+        if (it.csrc[i] >= 0) lds4[a.code_off + tid + i * 256] = cv[i];
+}
+
+template <int kStageItems>
+__device__ __forceinline__ void stage_store(const CodeConvArgs &a, const StageItems<kStageItems> &it, const floatx4 (&v)[kStageItems][2],
                                             uintx4 *lds4, int n_items)
 {
 #pragma unroll
@@ -171,9 +218,10 @@ __device__ __forceinline__ void stage_store(const CodeConvArgs &a, const StageIt
     }
 }
 
-template <int KS, int STRIDE, int NT>
+template <int KS, int STRIDE, int NT, int KI>
 __global__ __launch_bounds__(256, 2) void conv_codes_kernel(CodeConvArgs a)
 {
+    constexpr int kStageItems = KI;
     extern __shared__ float lds_raw[];
     uintx4 *lds4 = reinterpret_cast<uintx4 *>(lds_raw);
     constexpr int T = KS * KS;
@@ -199,7 +247,6 @@ __global__ __launch_bounds__(256, 2) void conv_codes_kernel(CodeConvArgs a)
 
     const int pix_units = 3 * a.PSU; // 16-byte units per staged pixel
     int lds_base[2];
-    int out_img[2], out_y[2], out_x[2];
     const int rw = a.R * a.Wout;
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
@@ -210,9 +257,6 @@ __global__ __launch_bounds__(256, 2) void conv_codes_kernel(CodeConvArgs a)
         const uint32_t ox = rem - oy * a.Wout;
         const bool in_region = g < (uint32_t)a.G; // lanes past the region's last pixel compute nothing useful
         lds_base[m] = in_region ? ((g * a.RIN + oy * STRIDE) * a.LW + ox * STRIDE) * pix_units + kh : kh;
-        out_img[m] = in_region ? img0 + (int)g : a.N;
-        out_y[m] = oy0 + oy;
-        out_x[m] = ox;
     }
 
     floatx16 acc[2][NT];
@@ -225,175 +269,182 @@ __global__ __launch_bounds__(256, 2) void conv_codes_kernel(CodeConvArgs a)
 
     const int c8shift = __ffs(a.CKC >> 3) - 1; // CKC is 16, 32 or 64
     const bool active = ct0 < a.cout_tiles;    // wavefronts past the last output-channel tile only help staging
-    const uint16_t *wbase[NT];                 // the wavefront's code tiles (uniform)
-#pragma unroll
-    for (int n = 0; n < NT; ++n) wbase[n] = a.codes + (size_t)min(ct0 + n, a.cout_tiles - 1) * T * a.CB * 512;
-
-    StageItems items;
-    stage_plan<STRIDE, PAD>(a, items, c8shift, img0, oy0, tid);
+    StageItems<KI> items;
+    stage_plan<STRIDE, PAD, T, KI>(a, items, c8shift, img0, oy0, tid, blockIdx.y * a.tiles_per_wg);
     const int n_items = (a.G * a.RIN * (a.LW << c8shift) + 255) >> 8; // <= kStageItems (host)
     const float *in0 = a.in + (size_t)img0 * a.Hin * a.Win * a.Cin;
+    const int ncbf = a.CKC >> 4; // blocks of a full pass
+
+    // What the next pass needs - its activations and its codes - is requested before the current
+    // pass's MFMA loop and travels while it runs; the loop itself reads LDS only, so it never waits
+    // behind these reads.
+    floatx4 staged[kStageItems][2];
+    uintx4 cstaged[kChunks];
+    stage_fetch(a, items, staged, in0, 0, c8shift, n_items, tid);
+    code_fetch(a, items, cstaged, 0, min(ncbf, a.CB));
 
     for (int c0 = 0; c0 < a.CB * 16; c0 += a.CKC) {
-        {
-            // The pass's activations: all reads first, then split and written.  (Holding the next
-            // pass's reads in registers across the MFMA loop does not pay: memory reads return in
-            // order, so the loop's code reads would wait behind them.)  The other workgroup of the
-            // compute unit computes meanwhile.
-            floatx4 staged[kStageItems][2];
-            stage_fetch(a, items, staged, in0, c0, c8shift, n_items, tid);
-            if (c0) __syncthreads(); // the previous pass's LDS reads are done
-            stage_store(a, items, staged, lds4, n_items);
-        }
+        const int ncb = min(a.CKC, a.CB * 16 - c0) >> 4;
+        if (c0) __syncthreads(); // the previous pass's LDS reads are done
+        stage_store(a, items, staged, lds4, n_items);
+        code_store(a, items, cstaged, lds4, tid);
         __syncthreads();
+        if (c0 + a.CKC < a.CB * 16) {
+            stage_fetch(a, items, staged, in0, c0 + a.CKC, c8shift, n_items, tid);
+            code_fetch(a, items, cstaged, (c0 + a.CKC) >> 4, min(a.CKC, a.CB * 16 - c0 - a.CKC) >> 4);
+        }
 
-        if (active) {
-            // One flat sequence of (tap, channel block) steps, channel block fastest.  The codes of
-            // step k+2 are requested during step k (three register sets in rotation: they come from
-            // L2, about two steps away); the activations of step k+1 replace those of step k plane by
-            // plane, each plane as soon as the MFMAs that read it have been issued.  Both addresses
-            // advance by increments.
-            const int ncb = min(a.CKC, a.CB * 16 - c0) >> 4;
+        {
+            // One flat sequence of (tap, channel block) steps, channel block fastest.  The operands of
+            // step k+1 are read from LDS during step k: the codes into a second register set, the
+            // activations plane by plane into the set in use, each plane as soon as the MFMAs that
+            // read it have been issued.  Both LDS addresses advance by increments; the last step
+            // reads its own operands again instead of running past the end.  (Wavefronts without an
+            // output tile of their own run the loop on the last tile and store nothing.)
             const int steps = T * ncb;
-            const int w_tap_step = (a.CB - ncb + 1) * 512; // last block of a tap -> first block of the next
-            int woff = (c0 >> 4) * 512, wc = 0;            // codes: element offset in the tile, block within the pass
-            auto load_codes = [&](uintx4 (&wa)[NT]) {
-#pragma unroll
-                for (int n = 0; n < NT; ++n) wa[n] = *reinterpret_cast<const uintx4 *>(wbase[n] + woff + lane * 8);
-                if (++wc == ncb) {
-                    wc = 0;
-                    woff += w_tap_step;
-                } else {
-                    woff += 512;
-                }
-            };
+            const int w_tap_step = (ncbf - ncb + 1) * 64; // last block of a tap -> first block of the next
+            int woff = a.code_off + (wco * NT * T * ncbf) * 64 + lane, wc = 0;
             const int a_tap_step = pix_units - (ncb - 1) * 2, a_row_step = (a.LW - KS) * pix_units;
             int tapoff = 0, ac = 0, akx = 0; // activations: LDS offset of the step's tap and block
-            uintx4 xb[2][3];
-            auto load_plane = [&](int pc) {
+            uintx4 xb[2][3], wcur[NT], wnext[NT];
 #pragma unroll
-                for (int m = 0; m < 2; ++m) xb[m][pc] = lds4[lds_base[m] + tapoff + pc * a.PSU];
-            };
-            auto next_acts = [&]() {
-                if (++ac == ncb) {
-                    ac = 0;
-                    tapoff += a_tap_step;
-                    if (++akx == KS) {
-                        akx = 0;
-                        tapoff += a_row_step;
+            for (int n = 0; n < NT; ++n) wcur[n] = lds4[woff + n * (T * ncbf * 64)];
+#pragma unroll
+            for (int pc = 0; pc < 3; ++pc)
+#pragma unroll
+                for (int m = 0; m < 2; ++m) xb[m][pc] = lds4[lds_base[m] + pc * a.PSU];
+#pragma unroll 1
+            for (int k = 0; k < steps; ++k) {
+                if (k + 1 < steps) { // uniform: scalar address updates only
+                    if (++wc == ncb) {
+                        wc = 0;
+                        woff += w_tap_step;
+                    } else {
+                        woff += 64;
                     }
-                } else {
-                    tapoff += 2;
+                    if (++ac == ncb) {
+                        ac = 0;
+                        tapoff += a_tap_step;
+                        if (++akx == KS) {
+                            akx = 0;
+                            tapoff += a_row_step;
+                        }
+                    } else {
+                        tapoff += 2;
+                    }
                 }
-            };
-            auto mma_plane = [&](const uintx4 (&wa)[NT], int pc) {
 #pragma unroll
-                for (int m = 0; m < 2; ++m)
-#pragma unroll
-                    for (int n = 0; n < NT; ++n)
-                        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, wa[n]), __builtin_bit_cast(bf16x8, xb[m][pc]), acc[m][n], 0, 0, 0);
-            };
-            // step k: wa holds its codes, xb its activations; wa_later receives the codes of step k+2
-            auto step = [&](int k, const uintx4 (&wa)[NT], uintx4 (&wa_later)[NT]) {
-                if (k + 2 < steps) load_codes(wa_later);
-                __builtin_amdgcn_sched_barrier(0); // the request stays ahead of the step's MFMAs
-                const bool more = k + 1 < steps;
-                if (more) next_acts();
+                for (int n = 0; n < NT; ++n) wnext[n] = lds4[woff + n * (T * ncbf * 64)];
 #pragma unroll
                 for (int pc = 2; pc >= 0; --pc) { // smallest terms first
-                    mma_plane(wa, pc);
-                    if (more) load_plane(pc);
-                }
-            };
-            uintx4 w0[NT], w1[NT], w2[NT];
-            load_codes(w0);
-            if (steps > 1) load_codes(w1);
 #pragma unroll
-            for (int pc = 0; pc < 3; ++pc) load_plane(pc);
-            int k = 0;
-#pragma unroll 1
-            for (; k + 3 <= steps; k += 3) {
-                step(k, w0, w2);
-                step(k + 1, w1, w0);
-                step(k + 2, w2, w1);
+                    for (int m = 0; m < 2; ++m)
+#pragma unroll
+                        for (int n = 0; n < NT; ++n)
+                            acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8, wcur[n]), __builtin_bit_cast(bf16x8, xb[m][pc]), acc[m][n], 0, 0, 0);
+#pragma unroll
+                    for (int m = 0; m < 2; ++m) xb[m][pc] = lds4[lds_base[m] + tapoff + pc * a.PSU];
+                }
+#pragma unroll
+                for (int n = 0; n < NT; ++n) wcur[n] = wnext[n];
             }
-            if (k < steps) step(k, w0, w2);
-            if (k + 1 < steps) step(k + 1, w1, w0);
         }
     }
 
+    // ---- epilogue: scale, bias, residual, activation, through LDS.  A lane's accumulators are four
+    // consecutive output channels of one pixel at a time, and a store of those would put sixteen
+    // 16-byte pieces of sixteen different lines into every quarter of a store instruction; the
+    // memory system takes such pieces one request each.  So the wavefront first lays its 64 pixels
+    // x 32*NT channels out in LDS (its own stretch of it: the staged tensors are dead once every
+    // wavefront has left the last MFMA loop), then reads them back with consecutive lanes on
+    // consecutive 16-byte chunks of one pixel and stores whole lines.  Chunk c of row r lives in
+    // unit r * U + (c ^ (r % U)), which keeps both directions free of bank conflicts.
+    __syncthreads();
     if (!active) return;
-    // ---- epilogue: scale, bias, residual, activation.  Accumulator e of a lane is output channel
-    // 8 * (e / 4) + 4 * kh + e % 4 of its tile.  Everything a pixel's stores need is read before its
-    // first store, so the reads are in flight together instead of one round trip per store.
+    constexpr int U = 8 * NT; // 16-byte chunks of one pixel's channels in this wavefront's tile
+    uintx4 *tile = lds4 + wave * 64 * U;
+    {
+        floatx4 sc[NT][4], bi[NT][4];
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int co = (ct0 + n) * 32 + g4 * 8 + kh * 4;
+                sc[n][g4] = bi[n][g4] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (co < a.Cout) { // Cout % 4 == 0
+                    sc[n][g4] = *reinterpret_cast<const floatx4 *>(a.scales + co);
+                    bi[n][g4] = *reinterpret_cast<const floatx4 *>(a.bias + co);
+                }
+            }
+        // accumulator e of a lane is output channel 8 * (e / 4) + 4 * kh + e % 4 of its tile
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+            for (int n = 0; n < NT; ++n)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const int row = m * 32 + p, chunk = n * 8 + g4 * 2 + kh;
+                    floatx4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = __fmaf_rn(acc[m][n][g4 * 4 + e], sc[n][g4][e], bi[n][g4][e]);
+                    tile[row * U + (chunk ^ (row & (U - 1)))] = __builtin_bit_cast(uintx4, v);
+                }
+    }
+    // The region's pixels are consecutive in memory (whole rows of one image, or whole images):
+    // pixel P of the region is pixel first_px + P of the chunk.
     const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
-    floatx4 sc[NT][4], bi[NT][4];
+    const int px_img = a.Hout * a.Wout;
+    const size_t first_px = a.G > 1 ? (size_t)img0 * px_img : ((size_t)img0 * a.Hout + oy0) * a.Wout;
+    const int valid_px = a.G > 1 ? min(a.G, a.N - img0) * px_img : min(a.R, a.Hout - oy0) * a.Wout;
+    float *out0 = a.out + first_px * a.Cout;
+    const float *res0 = a.res ? a.res + first_px * a.Cout : nullptr;
+    constexpr int ROWS = 64 / U;            // pixels one instruction covers
+    const int chunk = lane & (U - 1), sub = lane / U;
+    const int co = ct0 * 32 + chunk * 4;    // Cout % 4 == 0
+    floatx4 rv[U];
 #pragma unroll
-    for (int n = 0; n < NT; ++n)
+    for (int it = 0; it < U; ++it) {
+        const int P = wpx * 64 + it * ROWS + sub;
+        rv[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (res0 && co < a.Cout && P < valid_px) rv[it] = global_load4(res0 + P * a.Cout + co);
+    }
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-            const int co = (ct0 + n) * 32 + g4 * 8 + kh * 4;
-            sc[n][g4] = bi[n][g4] = floatx4{0.f, 0.f, 0.f, 0.f};
-            if (co < a.Cout) { // Cout % 4 == 0
-                sc[n][g4] = *reinterpret_cast<const floatx4 *>(a.scales + co);
-                bi[n][g4] = *reinterpret_cast<const floatx4 *>(a.bias + co);
-            }
-        }
+    for (int it = 0; it < U; ++it) {
+        const int row = it * ROWS + sub, P = wpx * 64 + row;
+        floatx4 v = __builtin_bit_cast(floatx4, tile[row * U + (chunk ^ (row & (U - 1)))]) + rv[it];
 #pragma unroll
-    for (int m = 0; m < 2; ++m) {
-        if (out_img[m] >= a.N || out_y[m] >= a.Hout) continue;
-        const size_t pix = (((size_t)out_img[m] * a.Hout + out_y[m]) * a.Wout + out_x[m]) * a.Cout;
-        float *out_p = a.out + pix;
-        floatx4 rv[NT][4];
-#pragma unroll
-        for (int n = 0; n < NT; ++n)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const int co = (ct0 + n) * 32 + g4 * 8 + kh * 4;
-                rv[n][g4] = floatx4{0.f, 0.f, 0.f, 0.f};
-                if (a.res && co < a.Cout) rv[n][g4] = global_load4(a.res + pix + co);
-            }
-#pragma unroll
-        for (int n = 0; n < NT; ++n)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const int co = (ct0 + n) * 32 + g4 * 8 + kh * 4;
-                if (co >= a.Cout) continue;
-                floatx4 v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    v[e] = __builtin_amdgcn_fmed3f(__fmaf_rn(acc[m][n][g4 * 4 + e], sc[n][g4][e], bi[n][g4][e]) + rv[n][g4][e], lo, hi);
-                *reinterpret_cast<floatx4 *>(out_p + co) = v;
-            }
+        for (int e = 0; e < 4; ++e) v[e] = __builtin_amdgcn_fmed3f(v[e], lo, hi);
+        if (co < a.Cout && P < valid_px) *reinterpret_cast<floatx4 *>(out0 + P * a.Cout + co) = v;
     }
 }
 
 template <int KS, int STRIDE>
-static hipError_t launch_codes_nt(const CodeConvArgs &a, int nt, size_t lds_bytes, dim3 grid, hipStream_t st)
+static hipError_t launch_codes_nt(const CodeConvArgs &a, int nt, int ki, size_t lds_bytes, dim3 grid, hipStream_t st)
 {
-    switch (nt) {
-    case 1: hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, 1>), grid, dim3(256), lds_bytes, st, a); break;
-    case 2: hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, 2>), grid, dim3(256), lds_bytes, st, a); break;
-    default: return hipErrorInvalidValue;
-    }
+    constexpr int K1 = kCodeStageItems, K2 = 2 * kCodeStageItems;
+    if (nt == 1 && ki == K1) hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, 1, K1>), grid, dim3(256), lds_bytes, st, a);
+    else if (nt == 2 && ki == K1) hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, 2, K1>), grid, dim3(256), lds_bytes, st, a);
+    else if (nt == 1 && ki == K2) hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, 1, K2>), grid, dim3(256), lds_bytes, st, a);
+    else if (nt == 2 && ki == K2) hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, 2, K2>), grid, dim3(256), lds_bytes, st, a);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
-hipError_t launch_conv_codes(const CodeConvArgs &a, int ks, int stride, int nt, size_t lds_bytes, dim3 grid,
+hipError_t launch_conv_codes(const CodeConvArgs &a, int ks, int stride, int nt, int stage_items, size_t lds_bytes, dim3 grid,
                              hipStream_t st)
 {
-    if (ks == 3 && stride == 1) return launch_codes_nt<3, 1>(a, nt, lds_bytes, grid, st);
-    if (ks == 3 && stride == 2) return launch_codes_nt<3, 2>(a, nt, lds_bytes, grid, st);
-    if (ks == 1 && stride == 1) return launch_codes_nt<1, 1>(a, nt, lds_bytes, grid, st);
-    if (ks == 1 && stride == 2) return launch_codes_nt<1, 2>(a, nt, lds_bytes, grid, st);
+    if (ks == 3 && stride == 1) return launch_codes_nt<3, 1>(a, nt, stage_items, lds_bytes, grid, st);
+    if (ks == 3 && stride == 2) return launch_codes_nt<3, 2>(a, nt, stage_items, lds_bytes, grid, st);
+    if (ks == 1 && stride == 1) return launch_codes_nt<1, 1>(a, nt, stage_items, lds_bytes, grid, st);
+    if (ks == 1 && stride == 2) return launch_codes_nt<1, 2>(a, nt, stage_items, lds_bytes, grid, st);
     return hipErrorInvalidValue;
 }
 
-template <int KS, int STRIDE, int NT>
+template <int KS, int STRIDE, int NT, int KI>
 static hipError_t codes_lds_t()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_codes_kernel<KS, STRIDE, NT>),
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_codes_kernel<KS, STRIDE, NT, KI>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
 }
 
@@ -401,9 +452,11 @@ static hipError_t codes_lds_t()
 hipError_t conv_codes_set_lds_limits()
 {
     hipError_t e = hipSuccess;
-#define AIQ_SET(KS, ST)                                  \
-    if (e == hipSuccess) e = codes_lds_t<KS, ST, 1>();   \
-    if (e == hipSuccess) e = codes_lds_t<KS, ST, 2>();
+#define AIQ_SET(KS, ST)                                                              \
+    if (e == hipSuccess) e = codes_lds_t<KS, ST, 1, kCodeStageItems>();              \
+    if (e == hipSuccess) e = codes_lds_t<KS, ST, 2, kCodeStageItems>();              \
+    if (e == hipSuccess) e = codes_lds_t<KS, ST, 1, 2 * kCodeStageItems>();          \
+    if (e == hipSuccess) e = codes_lds_t<KS, ST, 2, 2 * kCodeStageItems>();
     AIQ_SET(3, 1)
     AIQ_SET(3, 2)
     AIQ_SET(1, 1)

@@ -162,29 +162,35 @@ aiq_status plan_conv(Node &nd)
 }
 
 // Tiling of the integer-code convolution (conv_codes_kernel): output-channel tiles are 32 wide,
-// a wavefront holds one or two of them for 64 pixels, and a staged pixel takes three bf16 planes
-// of CKC channels, each padded by 16 bytes.  False if even 16 channels do not fit the LDS.
+// a wavefront holds one or two of them for 64 pixels.  Per pass of CKC channels the LDS holds the
+// region's input rows (per pixel three bf16 planes of CKC channels, each padded by 16 bytes) and
+// the codes of the workgroup's tiles for those channels; a thread stages at most kCodeStageItems
+// activation items and kCodeStageChunks code chunks per pass.  False if no tiling fits.
 struct CodePlan {
-    int nt, wave_px_split, R, G, regions_per_image, CB, CKC, RIN, LW, PSU, cout_tiles, grid_y;
+    int nt, wave_px_split, R, G, regions_per_image, CB, CKC, RIN, LW, PSU, cout_tiles, grid_y, code_off, stage_items;
     size_t lds_bytes;
 };
 
 bool plan_code_conv(const Node &nd, CodePlan &p)
 {
     const aiq_layer_desc &d = nd.d;
+    const int T = d.kh * d.kw;
     // Preferred split of the four wavefronts as for the fp32 kernel (most output channels per
     // workgroup at no more than 1/8 of the MFMAs wasted); if the region that goes with it does
-    // not fit the LDS, more wavefronts go along the output channels and the region shrinks.
-    for (int wco_min = 1; wco_min <= 4; wco_min *= 2) {
+    // not fit, more wavefronts go along the output channels and the region shrinks.
+    for (int wco_min = 1; wco_min <= 4; wco_min *= 2)
+    for (int ki = kCodeStageItems; ki <= 2 * kCodeStageItems; ki += kCodeStageItems) {
         p = CodePlan{};
+        p.stage_items = ki;
         p.cout_tiles = (d.cout + 31) / 32;
         p.CB = (d.cin + 15) / 16;
         int wco = 0, best_cover = 0;
         for (int nt = 1; nt <= 2; ++nt)
             for (int w = wco_min; w <= 4; w *= 2) {
                 const int per_wg = nt * w;
+                const bool smallest = nt == 1 && w == wco_min;
                 const int waste = (p.cout_tiles + per_wg - 1) / per_wg * per_wg - p.cout_tiles;
-                if (waste * 8 > p.cout_tiles && !(nt == 1 && w == wco_min)) continue;
+                if (!smallest && (waste * 8 > p.cout_tiles || per_wg * T * 64 > kCodeStageChunks * 256)) continue;
                 if (per_wg > best_cover || (per_wg == best_cover && nt > p.nt)) {
                     best_cover = per_wg;
                     p.nt = nt;
@@ -209,17 +215,19 @@ bool plan_code_conv(const Node &nd, CodePlan &p)
         p.CKC = cp >= 64 ? 64 : (cp >= 32 ? 32 : 16);
         p.RIN = (p.R - 1) * d.stride + d.kh;
         p.LW = d.win + 2 * d.pad;
-        // two workgroups per compute unit where the region allows it, as for the fp32 kernel; a thread
-        // stages at most kCodeStageItems items (eight channels of one pixel) per pass
-        int items;
+        // two workgroups per compute unit where the region allows it, as for the fp32 kernel
+        bool fits;
         for (;;) {
             p.PSU = p.CKC / 8 + 1;
-            p.lds_bytes = (size_t)16 * p.G * p.RIN * p.LW * 3 * p.PSU;
-            items = p.G * p.RIN * p.LW * (p.CKC / 8);
-            if ((p.lds_bytes <= 80 * 1024 && items <= kCodeStageItems * 256) || p.CKC == 16) break;
+            p.code_off = p.G * p.RIN * p.LW * 3 * p.PSU;
+            const int chunks = p.nt * wco * T * (p.CKC / 16) * 64;
+            // the epilogue lays every wavefront's 64 pixels x 32 * nt channels out in LDS
+            p.lds_bytes = std::max((size_t)16 * (p.code_off + chunks), (size_t)4 * 64 * 32 * p.nt * sizeof(float));
+            fits = p.G * p.RIN * p.LW * (p.CKC / 8) <= ki * 256 && chunks <= kCodeStageChunks * 256;
+            if ((fits && p.lds_bytes <= 80 * 1024) || p.CKC == 16) break;
             p.CKC /= 2;
         }
-        if (p.lds_bytes <= 160 * 1024 && items <= kCodeStageItems * 256) return true;
+        if (fits && p.lds_bytes <= 160 * 1024) return true;
     }
     return false;
 }
@@ -1658,13 +1666,15 @@ aiq_status aiq_deploy_forward(aiq_deployed *d, const float *images, int32_t N, i
             a.PSU = p.PSU;
             a.wave_px_split = p.wave_px_split;
             a.cout_tiles = p.cout_tiles;
+            a.tiles_per_wg = p.nt * (4 / p.wave_px_split);
+            a.code_off = p.code_off;
             a.div_rin = make_fastdiv(p.RIN);
             a.div_wout = make_fastdiv(nd.wout);
             a.div_rw = make_fastdiv(p.R * nd.wout);
             a.div_per_row = make_fastdiv(p.LW * (p.CKC / 8));
             const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
             ProfScope ps(m, st, AIQ_K_CONV_CODES, nd.flops_per_image * n, nd.act_bytes_per_image * n);
-            AIQ_HIP(launch_conv_codes(a, ld.kh, ld.stride, p.nt, p.lds_bytes, dim3(gx, p.grid_y, 1), st));
+            AIQ_HIP(launch_conv_codes(a, ld.kh, ld.stride, p.nt, p.stage_items, p.lds_bytes, dim3(gx, p.grid_y, 1), st));
         }
     }
     return AIQ_OK;

@@ -283,7 +283,9 @@ hipError_t launch_mbconv(const MbShape &sh, const MbArgs &a, int s_total, hipStr
 // matrix pipe (aiq_deploy.hip).  One scheme, so there is no scheme axis.
 namespace aiq {
 
-constexpr int kCodeStageItems = 6; // items (eight channels of one pixel) a thread stages per pass, at most
+constexpr int kCodeStageItems = 3;  // items (eight channels of one pixel) a thread stages per pass; twice that in the
+                                    // kernel variant for long regions
+constexpr int kCodeStageChunks = 5; // 16-byte chunks of codes a thread stages per pass, at most
 
 struct CodeConvArgs {
     const float *in;       // [N][Hin][Win][Cin]
@@ -304,13 +306,15 @@ struct CodeConvArgs {
     int32_t PSU;           // 16-byte units of one pixel's plane: CKC / 8 + 1 (odd: conflict-free 16-byte reads)
     int32_t wave_px_split; // waves along pixels (4, 2 or 1); 4/wave_px_split along output channels
     int32_t cout_tiles;    // ceil(Cout/32)
+    int32_t tiles_per_wg;  // output-channel tiles of one workgroup: NT * 4 / wave_px_split
+    int32_t code_off;      // LDS unit where the pass's codes start (after the activations)
     FastDiv div_rin, div_wout, div_rw, div_per_row; // RIN, Wout, R*Wout, LW * CKC / 8
 };
 
 // codes: int32 [cout][cin][taps]; out: cleared buffer in the layout above
 hipError_t launch_pack_codes(const int32_t *codes, uint16_t *out, int cout, int cin, int taps, hipStream_t st);
-hipError_t launch_conv_codes(const CodeConvArgs &a, int ks, int stride, int nt, size_t lds_bytes, dim3 grid,
-                             hipStream_t st);
+hipError_t launch_conv_codes(const CodeConvArgs &a, int ks, int stride, int nt, int stage_items, size_t lds_bytes,
+                             dim3 grid, hipStream_t st);
 hipError_t conv_codes_set_lds_limits();
 
 } // namespace aiq
