@@ -47,8 +47,8 @@ TRAFFIC = {
     },
     ("plainconvnet20_deploy_n2048", "conv_codes"): {  # average over the 19 launches of one deployed forward pass
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_deploy.hip",
-        "sha256": "7ef684095cbf506a43e56848a5717b7ed517a0e21ccb857e1f61386ff5547d3d",
-        "bytes_per_launch": 560913570,
+        "sha256": "ce123cda9d66e17310aa301df3b2d88b7764cab85ce19b87eb9798837979c5b4",
+        "bytes_per_launch": 487721283,
     },
     ("quantize_stress_8192x4608_b8", "quantize"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
