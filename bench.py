@@ -47,7 +47,7 @@ TRAFFIC = {
     },
     ("plainconvnet20_deploy_n2048", "conv_codes"): {  # average over the 19 launches of one deployed forward pass
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_deploy.hip",
-        "sha256": "ce123cda9d66e17310aa301df3b2d88b7764cab85ce19b87eb9798837979c5b4",
+        "sha256": "9ccf90420a21e2a5384264bd3e5d363b5d73b025dd09225048426c8ad1968647",
         "bytes_per_launch": 487721283,
     },
     ("quantize_stress_8192x4608_b8", "quantize"): {

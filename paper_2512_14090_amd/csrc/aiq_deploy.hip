@@ -89,7 +89,8 @@ hipError_t launch_pack_codes(const int32_t *codes, uint16_t *out, int cout, int 
 //
 // Implicit GEMM on v_mfma_f32_32x32x16_bf16: A = codes (rows = 32 output channels), B = 32
 // output pixels, k = 16 input channels of one tap.  A lane's sixteen accumulator values are
-// four groups of four consecutive output channels of one pixel: four 16-byte NHWC stores.
+// four groups of four consecutive output channels of one pixel; the epilogue passes them through
+// LDS so that the NHWC stores cover whole lines.
 //
 // Workgroup = 4 wavefronts; per pass of CKC channels it stages in LDS the input rows of its
 // region, already split (per pixel three planes - hi, mid, lo - of CKC bf16 channels), and the
