@@ -220,7 +220,7 @@ __device__ __forceinline__ void stage_store(const CodeConvArgs &a, const StageIt
 }
 
 template <int KS, int STRIDE, int NT, int KI>
-__global__ __launch_bounds__(256, 2) void conv_codes_kernel(CodeConvArgs a)
+__global__ __launch_bounds__(256, 3) void conv_codes_kernel(CodeConvArgs a)
 {
     constexpr int kStageItems = KI;
     extern __shared__ float lds_raw[];
@@ -280,20 +280,19 @@ __global__ __launch_bounds__(256, 2) void conv_codes_kernel(CodeConvArgs a)
     // pass's MFMA loop and travels while it runs; the loop itself reads LDS only, so it never waits
     // behind these reads.
     floatx4 staged[kStageItems][2];
-    uintx4 cstaged[kChunks];
     stage_fetch(a, items, staged, in0, 0, c8shift, n_items, tid);
-    code_fetch(a, items, cstaged, 0, min(ncbf, a.CB));
 
     for (int c0 = 0; c0 < a.CB * 16; c0 += a.CKC) {
         const int ncb = min(a.CKC, a.CB * 16 - c0) >> 4;
-        if (c0) __syncthreads(); // the previous pass's LDS reads are done
-        stage_store(a, items, staged, lds4, n_items);
-        code_store(a, items, cstaged, lds4, tid);
-        __syncthreads();
-        if (c0 + a.CKC < a.CB * 16) {
-            stage_fetch(a, items, staged, in0, c0 + a.CKC, c8shift, n_items, tid);
-            code_fetch(a, items, cstaged, (c0 + a.CKC) >> 4, min(a.CKC, a.CB * 16 - c0 - a.CKC) >> 4);
+        {
+            uintx4 cstaged[kChunks];
+            code_fetch(a, items, cstaged, c0 >> 4, ncb);
+            if (c0) __syncthreads(); // the previous pass's LDS reads are done
+            stage_store(a, items, staged, lds4, n_items);
+            code_store(a, items, cstaged, lds4, tid);
         }
+        __syncthreads();
+        if (c0 + a.CKC < a.CB * 16) stage_fetch(a, items, staged, in0, c0 + a.CKC, c8shift, n_items, tid);
 
         {
             // One flat sequence of (tap, channel block) steps, channel block fastest.  The operands of
@@ -356,42 +355,27 @@ __global__ __launch_bounds__(256, 2) void conv_codes_kernel(CodeConvArgs a)
     // ---- epilogue: scale, bias, residual, activation, through LDS.  A lane's accumulators are four
     // consecutive output channels of one pixel at a time, and a store of those would put sixteen
     // 16-byte pieces of sixteen different lines into every quarter of a store instruction; the
-    // memory system takes such pieces one request each.  So the wavefront first lays its 64 pixels
-    // x 32*NT channels out in LDS (its own stretch of it: the staged tensors are dead once every
+    // memory system takes such pieces one request each.  So the wavefront lays its pixels (32 at a
+    // time) x 32*NT channels out in LDS (its own stretch of it: the staged tensors are dead once every
     // wavefront has left the last MFMA loop), then reads them back with consecutive lanes on
     // consecutive 16-byte chunks of one pixel and stores whole lines.  Chunk c of row r lives in
     // unit r * U + (c ^ (r % U)), which keeps both directions free of bank conflicts.
     __syncthreads();
     if (!active) return;
     constexpr int U = 8 * NT; // 16-byte chunks of one pixel's channels in this wavefront's tile
-    uintx4 *tile = lds4 + wave * 64 * U;
-    {
-        floatx4 sc[NT][4], bi[NT][4];
+    uintx4 *tile = lds4 + wave * 32 * U; // 32 pixels at a time (one MFMA tile row), twice
+    floatx4 sc[NT][4], bi[NT][4];
 #pragma unroll
-        for (int n = 0; n < NT; ++n)
+    for (int n = 0; n < NT; ++n)
 #pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const int co = (ct0 + n) * 32 + g4 * 8 + kh * 4;
-                sc[n][g4] = bi[n][g4] = floatx4{0.f, 0.f, 0.f, 0.f};
-                if (co < a.Cout) { // Cout % 4 == 0
-                    sc[n][g4] = *reinterpret_cast<const floatx4 *>(a.scales + co);
-                    bi[n][g4] = *reinterpret_cast<const floatx4 *>(a.bias + co);
-                }
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const int co = (ct0 + n) * 32 + g4 * 8 + kh * 4;
+            sc[n][g4] = bi[n][g4] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (co < a.Cout) { // Cout % 4 == 0
+                sc[n][g4] = *reinterpret_cast<const floatx4 *>(a.scales + co);
+                bi[n][g4] = *reinterpret_cast<const floatx4 *>(a.bias + co);
             }
-        // accumulator e of a lane is output channel 8 * (e / 4) + 4 * kh + e % 4 of its tile
-#pragma unroll
-        for (int m = 0; m < 2; ++m)
-#pragma unroll
-            for (int n = 0; n < NT; ++n)
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    const int row = m * 32 + p, chunk = n * 8 + g4 * 2 + kh;
-                    floatx4 v;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = __fmaf_rn(acc[m][n][g4 * 4 + e], sc[n][g4][e], bi[n][g4][e]);
-                    tile[row * U + (chunk ^ (row & (U - 1)))] = __builtin_bit_cast(uintx4, v);
-                }
-    }
+        }
     // The region's pixels are consecutive in memory (whole rows of one image, or whole images):
     // pixel P of the region is pixel first_px + P of the chunk.
     const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
@@ -401,22 +385,37 @@ __global__ __launch_bounds__(256, 2) void conv_codes_kernel(CodeConvArgs a)
     float *out0 = a.out + first_px * a.Cout;
     const float *res0 = a.res ? a.res + first_px * a.Cout : nullptr;
     constexpr int ROWS = 64 / U;            // pixels one instruction covers
+    constexpr int ITS = 32 / ROWS;          // instructions per half
     const int chunk = lane & (U - 1), sub = lane / U;
     const int co = ct0 * 32 + chunk * 4;    // Cout % 4 == 0
-    floatx4 rv[U];
 #pragma unroll
-    for (int it = 0; it < U; ++it) {
-        const int P = wpx * 64 + it * ROWS + sub;
-        rv[it] = floatx4{0.f, 0.f, 0.f, 0.f};
-        if (res0 && co < a.Cout && P < valid_px) rv[it] = global_load4(res0 + P * a.Cout + co);
-    }
+    for (int m = 0; m < 2; ++m) {
+        // accumulator e of a lane is output channel 8 * (e / 4) + 4 * kh + e % 4 of its tile
 #pragma unroll
-    for (int it = 0; it < U; ++it) {
-        const int row = it * ROWS + sub, P = wpx * 64 + row;
-        floatx4 v = __builtin_bit_cast(floatx4, tile[row * U + (chunk ^ (row & (U - 1)))]) + rv[it];
+        for (int n = 0; n < NT; ++n)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = __builtin_amdgcn_fmed3f(v[e], lo, hi);
-        if (co < a.Cout && P < valid_px) *reinterpret_cast<floatx4 *>(out0 + P * a.Cout + co) = v;
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int c = n * 8 + g4 * 2 + kh;
+                floatx4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = __fmaf_rn(acc[m][n][g4 * 4 + e], sc[n][g4][e], bi[n][g4][e]);
+                tile[p * U + (c ^ (p & (U - 1)))] = __builtin_bit_cast(uintx4, v);
+            }
+        floatx4 rv[ITS];
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            const int P = wpx * 64 + m * 32 + it * ROWS + sub;
+            rv[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (res0 && co < a.Cout && P < valid_px) rv[it] = global_load4(res0 + P * a.Cout + co);
+        }
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            const int row = it * ROWS + sub, P = wpx * 64 + m * 32 + row;
+            floatx4 v = __builtin_bit_cast(floatx4, tile[row * U + (chunk ^ (row & (U - 1)))]) + rv[it];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = __builtin_amdgcn_fmed3f(v[e], lo, hi);
+            if (co < a.Cout && P < valid_px) *reinterpret_cast<floatx4 *>(out0 + P * a.Cout + co) = v;
+        }
     }
 }
 

@@ -218,13 +218,13 @@ bool plan_code_conv(const Node &nd, CodePlan &p)
         // two workgroups per compute unit where the region allows it, as for the fp32 kernel
         bool fits;
         for (;;) {
-            p.PSU = p.CKC / 8 + 1;
+            p.PSU = p.CKC / 8;
             p.code_off = p.G * p.RIN * p.LW * 3 * p.PSU;
             const int chunks = p.nt * wco * T * (p.CKC / 16) * 64;
-            // the epilogue lays every wavefront's 64 pixels x 32 * nt channels out in LDS
-            p.lds_bytes = std::max((size_t)16 * (p.code_off + chunks), (size_t)4 * 64 * 32 * p.nt * sizeof(float));
+            // the epilogue lays every wavefront's pixels, 32 at a time, x 32 * nt channels out in LDS
+            p.lds_bytes = std::max((size_t)16 * (p.code_off + chunks), (size_t)4 * 32 * 32 * p.nt * sizeof(float));
             fits = p.G * p.RIN * p.LW * (p.CKC / 8) <= ki * 256 && chunks <= kCodeStageChunks * 256;
-            if ((fits && p.lds_bytes <= 80 * 1024) || p.CKC == 16) break;
+            if ((fits && p.lds_bytes <= 53 * 1024) || p.CKC == 16) break;
             p.CKC /= 2;
         }
         if (fits && p.lds_bytes <= 160 * 1024) return true;
