@@ -220,7 +220,7 @@ __device__ __forceinline__ void stage_store(const CodeConvArgs &a, const StageIt
 }
 
 template <int KS, int STRIDE, int NT, int KI>
-__global__ __launch_bounds__(256, 3) void conv_codes_kernel(CodeConvArgs a)
+__global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : 3) void conv_codes_kernel(CodeConvArgs a)
 {
     constexpr int kStageItems = KI;
     extern __shared__ float lds_raw[];
@@ -352,7 +352,7 @@ __global__ __launch_bounds__(256, 3) void conv_codes_kernel(CodeConvArgs a)
         }
     }
 
-    // ---- epilogue: scale, bias, residual, activation, through LDS.  A lane's accumulators are four
+    // ---- epilogue: through LDS, then scale, bias, residual, activation.  A lane's accumulators are four
     // consecutive output channels of one pixel at a time, and a store of those would put sixteen
     // 16-byte pieces of sixteen different lines into every quarter of a store instruction; the
     // memory system takes such pieces one request each.  So the wavefront lays its pixels (32 at a
@@ -364,18 +364,6 @@ __global__ __launch_bounds__(256, 3) void conv_codes_kernel(CodeConvArgs a)
     if (!active) return;
     constexpr int U = 8 * NT; // 16-byte chunks of one pixel's channels in this wavefront's tile
     uintx4 *tile = lds4 + wave * 32 * U; // 32 pixels at a time (one MFMA tile row), twice
-    floatx4 sc[NT][4], bi[NT][4];
-#pragma unroll
-    for (int n = 0; n < NT; ++n)
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-            const int co = (ct0 + n) * 32 + g4 * 8 + kh * 4;
-            sc[n][g4] = bi[n][g4] = floatx4{0.f, 0.f, 0.f, 0.f};
-            if (co < a.Cout) { // Cout % 4 == 0
-                sc[n][g4] = *reinterpret_cast<const floatx4 *>(a.scales + co);
-                bi[n][g4] = *reinterpret_cast<const floatx4 *>(a.bias + co);
-            }
-        }
     // The region's pixels are consecutive in memory (whole rows of one image, or whole images):
     // pixel P of the region is pixel first_px + P of the chunk.
     const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
@@ -387,7 +375,12 @@ __global__ __launch_bounds__(256, 3) void conv_codes_kernel(CodeConvArgs a)
     constexpr int ROWS = 64 / U;            // pixels one instruction covers
     constexpr int ITS = 32 / ROWS;          // instructions per half
     const int chunk = lane & (U - 1), sub = lane / U;
-    const int co = ct0 * 32 + chunk * 4;    // Cout % 4 == 0
+    const int co = ct0 * 32 + chunk * 4;    // Cout % 4 == 0; in the read-back a lane keeps one chunk: one scale, one bias
+    floatx4 sc = {0.f, 0.f, 0.f, 0.f}, bi = {0.f, 0.f, 0.f, 0.f};
+    if (co < a.Cout) {
+        sc = *reinterpret_cast<const floatx4 *>(a.scales + co);
+        bi = *reinterpret_cast<const floatx4 *>(a.bias + co);
+    }
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
         // accumulator e of a lane is output channel 8 * (e / 4) + 4 * kh + e % 4 of its tile
@@ -396,9 +389,7 @@ __global__ __launch_bounds__(256, 3) void conv_codes_kernel(CodeConvArgs a)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
                 const int c = n * 8 + g4 * 2 + kh;
-                floatx4 v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = __fmaf_rn(acc[m][n][g4 * 4 + e], sc[n][g4][e], bi[n][g4][e]);
+                const floatx4 v = {acc[m][n][g4 * 4], acc[m][n][g4 * 4 + 1], acc[m][n][g4 * 4 + 2], acc[m][n][g4 * 4 + 3]};
                 tile[p * U + (c ^ (p & (U - 1)))] = __builtin_bit_cast(uintx4, v);
             }
         floatx4 rv[ITS];
@@ -411,9 +402,9 @@ __global__ __launch_bounds__(256, 3) void conv_codes_kernel(CodeConvArgs a)
 #pragma unroll
         for (int it = 0; it < ITS; ++it) {
             const int row = it * ROWS + sub, P = wpx * 64 + m * 32 + row;
-            floatx4 v = __builtin_bit_cast(floatx4, tile[row * U + (chunk ^ (row & (U - 1)))]) + rv[it];
+            floatx4 v = __builtin_bit_cast(floatx4, tile[row * U + (chunk ^ (row & (U - 1)))]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = __builtin_amdgcn_fmed3f(v[e], lo, hi);
+            for (int e = 0; e < 4; ++e) v[e] = __builtin_amdgcn_fmed3f(__fmaf_rn(v[e], sc[e], bi[e]) + rv[it][e], lo, hi);
             if (co < a.Cout && P < valid_px) *reinterpret_cast<floatx4 *>(out0 + P * a.Cout + co) = v;
         }
     }

@@ -215,7 +215,8 @@ bool plan_code_conv(const Node &nd, CodePlan &p)
         p.CKC = cp >= 64 ? 64 : (cp >= 32 ? 32 : 16);
         p.RIN = (p.R - 1) * d.stride + d.kh;
         p.LW = d.win + 2 * d.pad;
-        // two workgroups per compute unit where the region allows it, as for the fp32 kernel
+        // three workgroups per compute unit where the region allows it (the kernel variant with the
+        // longer staging list needs more registers: two)
         bool fits;
         for (;;) {
             p.PSU = p.CKC / 8;
@@ -224,7 +225,7 @@ bool plan_code_conv(const Node &nd, CodePlan &p)
             // the epilogue lays every wavefront's pixels, 32 at a time, x 32 * nt channels out in LDS
             p.lds_bytes = std::max((size_t)16 * (p.code_off + chunks), (size_t)4 * 32 * 32 * p.nt * sizeof(float));
             fits = p.G * p.RIN * p.LW * (p.CKC / 8) <= ki * 256 && chunks <= kCodeStageChunks * 256;
-            if ((fits && p.lds_bytes <= 53 * 1024) || p.CKC == 16) break;
+            if ((fits && p.lds_bytes <= (size_t)(ki == kCodeStageItems ? 53 : 80) * 1024) || p.CKC == 16) break;
             p.CKC /= 2;
         }
         if (fits && p.lds_bytes <= 160 * 1024) return true;
