@@ -47,8 +47,8 @@ TRAFFIC = {
     },
     ("plainconvnet20_deploy_n2048", "conv_codes"): {  # average over the 19 launches of one deployed forward pass
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_deploy.hip",
-        "sha256": "9ccf90420a21e2a5384264bd3e5d363b5d73b025dd09225048426c8ad1968647",
-        "bytes_per_launch": 487721283,
+        "sha256": "69856e9db095f700e698b7ffb52171782a79f44dab0c174597fb6dfc9f8d4865",
+        "bytes_per_launch": 500305273,
     },
     ("quantize_stress_8192x4608_b8", "quantize"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",

@@ -276,9 +276,11 @@ __global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : 3) void conv_codes_
     const float *in0 = a.in + (size_t)img0 * a.Hin * a.Win * a.Cin;
     const int ncbf = a.CKC >> 4; // blocks of a full pass
 
-    // What the next pass needs - its activations and its codes - is requested before the current
-    // pass's MFMA loop and travels while it runs; the loop itself reads LDS only, so it never waits
-    // behind these reads.
+    // The next pass's activations are requested before the current pass's MFMA loop and travel
+    // while it runs; the loop itself reads LDS only, so it never waits behind these reads.  The
+    // pass's codes (L2-resident) are requested at its start and arrive while the activations are
+    // split: holding them a pass ahead as well would cost the registers that let three workgroups
+    // share a compute unit.
     floatx4 staged[kStageItems][2];
     stage_fetch(a, items, staged, in0, 0, c8shift, n_items, tid);
 
