@@ -94,9 +94,10 @@ hipError_t launch_pack_codes(const int32_t *codes, uint16_t *out, int cout, int 
 //
 // Workgroup = 4 wavefronts; per pass of CKC channels it stages in LDS the input rows of its
 // region, already split (per pixel three planes - hi, mid, lo - of CKC bf16 channels), and the
-// codes of its output-channel tiles for those channels.  A wavefront owns 64 pixels x 32*NT
-// output channels and issues, per tap and block of 16 channels, 2 * NT * 3 MFMAs from six + NT
-// 16-byte LDS reads.
+// codes of its output-channel tiles for those channels.  A wavefront owns 32*MT pixels x 32*NT
+// output channels (MT = 2; 1 for layers of at most 32 output channels: short workgroups whose
+// fixed latencies only more workgroups in flight can cover - four per compute unit) and issues, per tap and block of 16 channels,
+// MT * NT * 3 MFMAs from 3 * MT + NT 16-byte LDS reads.
 
 // Staging.  One item = eight channels of one staged pixel: two 16-byte global reads, three 16-byte
 // LDS writes (the hi, mid and lo planes).  Item tid + 256 * i belongs to thread tid; which pixel
@@ -219,8 +220,8 @@ __device__ __forceinline__ void stage_store(const CodeConvArgs &a, const StageIt
     }
 }
 
-template <int KS, int STRIDE, int NT, int KI>
-__global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : 3) void conv_codes_kernel(CodeConvArgs a)
+template <int KS, int STRIDE, int NT, int KI, int MT>
+__global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : (MT == 1 ? 4 : 3)) void conv_codes_kernel(CodeConvArgs a)
 {
     constexpr int kStageItems = KI;
     extern __shared__ float lds_raw[];
@@ -247,11 +248,11 @@ __global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : 3) void conv_codes_
     const int p = lane & 31, kh = lane >> 5; // pixel within the tile of 32; which eight of the 16 channels
 
     const int pix_units = 3 * a.PSU; // 16-byte units per staged pixel
-    int lds_base[2];
+    int lds_base[MT];
     const int rw = a.R * a.Wout;
 #pragma unroll
-    for (int m = 0; m < 2; ++m) {
-        const uint32_t P = (uint32_t)(wpx * 64 + m * 32 + p);
+    for (int m = 0; m < MT; ++m) {
+        const uint32_t P = (uint32_t)(wpx * (32 * MT) + m * 32 + p);
         const uint32_t g = fd_div(P, a.div_rw);
         const uint32_t rem = P - g * rw;
         const uint32_t oy = fd_div(rem, a.div_wout);
@@ -260,9 +261,9 @@ __global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : 3) void conv_codes_
         lds_base[m] = in_region ? ((g * a.RIN + oy * STRIDE) * a.LW + ox * STRIDE) * pix_units + kh : kh;
     }
 
-    floatx16 acc[2][NT];
+    floatx16 acc[MT][NT];
 #pragma unroll
-    for (int m = 0; m < 2; ++m)
+    for (int m = 0; m < MT; ++m)
 #pragma unroll
         for (int n = 0; n < NT; ++n)
 #pragma unroll
@@ -308,13 +309,13 @@ __global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : 3) void conv_codes_
             int woff = a.code_off + (wco * NT * T * ncbf) * 64 + lane, wc = 0;
             const int a_tap_step = pix_units - (ncb - 1) * 2, a_row_step = (a.LW - KS) * pix_units;
             int tapoff = 0, ac = 0, akx = 0; // activations: LDS offset of the step's tap and block
-            uintx4 xb[2][3], wcur[NT], wnext[NT];
+            uintx4 xb[MT][3], wcur[NT], wnext[NT];
 #pragma unroll
             for (int n = 0; n < NT; ++n) wcur[n] = lds4[woff + n * (T * ncbf * 64)];
 #pragma unroll
             for (int pc = 0; pc < 3; ++pc)
 #pragma unroll
-                for (int m = 0; m < 2; ++m) xb[m][pc] = lds4[lds_base[m] + pc * a.PSU];
+                for (int m = 0; m < MT; ++m) xb[m][pc] = lds4[lds_base[m] + pc * a.PSU];
 #pragma unroll 1
             for (int k = 0; k < steps; ++k) {
                 if (k + 1 < steps) { // uniform: scalar address updates only
@@ -340,13 +341,13 @@ __global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : 3) void conv_codes_
 #pragma unroll
                 for (int pc = 2; pc >= 0; --pc) { // smallest terms first
 #pragma unroll
-                    for (int m = 0; m < 2; ++m)
+                    for (int m = 0; m < MT; ++m)
 #pragma unroll
                         for (int n = 0; n < NT; ++n)
                             acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                                 __builtin_bit_cast(bf16x8, wcur[n]), __builtin_bit_cast(bf16x8, xb[m][pc]), acc[m][n], 0, 0, 0);
 #pragma unroll
-                    for (int m = 0; m < 2; ++m) xb[m][pc] = lds4[lds_base[m] + tapoff + pc * a.PSU];
+                    for (int m = 0; m < MT; ++m) xb[m][pc] = lds4[lds_base[m] + tapoff + pc * a.PSU];
                 }
 #pragma unroll
                 for (int n = 0; n < NT; ++n) wcur[n] = wnext[n];
@@ -384,7 +385,7 @@ __global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : 3) void conv_codes_
         bi = *reinterpret_cast<const floatx4 *>(a.bias + co);
     }
 #pragma unroll
-    for (int m = 0; m < 2; ++m) {
+    for (int m = 0; m < MT; ++m) {
         // accumulator e of a lane is output channel 8 * (e / 4) + 4 * kh + e % 4 of its tile
 #pragma unroll
         for (int n = 0; n < NT; ++n)
@@ -397,13 +398,13 @@ __global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : 3) void conv_codes_
         floatx4 rv[ITS];
 #pragma unroll
         for (int it = 0; it < ITS; ++it) {
-            const int P = wpx * 64 + m * 32 + it * ROWS + sub;
+            const int P = wpx * (32 * MT) + m * 32 + it * ROWS + sub;
             rv[it] = floatx4{0.f, 0.f, 0.f, 0.f};
             if (res0 && co < a.Cout && P < valid_px) rv[it] = global_load4(res0 + P * a.Cout + co);
         }
 #pragma unroll
         for (int it = 0; it < ITS; ++it) {
-            const int row = it * ROWS + sub, P = wpx * 64 + m * 32 + row;
+            const int row = it * ROWS + sub, P = wpx * (32 * MT) + m * 32 + row;
             floatx4 v = __builtin_bit_cast(floatx4, tile[row * U + (chunk ^ (row & (U - 1)))]);
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = __builtin_amdgcn_fmed3f(__fmaf_rn(v[e], sc[e], bi[e]) + rv[it][e], lo, hi);
@@ -413,31 +414,38 @@ __global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : 3) void conv_codes_
 }
 
 template <int KS, int STRIDE>
-static hipError_t launch_codes_nt(const CodeConvArgs &a, int nt, int ki, size_t lds_bytes, dim3 grid, hipStream_t st)
+static hipError_t launch_codes_nt(const CodeConvArgs &a, int nt, int ki, int mt, size_t lds_bytes, dim3 grid, hipStream_t st)
 {
     constexpr int K1 = kCodeStageItems, K2 = 2 * kCodeStageItems;
-    if (nt == 1 && ki == K1) hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, 1, K1>), grid, dim3(256), lds_bytes, st, a);
-    else if (nt == 2 && ki == K1) hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, 2, K1>), grid, dim3(256), lds_bytes, st, a);
-    else if (nt == 1 && ki == K2) hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, 1, K2>), grid, dim3(256), lds_bytes, st, a);
-    else if (nt == 2 && ki == K2) hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, 2, K2>), grid, dim3(256), lds_bytes, st, a);
-    else return hipErrorInvalidValue;
-    return hipGetLastError();
-}
-
-hipError_t launch_conv_codes(const CodeConvArgs &a, int ks, int stride, int nt, int stage_items, size_t lds_bytes, dim3 grid,
-                             hipStream_t st)
-{
-    if (ks == 3 && stride == 1) return launch_codes_nt<3, 1>(a, nt, stage_items, lds_bytes, grid, st);
-    if (ks == 3 && stride == 2) return launch_codes_nt<3, 2>(a, nt, stage_items, lds_bytes, grid, st);
-    if (ks == 1 && stride == 1) return launch_codes_nt<1, 1>(a, nt, stage_items, lds_bytes, grid, st);
-    if (ks == 1 && stride == 2) return launch_codes_nt<1, 2>(a, nt, stage_items, lds_bytes, grid, st);
+#define AIQ_LAUNCH(NT_, KI_, MT_)                                                                                     \
+    if (nt == NT_ && ki == KI_ && mt == MT_) {                                                                       \
+        hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, NT_, KI_, MT_>), grid, dim3(256), lds_bytes, st, a);       \
+        return hipGetLastError();                                                                                    \
+    }
+    AIQ_LAUNCH(1, K1, 2)
+    AIQ_LAUNCH(2, K1, 2)
+    AIQ_LAUNCH(1, K2, 2)
+    AIQ_LAUNCH(2, K2, 2)
+    AIQ_LAUNCH(1, K1, 1)
+    AIQ_LAUNCH(1, K2, 1)
+#undef AIQ_LAUNCH
     return hipErrorInvalidValue;
 }
 
-template <int KS, int STRIDE, int NT, int KI>
+hipError_t launch_conv_codes(const CodeConvArgs &a, int ks, int stride, int nt, int stage_items, int mt, size_t lds_bytes,
+                             dim3 grid, hipStream_t st)
+{
+    if (ks == 3 && stride == 1) return launch_codes_nt<3, 1>(a, nt, stage_items, mt, lds_bytes, grid, st);
+    if (ks == 3 && stride == 2) return launch_codes_nt<3, 2>(a, nt, stage_items, mt, lds_bytes, grid, st);
+    if (ks == 1 && stride == 1) return launch_codes_nt<1, 1>(a, nt, stage_items, mt, lds_bytes, grid, st);
+    if (ks == 1 && stride == 2) return launch_codes_nt<1, 2>(a, nt, stage_items, mt, lds_bytes, grid, st);
+    return hipErrorInvalidValue;
+}
+
+template <int KS, int STRIDE, int NT, int KI, int MT>
 static hipError_t codes_lds_t()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_codes_kernel<KS, STRIDE, NT, KI>),
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_codes_kernel<KS, STRIDE, NT, KI, MT>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
 }
 
@@ -445,11 +453,13 @@ static hipError_t codes_lds_t()
 hipError_t conv_codes_set_lds_limits()
 {
     hipError_t e = hipSuccess;
-#define AIQ_SET(KS, ST)                                                              \
-    if (e == hipSuccess) e = codes_lds_t<KS, ST, 1, kCodeStageItems>();              \
-    if (e == hipSuccess) e = codes_lds_t<KS, ST, 2, kCodeStageItems>();              \
-    if (e == hipSuccess) e = codes_lds_t<KS, ST, 1, 2 * kCodeStageItems>();          \
-    if (e == hipSuccess) e = codes_lds_t<KS, ST, 2, 2 * kCodeStageItems>();
+#define AIQ_SET(KS, ST)                                                                 \
+    if (e == hipSuccess) e = codes_lds_t<KS, ST, 1, kCodeStageItems, 2>();              \
+    if (e == hipSuccess) e = codes_lds_t<KS, ST, 2, kCodeStageItems, 2>();              \
+    if (e == hipSuccess) e = codes_lds_t<KS, ST, 1, 2 * kCodeStageItems, 2>();          \
+    if (e == hipSuccess) e = codes_lds_t<KS, ST, 2, 2 * kCodeStageItems, 2>();          \
+    if (e == hipSuccess) e = codes_lds_t<KS, ST, 1, kCodeStageItems, 1>();              \
+    if (e == hipSuccess) e = codes_lds_t<KS, ST, 1, 2 * kCodeStageItems, 1>();
     AIQ_SET(3, 1)
     AIQ_SET(3, 2)
     AIQ_SET(1, 1)

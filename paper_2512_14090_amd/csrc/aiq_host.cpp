@@ -167,7 +167,7 @@ aiq_status plan_conv(Node &nd)
 // the codes of the workgroup's tiles for those channels; a thread stages at most kCodeStageItems
 // activation items and kCodeStageChunks code chunks per pass.  False if no tiling fits.
 struct CodePlan {
-    int nt, wave_px_split, R, G, regions_per_image, CB, CKC, RIN, LW, PSU, cout_tiles, grid_y, code_off, stage_items;
+    int nt, mt, wave_px_split, R, G, regions_per_image, CB, CKC, RIN, LW, PSU, cout_tiles, grid_y, code_off, stage_items;
     size_t lds_bytes;
 };
 
@@ -177,58 +177,66 @@ bool plan_code_conv(const Node &nd, CodePlan &p)
     const int T = d.kh * d.kw;
     // Preferred split of the four wavefronts as for the fp32 kernel (most output channels per
     // workgroup at no more than 1/8 of the MFMAs wasted); if the region that goes with it does
-    // not fit, more wavefronts go along the output channels and the region shrinks.
-    for (int wco_min = 1; wco_min <= 4; wco_min *= 2)
-    for (int ki = kCodeStageItems; ki <= 2 * kCodeStageItems; ki += kCodeStageItems) {
-        p = CodePlan{};
-        p.stage_items = ki;
-        p.cout_tiles = (d.cout + 31) / 32;
-        p.CB = (d.cin + 15) / 16;
-        int wco = 0, best_cover = 0;
+    // not fit, more wavefronts go along the output channels and the region shrinks.  A wavefront
+    // with a single output tile takes one pixel tile instead of two where four such workgroups fit a
+    // compute unit.
+    for (int wco_min = 1; wco_min <= 4; wco_min *= 2) {
+        const int cout_tiles = (d.cout + 31) / 32;
+        int nt_sel = 1, wco = 0, best_cover = 0;
         for (int nt = 1; nt <= 2; ++nt)
             for (int w = wco_min; w <= 4; w *= 2) {
                 const int per_wg = nt * w;
                 const bool smallest = nt == 1 && w == wco_min;
-                const int waste = (p.cout_tiles + per_wg - 1) / per_wg * per_wg - p.cout_tiles;
-                if (!smallest && (waste * 8 > p.cout_tiles || per_wg * T * 64 > kCodeStageChunks * 256)) continue;
-                if (per_wg > best_cover || (per_wg == best_cover && nt > p.nt)) {
+                const int waste = (cout_tiles + per_wg - 1) / per_wg * per_wg - cout_tiles;
+                if (!smallest && (waste * 8 > cout_tiles || per_wg * T * 64 > kCodeStageChunks * 256)) continue;
+                if (per_wg > best_cover || (per_wg == best_cover && nt > nt_sel)) {
                     best_cover = per_wg;
-                    p.nt = nt;
+                    nt_sel = nt;
                     wco = w;
                 }
             }
-        p.wave_px_split = 4 / wco;
-        p.grid_y = (p.cout_tiles + p.nt * wco - 1) / (p.nt * wco);
-        const int region_px = 64 * p.wave_px_split;
-        const int px_img = nd.hout * nd.wout;
-        if (px_img >= region_px) {
-            p.G = 1;
-            p.R = std::min(region_px / nd.wout, nd.hout);
-            if (p.R < 1) continue;
-            p.regions_per_image = (nd.hout + p.R - 1) / p.R;
-        } else {
-            p.G = region_px / px_img;
-            p.R = nd.hout;
-            p.regions_per_image = 1;
+        for (int mt = nt_sel == 1 ? 1 : 2; mt <= 2; ++mt)
+        for (int ki = kCodeStageItems; ki <= 2 * kCodeStageItems; ki += kCodeStageItems) {
+            p = CodePlan{};
+            p.stage_items = ki;
+            p.mt = mt;
+            p.nt = nt_sel;
+            p.cout_tiles = cout_tiles;
+            p.CB = (d.cin + 15) / 16;
+            p.wave_px_split = 4 / wco;
+            p.grid_y = (p.cout_tiles + p.nt * wco - 1) / (p.nt * wco);
+            const int region_px = 32 * mt * p.wave_px_split;
+            const int px_img = nd.hout * nd.wout;
+            if (px_img >= region_px) {
+                p.G = 1;
+                p.R = std::min(region_px / nd.wout, nd.hout);
+                if (p.R < 1) continue;
+                p.regions_per_image = (nd.hout + p.R - 1) / p.R;
+            } else {
+                p.G = region_px / px_img;
+                p.R = nd.hout;
+                p.regions_per_image = 1;
+            }
+            const int cp = p.CB * 16;
+            p.CKC = cp >= 64 ? 64 : (cp >= 32 ? 32 : 16);
+            p.RIN = (p.R - 1) * d.stride + d.kh;
+            p.LW = d.win + 2 * d.pad;
+            // three workgroups per compute unit where the region allows it (the kernel variants with
+            // the longer staging list or four pixel tiles need more registers: two)
+            const size_t lds_limit = (size_t)(ki != kCodeStageItems ? 80 : (mt == 1 ? 40 : 53)) * 1024;
+            bool fits;
+            for (;;) {
+                p.PSU = p.CKC / 8;
+                p.code_off = p.G * p.RIN * p.LW * 3 * p.PSU;
+                const int chunks = p.nt * wco * T * (p.CKC / 16) * 64;
+                // the epilogue lays every wavefront's pixels, 32 at a time, x 32 * nt channels out in LDS
+                p.lds_bytes = std::max((size_t)16 * (p.code_off + chunks), (size_t)4 * 32 * 32 * p.nt * sizeof(float));
+                fits = p.G * p.RIN * p.LW * (p.CKC / 8) <= ki * 256 && chunks <= kCodeStageChunks * 256;
+                if ((fits && p.lds_bytes <= lds_limit) || p.CKC == 16) break;
+                p.CKC /= 2;
+            }
+            if (fits && p.lds_bytes <= (mt == 1 ? lds_limit : (size_t)160 * 1024)) return true;
         }
-        const int cp = p.CB * 16;
-        p.CKC = cp >= 64 ? 64 : (cp >= 32 ? 32 : 16);
-        p.RIN = (p.R - 1) * d.stride + d.kh;
-        p.LW = d.win + 2 * d.pad;
-        // three workgroups per compute unit where the region allows it (the kernel variant with the
-        // longer staging list needs more registers: two)
-        bool fits;
-        for (;;) {
-            p.PSU = p.CKC / 8;
-            p.code_off = p.G * p.RIN * p.LW * 3 * p.PSU;
-            const int chunks = p.nt * wco * T * (p.CKC / 16) * 64;
-            // the epilogue lays every wavefront's pixels, 32 at a time, x 32 * nt channels out in LDS
-            p.lds_bytes = std::max((size_t)16 * (p.code_off + chunks), (size_t)4 * 32 * 32 * p.nt * sizeof(float));
-            fits = p.G * p.RIN * p.LW * (p.CKC / 8) <= ki * 256 && chunks <= kCodeStageChunks * 256;
-            if ((fits && p.lds_bytes <= (size_t)(ki == kCodeStageItems ? 53 : 80) * 1024) || p.CKC == 16) break;
-            p.CKC /= 2;
-        }
-        if (fits && p.lds_bytes <= 160 * 1024) return true;
     }
     return false;
 }
@@ -1675,7 +1683,7 @@ aiq_status aiq_deploy_forward(aiq_deployed *d, const float *images, int32_t N, i
             a.div_per_row = make_fastdiv(p.LW * (p.CKC / 8));
             const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
             ProfScope ps(m, st, AIQ_K_CONV_CODES, nd.flops_per_image * n, nd.act_bytes_per_image * n);
-            AIQ_HIP(launch_conv_codes(a, ld.kh, ld.stride, p.nt, p.stage_items, p.lds_bytes, dim3(gx, p.grid_y, 1), st));
+            AIQ_HIP(launch_conv_codes(a, ld.kh, ld.stride, p.nt, p.stage_items, p.mt, p.lds_bytes, dim3(gx, p.grid_y, 1), st));
         }
     }
     return AIQ_OK;

@@ -313,7 +313,7 @@ struct CodeConvArgs {
 
 // codes: int32 [cout][cin][taps]; out: cleared buffer in the layout above
 hipError_t launch_pack_codes(const int32_t *codes, uint16_t *out, int cout, int cin, int taps, hipStream_t st);
-hipError_t launch_conv_codes(const CodeConvArgs &a, int ks, int stride, int nt, int stage_items, size_t lds_bytes,
+hipError_t launch_conv_codes(const CodeConvArgs &a, int ks, int stride, int nt, int stage_items, int mt, size_t lds_bytes,
                              dim3 grid, hipStream_t st);
 hipError_t conv_codes_set_lds_limits();
 
