@@ -47,8 +47,8 @@ TRAFFIC = {
     },
     ("plainconvnet20_deploy_n2048", "conv_codes"): {  # average over the 19 launches of one deployed forward pass
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_deploy.hip",
-        "sha256": "69856e9db095f700e698b7ffb52171782a79f44dab0c174597fb6dfc9f8d4865",
-        "bytes_per_launch": 500305273,
+        "sha256": "d300d3db0c2df217244dcabcd424076616bcaeaf412946c01c4578ba0d456635",
+        "bytes_per_launch": 496839411,
     },
     ("quantize_stress_8192x4608_b8", "quantize"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
