@@ -12,8 +12,22 @@ tensors).
 One numpy ``Generator(PCG64(seed))`` with ``seed = 14090 + workload index`` is
 consumed in a fixed order: per node (weights, then BN statistics or classifier
 bias), then images, then schemes.
+
+Workloads 7-10 repeat 2, 3, 5 and 6 (own seeds) with a *centred classifier*:
+with random weights the pooled feature vector is dominated by a component
+common to all images, so the plain recipe makes the FP32 model predict one
+class for every image and no scheme ever changes a prediction.  For these
+workloads the classifier bias is a stored constant (``centred_bias.json``)
+equal to minus the classifier's response to the mean pooled feature of the
+workload's first 64 images, so that the FP32 predictions spread over the
+classes and low-bit layers flip a visible fraction of them.  The constants are
+written by ``oracle/write_centred_bias.py`` (CPU oracle only); this module just
+reads them.
 """
 from __future__ import annotations
+
+import json
+import os
 
 import numpy as np
 
@@ -62,11 +76,23 @@ def make_images(n, rng, hin=32):
     return rng.standard_normal((n, hin, hin, 3)).astype(np.float32)
 
 
+CENTRED_OF = {7: 2, 8: 3, 9: 5, 10: 6}  # workload -> the workload whose structure it repeats
+CENTRE_IMAGES = 64                       # images the stored classifier bias was formed on
+_BIAS_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "centred_bias.json")
+
+
+def centred_bias(index):
+    """Stored classifier bias (fp32 [classes]) of a centred workload; KeyError if it was never written."""
+    with open(_BIAS_FILE) as f:
+        table = json.load(f)
+    return np.array([float.fromhex(v) for v in table[str(index)]], dtype=np.float32)
+
+
 def _choice_schemes(rng, s, L, alphabet):
     return rng.choice(np.array(alphabet, dtype=np.uint8), size=(s, L)).astype(np.uint8)
 
 
-def make_workload(index, n_images=None, n_schemes=None):
+def make_workload(index, n_images=None, n_schemes=None, centred=True):
     """The benchmark workloads, numbered as the five configurations.
 
     0: ResNet-8, 256 images, 1 scheme from {32,8,4}
@@ -78,10 +104,14 @@ def make_workload(index, n_images=None, n_schemes=None):
     6: HeavyEarlyResNet20 sensitivity sweep, 256 images, 40 single-layer schemes
   (5 and 6 are the paper's two variant models with the candidate batch of its per-layer
   sensitivity table; they are not among the five benchmark configurations.)
+    7, 8, 9, 10: workloads 2, 3, 5, 6 again with their own seeds and a centred classifier (module
+  docstring); ``centred=False`` leaves the drawn classifier bias in place (used by the script that
+  writes the stored constants).
     ``n_images`` / ``n_schemes`` shrink a workload for tests; the draw order is
     unchanged so weights do not depend on them.
     """
     rng = np.random.Generator(np.random.PCG64(14090 + index))
+    seed_index, index = index, CENTRED_OF.get(index, index)
     if index == 0:
         nodes, n, name = G.resnet_cifar(1), 256, "resnet8_n256_s1"
     elif index in (1, 2, 4):
@@ -96,7 +126,7 @@ def make_workload(index, n_images=None, n_schemes=None):
     elif index == 6:
         nodes, n, name = G.heavy_early_resnet20(), 256, "heavyearlyresnet20_sensitivity_n256_s40"
     else:
-        raise ValueError("workload index must be 0..6")
+        raise ValueError("workload index must be 0..10")
     L = G.n_scheme_layers(nodes)
     weights, biases = make_model(nodes, rng)
     n = n if n_images is None else n_images
@@ -118,6 +148,11 @@ def make_workload(index, n_images=None, n_schemes=None):
         schemes = _choice_schemes(rng, 64, L, BITS_ALPHABET)
     if n_schemes is not None:
         schemes = schemes[:n_schemes]
+    if seed_index != index:
+        name += "_centred"
+        if centred:
+            biases[-1] = centred_bias(seed_index)
+    index = seed_index
     return dict(name=name, index=index, nodes=nodes, desc=G.desc_array(nodes), L=L,
                 weights=weights, biases=biases, images=images,
                 schemes=np.ascontiguousarray(schemes), chunk=1024)

@@ -54,22 +54,62 @@ def test_search_matches_oracle_on_resnet8(env, method, kwargs, layerwise):
     m.close()
 
 
+_REF_SEARCH = {}
+
+
+@pytest.mark.parametrize("layerwise", [False, True])
+@pytest.mark.parametrize("method", ["greedy", "cd"])
+def test_search_on_resnet20_with_accuracy_loss_on_the_path(env, method, layerwise):
+    """ResNet-20 with the centred classifier (workload 7, 64 images): single-layer moves cost accuracy, so the
+    loss trades AI against AccLoss > 0 and the searches have real decisions to take.  Three greedy iterations
+    and one coordinate-descent sweep, move for move against the oracle's loops on the oracle's forward pass,
+    with and without the shared forward prefix, LDS-resident and layer by layer."""
+    torch, aiq, search = env["torch"], env["aiq"], env["search"]
+    wl = env["synth"].make_workload(7, n_images=64)
+    bits, lam, n = (32, 8, 4), 0.9, 64
+    print(f"resnet20 centred search {method} layerwise={layerwise}", flush=True)
+    if method not in _REF_SEARCH:
+        ai_fn, accloss_many = search.model_callbacks(wl["desc"], wl["weights"], wl["biases"], wl["images"])
+        if method == "greedy":
+            _REF_SEARCH[method] = search.greedy(wl["L"], bits, lam, ai_fn, accloss_many, max_iters=3)
+        else:
+            _REF_SEARCH[method] = search.coordinate_descent(wl["L"], bits, lam, ai_fn, accloss_many, max_passes=1)
+    q_ref, t_ref = _REF_SEARCH[method]
+    # the path is not the degenerate one: moves were accepted, and accepted moves cost agreement
+    assert len(t_ref) >= 3
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=layerwise)
+    img = torch.from_numpy(wl["images"]).cuda()
+    for share in (False, True):
+        q, trace = m.search(wl["desc"], img, method=method, bits=bits, lam=lam, chunk=64,
+                            max_iters=3 if method == "greedy" else 1, share_prefix=share)
+        np.testing.assert_array_equal(q, q_ref)
+        _compare(trace, t_ref)
+        assert trace[0]["agree"] == n
+        assert min(t["agree"] for t in trace[1:]) < n, [t["agree"] for t in trace]
+    m.close()
+
+
 @pytest.mark.parametrize("builder", ["plain", "heavy", "resnet8"])
 def test_layer_sensitivity_table(env, builder):
     """Single-layer 8-bit / 4-bit agreement counts (the sensitivity columns of the paper's Table 1) for the
-    two variant models and ResNet-8, against the oracle scoring the same single-layer schemes."""
+    two variant models (workloads 9 and 10: centred classifier, so the counts are not all N) and ResNet-8,
+    against the oracle scoring the same single-layer schemes."""
     torch, aiq, oracle, synth = env["torch"], env["aiq"], env["oracle"], env["synth"]
     import sys, os
     sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
     from parity import near_tied
-    nodes = {"plain": synth.plain_convnet20, "heavy": synth.heavy_early_resnet20,
-             "resnet8": lambda: synth.resnet_cifar(1)}[builder]()
-    rng = np.random.Generator(np.random.PCG64(41))
-    w, b = synth.make_model(nodes, rng)
-    n = 12 if builder != "resnet8" else 40
-    images = synth.make_images(n, rng)
-    desc = synth.desc_array(nodes)
-    L = synth.n_scheme_layers(nodes)
+    if builder == "resnet8":
+        nodes = synth.resnet_cifar(1)
+        rng = np.random.Generator(np.random.PCG64(41))
+        w, b = synth.make_model(nodes, rng)
+        n = 40
+        images = synth.make_images(n, rng)
+        desc = synth.desc_array(nodes)
+        L = synth.n_scheme_layers(nodes)
+    else:
+        n = 12 if builder == "plain" else 16
+        wl = synth.make_workload(9 if builder == "plain" else 10, n_images=n)
+        w, b, images, desc, L = wl["weights"], wl["biases"], wl["images"], wl["desc"], wl["L"]
     bits = (8, 4)
     print(f"sensitivity {builder}: L={L} N={n}", flush=True)
     m = aiq.Model(desc, w, b)
@@ -84,6 +124,8 @@ def test_layer_sensitivity_table(env, builder):
     assert got.shape == (L, len(bits))
     assert (np.abs(got.reshape(-1).astype(np.int64) - ref["agree"]) <= slack).all(), (got.reshape(-1), ref["agree"])
     assert (got <= n).all() and (got >= 0).all()
+    if builder != "resnet8":
+        assert (got < n).sum() >= L // 2, got  # sensitivities that are not identically zero
 
 
 def test_search_argument_errors(env):
