@@ -20,6 +20,9 @@
  *    Device work is enqueued on it and not synchronised.
  *  - Arguments are validated before any device work; on a non-OK status found
  *    by validation no output buffer has been touched.
+ *  - Small HOST arrays an entry point takes (schemes, a reference scheme) are read in full
+ *    before it returns - they reach the device as kernel arguments - so the caller may reuse
+ *    them at once, whatever kind of host memory they live in.
  *  - One aiq_model must not be used from two threads at once.
  *  - There is no CPU fallback: without a usable GPU every device entry point
  *    returns AIQ_DEVICE_ERROR.
@@ -159,7 +162,9 @@ aiq_status aiq_eval_workspace_bytes(const aiq_model *m, int32_t S, int32_t chunk
  * agree:     device int32 [S], overwritten.
  * workspace: device, >= aiq_eval_workspace_bytes(m, S, chunk), 256-byte aligned.
  * S = 0 or N = 0 is valid (agree is zero-filled).  Asynchronous on hip_stream.
- * Errors: INVALID_ARG, UNSUPPORTED_BITS, WORKSPACE_TOO_SMALL, DEVICE_ERROR.
+ * S + 1 may not exceed 65535 (INVALID_ARG): the schemes, plus the all-FP32 pass, form one grid axis.
+ * Errors: INVALID_ARG (also a workspace that is not 256-byte aligned), UNSUPPORTED_BITS,
+ * WORKSPACE_TOO_SMALL, DEVICE_ERROR.
  */
 aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const uint8_t *schemes, int32_t S,
                             int32_t chunk, int32_t *top1_base, int32_t base_valid, float *logits,
@@ -179,7 +184,8 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
  * through per-layer checkpoints of one workgroup's LDS; the layer-by-layer kernels keep the
  * reference pass's activations per layer and launch each layer only for the schemes that
  * have left the reference by then.  Models for which aiq_model_shares_prefix is 0 (none at
- * present) run every scheme whole.  workspace >= aiq_eval_shared_workspace_bytes(m, S, chunk); other
+ * present) run every scheme whole.  Asynchronous on hip_stream like aiq_eval_schemes: the call
+ * enqueues its work and does not wait for the stream.  workspace >= aiq_eval_shared_workspace_bytes(m, S, chunk); other
  * arguments, ownership and errors as for aiq_eval_schemes (ref_scheme NULL: INVALID_ARG).
  */
 int32_t aiq_model_shares_prefix(const aiq_model *m); /* 1, 0, or -1 for a NULL model */

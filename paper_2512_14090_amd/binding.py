@@ -46,14 +46,28 @@ def library_path():
     return _LIB_PATH
 
 
+def library_is_stale():
+    """True if a source or header is newer than the built library (or nothing is built)."""
+    from . import build as _build
+    return _build.stale()
+
+
 def load_library():
-    """Loads the built library; builds it first only if nothing is built."""
+    """Loads the built library; builds it first only if nothing is built.  A library older than its
+    sources is loaded as it is, with a warning (building is a step of its own: __graft_entry__.build());
+    AIQ_REQUIRE_FRESH=1 in the environment turns the warning into an error."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(_LIB_PATH):
         from . import build as _build
         _build.build(force=True)
+    elif library_is_stale():
+        msg = f"{_LIB_PATH} is older than its sources: rebuild with paper_2512_14090_amd.build.build()"
+        if os.environ.get("AIQ_REQUIRE_FRESH") == "1":
+            raise RuntimeError(msg)
+        import warnings
+        warnings.warn(msg, RuntimeWarning, stacklevel=2)
     lib = C.CDLL(_LIB_PATH)
     lib.aiq_status_str.restype = C.c_char_p
     lib.aiq_status_str.argtypes = [C.c_int32]
@@ -189,6 +203,7 @@ class Model:
         self.L = int(self._lib.aiq_model_scheme_layers(h))
         self.classes = int(self._lib.aiq_model_classes(h))
         self._workspace = None
+        self._ws_streams = []
 
     def close(self):
         if self._h:
@@ -211,11 +226,21 @@ class Model:
                    "aiq_eval_workspace_bytes")
         return out.value
 
-    def _get_workspace(self, nbytes, device):
+    def _get_workspace(self, nbytes, device, stream=None):
+        """The model's workspace tensor, regrown when too small.  Work enqueued earlier, possibly on another
+        stream than the allocator knows of, may still be using the old one: every stream that has used it is
+        drained before it is released."""
         import torch
         if self._workspace is None or self._workspace.numel() < nbytes or self._workspace.device != device:
+            if self._workspace is not None:
+                for st in self._ws_streams:
+                    st.synchronize()
+            self._ws_streams = []
             self._workspace = None
             self._workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        st = stream if hasattr(stream, "synchronize") else torch.cuda.current_stream(device)
+        if all(st != u for u in self._ws_streams):
+            self._ws_streams.append(st)
         return self._workspace
 
     def eval_schemes(self, images, schemes, chunk=1024, top1_base=None, want_logits=False, want_top1=False,
@@ -255,7 +280,7 @@ class Model:
                 top1 = torch.empty((S, N), dtype=torch.int32, device=dev)
         chunk = max(1, min(int(chunk), max(N, 1)))
         nbytes = self.workspace_bytes(S, chunk, shared=ref_scheme is not None)
-        ws = self._get_workspace(nbytes, dev)
+        ws = self._get_workspace(nbytes, dev, stream)
         lg = None if logits is None else logits.data_ptr()
         t1 = None if top1 is None else top1.data_ptr()
         if ref_scheme is None:
@@ -289,7 +314,7 @@ class Model:
         need = C.c_size_t(0)
         _check(self._lib.aiq_search_workspace_bytes(self._h, N, chunk, len(bits), C.byref(need)),
                "aiq_search_workspace_bytes")
-        ws = self._get_workspace(need.value, images.device)
+        ws = self._get_workspace(need.value, images.device, stream)
         scheme = np.zeros(self.L, dtype=np.uint8)
         cap = 4096
         trace = (_SearchStep * cap)()
@@ -310,7 +335,7 @@ class Model:
         need = C.c_size_t(0)
         _check(self._lib.aiq_sensitivity_workspace_bytes(self._h, N, chunk, len(b), C.byref(need)),
                "aiq_sensitivity_workspace_bytes")
-        ws = self._get_workspace(need.value, images.device)
+        ws = self._get_workspace(need.value, images.device, stream)
         out = np.zeros((self.L, len(b)), dtype=np.int32)
         _check(self._lib.aiq_layer_sensitivity(self._h, images.data_ptr(), N, chunk, b.ctypes.data, len(b),
                                                ws.data_ptr(), ws.numel(), _stream_ptr(stream), out.ctypes.data),
@@ -378,6 +403,8 @@ class Deployed:
         chunk = max(1, min(int(chunk), max(N, 1)))
         nbytes = self.workspace_bytes(chunk)
         if self._workspace is None or self._workspace.numel() < nbytes or self._workspace.device != dev:
+            if self._workspace is not None:
+                torch.cuda.synchronize(dev)  # earlier forwards, on whatever stream, may still use the old one
             self._workspace = None
             self._workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
         ws = self._workspace

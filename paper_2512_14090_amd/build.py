@@ -38,12 +38,21 @@ def build(force=True, verbose=False):
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    # stand-alone copy kernel used to calibrate the HBM traffic counters
-    probe = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", os.path.join(CSRC, "copy_probe.hip"), "-o",
-             os.path.join(HERE, "copy_probe")]
-    subprocess.run(probe, check=True)
     return LIB
 
 
+def build_copy_probe():
+    """Optional, not part of build(): the stand-alone copy kernel of known size against which the HBM traffic
+    counters (FETCH_SIZE, WRITE_SIZE) are calibrated.  Returns the path of the executable."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = os.path.join(HERE, "copy_probe")
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-value",
+                    os.path.join(CSRC, "copy_probe.hip"), "-o", out], check=True)
+    return out
+
+
 if __name__ == "__main__":
-    print(build(force=True, verbose="-v" in sys.argv))
+    if "--copy-probe" in sys.argv:
+        print(build_copy_probe())
+    else:
+        print(build(force=True, verbose="-v" in sys.argv))

@@ -1,7 +1,8 @@
 // Host side of libaiq.so: argument validation, the analytic arithmetic-intensity
 // model, the per-call plan (which (layer, bit-width) bank slots to fill, which
 // kernel configuration each layer gets) and the launch sequence.  Every step of the
-// scored path itself runs in the kernels of aiq_kernels.hip.
+// scored path itself runs in the kernels of the .hip files; this file holds no device code
+// and compiles as plain C++ against the HIP runtime API.
 #include "../../include/aiq.h"
 #include "aiq_internal.h"
 
@@ -1083,6 +1084,7 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
     if (S > 0 && (!schemes || !agree)) return AIQ_INVALID_ARG;
     if (N > 0 && (!images || !top1_base || !workspace)) return AIQ_INVALID_ARG;
     if (base_valid != 0 && base_valid != 1) return AIQ_INVALID_ARG;
+    if (S + 1 > 65535) return AIQ_INVALID_ARG; // the scheme axis (plus the FP32 pass) is a grid y / z extent
     for (size_t i = 0; i < (size_t)S * m->L; ++i)
         if (!bits_supported(schemes[i])) return AIQ_UNSUPPORTED_BITS;
     if (ref)
@@ -1121,8 +1123,7 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
             }
         }
     }
-    if (S > 0)
-        AIQ_HIP(hipMemcpyAsync(schemes_dev, schemes, (size_t)S * m->L, hipMemcpyHostToDevice, st));
+    if (S > 0) AIQ_HIP(upload_bytes(schemes_dev, schemes, (size_t)S * m->L, st));
 
     // prefix sharing: op at which every scheme leaves the reference scheme, and what the
     // passes that start there execute
@@ -1157,10 +1158,8 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
             first_op[s_] = d < m->L ? m->slot_op[d] : n_ops - 1; // identical to ref: only the last op runs again
             resumed_flops_per_image += suffix[first_op[s_]];
         }
-        // first_op lives on the host stack of this call: the copy below must not outlive it
-        AIQ_HIP(hipMemcpyAsync(ref_dev, ref, (size_t)m->L, hipMemcpyHostToDevice, st));
-        AIQ_HIP(hipMemcpyAsync(first_op_dev, first_op.data(), sizeof(int32_t) * (S + 1), hipMemcpyHostToDevice, st));
-        AIQ_HIP(hipStreamSynchronize(st));
+        AIQ_HIP(upload_bytes(ref_dev, ref, (size_t)m->L, st));
+        AIQ_HIP(upload_bytes(first_op_dev, first_op.data(), sizeof(int32_t) * (S + 1), st));
     }
     // The same on the layer-by-layer path: the rows (schemes, plus the FP32 pass when it has to
     // run and is not the reference itself) are sorted by the node at which they leave the
@@ -1211,10 +1210,9 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
             ++active[rows[i].first];
         }
         for (int l = 1; l < n_nodes; ++l) active[l] += active[l - 1];
-        AIQ_HIP(hipMemcpyAsync(ref_dev, ref, (size_t)m->L, hipMemcpyHostToDevice, st));
-        AIQ_HIP(hipMemcpyAsync(sorted_dev, sorted.data(), sorted.size(), hipMemcpyHostToDevice, st));
-        AIQ_HIP(hipMemcpyAsync(row_map_dev, row_map.data(), sizeof(int32_t) * row_map.size(), hipMemcpyHostToDevice, st));
-        AIQ_HIP(hipStreamSynchronize(st)); // the host vectors above end with this call
+        AIQ_HIP(upload_bytes(ref_dev, ref, (size_t)m->L, st));
+        AIQ_HIP(upload_bytes(sorted_dev, sorted.data(), sorted.size(), st));
+        AIQ_HIP(upload_bytes(row_map_dev, row_map.data(), sizeof(int32_t) * row_map.size(), st));
     }
     if (any) {
         double qbytes = 0.0;

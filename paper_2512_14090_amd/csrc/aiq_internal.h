@@ -68,7 +68,9 @@ inline FastDiv make_fastdiv(uint32_t d)
     f.magic = d <= 1 ? 0u : (uint32_t)((0x100000000ull / d) + 1ull);
     return f;
 }
+#ifdef __HIPCC__
 __device__ inline uint32_t fd_div(uint32_t n, FastDiv f) { return f.d <= 1 ? n : __umulhi(n, f.magic); }
+#endif
 
 // Arguments of the dense (3x3 / 1x1) MFMA convolution.
 struct ConvArgs {
@@ -168,6 +170,10 @@ hipError_t launch_depthwise(const DepthwiseArgs &a, int s_total, hipStream_t st)
 hipError_t launch_head(const HeadArgs &a, int s_total, hipStream_t st);
 hipError_t launch_agree(const AgreeArgs &a, hipStream_t st);
 hipError_t launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t st);
+// Small host tables (schemes, row maps) to device memory as kernel arguments, 2 KB per launch: the bytes are
+// taken when the launch is enqueued, so the host buffer is free again when the call returns, nothing waits
+// for the stream, and the step can be captured in a HIP graph.
+hipError_t upload_bytes(void *dst_dev, const void *src_host, size_t nbytes, hipStream_t st);
 hipError_t conv_set_lds_limits();
 
 } // namespace aiq

@@ -10,6 +10,7 @@
 #include "aiq_internal.h"
 
 #include <algorithm>
+#include <cstring>
 
 namespace aiq {
 
@@ -1061,6 +1062,35 @@ hipError_t launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t st)
     if (n == 0) return hipSuccess;
     hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
     return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ host tables as kernel arguments
+
+constexpr int kUploadWords = 512;
+struct UploadSlice {
+    uint32_t w[kUploadWords];
+};
+
+__global__ __launch_bounds__(256) void upload_kernel(UploadSlice src, uint8_t *dst, int nbytes)
+{
+    // byte by byte: the destination needs no alignment
+    const uint8_t *b = reinterpret_cast<const uint8_t *>(src.w);
+    for (int i = threadIdx.x; i < nbytes; i += 256) dst[i] = b[i];
+}
+
+hipError_t upload_bytes(void *dst_dev, const void *src_host, size_t nbytes, hipStream_t st)
+{
+    const uint8_t *src = static_cast<const uint8_t *>(src_host);
+    uint8_t *dst = static_cast<uint8_t *>(dst_dev);
+    for (size_t off = 0; off < nbytes; off += sizeof(UploadSlice)) {
+        UploadSlice sl;
+        const size_t n = std::min(sizeof(UploadSlice), nbytes - off);
+        std::memcpy(sl.w, src + off, n);
+        hipLaunchKernelGGL(upload_kernel, dim3(1), dim3(256), 0, st, sl, dst + off, (int)n);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 } // namespace aiq

@@ -1,6 +1,7 @@
 // Plain copy kernel of known size: the calibration run for the HBM traffic counters
 // (FETCH_SIZE / WRITE_SIZE per dispatch are scaled by what they read for this copy).
-// Built as a stand-alone program by build.py; not part of libaiq.so.
+// Built as a stand-alone program by build.build_copy_probe() (python -m paper_2512_14090_amd.build --copy-probe);
+// not part of libaiq.so and not built by build().
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstdlib>
