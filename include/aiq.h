@@ -172,6 +172,32 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
                             void *hip_stream);
 
 /*
+ * aiq_eval_schemes for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * aiq_eval_schemes, minus the workspace: the library's own fixed array of
+ * AIQ_NOALLOC_SCRATCH_BYTES takes its place (one copy per GPU, part of the loaded code, held until
+ * the process ends; its address is looked up once per device, on the first call with that
+ * device current).  The call allocates and frees nothing on the device, copies nothing from
+ * host memory (the scheme table travels as kernel arguments) and does not wait for the stream.
+ * It fits models whose scoring workspace is small: the LDS-resident ResNets need
+ * S*L + 4*S*chunk bytes plus alignment; a model that runs layer by layer needs its activation
+ * buffers and is refused.  aiq_eval_noalloc_workspace_bytes reports what a call would need
+ * (needed) and what the array holds (available); either pointer may be NULL.
+ * Every call on one GPU uses that GPU's one array, which keeps what the last call left there;
+ * nothing in it has to start at zero (the scheme table and the per-chunk top-1 buffer are
+ * written before they are read).  Calls that overlap on one GPU - two streams, two threads,
+ * two models - race on it: serialise them.
+ * Errors: as aiq_eval_schemes; WORKSPACE_TOO_SMALL when the need exceeds the array (nothing is
+ * launched and no output is touched).
+ */
+#define AIQ_NOALLOC_SCRATCH_BYTES (2u << 20)
+aiq_status aiq_eval_noalloc_workspace_bytes(const aiq_model *m, int32_t S, int32_t chunk, size_t *needed,
+                                            size_t *available);
+aiq_status aiq_eval_schemes_noalloc(aiq_model *m, const float *images, int32_t N, const uint8_t *schemes, int32_t S,
+                                    int32_t chunk, int32_t *top1_base, int32_t base_valid, float *logits,
+                                    int32_t *top1, int32_t *agree, void *hip_stream);
+
+/*
  * aiq_eval_schemes with a shared forward prefix.  The schemes of one search step are all
  * derived from one scheme by changing a single layer (paper: Search Over Mixed-Precision
  * Schemes - greedy lowers one layer of the current scheme, coordinate descent varies one

@@ -13,7 +13,7 @@ _lib = None
 EXPORTED_SYMBOLS = (
     "aiq_status_str", "aiq_last_hip_error", "aiq_layer_ai", "aiq_quantize_weights", "aiq_quantize_weights_ex", "aiq_model_create",
     "aiq_model_create_ex", "aiq_model_is_lds_resident", "aiq_model_lds_resident_blocks", "aiq_model_destroy", "aiq_model_scheme_layers", "aiq_model_classes", "aiq_eval_workspace_bytes",
-    "aiq_eval_schemes", "aiq_model_shares_prefix", "aiq_eval_shared_workspace_bytes", "aiq_eval_schemes_shared",
+    "aiq_eval_schemes", "aiq_eval_schemes_noalloc", "aiq_eval_noalloc_workspace_bytes", "aiq_model_shares_prefix", "aiq_eval_shared_workspace_bytes", "aiq_eval_schemes_shared",
     "aiq_profile_enable", "aiq_profile_read", "aiq_search_workspace_bytes",
     "aiq_search_greedy", "aiq_search_coordinate_descent", "aiq_sensitivity_workspace_bytes", "aiq_layer_sensitivity",
     "aiq_deploy_create", "aiq_deploy_destroy", "aiq_deploy_code_layers", "aiq_deploy_workspace_bytes",
@@ -91,6 +91,10 @@ def load_library():
     lib.aiq_eval_schemes.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
                                      C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_size_t, C.c_void_p]
+    lib.aiq_eval_schemes_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
+                                             C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.aiq_eval_noalloc_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t),
+                                                     C.POINTER(C.c_size_t)]
     lib.aiq_model_shares_prefix.argtypes = [C.c_void_p]
     lib.aiq_eval_shared_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
     lib.aiq_eval_schemes_shared.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
@@ -297,6 +301,30 @@ class Model:
                                                    agree.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(stream))
             _check(st, "aiq_eval_schemes_shared")
         return dict(agree=agree[:S], top1_base=top1_base[:N], logits=logits, top1=top1)
+
+    def noalloc_workspace_bytes(self, S, chunk):
+        """aiq_eval_noalloc_workspace_bytes: (bytes a call would need, bytes the library's fixed array holds)."""
+        need, have = C.c_size_t(0), C.c_size_t(0)
+        _check(self._lib.aiq_eval_noalloc_workspace_bytes(self._h, int(S), int(chunk), C.byref(need), C.byref(have)),
+               "aiq_eval_noalloc_workspace_bytes")
+        return need.value, have.value
+
+    def eval_schemes_noalloc(self, images, schemes, out, chunk=1024, base_valid=False, stream=None):
+        """aiq_eval_schemes_noalloc: scoring without any device allocation.  out: dict of CUDA tensors the caller
+        has allocated - top1_base int32 [N] and agree int32 [S] (required), logits fp32 [S][N][classes] and top1
+        int32 [S][N] (optional).  Nothing is allocated here either.  Returns out."""
+        sch = np.ascontiguousarray(schemes, dtype=np.uint8)
+        if sch.ndim != 2 or sch.shape[1] != self.L:
+            raise AiqError(3, "aiq_eval_schemes_noalloc: scheme length differs from the model's L")
+        S, N = sch.shape[0], images.shape[0]
+        lg, t1 = out.get("logits"), out.get("top1")
+        st = self._lib.aiq_eval_schemes_noalloc(self._h, images.data_ptr(), N, sch.ctypes.data, S, int(chunk),
+                                                out["top1_base"].data_ptr(), 1 if base_valid else 0,
+                                                None if lg is None else lg.data_ptr(),
+                                                None if t1 is None else t1.data_ptr(), out["agree"].data_ptr(),
+                                                _stream_ptr(stream))
+        _check(st, "aiq_eval_schemes_noalloc")
+        return out
 
     def search(self, desc, images, method="greedy", bits=(32, 8, 4), lam=0.9, batch=1, max_iters=0,
                only_fp32_layers=False, chunk=1024, stream=None, share_prefix=True):

@@ -1475,6 +1475,30 @@ aiq_status aiq_eval_schemes(aiq_model *m, const float *images, int32_t N, const 
                      workspace_bytes, hip_stream);
 }
 
+aiq_status aiq_eval_noalloc_workspace_bytes(const aiq_model *m, int32_t S, int32_t chunk, size_t *needed,
+                                            size_t *available)
+{
+    if (!m || S < 0 || chunk < 1 || (!needed && !available)) return AIQ_INVALID_ARG;
+    if (needed) *needed = workspace_layout(m, S, chunk).total;
+    if (available) *available = AIQ_NOALLOC_SCRATCH_BYTES;
+    return AIQ_OK;
+}
+
+aiq_status aiq_eval_schemes_noalloc(aiq_model *m, const float *images, int32_t N, const uint8_t *schemes, int32_t S,
+                                    int32_t chunk, int32_t *top1_base, int32_t base_valid, float *logits,
+                                    int32_t *top1, int32_t *agree, void *hip_stream)
+{
+    if (!m || N < 0 || S < 0 || chunk < 1) return AIQ_INVALID_ARG;
+    // the size check uses the chunk the scoring will really use
+    const int32_t eff_chunk = std::min(chunk, std::max(N, 1));
+    if (workspace_layout(m, S, eff_chunk).total > (size_t)AIQ_NOALLOC_SCRATCH_BYTES) return AIQ_WORKSPACE_TOO_SMALL;
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    AIQ_HIP(noalloc_scratch(&ws, &ws_bytes));
+    return eval_impl(m, images, N, schemes, S, nullptr, chunk, top1_base, base_valid, logits, top1, agree, ws, ws_bytes,
+                     hip_stream);
+}
+
 int32_t aiq_model_shares_prefix(const aiq_model *m)
 {
     if (!m) return -1;

@@ -174,6 +174,8 @@ hipError_t launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t st);
 // taken when the launch is enqueued, so the host buffer is free again when the call returns, nothing waits
 // for the stream, and the step can be captured in a HIP graph.
 hipError_t upload_bytes(void *dst_dev, const void *src_host, size_t nbytes, hipStream_t st);
+// The library's own fixed workspace for aiq_eval_schemes_noalloc: address of the current device's copy and its size.
+hipError_t noalloc_scratch(void **ptr, size_t *bytes);
 hipError_t conv_set_lds_limits();
 
 } // namespace aiq

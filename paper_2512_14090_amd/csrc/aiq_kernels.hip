@@ -7,6 +7,7 @@
 // accuracy under the scheme is measured by running it).  The scheme axis is a grid
 // dimension: block z scores scheme z, picking each layer's weights from the bank
 // slot of that scheme's bit-width.
+#include "../../include/aiq.h"
 #include "aiq_internal.h"
 
 #include <algorithm>
@@ -1062,6 +1063,35 @@ hipError_t launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t st)
     if (n == 0) return hipSuccess;
     hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
     return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ fixed workspace (no-allocation entry point)
+//
+// One copy per GPU, part of the loaded code object, held until the process ends.  In host code the
+// array's name is only a handle for the runtime, never an address: noalloc_scratch() asks the
+// runtime, once per device and with that device current, where that device keeps its copy, and
+// everything else (kernel arguments included) uses the pointer it returns.
+
+static __device__ __align__(256) unsigned char scratch[AIQ_NOALLOC_SCRATCH_BYTES];
+
+hipError_t noalloc_scratch(void **ptr, size_t *bytes)
+{
+    constexpr int kMaxDevices = 64;
+    static void *per_device[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!per_device[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p || (reinterpret_cast<uintptr_t>(p) & 255)) return hipErrorInvalidSymbol;
+        per_device[dev] = p;
+    }
+    *ptr = per_device[dev];
+    *bytes = sizeof(scratch);
+    return hipSuccess;
 }
 
 // ------------------------------------------------------------------ host tables as kernel arguments
