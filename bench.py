@@ -98,6 +98,93 @@ def cpu_baseline(wl, budget_schemes=8, budget_images=192):
             "sample": f"first {s} schemes x first {n} images of the workload (+ its FP32 base pass), {dt:.1f} s"}
 
 
+def time_workload(torch, aiq, synth, index, steps, warmup, layerwise=False):
+    """A few steps of another workload (one aiq_eval_schemes call each) with the per-class HIP-event timing on:
+    returns (scheme-images/s, ms per step, per-class profile, agreement counts of the last step)."""
+    wl = synth.make_workload(index)
+    S, L = wl["schemes"].shape
+    N = wl["images"].shape[0]
+    model = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=layerwise)
+    images = torch.from_numpy(wl["images"]).cuda()
+    out = {"top1_base": torch.empty(N, dtype=torch.int32, device="cuda"),
+           "agree": torch.empty(S, dtype=torch.int32, device="cuda")}
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        model.eval_schemes(images, wl["schemes"], chunk=wl["chunk"], out=out, stream=stream)
+    torch.cuda.synchronize()
+    model.profile_enable(True)
+    for c in range(7):
+        model.profile_read(c)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        r = model.eval_schemes(images, wl["schemes"], chunk=wl["chunk"], out=out, stream=stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    model.profile_enable(False)
+    names = ("quantize", "conv_mfma", "depthwise", "head", "agree", "resnet_fused", "mbconv")
+    prof = {name: model.profile_read(c) for c, name in enumerate(names)}
+    agree = r["agree"].cpu().numpy()
+    model.close()
+    return wl, S * N * steps / dt, dt / steps * 1e3, prof, agree
+
+
+def extra_legs(args, torch, aiq, synth):
+    """Short secondary measurements that ride along with the default run (the headline stays the ResNet-20 greedy
+    step): the quantizer on a bandwidth-stress shape, the MobileNetV2 configuration on its LDS-resident block kernel,
+    the stand-alone depthwise kernel (the same configuration forced layer by layer), and the ResNet-20 greedy step on
+    the model with the centred classifier, whose agreement counts are not all N."""
+    legs = {}
+    # quantizer, 8192 x 4608 at 8 bits: 8 bytes moved per weight (+ 4 per row for the scale)
+    cout, k = 8192, 4608
+    import ctypes as C
+    lib = aiq.load_library()
+    w = torch.randn(cout, k, device="cuda") * 0.02
+    w_dq = torch.empty_like(w)
+    scales = torch.empty(cout, device="cuda")
+    st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    for _ in range(3):
+        assert lib.aiq_quantize_weights(w.data_ptr(), cout, k, 8, w_dq.data_ptr(), scales.data_ptr(), None, st) == 0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    e0.record()
+    for _ in range(reps):
+        lib.aiq_quantize_weights(w.data_ptr(), cout, k, 8, w_dq.data_ptr(), scales.data_ptr(), None, st)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    nbytes = 8.0 * cout * k + 4.0 * cout
+    legs["quantize_stress"] = {"workload": f"quantize_stress_{cout}x{k}_b8", "kernel": "quantize_rows_kernel",
+                               "bound": "hbm", "achieved": nbytes / ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                               "frac": nbytes / ms / 1e6 / PEAK_HBM_GBS, "avg_launch_ms": ms, "launches": reps,
+                               "algorithmic_gbytes_per_launch": nbytes / 1e9}
+    del w, w_dq, scales
+    # MobileNetV2 (configuration 3): LDS-resident inverted-residual blocks
+    wl, value, ms_step, prof, agree = time_workload(torch, aiq, synth, 3, 3, 1)
+    k_ = prof["mbconv"]
+    tf = k_["flops"] / (k_["total_ms"] * 1e-3) / 1e12
+    legs["mobilenetv2"] = {"workload": wl["name"], "value": value, "unit": "scheme-images/s", "ms_per_step": ms_step, "steps": 3,
+                           "kernel": "mbconv_kernel", "bound": "mfma", "achieved": tf, "peak": PEAK_MFMA_F32_TFLOPS,
+                           "unit_roofline": "TFLOP/s", "frac": tf / PEAK_MFMA_F32_TFLOPS,
+                           "kernel_ms_per_step": k_["total_ms"] / 3, "launches": k_["launches"]}
+    # the same configuration layer by layer: the stand-alone depthwise kernel (17 launches per step)
+    wl, value, ms_step, prof, agree = time_workload(torch, aiq, synth, 3, 2, 1, layerwise=True)
+    k_ = prof["depthwise"]
+    gbs = k_["bytes"] / (k_["total_ms"] * 1e-3) / 1e9
+    legs["depthwise_layerwise"] = {"workload": wl["name"] + "_layerwise", "value": value, "unit": "scheme-images/s",
+                                   "ms_per_step": ms_step, "steps": 2, "kernel": "depthwise3x3_kernel", "bound": "hbm",
+                                   "achieved": gbs, "peak": PEAK_HBM_GBS, "unit_roofline": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                                   "kernel_ms_per_step": k_["total_ms"] / 2, "launches": k_["launches"],
+                                   "algorithmic_gbytes_per_step": k_["bytes"] / 2 / 1e9}
+    # ResNet-20 greedy step with the centred classifier: same launches as the headline, non-trivial agreement
+    wl, value, ms_step, prof, agree = time_workload(torch, aiq, synth, 7, 3, 1)
+    legs["centred_greedy_step"] = {"workload": wl["name"], "value": value, "unit": "scheme-images/s", "ms_per_step": ms_step,
+                                   "steps": 3, "images": int(wl["images"].shape[0]),
+                                   "agree_min_max": [int(agree.min()), int(agree.max())],
+                                   "agree_8bit_moves": [int(v) for v in agree[0::2]],
+                                   "agree_4bit_moves": [int(v) for v in agree[1::2]]}
+    return legs
+
+
 def stress_quantize(args, torch, aiq):
     """aiq_quantize_weights on a matrix far larger than the caches: 8 bytes moved per weight."""
     import ctypes as C
@@ -306,6 +393,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=2, help="0..4 (benchmark configurations; 2 = ResNet-20 greedy step, the headline), 5 / 6 = variant models")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-legs", action="store_true",
+                    help="skip the short secondary measurements of the default run (quantizer stress shape, MobileNetV2, "
+                         "stand-alone depthwise kernel, centred workload)")
     ap.add_argument("--layerwise", action="store_true", help="force the layer-by-layer kernels")
     ap.add_argument("--roofline-class", default="auto",
                     choices=("auto", "conv_mfma", "depthwise", "head", "resnet_fused", "mbconv"),
@@ -444,9 +534,11 @@ def main():
             "kernel_tflops": fz["flops"] / (fz["total_ms"] * 1e-3) / 1e12 if fz["total_ms"] > 0 else 0.0,
             "outputs_identical": bool((r2["agree"].cpu().numpy() == agree).all()
                                       and (out2["top1_base"] == out["top1_base"]).all().item())}
+    model.close()
+    if args.workload == 2 and not args.layerwise and not args.no_extra_legs:
+        line["extra_legs"] = extra_legs(args, torch, aiq, synth)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl)
-    model.close()
     print(json.dumps(line))
 
 
