@@ -130,29 +130,38 @@ __global__ __launch_bounds__(256) void quantize_batch_kernel(const QuantJob *job
     if (c < j.cout) quantize_channel(j, c, threadIdx.x & 63);
 }
 
-// Plain [cout][k] rows with k % 4 == 0 and 16-byte aligned pointers: the wavefront keeps its
-// whole row in registers (NV 16-byte elements per lane), so every weight is read from memory
-// once and written once, 16 bytes per lane per access; a workgroup's four rows are one
-// contiguous stretch of memory.  Same arithmetic, step for step, as quantize_channel.
-template <int NV>
+// Plain [cout][k] rows with k % 4 == 0 and 16-byte aligned pointers: the WPR wavefronts that share
+// a row keep it in registers (NV 16-byte elements per lane), so every weight is read from memory
+// once and written once, 16 bytes per lane per access, all reads of a workgroup in flight before
+// its first write.  Long rows take a whole workgroup (WPR = 4, absmax combined through LDS): a
+// workgroup then lives for one short burst of reads and one of writes and makes room for the next,
+// which the memory system rewards (5.2 -> 5.9 TB/s on 8192 x 4608 against one wavefront per row;
+// a copy kernel shows the same preference for short-lived workgroups over looping ones).
+// Same arithmetic, step for step, as quantize_channel.
+template <int NV, int WPR>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantJob j)
 {
-    const int c = blockIdx.x * kQuantChannelsPerBlock + (threadIdx.x >> 6);
-    if (c >= j.cout) return;
-    const int lane = threadIdx.x & 63;
+    __shared__ float wave_amax[4];
+    constexpr int RPB = kQuantChannelsPerBlock / WPR; // rows per workgroup
+    const int wave = threadIdx.x >> 6;
+    const int c = blockIdx.x * RPB + wave / WPR;
+    const bool live = c < j.cout; // (with WPR > 1 every wavefront reaches the barrier below)
+    if (WPR == 1 && !live) return;
+    const int lane = (wave % WPR) * 64 + (threadIdx.x & 63); // position among the row's 64 * WPR lanes
     const int k4 = j.k >> 2;
-    const floatx4 *row = reinterpret_cast<const floatx4 *>(j.w + (size_t)c * j.k);
-    floatx4 *out = reinterpret_cast<floatx4 *>(j.out + (size_t)c * j.k);
+    const floatx4 *row = reinterpret_cast<const floatx4 *>(j.w + (size_t)(live ? c : 0) * j.k);
+    floatx4 *out = reinterpret_cast<floatx4 *>(j.out + (size_t)(live ? c : 0) * j.k);
     floatx4 v[NV];
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
-        const int i = u * 64 + lane;
-        v[u] = i < k4 ? __builtin_nontemporal_load(row + i) : floatx4{0.f, 0.f, 0.f, 0.f};
+        const int i = u * (64 * WPR) + lane;
+        v[u] = (live && i < k4) ? __builtin_nontemporal_load(row + i) : floatx4{0.f, 0.f, 0.f, 0.f};
     }
     if (j.bits == 32) {
+        if (!live) return; // no barrier on this path
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
-            const int i = u * 64 + lane;
+            const int i = u * (64 * WPR) + lane;
             if (i < k4) __builtin_nontemporal_store(v[u], out + i);
         }
         if (lane == 0 && j.scales) j.scales[c] = 1.0f;
@@ -166,7 +175,15 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantJob j)
         for (int u = 0; u < NV; ++u)
             amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v[u].x), fabsf(v[u].y))), fmaxf(fabsf(v[u].z), fabsf(v[u].w)));
         amax = wave_max(amax);
+        if (WPR > 1) { // the maximum is exact whatever the order: combine the row's wavefronts through LDS
+            if ((threadIdx.x & 63) == 0) wave_amax[wave] = amax;
+            __syncthreads();
+            const int w0 = (wave / WPR) * WPR;
+#pragma unroll
+            for (int q = 0; q < WPR; ++q) amax = fmaxf(amax, wave_amax[w0 + q]);
+        }
     }
+    if (!live) return;
     const int qmax = (1 << (j.bits - 1)) - 1;
     const float s = amax > 0.0f ? __fdiv_rn(amax, (float)qmax) : 1.0f;
     if (lane == 0 && j.scales) j.scales[c] = s;
@@ -174,7 +191,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantJob j)
     intx4 *codes = j.codes ? reinterpret_cast<intx4 *>(j.codes + (size_t)c * j.k) : nullptr;
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
-        const int i = u * 64 + lane;
+        const int i = u * (64 * WPR) + lane;
         if (i >= k4) continue;
         intx4 q;
         floatx4 d;
@@ -190,10 +207,11 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantJob j)
     }
 }
 
-template <int NV>
-static hipError_t launch_quantize_rows(const QuantJob &job, int blocks, hipStream_t st)
+template <int NV, int WPR>
+static hipError_t launch_quantize_rows(const QuantJob &job, hipStream_t st)
 {
-    hipLaunchKernelGGL((quantize_rows_kernel<NV>), dim3(blocks), dim3(256), 0, st, job);
+    constexpr int RPB = kQuantChannelsPerBlock / WPR;
+    hipLaunchKernelGGL((quantize_rows_kernel<NV, WPR>), dim3((job.cout + RPB - 1) / RPB), dim3(256), 0, st, job);
     return hipGetLastError();
 }
 
@@ -203,13 +221,18 @@ hipError_t launch_quantize_single(const QuantJob &job, hipStream_t st)
     const int blocks = (job.cout + kQuantChannelsPerBlock - 1) / kQuantChannelsPerBlock;
     const bool aligned = ((reinterpret_cast<uintptr_t>(job.w) | reinterpret_cast<uintptr_t>(job.out) |
                            reinterpret_cast<uintptr_t>(job.codes)) & 15) == 0;
-    if (job.layout == kLayoutPlain && job.k > 0 && (job.k & 3) == 0 && aligned && job.k <= 4 * 64 * 20) {
-        const int nv = (job.k / 4 + 63) / 64;
-        if (nv <= 1) return launch_quantize_rows<1>(job, blocks, st);
-        if (nv <= 2) return launch_quantize_rows<2>(job, blocks, st);
-        if (nv <= 5) return launch_quantize_rows<5>(job, blocks, st);
-        if (nv <= 10) return launch_quantize_rows<10>(job, blocks, st);
-        return launch_quantize_rows<20>(job, blocks, st);
+    if (job.layout == kLayoutPlain && job.k > 0 && (job.k & 3) == 0 && aligned && job.k <= 4 * 256 * 20) {
+        const int k4 = job.k / 4;
+        // rows of up to 64 / 128 16-byte elements: one / two wavefronts per row; longer rows: the workgroup
+        if (k4 <= 64) return launch_quantize_rows<1, 1>(job, st);
+        if (k4 <= 128) return launch_quantize_rows<1, 2>(job, st);
+        const int nv = (k4 + 255) / 256;
+        if (nv <= 1) return launch_quantize_rows<1, 4>(job, st);
+        if (nv <= 2) return launch_quantize_rows<2, 4>(job, st);
+        if (nv <= 3) return launch_quantize_rows<3, 4>(job, st);
+        if (nv <= 5) return launch_quantize_rows<5, 4>(job, st);
+        if (nv <= 10) return launch_quantize_rows<10, 4>(job, st);
+        return launch_quantize_rows<20, 4>(job, st);
     }
     hipLaunchKernelGGL(quantize_single_kernel, dim3(blocks), dim3(256), 0, st, job);
     return hipGetLastError();
@@ -839,15 +862,19 @@ hipError_t launch_pointwise(const PointwiseArgs &a, int nt, size_t lds_bytes, di
 // ------------------------------------------------------------------ depthwise 3x3
 //
 // Bandwidth-bound: 18 FLOP per output element.  One thread owns four consecutive channels
-// (16 bytes along the NHWC channel axis) of XG adjacent output columns and walks down the
-// whole image with the 3-row window in registers: the nine filter taps are loaded once, every
-// input row is loaded once per thread ((XG-1)*STRIDE + 3 16-byte loads for XG outputs, the two
-// outer ones shared with the neighbouring threads through L1), rows are requested PF output
-// rows ahead of their use, results leave with nontemporal 16-byte stores.  The (column group,
-// channel group) positions of all images of the chunk form one flat thread axis, so a
-// workgroup's accesses per row are one contiguous stretch of memory.
+// (16 bytes along the NHWC channel axis) of XG adjacent output columns in a band of RB output
+// rows and walks down the band with the 3-row window in registers: the nine filter taps are loaded
+// once, every input row of the band once per thread ((XG-1)*STRIDE + 3 16-byte loads for XG outputs,
+// the two outer ones shared with the neighbouring threads through L1), rows are requested PF output
+// rows ahead of their use, results leave with nontemporal 16-byte stores.  With PF = RB every load
+// of the band is in flight before the first store: a workgroup lives for one burst of reads and one
+// of writes and then makes room for the next, which this memory system serves faster than long-lived
+// workgroups that alternate (5.14 -> 5.7 TB/s over MobileNetV2's depthwise layers against threads that
+// walk the whole image height).  The two halo rows a band shares with its neighbours come from L2:
+// the (image, band, column group, channel group) positions of the chunk form one flat thread axis in
+// memory order, and one XCD takes a contiguous stretch of it.
 
-template <int STRIDE, int XG, int PF>
+template <int STRIDE, int XG, int PF, int RB>
 __global__ __launch_bounds__(256) void depthwise3x3_kernel(DepthwiseArgs a)
 {
     constexpr int WIN = (XG - 1) * STRIDE + 3; // input columns per window row
@@ -855,12 +882,15 @@ __global__ __launch_bounds__(256) void depthwise3x3_kernel(DepthwiseArgs a)
     const int s = blockIdx.z;
     const int c4n = a.C >> 2;
     const uint32_t P = (uint32_t)(a.Wout / XG) * c4n;
+    const uint32_t bands = (uint32_t)(a.Hout + RB - 1) / RB;
     // Workgroups are handed to the eight XCDs in turn, each with its own L2.  Neighbouring
-    // workgroups share halo columns, so each XCD gets one contiguous eighth of the flat axis
-    // instead of every eighth workgroup: the shared columns then meet in one L2.
+    // workgroups share halo columns and rows, so each XCD gets one contiguous eighth of the flat axis
+    // instead of every eighth workgroup: the shared pixels then meet in one L2.
     const uint32_t gidx = xcd_contiguous_block(blockIdx.x, gridDim.x) * 256u + threadIdx.x;
-    if (gidx >= (uint32_t)a.N * P) return;
-    const uint32_t img = gidx / P, pos = gidx - img * P;
+    if (gidx >= (uint32_t)a.N * bands * P) return;
+    const uint32_t ib = gidx / P, pos = gidx - ib * P;
+    const uint32_t img = ib / bands, band = ib - img * bands;
+    const int oy0 = band * RB;
     const uint32_t xg = fd_div(pos, a.div_c4);
     const int c = (pos - xg * c4n) * 4, ox0 = xg * XG;
     const float *wq = a.bank[scheme_bits_index(a.schemes, s, a.S, a.L, a.slot)];
@@ -876,8 +906,10 @@ __global__ __launch_bounds__(256) void depthwise3x3_kernel(DepthwiseArgs a)
     const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};
     const int ix0 = ox0 * STRIDE - 1;
     const bool ok_first = ix0 >= 0, ok_last = ix0 + WIN - 1 < a.Win; // only the outer columns can fall outside
+    // last input row this band reads: rows beyond it (or beyond the image) are never fetched
+    const int iy_end = min(a.Hin - 1, (min(oy0 + RB, a.Hout) - 1) * STRIDE + 1);
     auto load_row = [&](int iy, floatx4 (&r)[WIN]) {
-        if (iy < 0 || iy >= a.Hin) {
+        if (iy < 0 || iy > iy_end) {
 #pragma unroll
             for (int k = 0; k < WIN; ++k) r[k] = zero;
             return;
@@ -892,38 +924,46 @@ __global__ __launch_bounds__(256) void depthwise3x3_kernel(DepthwiseArgs a)
     // r[q] holds input row oy*STRIDE - 1 + q
     floatx4 r[NB][WIN];
 #pragma unroll
-    for (int q = 0; q < NB; ++q) load_row(q - 1, r[q]);
-    for (int oy = 0; oy < a.Hout; ++oy) {
+    for (int q = 0; q < NB; ++q) load_row(oy0 * STRIDE - 1 + q, r[q]);
 #pragma unroll
-        for (int x = 0; x < XG; ++x) {
-            floatx4 acc = bias;
+    for (int i = 0; i < RB; ++i) {
+        const int oy = oy0 + i;
+        if (oy < a.Hout) {
 #pragma unroll
-            for (int k = 0; k < 3; ++k) {
-                acc += r[0][x * STRIDE + k] * w[k];
-                acc += r[1][x * STRIDE + k] * w[3 + k];
-                acc += r[2][x * STRIDE + k] * w[6 + k];
+            for (int x = 0; x < XG; ++x) {
+                floatx4 acc = bias;
+#pragma unroll
+                for (int k = 0; k < 3; ++k) {
+                    acc += r[0][x * STRIDE + k] * w[k];
+                    acc += r[1][x * STRIDE + k] * w[3 + k];
+                    acc += r[2][x * STRIDE + k] * w[6 + k];
+                }
+                acc.x = __builtin_amdgcn_fmed3f(acc.x, lo, hi);
+                acc.y = __builtin_amdgcn_fmed3f(acc.y, lo, hi);
+                acc.z = __builtin_amdgcn_fmed3f(acc.z, lo, hi);
+                acc.w = __builtin_amdgcn_fmed3f(acc.w, lo, hi);
+                __builtin_nontemporal_store(acc, reinterpret_cast<floatx4 *>(out + ((size_t)oy * a.Wout + x) * a.C));
             }
-            acc.x = __builtin_amdgcn_fmed3f(acc.x, lo, hi);
-            acc.y = __builtin_amdgcn_fmed3f(acc.y, lo, hi);
-            acc.z = __builtin_amdgcn_fmed3f(acc.z, lo, hi);
-            acc.w = __builtin_amdgcn_fmed3f(acc.w, lo, hi);
-            __builtin_nontemporal_store(acc, reinterpret_cast<floatx4 *>(out + ((size_t)oy * a.Wout + x) * a.C));
         }
+        if (i + 1 < RB) {
 #pragma unroll
-        for (int q = 0; q + STRIDE < NB; ++q)
+            for (int q = 0; q + STRIDE < NB; ++q)
 #pragma unroll
-            for (int k = 0; k < WIN; ++k) r[q][k] = r[q + STRIDE][k];
+                for (int k = 0; k < WIN; ++k) r[q][k] = r[q + STRIDE][k];
+            if (i + 1 + PF < RB) { // the band's last output row is i = RB - 1
 #pragma unroll
-        for (int i = 0; i < STRIDE; ++i) load_row((oy + 1) * STRIDE - 1 + NB - STRIDE + i, r[NB - STRIDE + i]);
+                for (int j = 0; j < STRIDE; ++j) load_row((oy + 1) * STRIDE - 1 + NB - STRIDE + j, r[NB - STRIDE + j]);
+            }
+        }
     }
 }
 
-template <int STRIDE, int XG, int PF>
+template <int STRIDE, int XG, int PF, int RB>
 static hipError_t launch_depthwise_t(const DepthwiseArgs &a, int s_total, hipStream_t st)
 {
-    const size_t threads = (size_t)a.N * (a.Wout / XG) * (a.C >> 2);
+    const size_t threads = (size_t)a.N * ((a.Hout + RB - 1) / RB) * (a.Wout / XG) * (a.C >> 2);
     if (threads > 0xffffffffull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((depthwise3x3_kernel<STRIDE, XG, PF>), dim3((unsigned)((threads + 255) / 256), 1, s_total),
+    hipLaunchKernelGGL((depthwise3x3_kernel<STRIDE, XG, PF, RB>), dim3((unsigned)((threads + 255) / 256), 1, s_total),
                        dim3(256), 0, st, a);
     return hipGetLastError();
 }
@@ -931,13 +971,15 @@ static hipError_t launch_depthwise_t(const DepthwiseArgs &a, int s_total, hipStr
 hipError_t launch_depthwise(const DepthwiseArgs &a, int s_total, hipStream_t st)
 {
     if (a.N == 0 || s_total == 0) return hipSuccess;
+    // bands of eight output rows with every row of the band requested up front (stride 2: two rows
+    // of outputs ahead, the window being twice as tall); narrower column groups for odd widths
     if (a.stride == 1) {
-        if (a.Wout % 4 == 0) return launch_depthwise_t<1, 4, 2>(a, s_total, st);
-        if (a.Wout % 2 == 0) return launch_depthwise_t<1, 2, 2>(a, s_total, st);
-        return launch_depthwise_t<1, 1, 2>(a, s_total, st);
+        if (a.Wout % 4 == 0) return launch_depthwise_t<1, 4, 8, 8>(a, s_total, st);
+        if (a.Wout % 2 == 0) return launch_depthwise_t<1, 2, 8, 8>(a, s_total, st);
+        return launch_depthwise_t<1, 1, 8, 8>(a, s_total, st);
     }
-    if (a.Wout % 2 == 0) return launch_depthwise_t<2, 2, 1>(a, s_total, st);
-    return launch_depthwise_t<2, 1, 1>(a, s_total, st);
+    if (a.Wout % 2 == 0) return launch_depthwise_t<2, 2, 4, 8>(a, s_total, st);
+    return launch_depthwise_t<2, 1, 4, 8>(a, s_total, st);
 }
 
 // ------------------------------------------------------------------ classifier head
