@@ -78,17 +78,25 @@ def quantize_weights(w, bits, want_codes=True, per_tensor=False):
     return w_dq, scales, codes
 
 
-def layer_ai(desc, scheme, batch=1):
-    """Returns (flops[n_layers], bytes[n_layers], global_ai)."""
+def quantize_activations(x, bits):
+    """Activation fake-quantization of one tensor (any shape, one scale for all of it): returns fp64 array."""
+    y = np.ascontiguousarray(x, dtype=np.float64).copy()
+    _check(lib().oracle_quantize_activations(_p(y, C.c_double), C.c_int64(y.size), int(bits)))
+    return y
+
+
+def layer_ai(desc, scheme, batch=1, act_quant=False):
+    """Returns (flops[n_layers], bytes[n_layers], global_ai).  act_quant: input activations counted at the
+    layer's width as well."""
     desc = np.ascontiguousarray(desc, dtype=np.int32)
     n = desc.shape[0]
     scheme = None if scheme is None else np.ascontiguousarray(scheme, dtype=np.uint8)
     flops = np.empty(n, dtype=np.float64)
     byts = np.empty(n, dtype=np.float64)
     ai = C.c_double(0.0)
-    _check(lib().oracle_layer_ai(_p(desc, C.c_int32), n, _p(scheme, C.c_uint8),
-                                 0 if scheme is None else scheme.shape[0], int(batch),
-                                 _p(flops, C.c_double), _p(byts, C.c_double), C.byref(ai)))
+    _check(lib().oracle_layer_ai_ex(_p(desc, C.c_int32), n, _p(scheme, C.c_uint8),
+                                    0 if scheme is None else scheme.shape[0], int(batch), 1 if act_quant else 0,
+                                    _p(flops, C.c_double), _p(byts, C.c_double), C.byref(ai)))
     return flops, byts, ai.value
 
 
@@ -124,8 +132,11 @@ def forward(desc, weights, biases, images, want_acts=False):
     return dict(logits=logits, top1=top1, acts=acts, macs_per_image=macs.value)
 
 
-def eval_schemes(desc, weights, biases, images, schemes, want_logits=True, per_tensor=False):
-    """Score schemes uint8 [S][L].  Returns dict(logits_base, top1_base, logits, top1, agree)."""
+def eval_schemes(desc, weights, biases, images, schemes, want_logits=True, per_tensor=False, act_quant=False,
+                 want_acts=False):
+    """Score schemes uint8 [S][L].  Returns dict(logits_base, top1_base, logits, top1, agree[, acts]).
+    act_quant: a layer at b bits also reads its input activations at b bits.
+    want_acts: every node's output under every scheme, fp64 [S][N][sum of node outputs]."""
     desc = np.ascontiguousarray(desc, dtype=np.int32)
     images = np.ascontiguousarray(images, dtype=np.float32)
     schemes = np.ascontiguousarray(schemes, dtype=np.uint8)
@@ -137,12 +148,14 @@ def eval_schemes(desc, weights, biases, images, schemes, want_logits=True, per_t
     logits = np.empty((S, N, ncls), dtype=np.float64) if want_logits else None
     top1 = np.empty((S, N), dtype=np.int32)
     agree = np.empty(S, dtype=np.int32)
-    _check(lib().oracle_eval_schemes_ex(_p(desc, C.c_int32), n_layers, _ptr_array(weights), _ptr_array(biases),
+    acts = np.empty((S, N, sum(node_out_elems(desc))), dtype=np.float64) if want_acts else None
+    _check(lib().oracle_eval_schemes_aq(_p(desc, C.c_int32), n_layers, _ptr_array(weights), _ptr_array(biases),
                                         _p(images, C.c_float), N, _p(schemes, C.c_uint8), S, L,
-                                        1 if per_tensor else 0,
+                                        1 if per_tensor else 0, 1 if act_quant else 0,
                                         _p(logits_base, C.c_double), _p(top1_base, C.c_int32),
-                                        _p(logits, C.c_double), _p(top1, C.c_int32), _p(agree, C.c_int32)))
-    return dict(logits_base=logits_base, top1_base=top1_base, logits=logits, top1=top1, agree=agree)
+                                        _p(logits, C.c_double), _p(top1, C.c_int32), _p(agree, C.c_int32),
+                                        _p(acts, C.c_double)))
+    return dict(logits_base=logits_base, top1_base=top1_base, logits=logits, top1=top1, agree=agree, acts=acts)
 
 
 def conv_layer(desc_row, x, w, bias, res=None):

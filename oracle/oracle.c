@@ -20,6 +20,9 @@
  * integers and scales that must be reproducible bit for bit); everything in
  * the forward pass is binary64 direct loops.
  *
+ * Activation fake-quantization (a variant; the paper gives a layer only a bit-width) is stated
+ * next to quantize_activations below and pinned by tests/test_oracle_activations.py.
+ *
  * Parity status: quantizer, convolution, depthwise, classifier head and the AI
  * model are pinned by tests/test_oracle_*.py (hand-worked rows, closed forms,
  * library matmul / einsum special cases, the paper's AI gains).  Trained-model
@@ -128,8 +131,23 @@ static int out_size(int in, int k, int stride, int pad) { return (in + 2 * pad -
  * and AI = sum FLOPs / sum Bytes over all layers.  Layers outside the scheme count at 32 bits.
  * With batch = 1 this reproduces the paper's ResNet-20 gains (about +42 % at uniform 8 bits).
  */
+int oracle_layer_ai_ex(const int32_t *desc, int n_layers, const uint8_t *scheme, int L, int batch, int act_quant,
+                       double *flops, double *bytes, double *global_ai);
+
 int oracle_layer_ai(const int32_t *desc, int n_layers, const uint8_t *scheme, int L, int batch,
                     double *flops, double *bytes, double *global_ai)
+{
+    return oracle_layer_ai_ex(desc, n_layers, scheme, L, batch, 0, flops, bytes, global_ai);
+}
+
+/*
+ * The same with activation fake-quantization counted (act_quant != 0): a layer at b bits reads its
+ * input activations at b bits as well, so
+ *   Bytes = n_weights * b/8 + batch * (input elements * b/8 + 4 * output elements);
+ * outputs are written in fp32 (the next layer quantizes what it reads to its own width).
+ */
+int oracle_layer_ai_ex(const int32_t *desc, int n_layers, const uint8_t *scheme, int L, int batch, int act_quant,
+                       double *flops, double *bytes, double *global_ai)
 {
     if (!desc || n_layers <= 0 || batch < 1 || !global_ai) return 1;
     double sum_f = 0.0, sum_b = 0.0;
@@ -157,7 +175,8 @@ int oracle_layer_ai(const int32_t *desc, int n_layers, const uint8_t *scheme, in
             out_e = (double)ho * wo * d[F_COUT];
         }
         double f = 2.0 * macs * batch;
-        double b = n_w * bits / 8.0 + 4.0 * batch * (in_e + out_e);
+        double in_bytes = act_quant ? in_e * bits / 8.0 : 4.0 * in_e;
+        double b = n_w * bits / 8.0 + batch * (in_bytes + 4.0 * out_e);
         if (flops) flops[l] = f;
         if (bytes) bytes[l] = b;
         sum_f += f;
@@ -214,8 +233,51 @@ static int64_t conv_layer(const int32_t *d, const double *x, const float *w, con
     return macs;
 }
 
-/* Classifier: global average pool over hin*win, then z[j] = bias[j] + sum_c p[c] * w[j][c]. */
-static int64_t fc_layer(const int32_t *d, const double *x, const float *w, const float *bias, double *z)
+/*
+ * Activation fake-quantization (variant)                        [Problem Formulation: a layer gets a
+ *                                                                bit-width; the paper does not say whether
+ *                                                                that width also applies to what the layer
+ *                                                                reads]
+ * Reading: a layer at b < 32 bits reads its input tensor quantized to b bits, symmetric, with one
+ * scale per image taken from that image's own tensor (no calibration data is needed):
+ *   amax = max |x| over the tensor,  qmax = 2^(b-1) - 1,  s = amax / qmax  (1 if the tensor is zero),
+ *   x_q = clamp(round_half_even(x / s), -qmax, +qmax) * s,
+ * the same rule as for a weight row, every step one IEEE binary32 operation on the activation
+ * rounded to binary32.  The residual input of a layer is added unquantized; the classifier reads the
+ * pooled vector quantized.  b = 32: nothing happens.  x is replaced in place.
+ */
+static void quantize_activations(double *x, size_t n, int bits)
+{
+    if (bits == 32) return;
+    const int32_t qmax = (1 << (bits - 1)) - 1;
+    float amax = 0.0f;
+    for (size_t i = 0; i < n; ++i) {
+        float a = fabsf((float)x[i]);
+        if (a > amax) amax = a;
+    }
+    volatile float s = (amax > 0.0f) ? amax / (float)qmax : 1.0f;
+    for (size_t i = 0; i < n; ++i) {
+        volatile float t = (float)x[i] / s;
+        int32_t q = (int32_t)rintf(t);
+        if (q > qmax) q = qmax;
+        if (q < -qmax) q = -qmax;
+        volatile float d = (float)q * s;
+        x[i] = (double)d;
+    }
+}
+
+/* Exposed so that tests can pin the rule on hand-worked tensors.  x: n doubles, replaced in place. */
+int oracle_quantize_activations(double *x, int64_t n, int bits)
+{
+    if (!bits_supported(bits)) return 2;
+    if (!x || n < 0) return 1;
+    quantize_activations(x, (size_t)n, bits);
+    return 0;
+}
+
+/* Classifier: global average pool over hin*win, then z[j] = bias[j] + sum_c p[c] * w[j][c].
+ * act_bits < 32: the pooled vector is quantized before the matrix reads it. */
+static int64_t fc_layer(const int32_t *d, const double *x, const float *w, const float *bias, double *z, int act_bits)
 {
     const int cin = d[F_CIN], cout = d[F_COUT], hw = d[F_HIN] * d[F_WIN];
     double *p = (double *)malloc(sizeof(double) * cin);
@@ -224,6 +286,7 @@ static int64_t fc_layer(const int32_t *d, const double *x, const float *w, const
         for (int i = 0; i < hw; ++i) s += x[(size_t)i * cin + c];
         p[c] = s / (double)hw;
     }
+    quantize_activations(p, (size_t)cin, act_bits);
     int64_t macs = 0;
     for (int j = 0; j < cout; ++j) {
         double acc = (double)bias[j];
@@ -282,8 +345,12 @@ int oracle_check_graph(const int32_t *desc, int n_layers, int hin0, int win0, in
  * n_classes doubles.  acts (nullable) receives every node's output, concatenated in node
  * order.  Returns total multiply-adds.
  */
+static size_t node_out_elems(const int32_t *d);
+
+/* act_bits: NULL, or per node the width its input activations are quantized to (32 = not at all). */
 static int64_t forward_image(const int32_t *desc, int n_layers, const float *const *w,
-                             const float *const *bias, const float *image, double *logits, double *acts)
+                             const float *const *bias, const float *image, double *logits, double *acts,
+                             const int *act_bits)
 {
     const int32_t *d0 = desc;
     size_t in_elems = (size_t)d0[F_HIN] * d0[F_WIN] * d0[F_CIN];
@@ -298,10 +365,20 @@ static int64_t forward_image(const int32_t *desc, int n_layers, const float *con
         const double *r = d[F_RESIDUAL] < 0 ? NULL : out[d[F_RESIDUAL]];
         size_t n_out = node_out_elems(d);
         out[l] = (double *)malloc(sizeof(double) * n_out);
-        if (d[F_KIND] == KIND_FC)
-            macs += fc_layer(d, x, w[l], bias[l], out[l]);
-        else
+        const int ab = act_bits ? act_bits[l] : 32;
+        if (d[F_KIND] == KIND_FC) {
+            macs += fc_layer(d, x, w[l], bias[l], out[l], ab);
+        } else if (ab != 32) {
+            /* the layer reads a quantized copy: other readers of the same tensor see it as it is */
+            size_t n_in = (size_t)d[F_HIN] * d[F_WIN] * d[F_CIN];
+            double *xq = (double *)malloc(sizeof(double) * n_in);
+            memcpy(xq, x, sizeof(double) * n_in);
+            quantize_activations(xq, n_in, ab);
+            macs += conv_layer(d, xq, w[l], bias[l], r, out[l]);
+            free(xq);
+        } else {
             macs += conv_layer(d, x, w[l], bias[l], r, out[l]);
+        }
         if (acts) {
             memcpy(acts + acts_off, out[l], sizeof(double) * n_out);
             acts_off += n_out;
@@ -345,7 +422,7 @@ int oracle_forward(const int32_t *desc, int n_layers, const float *const *w, con
 #pragma omp parallel for schedule(dynamic, 1)
     for (int n = 0; n < N; ++n) {
         int64_t m = forward_image(desc, n_layers, w, bias, images + (size_t)n * img_elems,
-                                  logits + (size_t)n * ncls, acts ? acts + (size_t)n * acts_per : NULL);
+                                  logits + (size_t)n * ncls, acts ? acts + (size_t)n * acts_per : NULL, NULL);
         if (top1) top1[n] = argmax(logits + (size_t)n * ncls, ncls);
         if (n == 0) macs0 = m;
     }
@@ -377,11 +454,27 @@ int oracle_eval_schemes(const int32_t *desc, int n_layers, const float *const *w
                                   logits, top1, agree);
 }
 
+int oracle_eval_schemes_aq(const int32_t *desc, int n_layers, const float *const *w, const float *const *bias,
+                           const float *images, int N, const uint8_t *schemes, int S, int L, int per_tensor,
+                           int act_quant, double *logits_base, int32_t *top1_base, double *logits, int32_t *top1,
+                           int32_t *agree, double *acts);
+
 /* per_tensor != 0: every scheme layer is quantized with one scale per layer instead of one per output channel. */
 int oracle_eval_schemes_ex(const int32_t *desc, int n_layers, const float *const *w, const float *const *bias,
                            const float *images, int N, const uint8_t *schemes, int S, int L, int per_tensor,
                            double *logits_base, int32_t *top1_base, double *logits, int32_t *top1,
                            int32_t *agree)
+{
+    return oracle_eval_schemes_aq(desc, n_layers, w, bias, images, N, schemes, S, L, per_tensor, 0, logits_base,
+                                  top1_base, logits, top1, agree, NULL);
+}
+
+/* act_quant != 0: a scheme layer at b bits also reads its input activations at b bits (quantize_activations).
+ * acts (nullable): every node's output under every scheme, [S][N][sum of node outputs]. */
+int oracle_eval_schemes_aq(const int32_t *desc, int n_layers, const float *const *w, const float *const *bias,
+                           const float *images, int N, const uint8_t *schemes, int S, int L, int per_tensor,
+                           int act_quant, double *logits_base, int32_t *top1_base, double *logits, int32_t *top1,
+                           int32_t *agree, double *acts)
 {
     if (!desc || !w || !bias || !images || !schemes || !logits_base || !top1_base || !agree) return 1;
     if (N < 0 || S < 0) return 1;
@@ -403,14 +496,18 @@ int oracle_eval_schemes_ex(const int32_t *desc, int n_layers, const float *const
     rc = oracle_forward(desc, n_layers, w, bias, images, N, logits_base, top1_base, NULL, NULL);
     if (rc) return rc;
 
+    size_t acts_per = 0;
+    for (int l = 0; l < n_layers; ++l) acts_per += node_out_elems(desc + (size_t)l * N_FIELDS);
     for (int s = 0; s < S; ++s) {
         float **wq = (float **)calloc(n_layers, sizeof(float *));
+        int *ab = (int *)malloc(sizeof(int) * n_layers);
         for (int l = 0; l < n_layers; ++l) {
             const int32_t *d = desc + (size_t)l * N_FIELDS;
             int cout = d[F_COUT];
             int k = d[F_KIND] == KIND_FC ? d[F_CIN]
                     : (d[F_KIND] == KIND_DEPTHWISE ? 1 : d[F_CIN]) * d[F_KH] * d[F_KW];
             int bits = d[F_SLOT] >= 0 ? schemes[(size_t)s * L + d[F_SLOT]] : 32;
+            ab[l] = act_quant ? bits : 32;
             wq[l] = (float *)malloc(sizeof(float) * (size_t)cout * k);
             float *sc = (float *)malloc(sizeof(float) * cout);
             if (per_tensor)
@@ -425,7 +522,7 @@ int oracle_eval_schemes_ex(const int32_t *desc, int n_layers, const float *const
             double z[64];
             double *zp = logits ? logits + ((size_t)s * N + n) * ncls : z;
             forward_image(desc, n_layers, (const float *const *)wq, bias, images + (size_t)n * img_elems, zp,
-                          NULL);
+                          acts ? acts + ((size_t)s * N + n) * acts_per : NULL, ab);
             int32_t t = argmax(zp, ncls);
             if (top1) top1[(size_t)s * N + n] = t;
             count += (t == top1_base[n]);
@@ -433,6 +530,7 @@ int oracle_eval_schemes_ex(const int32_t *desc, int n_layers, const float *const
         agree[s] = count;
         for (int l = 0; l < n_layers; ++l) free(wq[l]);
         free(wq);
+        free(ab);
     }
     return 0;
 }
@@ -442,7 +540,7 @@ int oracle_conv_layer(const int32_t *d, const double *x, const float *w, const f
                       double *y, int64_t *macs)
 {
     if (!d || !x || !w || !bias || !y) return 1;
-    int64_t m = d[F_KIND] == KIND_FC ? fc_layer(d, x, w, bias, y) : conv_layer(d, x, w, bias, res, y);
+    int64_t m = d[F_KIND] == KIND_FC ? fc_layer(d, x, w, bias, y, 32) : conv_layer(d, x, w, bias, res, y);
     if (macs) *macs = m;
     return 0;
 }
