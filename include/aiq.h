@@ -85,6 +85,16 @@ typedef struct {
  */
 aiq_status aiq_layer_ai(const aiq_layer_desc *layers, int32_t n_layers, const uint8_t *scheme, int32_t L,
                         int32_t batch, double *flops_per_layer, double *bytes_per_layer, double *global_ai);
+/*
+ * The same for the variant in which a layer at b bits also reads its input activations at b bits
+ * (AIQ_MODEL_ACT_QUANT below; the paper's Problem Formulation gives a layer one bit-width and does not
+ * say what it covers).  act_quant = 1:
+ *   Bytes_l = n_weights_l * bits_l / 8 + batch * (in_elems_l * bits_l / 8 + 4 * out_elems_l);
+ * act_quant = 0 is aiq_layer_ai.  Errors as aiq_layer_ai; act_quant outside {0, 1}: INVALID_ARG.
+ */
+aiq_status aiq_layer_ai_ex(const aiq_layer_desc *layers, int32_t n_layers, const uint8_t *scheme, int32_t L,
+                           int32_t batch, int32_t act_quant, double *flops_per_layer, double *bytes_per_layer,
+                           double *global_ai);
 
 /*
  * Symmetric per-output-channel quantize -> dequantize of one weight matrix
@@ -128,8 +138,19 @@ aiq_status aiq_model_create(const aiq_layer_desc *layers, int32_t n_layers, cons
  * Same, with flags.  AIQ_MODEL_LAYERWISE: always run layer by layer through HBM, also for
  * graphs (CIFAR-style ResNets of 16/32/64 channels) whose activations would otherwise stay
  * in LDS for the whole network.  Both strategies compute the same function.
+ * AIQ_MODEL_PER_TENSOR: one quantization scale per layer instead of one per output channel.
+ * AIQ_MODEL_ACT_QUANT: activation fake-quantization (a variant; the paper's Problem Formulation gives a
+ * layer a bit-width and says nothing of activations).  A scheme layer at b < 32 bits reads its input
+ * tensor quantized to b bits by the weight rule with one scale per image, taken from that image's own
+ * tensor: amax = max |x|, s = amax / (2^(b-1)-1) (1 if the tensor is zero),
+ * x_q = clamp(round-half-even(x / s)) * s, each step one IEEE binary32 operation.  The residual input
+ * of a layer is added unquantized, layers outside every scheme read their input as it is, the
+ * classifier reads the pooled vector quantized.  Implies AIQ_MODEL_LAYERWISE.  The search drivers then
+ * count activation bytes at the layer's width (aiq_layer_ai_ex).  Rounding an activation is a
+ * discontinuity: two correct implementations whose activations differ in the last bit can assign
+ * neighbouring codes, so outputs of deep networks are compared layer by layer (aiq_forward_nodes).
  */
-enum { AIQ_MODEL_LAYERWISE = 1, AIQ_MODEL_PER_TENSOR = 2 };
+enum { AIQ_MODEL_LAYERWISE = 1, AIQ_MODEL_PER_TENSOR = 2, AIQ_MODEL_ACT_QUANT = 4 };
 aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, const float *const *w_host,
                                const float *const *bias_host, uint32_t flags, aiq_model **out);
 /* 1 if the model runs LDS-resident (one launch for the whole network), 0 if not, -1 for NULL. */
@@ -290,6 +311,22 @@ aiq_status aiq_sensitivity_workspace_bytes(const aiq_model *m, int32_t N, int32_
 aiq_status aiq_layer_sensitivity(aiq_model *m, const float *images, int32_t N, int32_t chunk, const uint8_t *bits,
                                  int32_t n_bits, void *workspace, size_t workspace_bytes, void *hip_stream,
                                  int32_t *agree_out);
+
+/*
+ * One scheme, every node's output (the forward pass of the scored model, paper: Introduction item (ii),
+ * opened up for inspection): runs scheme (HOST uint8 [L]) on N images layer by layer and leaves node l's
+ * output in node_out[l] (HOST array of aiq_model_nodes(m) DEVICE pointers, each fp32
+ * [N][aiq_node_output_elems(m, l)], NHWC; the last node's are the logits).  Lets a caller check any
+ * layer in isolation from the tensors it actually read, which is how results are compared where
+ * activation rounding makes end-to-end outputs discontinuous.  m must run layer by layer
+ * (AIQ_MODEL_LAYERWISE or AIQ_MODEL_ACT_QUANT; else UNSUPPORTED_LAYER).  workspace: device, 256-byte
+ * aligned, >= aiq_eval_workspace_bytes(m, 1, N).  Asynchronous on hip_stream.
+ * Errors: INVALID_ARG, UNSUPPORTED_BITS, UNSUPPORTED_LAYER, WORKSPACE_TOO_SMALL, DEVICE_ERROR.
+ */
+int32_t aiq_model_nodes(const aiq_model *m); /* -1 for NULL */
+aiq_status aiq_node_output_elems(const aiq_model *m, int32_t node, size_t *elems);
+aiq_status aiq_forward_nodes(aiq_model *m, const float *images, int32_t N, const uint8_t *scheme,
+                             float *const *node_out, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Deployed inference of one scheme (paper: Implementation, experiment (3); Results, Analysis of

@@ -7,6 +7,6 @@ the built library, or without a GPU, the device entry points raise.
 """
 from .binding import (  # noqa: F401
     AiqError, Model, Deployed, layer_ai, quantize_weights, library_path, load_library, EXPORTED_SYMBOLS,
-    K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV, K_CONV_CODES, MODEL_LAYERWISE, MODEL_PER_TENSOR,
+    K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV, K_CONV_CODES, MODEL_LAYERWISE, MODEL_PER_TENSOR, MODEL_ACT_QUANT,
     DEPLOY_FP32_MATRIX,
 )

@@ -11,7 +11,8 @@ _LIB_PATH = os.path.join(_HERE, "libaiq.so")
 _lib = None
 
 EXPORTED_SYMBOLS = (
-    "aiq_status_str", "aiq_last_hip_error", "aiq_layer_ai", "aiq_quantize_weights", "aiq_quantize_weights_ex", "aiq_model_create",
+    "aiq_status_str", "aiq_last_hip_error", "aiq_layer_ai", "aiq_layer_ai_ex", "aiq_model_nodes", "aiq_node_output_elems",
+    "aiq_forward_nodes", "aiq_quantize_weights", "aiq_quantize_weights_ex", "aiq_model_create",
     "aiq_model_create_ex", "aiq_model_is_lds_resident", "aiq_model_lds_resident_blocks", "aiq_model_destroy", "aiq_model_scheme_layers", "aiq_model_classes", "aiq_eval_workspace_bytes",
     "aiq_eval_schemes", "aiq_eval_schemes_noalloc", "aiq_eval_noalloc_workspace_bytes", "aiq_model_shares_prefix", "aiq_eval_shared_workspace_bytes", "aiq_eval_schemes_shared",
     "aiq_profile_enable", "aiq_profile_read", "aiq_search_workspace_bytes",
@@ -22,6 +23,7 @@ EXPORTED_SYMBOLS = (
 K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV, K_CONV_CODES = range(8)
 MODEL_LAYERWISE = 1
 MODEL_PER_TENSOR = 2
+MODEL_ACT_QUANT = 4
 DEPLOY_FP32_MATRIX = 1
 _DESC_INTS = 13
 
@@ -74,6 +76,12 @@ def load_library():
     lib.aiq_last_hip_error.restype = C.c_int32
     lib.aiq_layer_ai.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                  C.POINTER(C.c_double)]
+    lib.aiq_layer_ai_ex.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                    C.c_void_p, C.POINTER(C.c_double)]
+    lib.aiq_model_nodes.argtypes = [C.c_void_p]
+    lib.aiq_node_output_elems.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]
+    lib.aiq_forward_nodes.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                      C.c_void_p]
     lib.aiq_quantize_weights.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_void_p]
     lib.aiq_quantize_weights_ex.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
@@ -147,16 +155,21 @@ def _stream_ptr(stream):
     return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
 
 
-def layer_ai(desc, scheme, batch=1):
-    """aiq_layer_ai: returns (flops[n_layers], bytes[n_layers], global_ai).  Host only."""
+def layer_ai(desc, scheme, batch=1, act_quant=False):
+    """aiq_layer_ai / aiq_layer_ai_ex: returns (flops[n_layers], bytes[n_layers], global_ai).  Host only."""
     d = _desc(desc)
     sch = None if scheme is None else np.ascontiguousarray(scheme, dtype=np.uint8)
     flops = np.empty(d.shape[0], dtype=np.float64)
     byts = np.empty(d.shape[0], dtype=np.float64)
     ai = C.c_double(0.0)
-    st = load_library().aiq_layer_ai(d.ctypes.data, d.shape[0], None if sch is None else sch.ctypes.data,
-                                     0 if sch is None else sch.shape[0], int(batch), flops.ctypes.data,
-                                     byts.ctypes.data, C.byref(ai))
+    if act_quant:
+        st = load_library().aiq_layer_ai_ex(d.ctypes.data, d.shape[0], None if sch is None else sch.ctypes.data,
+                                            0 if sch is None else sch.shape[0], int(batch), 1, flops.ctypes.data,
+                                            byts.ctypes.data, C.byref(ai))
+    else:
+        st = load_library().aiq_layer_ai(d.ctypes.data, d.shape[0], None if sch is None else sch.ctypes.data,
+                                         0 if sch is None else sch.shape[0], int(batch), flops.ctypes.data,
+                                         byts.ctypes.data, C.byref(ai))
     _check(st, "aiq_layer_ai")
     return flops, byts, ai.value
 
@@ -186,7 +199,7 @@ def quantize_weights(w, bits, want_codes=True, stream=None, per_tensor=False):
 class Model:
     """Owns an aiq_model handle.  desc: int32 [n][13]; weights / biases: lists of fp32 numpy arrays."""
 
-    def __init__(self, desc, weights, biases, layerwise=False, per_tensor=False):
+    def __init__(self, desc, weights, biases, layerwise=False, per_tensor=False, act_quant=False):
         self._h = C.c_void_p(None)
         self._lib = load_library()
         d = _desc(desc)
@@ -198,7 +211,8 @@ class Model:
         wp = (C.c_void_p * n)(*[w.ctypes.data for w in ws])
         bp = (C.c_void_p * n)(*[b.ctypes.data for b in bs])
         h = C.c_void_p(None)
-        flags = (MODEL_LAYERWISE if layerwise else 0) | (MODEL_PER_TENSOR if per_tensor else 0)
+        flags = ((MODEL_LAYERWISE if layerwise else 0) | (MODEL_PER_TENSOR if per_tensor else 0) |
+                 (MODEL_ACT_QUANT if act_quant else 0))
         _check(self._lib.aiq_model_create_ex(d.ctypes.data, n, wp, bp, flags, C.byref(h)), "aiq_model_create_ex")
         self._h = h
         self.lds_resident = bool(self._lib.aiq_model_is_lds_resident(h))
@@ -301,6 +315,26 @@ class Model:
                                                    agree.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(stream))
             _check(st, "aiq_eval_schemes_shared")
         return dict(agree=agree[:S], top1_base=top1_base[:N], logits=logits, top1=top1)
+
+    def forward_nodes(self, images, scheme, stream=None):
+        """aiq_forward_nodes: one scheme (uint8 [L]) on images, every node's output.  Returns a list of CUDA fp32
+        tensors [N][elems] in node order (the last holds the logits), not synchronised."""
+        import torch
+        sch = np.ascontiguousarray(scheme, dtype=np.uint8)
+        if sch.shape != (self.L,):
+            raise AiqError(3, "aiq_forward_nodes: scheme length differs from the model's L")
+        N, dev = images.shape[0], images.device
+        n_nodes = int(self._lib.aiq_model_nodes(self._h))
+        outs = []
+        for l in range(n_nodes):
+            e = C.c_size_t(0)
+            _check(self._lib.aiq_node_output_elems(self._h, l, C.byref(e)), "aiq_node_output_elems")
+            outs.append(torch.empty((max(N, 1), e.value), dtype=torch.float32, device=dev))
+        ptrs = (C.c_void_p * n_nodes)(*[t.data_ptr() for t in outs])
+        ws = self._get_workspace(self.workspace_bytes(1, max(N, 1)), dev, stream)
+        _check(self._lib.aiq_forward_nodes(self._h, images.data_ptr(), N, sch.ctypes.data, ptrs, ws.data_ptr(),
+                                           ws.numel(), _stream_ptr(stream)), "aiq_forward_nodes")
+        return [t[:N] for t in outs]
 
     def noalloc_workspace_bytes(self, S, chunk):
         """aiq_eval_noalloc_workspace_bytes: (bytes a call would need, bytes the library's fixed array holds)."""

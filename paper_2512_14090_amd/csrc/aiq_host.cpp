@@ -82,6 +82,9 @@ struct aiq_model {
     // LDS-resident path (CIFAR-style ResNets)
     bool fused = false;
     bool per_tensor = false;       // one quantization scale per layer instead of one per output channel
+    bool act_quant = false;        // a layer at b bits also reads its input activations at b bits
+    size_t aq_elems = 0;           // largest input tensor of a scheme layer (per image)
+    float *aq_cur = nullptr;       // quantized-input buffer of the call in progress (part of its workspace)
     uint32_t *layer_amax = nullptr; // device: bit pattern of max |w| of every layer (per-tensor scales)
     int mb_blocks = 0;  // inverted-residual blocks run by the LDS-resident block kernel
     std::vector<FusedOp> fused_ops;
@@ -453,7 +456,7 @@ aiq_status dev_alloc(aiq_model *m, T **p, size_t n)
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WorkspaceLayout {
-    size_t schemes_off, top1_off, act_off, total;
+    size_t schemes_off, top1_off, act_off, aq_off, total;
     size_t buf_stride; // bytes of one activation buffer
     // prefix sharing only (0 otherwise): reference scheme, first op per scheme, the reference
     // pass's top-1, the checkpoint records of one chunk
@@ -471,6 +474,8 @@ WorkspaceLayout workspace_layout(const aiq_model *m, int S, int chunk, bool shar
     w.act_off = off;
     w.buf_stride = align_up(sizeof(float) * m->buf_elems * (size_t)(S + 1) * chunk, 256);
     off += w.buf_stride * m->n_bufs;
+    w.aq_off = off; // activation fake-quantization: the quantized copy of the input of the node being launched
+    if (m->act_quant) off += align_up(sizeof(float) * m->aq_elems * (size_t)(S + 1) * chunk, 256);
     if (shared && (m->fused_ckpt_floats > 0 || !m->fused)) {
         off = align_up(off, 256);
         w.ref_off = off;
@@ -533,7 +538,15 @@ int32_t aiq_last_hip_error(void) { return g_last_hip_error; }
 aiq_status aiq_layer_ai(const aiq_layer_desc *layers, int32_t n_layers, const uint8_t *scheme, int32_t L,
                         int32_t batch, double *flops_per_layer, double *bytes_per_layer, double *global_ai)
 {
+    return aiq_layer_ai_ex(layers, n_layers, scheme, L, batch, 0, flops_per_layer, bytes_per_layer, global_ai);
+}
+
+aiq_status aiq_layer_ai_ex(const aiq_layer_desc *layers, int32_t n_layers, const uint8_t *scheme, int32_t L,
+                           int32_t batch, int32_t act_quant, double *flops_per_layer, double *bytes_per_layer,
+                           double *global_ai)
+{
     if (!layers || n_layers <= 0 || batch < 1 || !global_ai || L < 0) return AIQ_INVALID_ARG;
+    if (act_quant != 0 && act_quant != 1) return AIQ_INVALID_ARG;
     // validate everything before writing anything
     for (int l = 0; l < n_layers; ++l) {
         const aiq_layer_desc &d = layers[l];
@@ -562,7 +575,8 @@ aiq_status aiq_layer_ai(const aiq_layer_desc *layers, int32_t n_layers, const ui
             out_e = ho * wo * d.cout;
         }
         const double f = 2.0 * batch * macs;
-        const double b = weights * bits / 8.0 + 4.0 * batch * (in_e + out_e);
+        const double in_bytes = act_quant ? in_e * bits / 8.0 : 4.0 * in_e;
+        const double b = weights * bits / 8.0 + batch * (in_bytes + 4.0 * out_e);
         if (flops_per_layer) flops_per_layer[l] = f;
         if (bytes_per_layer) bytes_per_layer[l] = b;
         total_flops += f;
@@ -647,7 +661,8 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
                                const float *const *bias_host, uint32_t flags, aiq_model **out)
 {
     if (out) *out = nullptr;
-    if (flags & ~(uint32_t)(AIQ_MODEL_LAYERWISE | AIQ_MODEL_PER_TENSOR)) return AIQ_INVALID_ARG;
+    if (flags & ~(uint32_t)(AIQ_MODEL_LAYERWISE | AIQ_MODEL_PER_TENSOR | AIQ_MODEL_ACT_QUANT)) return AIQ_INVALID_ARG;
+    if (flags & AIQ_MODEL_ACT_QUANT) flags |= AIQ_MODEL_LAYERWISE; // the quantized copy of a layer's input lives in memory
     if (!layers || n_layers <= 0 || !w_host || !bias_host || !out) return AIQ_INVALID_ARG;
     for (int l = 0; l < n_layers; ++l)
         if (!w_host[l] || !bias_host[l]) return AIQ_INVALID_ARG;
@@ -789,6 +804,9 @@ aiq_status aiq_model_create_ex(const aiq_layer_desc *layers, int32_t n_layers, c
         return fail(AIQ_DEVICE_ERROR);
     std::vector<int32_t> block_job;
     m->per_tensor = (flags & AIQ_MODEL_PER_TENSOR) != 0;
+    m->act_quant = (flags & AIQ_MODEL_ACT_QUANT) != 0;
+    for (const Node &nd : m->nodes)
+        if (m->act_quant && nd.d.scheme_slot >= 0 && nd.d.kind != 2) m->aq_elems = std::max(m->aq_elems, nd.in_elems);
     if (m->per_tensor && (st = dev_alloc(m, &m->layer_amax, (size_t)n_layers)) != AIQ_OK) return fail(st);
     for (int l = 0; l < n_layers; ++l) {
         Node &nd = m->nodes[l];
@@ -907,12 +925,37 @@ struct HeadOut {
 };
 
 // One node (or one LDS-resident block, at its expand node) for the schemes the launch covers.
-aiq_status launch_node(aiq_model *m, hipStream_t st, const HeadOut &ho, size_t l, const NodeIO &io, int n, int n0)
+aiq_status launch_node(aiq_model *m, hipStream_t st, const HeadOut &ho, size_t l, const NodeIO &io_in, int n, int n0)
 {
     const Node &nd = m->nodes[l];
     const aiq_layer_desc &d = nd.d;
-    const double work = (double)io.s_total * n;
+    const double work = (double)io_in.s_total * n;
     if (nd.mb_role == 2) return AIQ_OK; // computed by the block kernel launched at its expand node
+    if (m->act_quant && d.scheme_slot >= 0 && d.kind != 2) {
+        // the layer reads a copy of its input quantized at its own width (the classifier does the same to the
+        // pooled vector inside its kernel)
+        if (!m->aq_cur) return AIQ_INVALID_ARG;
+        ActQuantArgs q{};
+        q.in = io_in.in;
+        q.out = m->aq_cur;
+        q.schemes = io_in.schemes;
+        q.in_scheme_stride = io_in.in_stride;
+        q.out_scheme_stride = (size_t)n * nd.in_elems;
+        q.S = io_in.S;
+        q.L = m->L;
+        q.slot = d.scheme_slot;
+        q.N = n;
+        q.elems = (int32_t)nd.in_elems;
+        {
+            ProfScope ps(m, st, AIQ_K_QUANTIZE, 0.0, 8.0 * nd.in_elems * work);
+            AIQ_HIP(launch_act_quantize(q, io_in.s_total, st));
+        }
+    }
+    NodeIO io = io_in;
+    if (m->act_quant && d.scheme_slot >= 0 && d.kind != 2) {
+        io.in = m->aq_cur;
+        io.in_stride = (size_t)n * nd.in_elems;
+    }
     if (nd.mb_role == 1) {
         const Node &dwn = m->nodes[l + 1], &pjn = m->nodes[l + 2];
         MbArgs a{};
@@ -1066,6 +1109,7 @@ aiq_status launch_node(aiq_model *m, hipStream_t st, const HeadOut &ho, size_t l
         }
         a.top1_base = io.top1_base_out;
         a.row_map = io.row_map;
+        a.act_quant = m->act_quant ? 1 : 0;
         ProfScope ps(m, st, AIQ_K_HEAD, nd.flops_per_image * work, nd.act_bytes_per_image * work);
         AIQ_HIP(launch_head(a, io.s_total, st));
     }
@@ -1108,6 +1152,7 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
     char *ws = static_cast<char *>(workspace);
     uint8_t *schemes_dev = reinterpret_cast<uint8_t *>(ws + wl.schemes_off);
     int32_t *top1_tmp = reinterpret_cast<int32_t *>(ws + wl.top1_off);
+    m->aq_cur = m->act_quant ? reinterpret_cast<float *>(ws + wl.aq_off) : nullptr;
 
     // plan: which (layer, bit-width) bank slots this call reads
     QuantMask mask{};
@@ -1522,6 +1567,68 @@ aiq_status aiq_eval_schemes_shared(aiq_model *m, const float *images, int32_t N,
                      workspace, workspace_bytes, hip_stream);
 }
 
+// ---------------------------------------------------------------- one scheme, every node's output
+
+int32_t aiq_model_nodes(const aiq_model *m) { return m ? (int32_t)m->nodes.size() : -1; }
+
+aiq_status aiq_node_output_elems(const aiq_model *m, int32_t node, size_t *elems)
+{
+    if (!m || !elems || node < 0 || node >= (int32_t)m->nodes.size()) return AIQ_INVALID_ARG;
+    *elems = m->nodes[node].out_elems;
+    return AIQ_OK;
+}
+
+aiq_status aiq_forward_nodes(aiq_model *m, const float *images, int32_t N, const uint8_t *scheme,
+                             float *const *node_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!m || N < 0 || !node_out || (m->L > 0 && !scheme)) return AIQ_INVALID_ARG;
+    if (N > 0 && (!images || !workspace)) return AIQ_INVALID_ARG;
+    for (int i = 0; i < m->L; ++i)
+        if (!bits_supported(scheme[i])) return AIQ_UNSUPPORTED_BITS;
+    if (m->fused || m->mb_blocks > 0) return AIQ_UNSUPPORTED_LAYER;
+    for (const Node &nd : m->nodes)
+        if (nd.pooled) return AIQ_UNSUPPORTED_LAYER;
+    for (size_t l = 0; l < m->nodes.size(); ++l)
+        if (N > 0 && !node_out[l]) return AIQ_INVALID_ARG;
+    if (N == 0) return AIQ_OK;
+    const WorkspaceLayout wl = workspace_layout(m, 1, N);
+    if (workspace_bytes < wl.total) return AIQ_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return AIQ_INVALID_ARG;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char *ws = static_cast<char *>(workspace);
+    uint8_t *schemes_dev = reinterpret_cast<uint8_t *>(ws + wl.schemes_off);
+    if (m->L > 0) AIQ_HIP(upload_bytes(schemes_dev, scheme, (size_t)m->L, st));
+    // the layers read the weight bank: fill the slots this scheme uses
+    QuantMask mask{};
+    bool any = false;
+    for (const Node &nd : m->nodes) {
+        if (nd.d.scheme_slot < 0) continue;
+        const int bi = bits_index(scheme[nd.d.scheme_slot]);
+        if (bi > 0) {
+            const int ji = nd.job0 + bi - 1;
+            mask.word[ji >> 6] |= 1ull << (ji & 63);
+            any = true;
+        }
+    }
+    if (any) AIQ_HIP(launch_quantize_batch(m->jobs_dev, m->block_job_dev, m->n_quant_blocks, mask, st));
+    m->aq_cur = m->act_quant ? reinterpret_cast<float *>(ws + wl.aq_off) : nullptr;
+    const size_t last = m->nodes.size() - 1;
+    const HeadOut ho{node_out[last], N, nullptr, reinterpret_cast<int32_t *>(ws + wl.top1_off), N};
+    for (size_t l = 0; l < m->nodes.size(); ++l) {
+        const Node &nd = m->nodes[l];
+        NodeIO io{};
+        io.schemes = schemes_dev;
+        io.S = 1;
+        io.s_total = 1;
+        io.in = nd.d.input < 0 ? images : node_out[nd.d.input];
+        io.out = node_out[l];
+        io.res = nd.d.residual >= 0 ? node_out[nd.d.residual] : nullptr;
+        aiq_status rc = launch_node(m, st, ho, l, io, N, 0);
+        if (rc != AIQ_OK) return rc;
+    }
+    return AIQ_OK;
+}
+
 // ---------------------------------------------------------------- deployed inference
 
 struct aiq_deployed {
@@ -1585,7 +1692,7 @@ aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags
         if (nd.d.scheme_slot < 0) continue;
         const int bits = scheme[nd.d.scheme_slot], bi = bits_index(bits);
         if (bi == 0) continue;
-        const bool on_codes = !(flags & AIQ_DEPLOY_FP32_MATRIX) && bits <= 8 && nd.d.kind == 0 && nd.d.input >= 0 &&
+        const bool on_codes = !(flags & AIQ_DEPLOY_FP32_MATRIX) && !m->act_quant && bits <= 8 && nd.d.kind == 0 && nd.d.input >= 0 &&
                               nd.layout == kLayoutMfma && plan_code_conv(nd, d->layer[l].plan);
         if (on_codes) {
             const CodePlan &p = d->layer[l].plan;
@@ -1652,6 +1759,7 @@ aiq_status aiq_deploy_forward(aiq_deployed *d, const float *images, int32_t N, i
     hipStream_t st = (hipStream_t)hip_stream;
     char *ws = static_cast<char *>(workspace);
     auto buf_ptr = [&](int b) { return reinterpret_cast<float *>(ws + wl.act_off + wl.buf_stride * b); };
+    m->aq_cur = m->act_quant ? reinterpret_cast<float *>(ws + wl.aq_off) : nullptr;
     const HeadOut ho{logits, N, top1, nullptr, chunk};
     for (int n0 = 0; n0 < N; n0 += chunk) {
         const int n = std::min(chunk, N - n0);
@@ -1734,7 +1842,7 @@ struct SearchCtx {
     double ai(const uint8_t *q, aiq_status *err) const
     {
         double v = 0.0;
-        aiq_status st_ = aiq_layer_ai(layers, n_layers, q, L, p->batch, nullptr, nullptr, &v);
+        aiq_status st_ = aiq_layer_ai_ex(layers, n_layers, q, L, p->batch, m->act_quant ? 1 : 0, nullptr, nullptr, &v);
         if (st_ != AIQ_OK) *err = st_;
         return v;
     }

@@ -129,6 +129,17 @@ struct DepthwiseArgs {
     FastDiv div_c4;
 };
 
+// Activation fake-quantization of one node's input: every (scheme, image) tensor of `elems` floats gets one
+// symmetric scale from its own largest magnitude and is rewritten at the width the scheme gives the node.
+struct ActQuantArgs {
+    const float *in;           // [S?][N][elems]
+    float *out;                // [s_total][N][elems]
+    const uint8_t *schemes;
+    size_t in_scheme_stride, out_scheme_stride;
+    int32_t S, L, slot;        // launch indices >= S (the FP32 pass) and width 32 copy
+    int32_t N, elems;
+};
+
 struct HeadArgs {
     const float *in;           // [S][N][HW][C]
     const float *bias;         // [classes]
@@ -145,6 +156,7 @@ struct HeadArgs {
     int32_t *top1_base;        // the FP32 pass writes top1_base[n]; may be nullptr when there is none
     const int32_t *row_map;    // device: output row of launch index s, < 0 = the FP32 pass; nullptr: row s, and
                                // indices >= S are the FP32 pass
+    int32_t act_quant;         // 1: the pooled vector is quantized at the classifier's width before the matrix reads it
 };
 
 struct AgreeArgs {
@@ -168,6 +180,7 @@ hipError_t launch_conv_stem(const ConvArgs &a, int nt, dim3 grid, hipStream_t st
 hipError_t launch_pointwise(const PointwiseArgs &a, int nt, size_t lds_bytes, dim3 grid, hipStream_t st);
 hipError_t launch_depthwise(const DepthwiseArgs &a, int s_total, hipStream_t st);
 hipError_t launch_head(const HeadArgs &a, int s_total, hipStream_t st);
+hipError_t launch_act_quantize(const ActQuantArgs &a, int s_total, hipStream_t st);
 hipError_t launch_agree(const AgreeArgs &a, hipStream_t st);
 hipError_t launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t st);
 // Small host tables (schemes, row maps) to device memory as kernel arguments, 2 KB per launch: the bytes are

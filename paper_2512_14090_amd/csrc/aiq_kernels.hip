@@ -33,6 +33,26 @@ __device__ inline int scheme_bits_index(const uint8_t *schemes, int s, int S, in
     return bits_index(schemes[(size_t)s * L + slot]);
 }
 
+__device__ inline int bits_of_index(int bi)
+{
+    switch (bi) {
+    case 1: return 16;
+    case 2: return 8;
+    case 3: return 6;
+    case 4: return 4;
+    case 5: return 2;
+    default: return 32;
+    }
+}
+
+// One value through the quantizer: IEEE division, round half to even, clamp, one multiplication.
+__device__ inline float quantize_value(float x, float s, int qmax)
+{
+    int q = (int)rintf(__fdiv_rn(x, s));
+    q = min(max(q, -qmax), qmax);
+    return __fmul_rn((float)q, s);
+}
+
 __device__ inline float apply_act(float v, int act)
 {
     if (act >= 1) v = fmaxf(v, 0.0f);
@@ -982,6 +1002,60 @@ hipError_t launch_depthwise(const DepthwiseArgs &a, int s_total, hipStream_t st)
     return launch_depthwise_t<2, 1, 4, 8>(a, s_total, st);
 }
 
+// ------------------------------------------------------------------ activation fake-quantization
+//
+// Variant in which a layer at b bits also reads its input at b bits: one workgroup per (scheme, image)
+// tensor takes the tensor's largest magnitude (exact in any order), forms the scale and rewrites the
+// tensor by the weight rule - same arithmetic, step for step, as quantize_channel.  The quantized copy
+// goes to a buffer of its own, since other readers of the tensor (residual links, layers of another
+// width) see it as it is; the consuming kernel is launched on the copy.  The second pass over the
+// tensor comes from L2.
+
+__global__ __launch_bounds__(256) void act_quantize_kernel(ActQuantArgs a)
+{
+    __shared__ float wmax[4];
+    const int n = blockIdx.x, s = blockIdx.y, tid = threadIdx.x;
+    const float *x = a.in + (size_t)s * a.in_scheme_stride + (size_t)n * a.elems;
+    float *y = a.out + (size_t)s * a.out_scheme_stride + (size_t)n * a.elems;
+    const int bits = bits_of_index(scheme_bits_index(a.schemes, s, a.S, a.L, a.slot));
+    const bool vec = (a.elems & 3) == 0 && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) & 15) == 0;
+    const int n4 = vec ? a.elems >> 2 : 0;
+    const floatx4 *x4 = reinterpret_cast<const floatx4 *>(x);
+    floatx4 *y4 = reinterpret_cast<floatx4 *>(y);
+    if (bits == 32) {
+        for (int i = tid; i < n4; i += 256) y4[i] = x4[i];
+        for (int i = n4 * 4 + tid; i < a.elems; i += 256) y[i] = x[i];
+        return;
+    }
+    float amax = 0.0f;
+    for (int i = tid; i < n4; i += 256) {
+        const floatx4 v = x4[i];
+        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+    }
+    for (int i = n4 * 4 + tid; i < a.elems; i += 256) amax = fmaxf(amax, fabsf(x[i]));
+    amax = wave_max(amax);
+    if ((tid & 63) == 0) wmax[tid >> 6] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    const int qmax = (1 << (bits - 1)) - 1;
+    const float sc = amax > 0.0f ? __fdiv_rn(amax, (float)qmax) : 1.0f;
+    for (int i = tid; i < n4; i += 256) {
+        const floatx4 v = x4[i];
+        floatx4 d;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) d[e] = quantize_value(v[e], sc, qmax);
+        y4[i] = d;
+    }
+    for (int i = n4 * 4 + tid; i < a.elems; i += 256) y[i] = quantize_value(x[i], sc, qmax);
+}
+
+hipError_t launch_act_quantize(const ActQuantArgs &a, int s_total, hipStream_t st)
+{
+    if (a.N == 0 || s_total == 0 || a.elems == 0) return hipSuccess;
+    hipLaunchKernelGGL(act_quantize_kernel, dim3(a.N, s_total), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ classifier head
 //
 // One workgroup per (scheme, image): global average pool, the classes x C matrix,
@@ -1035,6 +1109,22 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
         }
     }
     __syncthreads();
+
+    // activation fake-quantization: the pooled vector is rewritten at the classifier's width (one scale
+    // for the vector) before the matrix reads it
+    const int act_bits = a.act_quant ? bits_of_index(scheme_bits_index(a.schemes, s, a.S, a.L, a.slot)) : 32;
+    if (act_bits != 32) { // uniform over the workgroup
+        float amax = 0.0f;
+        for (int c = tid; c < a.C; c += 256) amax = fmaxf(amax, fabsf(pooled[c]));
+        amax = wave_max(amax);
+        if (lane == 0) partial[wave] = amax; // the partial-sum area is free again
+        __syncthreads();
+        amax = fmaxf(fmaxf(partial[0], partial[1]), fmaxf(partial[2], partial[3]));
+        const int qmax = (1 << (act_bits - 1)) - 1;
+        const float sc = amax > 0.0f ? __fdiv_rn(amax, (float)qmax) : 1.0f;
+        for (int c = tid; c < a.C; c += 256) pooled[c] = quantize_value(pooled[c], sc, qmax);
+        __syncthreads();
+    }
 
     // output row of this launch index: itself, unless the caller maps it; < 0 = the FP32 pass
     const int row = a.row_map ? a.row_map[s] : (s < a.S ? s : -1);

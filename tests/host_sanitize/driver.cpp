@@ -187,6 +187,30 @@ static void run_library(const Graph &g, uint32_t flags, std::mt19937 &rng)
         EXPECT(total > 0);
         EXPECT(aiq_profile_enable(m, 0) == AIQ_OK);
     }
+    // one scheme, every node's output (models that run layer by layer)
+    {
+        const int n_nodes = aiq_model_nodes(m);
+        EXPECT(n_nodes == n_layers);
+        std::vector<Buf *> outs;
+        std::vector<float *> ptrs;
+        for (int l = 0; l < n_nodes; ++l) {
+            size_t e = 0;
+            EXPECT(aiq_node_output_elems(m, l, &e) == AIQ_OK && e > 0);
+            outs.push_back(new Buf(sizeof(float) * e * 4));
+            ptrs.push_back(static_cast<float *>(outs.back()->p));
+        }
+        size_t need = 0;
+        EXPECT(aiq_eval_workspace_bytes(m, 1, 4, &need) == AIQ_OK);
+        Buf ws(need);
+        st = aiq_forward_nodes(m, f(images), 4, schemes.data(), ptrs.data(), ws.p, need, nullptr);
+        const bool layer_by_layer = (flags & (AIQ_MODEL_LAYERWISE | AIQ_MODEL_ACT_QUANT)) != 0 ||
+                                    (!aiq_model_is_lds_resident(m) && aiq_model_lds_resident_blocks(m) == 0);
+        EXPECT(layer_by_layer ? (st == AIQ_OK || st == AIQ_UNSUPPORTED_LAYER) : st == AIQ_UNSUPPORTED_LAYER);
+        if ((flags & (AIQ_MODEL_LAYERWISE | AIQ_MODEL_ACT_QUANT)) != 0) EXPECT(st == AIQ_OK);
+        if (need > 1)
+            EXPECT(aiq_forward_nodes(m, f(images), 4, schemes.data(), ptrs.data(), ws.p, need - 1, nullptr) != AIQ_OK);
+        for (Buf *b : outs) delete b;
+    }
     // deployed inference (models that run layer by layer only; the others are refused)
     for (int variant = 0; variant < 3; ++variant) {
         std::vector<uint8_t> q(L, 8);
@@ -194,7 +218,8 @@ static void run_library(const Graph &g, uint32_t flags, std::mt19937 &rng)
             for (int i = 0; i < L; ++i) q[i] = kBits[rng() % 6];
         aiq_deployed *dep = nullptr;
         st = aiq_deploy_create(m, q.data(), variant == 2 ? AIQ_DEPLOY_FP32_MATRIX : 0, &dep);
-        if (aiq_model_is_lds_resident(m) || aiq_model_lds_resident_blocks(m) > 0 || !(flags & AIQ_MODEL_LAYERWISE)) {
+        if (aiq_model_is_lds_resident(m) || aiq_model_lds_resident_blocks(m) > 0 ||
+            !(flags & (AIQ_MODEL_LAYERWISE | AIQ_MODEL_ACT_QUANT))) {
             if (st != AIQ_OK) {
                 EXPECT(st == AIQ_UNSUPPORTED_LAYER && !dep);
                 continue;
@@ -268,7 +293,7 @@ int main(int argc, char **argv)
         Graph g = make_graph(fields.data(), n, rng);
         const long before = aiq_stub_launch_count();
         for (uint32_t flags : {0u, (uint32_t)AIQ_MODEL_LAYERWISE, (uint32_t)AIQ_MODEL_PER_TENSOR,
-                               (uint32_t)(AIQ_MODEL_LAYERWISE | AIQ_MODEL_PER_TENSOR)})
+                               (uint32_t)(AIQ_MODEL_LAYERWISE | AIQ_MODEL_PER_TENSOR), (uint32_t)AIQ_MODEL_ACT_QUANT})
             run_library(g, flags, rng);
         if (oracle_images > 0) run_oracle(g, rng, oracle_images);
         std::printf("graph %d: %d layers, L = %d, %ld launches planned, failures so far %d\n", gi, n, g.L,

@@ -246,6 +246,17 @@ hipError_t launch_head(const HeadArgs &a, int s_total, hipStream_t)
     return hipSuccess;
 }
 
+hipError_t launch_act_quantize(const ActQuantArgs &a, int s_total, hipStream_t)
+{
+    ++g_launches;
+    touch_schemes(a.schemes, a.S, a.L);
+    for (int s = 0; s < s_total; ++s) {
+        touch_read(a.in + s * a.in_scheme_stride, (size_t)a.N * a.elems);
+        touch_write(a.out + s * a.out_scheme_stride, (size_t)a.N * a.elems);
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_agree(const AgreeArgs &a, hipStream_t)
 {
     ++g_launches;

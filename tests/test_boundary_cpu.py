@@ -53,6 +53,12 @@ def test_layer_ai_matches_oracle(aiq, builder):
             np.testing.assert_array_equal(f, rf)
             np.testing.assert_array_equal(b, rb)
             assert ai == rai
+            # the variant that counts input activations at the layer's width
+            f, b, ai = aiq.layer_ai(desc, scheme, batch, act_quant=True)
+            rf, rb, rai = oracle.layer_ai(desc, scheme, batch, act_quant=True)
+            np.testing.assert_array_equal(f, rf)
+            np.testing.assert_array_equal(b, rb)
+            assert ai == rai
 
 
 def test_layer_ai_errors_leave_outputs_untouched(aiq):
