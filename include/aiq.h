@@ -340,8 +340,12 @@ aiq_status aiq_forward_nodes(aiq_model *m, const float *images, int32_t N, const
  * times slower.  Results agree with aiq_eval_schemes to fp32 rounding (the accumulation order
  * differs and the scale multiplies the finished sum).  All other layers run on the fp32 kernels.
  *
- * aiq_deploy_create: m must have been created with AIQ_MODEL_LAYERWISE (else UNSUPPORTED_LAYER)
- * and must outlive the deployment; scheme: host uint8[L].  flags: AIQ_DEPLOY_FP32_MATRIX keeps
+ * aiq_deploy_create: m must outlive the deployment; scheme: host uint8[L].  A model that keeps its
+ * activations in LDS (created without AIQ_MODEL_LAYERWISE: CIFAR-style ResNets, inverted-residual
+ * blocks) is deployed on those kernels - the scheme runs as the single candidate of a scoring
+ * call, bit-identical to aiq_eval_schemes, at the FP32 model's own rate: for such models that is
+ * faster than any layer-by-layer path, and three bf16 planes per activation do not fit their LDS
+ * budget (aiq_deploy_code_layers is then 0).  Integer-code layers need AIQ_MODEL_LAYERWISE.  flags: AIQ_DEPLOY_FP32_MATRIX keeps
  * every layer on the fp32 kernels (the same model without the bf16 path, for comparison).
  * Quantizes and packs the weights; allocates device memory (codes and scales), freed by
  * aiq_deploy_destroy.  Synchronous.  It fills weight-bank slots of m: do not overlap it with

@@ -1122,11 +1122,14 @@ aiq_status launch_node(aiq_model *m, hipStream_t st, const HeadOut &ho, size_t l
 aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t *schemes, int32_t S,
                      const uint8_t *ref, int32_t chunk, int32_t *top1_base, int32_t base_valid, float *logits,
                      int32_t *top1, int32_t *agree, void *workspace, size_t workspace_bytes, void *hip_stream,
-                     CkptCache *cache = nullptr)
+                     CkptCache *cache = nullptr, bool want_agree = true)
 {
+    // want_agree = false (deployed inference of one scheme): no agreement count, no FP32 reference;
+    // agree and top1_base may then be null and base_valid must be 1
     if (!m || N < 0 || S < 0 || chunk < 1) return AIQ_INVALID_ARG;
-    if (S > 0 && (!schemes || !agree)) return AIQ_INVALID_ARG;
-    if (N > 0 && (!images || !top1_base || !workspace)) return AIQ_INVALID_ARG;
+    if (S > 0 && (!schemes || (want_agree && !agree))) return AIQ_INVALID_ARG;
+    if (N > 0 && (!images || (want_agree && !top1_base) || !workspace)) return AIQ_INVALID_ARG;
+    if (!want_agree && base_valid != 1) return AIQ_INVALID_ARG;
     if (base_valid != 0 && base_valid != 1) return AIQ_INVALID_ARG;
     if (S + 1 > 65535) return AIQ_INVALID_ARG; // the scheme axis (plus the FP32 pass) is a grid y / z extent
     for (size_t i = 0; i < (size_t)S * m->L; ++i)
@@ -1143,7 +1146,7 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
     if (N > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255)) return AIQ_INVALID_ARG;
 
     hipStream_t st = (hipStream_t)hip_stream;
-    if (S > 0) AIQ_HIP(launch_fill_i32(agree, 0, (size_t)S, st));
+    if (S > 0 && want_agree) AIQ_HIP(launch_fill_i32(agree, 0, (size_t)S, st));
     if (N == 0) return AIQ_OK;
     const bool run_base = base_valid == 0;
     const int s_total = S + (run_base ? 1 : 0);
@@ -1379,15 +1382,17 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
                              work * 4.0 * (m->nodes[0].in_elems + m->classes));
                 AIQ_HIP(launch_fused(a, s_total, kFusedPlain, st));
             }
-            AgreeArgs g{};
-            g.top1 = a.top1;
-            g.top1_stride = a.top1_stride;
-            g.top1_base = top1_base + n0;
-            g.agree = agree;
-            g.N = n;
-            g.S = S;
-            ProfScope ps(m, st, AIQ_K_AGREE, 0.0, 8.0 * S * n);
-            AIQ_HIP(launch_agree(g, st));
+            if (want_agree) {
+                AgreeArgs g{};
+                g.top1 = a.top1;
+                g.top1_stride = a.top1_stride;
+                g.top1_base = top1_base + n0;
+                g.agree = agree;
+                g.N = n;
+                g.S = S;
+                ProfScope ps(m, st, AIQ_K_AGREE, 0.0, 8.0 * S * n);
+                AIQ_HIP(launch_agree(g, st));
+            }
             continue;
         }
         if (!share_nodes) {
@@ -1493,7 +1498,7 @@ aiq_status eval_impl(aiq_model *m, const float *images, int32_t N, const uint8_t
                 }
             }
         }
-        if (S > 0) {
+        if (S > 0 && want_agree) {
             AgreeArgs g{};
             g.top1 = top1 ? top1 + n0 : top1_tmp;
             g.top1_stride = top1 ? N : chunk;
@@ -1643,6 +1648,7 @@ struct aiq_deployed {
     std::vector<Layer> layer; // per node
     std::vector<void *> allocations;
     int n_code_layers = 0;
+    bool resident = false; // the model keeps activations in LDS: the scheme runs on those kernels
 };
 
 void aiq_deploy_destroy(aiq_deployed *d)
@@ -1660,15 +1666,24 @@ aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags
     if (!m || !out || (m->L > 0 && !scheme) || (flags & ~(uint32_t)AIQ_DEPLOY_FP32_MATRIX)) return AIQ_INVALID_ARG;
     for (int i = 0; i < m->L; ++i)
         if (!bits_supported(scheme[i])) return AIQ_UNSUPPORTED_BITS;
-    if (m->fused || m->mb_blocks > 0) return AIQ_UNSUPPORTED_LAYER;
-    for (const Node &nd : m->nodes)
-        if (nd.pooled) return AIQ_UNSUPPORTED_LAYER;
+    bool resident = m->fused || m->mb_blocks > 0;
+    for (const Node &nd : m->nodes) resident = resident || nd.pooled;
 
     aiq_deployed *d = new (std::nothrow) aiq_deployed();
     if (!d) return AIQ_INVALID_ARG;
     d->m = m;
     d->scheme.assign(scheme, scheme + m->L);
     d->layer.resize(m->nodes.size());
+    if (resident) {
+        // A model whose activations stay in LDS (whole CIFAR-style ResNets, inverted-residual blocks) is
+        // deployed on those kernels, the scheme being the one "candidate" of a scoring call: the integer-code
+        // kernels work layer by layer through HBM and are slower than that for such models, and three bf16
+        // planes per activation do not fit the LDS budget of the resident kernels.  Nothing to prepare: the
+        // weight bank slots are filled by the forward call.
+        d->resident = true;
+        *out = d;
+        return AIQ_OK;
+    }
     auto fail = [&](aiq_status code) {
         aiq_deploy_destroy(d);
         return code;
@@ -1741,7 +1756,7 @@ aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags
 aiq_status aiq_deploy_workspace_bytes(const aiq_deployed *d, int32_t chunk, size_t *bytes)
 {
     if (!d || !bytes || chunk < 1) return AIQ_INVALID_ARG;
-    *bytes = workspace_layout(d->m, 0, chunk).total;
+    *bytes = workspace_layout(d->m, d->resident ? 1 : 0, chunk).total;
     return AIQ_OK;
 }
 
@@ -1753,6 +1768,9 @@ aiq_status aiq_deploy_forward(aiq_deployed *d, const float *images, int32_t N, i
     if (N == 0) return AIQ_OK;
     aiq_model *m = d->m;
     chunk = std::min(chunk, N);
+    if (d->resident)
+        return eval_impl(m, images, N, d->scheme.data(), 1, nullptr, chunk, nullptr, 1, logits, top1, nullptr, workspace,
+                         workspace_bytes, hip_stream, nullptr, false);
     const WorkspaceLayout wl = workspace_layout(m, 0, chunk);
     if (workspace_bytes < wl.total) return AIQ_WORKSPACE_TOO_SMALL;
     if (reinterpret_cast<uintptr_t>(workspace) & 255) return AIQ_INVALID_ARG;

@@ -191,8 +191,33 @@ def test_empty_and_errors(env):
         aiq.Deployed(m, np.full(L + 1, 8, np.uint8))
     assert e.value.code == 3
     m.close()
-    m2 = aiq.Model(wl["desc"], wl["weights"], wl["biases"])  # LDS-resident: not deployable layer by layer
-    with pytest.raises(aiq.AiqError) as e:
-        aiq.Deployed(m2, np.full(L, 8, np.uint8))
-    assert e.value.code == 6
-    m2.close()
+
+
+@pytest.mark.parametrize("index,n,chunk", [(0, 37, 16), (1, 24, 24), (3, 5, 3)])
+def test_lds_resident_models_deploy_on_their_own_kernels(env, index, n, chunk):
+    """A model that keeps its activations in LDS is deployed on those kernels: same bits as scoring the scheme,
+    parity with the oracle, no integer-code layers."""
+    torch, aiq, oracle = env["torch"], env["aiq"], env["oracle"]
+    wl = env["synth"].make_workload(index, n_images=n)
+    L = wl["L"]
+    rng = np.random.Generator(np.random.PCG64(90 + index))
+    schemes = [np.full(L, 8, np.uint8), rng.choice(np.array([32, 16, 8, 6, 4, 2], np.uint8), size=L), np.full(L, 32, np.uint8)]
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    assert m.lds_resident or m.lds_resident_blocks > 0
+    img = torch.from_numpy(wl["images"]).cuda()
+    ref = oracle.eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], np.stack(schemes))
+    scored = m.eval_schemes(img, np.stack(schemes), chunk=chunk, want_logits=True, want_top1=True)
+    torch.cuda.synchronize()
+    for i, q in enumerate(schemes):
+        d = aiq.Deployed(m, q)
+        assert d.code_layers == 0
+        out = d.forward(img, chunk=chunk, want_logits=True)
+        torch.cuda.synchronize()
+        assert torch.equal(out["logits"].view(torch.int32), scored["logits"][i].view(torch.int32))
+        assert torch.equal(out["top1"], scored["top1"][i])
+        assert logits_rel_error(out["logits"].cpu().numpy(), ref["logits"][i]) <= 1e-3
+        only_top1 = d.forward(img[:3], chunk=2)
+        torch.cuda.synchronize()
+        assert torch.equal(only_top1["top1"], scored["top1"][i][:3]) and only_top1["logits"] is None
+        d.close()
+    m.close()
