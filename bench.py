@@ -19,42 +19,45 @@ PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_BF16_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 
 # HBM bytes per launch of a kernel class from rocprofv3 counters (FETCH_SIZE x 2.000 and
-# WRITE_SIZE x 1.000, the factors a plain copy of known size gives; profiles/ has the runs).
+# WRITE_SIZE x 1.000, the factors a plain copy of known size gives; profiles/ has the runs): every
+# counter run taken is listed, `traffic` reports their mean and `traffic_min_max` their range.
 # Valid only for the kernel source it was measured on: keyed by the sha256 of that source (of the
 # sections of it that hold the kernel, where the file holds several).
 TRAFFIC = {
     ("resnet20_greedy_step_n1024_s40", "resnet_fused"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_fused.hip",
         "sha256": "56d1c2d483b20bd9b6d21cb09afec8e50edc7f4cc62b2032687c978bf27bee5e",
-        "bytes_per_launch": 62087680,
+        # six counter runs of the same source on four boxes (the first two known to 0.1 MB only): the weights'
+        # share of L2 misses varies from box to box; the images, 12.6 MB, are the floor
+        "bytes_per_launch_runs": [47800000, 48600000, 62087680, 105634176, 105667114, 105651221],
     },
     ("mobilenetv2_32_n512_s16", "mbconv"): {  # average over the 16 block launches of a step
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_mbconv.hip",
         "sha256": "e02a1f9407b013c8cf925ecbd3f4b3a8ad76bfb5683fbc093d4c6f4f10930233",
-        "bytes_per_launch": 1789082922,
+        "bytes_per_launch_runs": [1788612801, 1788065468, 1789082922],
     },
     ("mobilenetv2_32_n512_s16", "depthwise"): {  # layer by layer: average over the 17 depthwise launches
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
         "sections": ["helpers", "depthwise 3x3"],
-        "sha256": "040711c3eb32c64180a31d22474f57a158017a5ae53563812ff47f6dd63a8e60",
-        "bytes_per_launch": 7834003484,
+        "sha256": "65811df1a1b5452d5d11f3b4e797f798c05cb93645dcd9e8884274c408d78a46",
+        "bytes_per_launch_runs": [7861221648, 7861235939],
     },
     ("plainconvnet20_sensitivity_n256_s42", "conv_mfma"): {  # average over the 20 convolution launches of a step
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
         "sections": ["helpers", "dense convolution", "network stems"],
-        "sha256": "a7526213d5d9f3f925369b0a6a961a1088b8de29e471f53501d974fe8ecafab6",
-        "bytes_per_launch": 2694684770,
+        "sha256": "94a0512bc46511dd3bfcf6789a765a570fd919620254a258a93e5a2b169d7fae",
+        "bytes_per_launch_runs": [2694850414, 2694908681, 2694684770],
     },
     ("plainconvnet20_deploy_n2048", "conv_codes"): {  # average over the 19 launches of one deployed forward pass
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_deploy.hip",
         "sha256": "d300d3db0c2df217244dcabcd424076616bcaeaf412946c01c4578ba0d456635",
-        "bytes_per_launch": 496839411,
+        "bytes_per_launch_runs": [496839411],
     },
     ("quantize_stress_8192x4608_b8", "quantize"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
         "sections": ["helpers", "quantizer"],
-        "sha256": "6f555449544557c2da2d7e546baf7f5ac38bafb9683b015970fcafded6b2df5c",
-        "bytes_per_launch": 302327530,
+        "sha256": "93092566ed5a9d4c46dfca168d09eaa2ddd328d0f6d3107318b4136c841d7208",
+        "bytes_per_launch_runs": [302333420, 302333492],
     },
 }
 
@@ -77,12 +80,22 @@ def source_hash(path, sections=None):
 
 
 def measured_traffic(workload_name, cls):
+    """Mean of the counter runs taken for this kernel and workload (bytes per launch), or None."""
     rec = TRAFFIC.get((workload_name, cls))
     if not rec:
         return None
     if source_hash(rec["kernel_source"], rec.get("sections")) != rec["sha256"]:
         return None  # the kernel changed since the counters were taken
-    return rec["bytes_per_launch"]
+    runs = rec["bytes_per_launch_runs"]
+    return int(sum(runs) / len(runs))
+
+
+def traffic_min_max(workload_name, cls):
+    """[smallest, largest] of the counter runs behind measured_traffic, or None."""
+    if measured_traffic(workload_name, cls) is None:
+        return None
+    runs = TRAFFIC[(workload_name, cls)]["bytes_per_launch_runs"]
+    return [int(min(runs)), int(max(runs))]
 
 
 def cpu_baseline(wl, budget_schemes=8, budget_images=192):
@@ -219,6 +232,7 @@ def stress_quantize(args, torch, aiq):
             "roofline": {"bound": "hbm", "kernel": "quantize_rows_kernel (row in registers, one read and one write per weight)",
                          "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
                          "traffic": measured_traffic(f"quantize_stress_{cout}x{k}_b8", "quantize"),
+                         "traffic_min_max": traffic_min_max(f"quantize_stress_{cout}x{k}_b8", "quantize"),
                          "algorithmic_gbytes_per_launch": nbytes / 1e9, "avg_launch_ms": ms}}
     print(json.dumps(line))
 
@@ -366,6 +380,7 @@ def deploy_mode(args, torch, aiq, synth):
                             "achieved": kc["executed_bf16_tflops"], "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
                             "frac": kc["frac_of_bf16_peak"],
                             "traffic": measured_traffic(line["config"]["workload"], "conv_codes"),
+                            "traffic_min_max": traffic_min_max(line["config"]["workload"], "conv_codes"),
                             "algorithmic_gbytes_per_launch": kc["algorithmic_gbytes_per_s"] * kc["avg_launch_ms"] / 1e3,
                             "avg_launch_ms": kc["avg_launch_ms"],
                             "hbm": {"achieved": kc["algorithmic_gbytes_per_s"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -389,6 +404,7 @@ def print_hbm_line(args, wl, model, S, N, L, chunk, dt, agree, prof, cls):
                        "lds_resident_blocks": int(model.lds_resident_blocks)},
             "roofline": {"bound": "hbm", "kernel": label, "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": gbs / PEAK_HBM_GBS, "traffic": measured_traffic(wl["name"], cls),
+                         "traffic_min_max": traffic_min_max(wl["name"], cls),
                          "launches": k["launches"],
                          "avg_launch_ms": k["total_ms"] / max(k["launches"], 1),
                          "algorithmic_gbytes_per_launch": k["bytes"] / max(k["launches"], 1) / 1e9},
@@ -494,7 +510,7 @@ def main():
     roofline = {"bound": "mfma", "kernel": label,
                 "achieved": achieved, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_MFMA_F32_TFLOPS,
-                "traffic": measured_traffic(wl["name"], dom),
+                "traffic": measured_traffic(wl["name"], dom), "traffic_min_max": traffic_min_max(wl["name"], dom),
                 "launches": conv["launches"], "avg_launch_ms": conv["total_ms"] / max(conv["launches"], 1),
                 "algorithmic_gflop_per_launch": conv["flops"] / max(conv["launches"], 1) / 1e9,
                 "algorithmic_gbytes_per_launch": conv["bytes"] / max(conv["launches"], 1) / 1e9}
