@@ -93,8 +93,8 @@ hipError_t launch_pack_codes(const int32_t *codes, uint16_t *out, int cout, int 
 // LDS so that the NHWC stores cover whole lines.
 //
 // Workgroup = 4 wavefronts; per pass of CKC channels it stages in LDS the input rows of its
-// region, already split (per pixel three planes - hi, mid, lo - of CKC bf16 channels), and the
-// codes of its output-channel tiles for those channels.  A wavefront owns 32*MT pixels x 32*NT
+// region, already split (per pixel and eight-channel unit three neighbouring 16-byte pieces - hi,
+// mid, lo - of bf16 values), and the codes of its output-channel tiles for those channels.  A wavefront owns 32*MT pixels x 32*NT
 // output channels (MT = 2; 1 for layers of at most 32 output channels: short workgroups whose
 // fixed latencies only more workgroups in flight can cover - four per compute unit) and issues, per tap and block of 16 channels,
 // MT * NT * 3 MFMAs from 3 * MT + NT 16-byte LDS reads.
@@ -152,7 +152,7 @@ __device__ __forceinline__ void stage_plan(const CodeConvArgs &a, StageItems<kSt
             const int col = rem >> c8shift, c8 = rem & (c8n - 1);
             const int g = (int)fd_div((uint32_t)row, a.div_rin);
             const int iy = iy0 + row - g * a.RIN, ix = col - PAD;
-            it.dst[i] = (row * a.LW + col) * 3 * a.PSU + c8;
+            it.dst[i] = (row * a.LW + col) * 3 * a.PSU + c8 * 3;
             if ((unsigned)iy < (unsigned)a.Hin && (unsigned)ix < (unsigned)a.Win && g < g_lim)
                 it.src[i] = ((g * a.Hin + iy) * a.Win + ix) * a.Cin + c8 * 8;
         }
@@ -214,13 +214,14 @@ __device__ __forceinline__ void stage_store(const CodeConvArgs &a, const StageIt
         }
         uintx4 *d = lds4 + it.dst[i];
         d[0] = uintx4{pack2(hi[0], hi[1]), pack2(hi[2], hi[3]), pack2(hi[4], hi[5]), pack2(hi[6], hi[7])};
-        d[a.PSU] = uintx4{pack2(mid[0], mid[1]), pack2(mid[2], mid[3]), pack2(mid[4], mid[5]), pack2(mid[6], mid[7])};
-        d[2 * a.PSU] = uintx4{pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(lo[4], lo[5]), pack2(lo[6], lo[7])};
+        d[1] = uintx4{pack2(mid[0], mid[1]), pack2(mid[2], mid[3]), pack2(mid[4], mid[5]), pack2(mid[6], mid[7])};
+        d[2] = uintx4{pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(lo[4], lo[5]), pack2(lo[6], lo[7])};
         __builtin_amdgcn_sched_barrier(0); // one item's 24 temporaries at a time: the accumulators are live here
     }
 }
 
-template <int KS, int STRIDE, int NT, int KI, int MT>
+// ONE: every pass stages a single block of 16 channels (CKC == 16)
+template <int KS, int STRIDE, int NT, int KI, int MT, bool ONE>
 __global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : (MT == 1 ? 4 : 3)) void conv_codes_kernel(CodeConvArgs a)
 {
     constexpr int kStageItems = KI;
@@ -258,7 +259,7 @@ __global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : (MT == 1 ? 4 : 3)) 
         const uint32_t oy = fd_div(rem, a.div_wout);
         const uint32_t ox = rem - oy * a.Wout;
         const bool in_region = g < (uint32_t)a.G; // lanes past the region's last pixel compute nothing useful
-        lds_base[m] = in_region ? ((g * a.RIN + oy * STRIDE) * a.LW + ox * STRIDE) * pix_units + kh : kh;
+        lds_base[m] = in_region ? ((g * a.RIN + oy * STRIDE) * a.LW + ox * STRIDE) * pix_units + kh * 3 : kh * 3;
     }
 
     floatx16 acc[MT][NT];
@@ -298,59 +299,98 @@ __global__ __launch_bounds__(256, KI > kCodeStageItems ? 2 : (MT == 1 ? 4 : 3)) 
         if (c0 + a.CKC < a.CB * 16) stage_fetch(a, items, staged, in0, c0 + a.CKC, c8shift, n_items, tid);
 
         {
-            // One flat sequence of (tap, channel block) steps, channel block fastest.  The operands of
-            // step k+1 are read from LDS during step k: the codes into a second register set, the
-            // activations plane by plane into the set in use, each plane as soon as the MFMAs that
-            // read it have been issued.  Both LDS addresses advance by increments; the last step
-            // reads its own operands again instead of running past the end.  (Wavefronts without an
-            // output tile of their own run the loop on the last tile and store nothing.)
-            const int steps = T * ncb;
-            const int w_tap_step = (ncbf - ncb + 1) * 64; // last block of a tap -> first block of the next
-            int woff = a.code_off + (wco * NT * T * ncbf) * 64 + lane, wc = 0;
-            const int a_tap_step = pix_units - (ncb - 1) * 2, a_row_step = (a.LW - KS) * pix_units;
-            int tapoff = 0, ac = 0, akx = 0; // activations: LDS offset of the step's tap and block
+            // The reduction runs over (tap, channel block) steps, channel block fastest.  The operands of
+            // the next step are read from LDS during the current one: the codes into a second register
+            // set, the activations plane by plane into the set in use, each plane as soon as the MFMAs
+            // that read it have been issued.  The taps are unrolled, so which increment takes a lane's
+            // two kinds of LDS address to the next step (next block, next tap, next window row) is one
+            // scalar select on "last block of the tap"; the three planes of an eight-channel unit are
+            // neighbours, so they are reached by immediate offsets.  The last step reads its own
+            // operands again instead of running past the end.  (Wavefronts without an output tile of
+            // their own run the loop on the last tile and store nothing.)
+            // (addresses below are byte offsets into LDS)
+            const int w_tap_step = (ncbf - ncb + 1) * 1024; // last block of a tap -> first block of the next
+            const int a_tap_step = (pix_units - (ncb - 1) * 6) * 16, a_row_step = (a.LW - KS) * pix_units * 16;
+            const char *ldsb = reinterpret_cast<const char *>(lds_raw);
+            auto lds_at = [&](uint32_t off, int imm) { return *reinterpret_cast<const uintx4 *>(ldsb + off + imm); };
+            uint32_t wv[NT], xv[MT];
+#pragma unroll
+            for (int n = 0; n < NT; ++n) wv[n] = (uint32_t)(a.code_off + ((wco * NT + n) * T * ncbf) * 64 + lane) * 16u;
+#pragma unroll
+            for (int m = 0; m < MT; ++m) xv[m] = (uint32_t)lds_base[m] * 16u;
             uintx4 xb[MT][3], wcur[NT], wnext[NT];
 #pragma unroll
-            for (int n = 0; n < NT; ++n) wcur[n] = lds4[woff + n * (T * ncbf * 64)];
+            for (int n = 0; n < NT; ++n) wcur[n] = lds_at(wv[n], 0);
 #pragma unroll
             for (int pc = 0; pc < 3; ++pc)
 #pragma unroll
-                for (int m = 0; m < MT; ++m) xb[m][pc] = lds4[lds_base[m] + pc * a.PSU];
-#pragma unroll 1
-            for (int k = 0; k < steps; ++k) {
-                if (k + 1 < steps) { // uniform: scalar address updates only
-                    if (++wc == ncb) {
-                        wc = 0;
-                        woff += w_tap_step;
-                    } else {
-                        woff += 64;
+                for (int m = 0; m < MT; ++m) xb[m][pc] = lds_at(xv[m], pc * 16);
+            if constexpr (ONE) {
+                // Passes of one channel block (the staging of long regions allows no more): a pixel is 96
+                // bytes and a tap's codes 1024, so with the taps unrolled every operand sits at an
+                // immediate offset from the lane's code address or from its window row's address, and
+                // the two code register sets simply alternate: the loop issues no address arithmetic
+                // and no register copies between its MFMAs.
+                uint32_t xrow[MT][KS];
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+#pragma unroll
+                    for (int ky = 0; ky < KS; ++ky) xrow[m][ky] = xv[m] + (uint32_t)(ky * a.LW) * 96u;
+                uintx4 wset[2][NT];
+#pragma unroll
+                for (int n = 0; n < NT; ++n) wset[0][n] = wcur[n];
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    __builtin_amdgcn_sched_barrier(0); // a tap's prefetches stay inside the tap
+                    const int tn = t + 1, kyn = tn / KS, kxn = tn % KS;
+                    if (tn < T) {
+#pragma unroll
+                        for (int n = 0; n < NT; ++n) wset[tn & 1][n] = lds_at(wv[n], tn * 1024);
                     }
-                    if (++ac == ncb) {
-                        ac = 0;
-                        tapoff += a_tap_step;
-                        if (++akx == KS) {
-                            akx = 0;
-                            tapoff += a_row_step;
+#pragma unroll
+                    for (int pc = 2; pc >= 0; --pc) { // smallest terms first
+#pragma unroll
+                        for (int m = 0; m < MT; ++m)
+#pragma unroll
+                            for (int n = 0; n < NT; ++n)
+                                acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                    __builtin_bit_cast(bf16x8, wset[t & 1][n]), __builtin_bit_cast(bf16x8, xb[m][pc]), acc[m][n], 0, 0, 0);
+                        if (tn < T) {
+#pragma unroll
+                            for (int m = 0; m < MT; ++m) xb[m][pc] = lds_at(xrow[m][tn < T ? kyn : 0], kxn * 96 + pc * 16);
                         }
-                    } else {
-                        tapoff += 2;
                     }
                 }
+                __builtin_amdgcn_sched_barrier(0);
+            } else
 #pragma unroll
-                for (int n = 0; n < NT; ++n) wnext[n] = lds4[woff + n * (T * ncbf * 64)];
+            for (int t = 0; t < T; ++t) {
+                const int x_last = t + 1 == T ? 0 : ((t % KS) == KS - 1 ? a_tap_step + a_row_step : a_tap_step);
+                const int w_last = t + 1 == T ? 0 : w_tap_step;
+#pragma unroll 1
+                for (int cb = 0; cb < ncb; ++cb) {
+                    const bool last = cb + 1 == ncb; // uniform
+                    const uint32_t dw = last ? w_last : 1024, dx = last ? x_last : 96;
 #pragma unroll
-                for (int pc = 2; pc >= 0; --pc) { // smallest terms first
+                    for (int n = 0; n < NT; ++n) wv[n] += dw;
 #pragma unroll
-                    for (int m = 0; m < MT; ++m)
+                    for (int m = 0; m < MT; ++m) xv[m] += dx;
 #pragma unroll
-                        for (int n = 0; n < NT; ++n)
-                            acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                __builtin_bit_cast(bf16x8, wcur[n]), __builtin_bit_cast(bf16x8, xb[m][pc]), acc[m][n], 0, 0, 0);
+                    for (int n = 0; n < NT; ++n) wnext[n] = lds_at(wv[n], 0);
 #pragma unroll
-                    for (int m = 0; m < MT; ++m) xb[m][pc] = lds4[lds_base[m] + tapoff + pc * a.PSU];
+                    for (int pc = 2; pc >= 0; --pc) { // smallest terms first
+#pragma unroll
+                        for (int m = 0; m < MT; ++m)
+#pragma unroll
+                            for (int n = 0; n < NT; ++n)
+                                acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                    __builtin_bit_cast(bf16x8, wcur[n]), __builtin_bit_cast(bf16x8, xb[m][pc]), acc[m][n], 0, 0, 0);
+#pragma unroll
+                        for (int m = 0; m < MT; ++m) xb[m][pc] = lds_at(xv[m], pc * 16);
+                    }
+#pragma unroll
+                    for (int n = 0; n < NT; ++n) wcur[n] = wnext[n];
                 }
-#pragma unroll
-                for (int n = 0; n < NT; ++n) wcur[n] = wnext[n];
             }
         }
     }
@@ -419,7 +459,10 @@ static hipError_t launch_codes_nt(const CodeConvArgs &a, int nt, int ki, int mt,
     constexpr int K1 = kCodeStageItems, K2 = 2 * kCodeStageItems;
 #define AIQ_LAUNCH(NT_, KI_, MT_)                                                                                     \
     if (nt == NT_ && ki == KI_ && mt == MT_) {                                                                       \
-        hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, NT_, KI_, MT_>), grid, dim3(256), lds_bytes, st, a);       \
+        if (a.CKC == 16)                                                                                             \
+            hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, NT_, KI_, MT_, true>), grid, dim3(256), lds_bytes, st, a);  \
+        else                                                                                                         \
+            hipLaunchKernelGGL((conv_codes_kernel<KS, STRIDE, NT_, KI_, MT_, false>), grid, dim3(256), lds_bytes, st, a); \
         return hipGetLastError();                                                                                    \
     }
     AIQ_LAUNCH(1, K1, 2)
@@ -445,7 +488,10 @@ hipError_t launch_conv_codes(const CodeConvArgs &a, int ks, int stride, int nt, 
 template <int KS, int STRIDE, int NT, int KI, int MT>
 static hipError_t codes_lds_t()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_codes_kernel<KS, STRIDE, NT, KI, MT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_codes_kernel<KS, STRIDE, NT, KI, MT, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_codes_kernel<KS, STRIDE, NT, KI, MT, false>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
 }
 

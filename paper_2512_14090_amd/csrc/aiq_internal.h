@@ -324,7 +324,7 @@ struct CodeConvArgs {
     int32_t CB;            // ceil(Cin/16)
     int32_t CKC;           // channels staged per pass (16, 32 or 64)
     int32_t RIN, LW;       // LDS tile: rows, row width (pixels)
-    int32_t PSU;           // 16-byte units of one pixel's plane: CKC / 8 + 1 (odd: conflict-free 16-byte reads)
+    int32_t PSU;           // eight-channel units of one staged pixel: CKC / 8 (each holds its hi, mid, lo pieces: 48 bytes)
     int32_t wave_px_split; // waves along pixels (4, 2 or 1); 4/wave_px_split along output channels
     int32_t cout_tiles;    // ceil(Cout/32)
     int32_t tiles_per_wg;  // output-channel tiles of one workgroup: NT * 4 / wave_px_split
