@@ -449,23 +449,41 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(ConvArgs a)
             const int ncb = min(a.CKC, a.CB * 16 - c0) >> 4;
             const int cb0 = c0 >> 4;
             const int steps = T * ncb;
-            int lt = 0, lc = 0; // (tap, channel block) of the next step to load
+            // Addresses of the next step to load, as byte offsets that advance by one of a few uniform
+            // increments (next block of the tap, next tap of the window row, next window row): a
+            // counter and two selects per step instead of divisions and 64-bit products.
+            const uint32_t x_tap = (uint32_t)a.PS * 4u - (uint32_t)(ncb - 1) * 64u;
+            const uint32_t x_row = x_tap + (uint32_t)(a.LW - KS) * (uint32_t)a.PS * 4u;
+            const uint32_t w_tap = (uint32_t)(a.CB - ncb + 1) * 1024u;
+            const char *ldsb = reinterpret_cast<const char *>(lds);
+            const char *wbase[NT]; // uniform: weights of tile n, tap 0, first block of the pass
+#pragma unroll
+            for (int n = 0; n < NT; ++n) {
+                const int ct = min(ct0 + n, a.cout_tiles - 1);
+                wbase[n] = reinterpret_cast<const char *>(wq + ((size_t)ct * T * a.CB + cb0) * 256);
+            }
+            uint32_t wv = (uint32_t)lane * 16u, xv[4];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) xv[m] = (uint32_t)lds_base[m] * 16u;
+            int lc = 0, lkx = 0; // channel block and tap column of the next step to load
             auto load_step = [&](floatx4 (&wa)[NT], floatx4 (&xb)[4]) {
-                const int t = lt, cbl = lc;
-                if (++lc == ncb) {
+#pragma unroll
+                for (int n = 0; n < NT; ++n) wa[n] = *reinterpret_cast<const floatx4 *>(wbase[n] + wv);
+#pragma unroll
+                for (int m = 0; m < 4; ++m) xb[m] = *reinterpret_cast<const floatx4 *>(ldsb + xv[m]);
+                uint32_t dx = 64u, dw = 1024u;
+                if (++lc == ncb) { // uniform
                     lc = 0;
-                    ++lt;
+                    dw = w_tap;
+                    dx = x_tap;
+                    if (++lkx == KS) {
+                        lkx = 0;
+                        dx = x_row;
+                    }
                 }
-                const int ky = t / KS, kx = t - ky * KS;
-                const int tapoff = (ky * a.LW + kx) * ps4 + cbl * 4;
+                wv += dw;
 #pragma unroll
-                for (int n = 0; n < NT; ++n) {
-                    const int ct = min(ct0 + n, a.cout_tiles - 1);
-                    const float *wrow = wq + (((size_t)ct * T + t) * a.CB + cb0 + cbl) * 256; // uniform
-                    wa[n] = *reinterpret_cast<const floatx4 *>(wrow + lane * 4);
-                }
-#pragma unroll
-                for (int m = 0; m < 4; ++m) xb[m] = lds4[lds_base[m] + tapoff];
+                for (int m = 0; m < 4; ++m) xv[m] += dx;
             };
             auto mma_step = [&](const floatx4 (&wa)[NT], const floatx4 (&xb)[4]) {
 #pragma unroll
