@@ -356,16 +356,31 @@ aiq_status aiq_forward_nodes(aiq_model *m, const float *images, int32_t N, const
  * aiq_deploy_workspace_bytes(d, chunk) bytes (activation buffers for `chunk` images at a time).
  * Asynchronous on hip_stream.  N = 0 is a valid no-op.
  * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, DEVICE_ERROR.
+ *
+ * Models created with AIQ_MODEL_ACT_QUANT: a dense convolution of at most 8 bits whose input tensor has
+ * a multiple of 16 channels runs on the INT8 matrix pipe - its input is quantized to int8 codes with the
+ * image's scale (the variant's own rule), the weights are stored as int8 codes, the products are summed
+ * exactly in int32 and scaled once by s_w[c] * s_x[n]: the function is the one aiq_eval_schemes computes
+ * for that model up to fp32 rounding of the final scaling.  Other layers run as in scoring.
+ *
+ * aiq_deploy_forward_nodes: like aiq_forward_nodes for a deployed scheme - every node's output on N
+ * images in node_out[l] (HOST array of aiq_model_nodes(m) DEVICE pointers, fp32 [N][aiq_node_output_elems]),
+ * which is how the layers of the activation variant are compared one by one.  workspace: device,
+ * 256-byte aligned, >= aiq_deploy_workspace_bytes(d, N).  Not for models deployed on their LDS-resident
+ * kernels (UNSUPPORTED_LAYER).  Asynchronous on hip_stream.
+ * Errors: INVALID_ARG, UNSUPPORTED_LAYER, WORKSPACE_TOO_SMALL, DEVICE_ERROR.
  */
 typedef struct aiq_deployed aiq_deployed; /* opaque */
 enum { AIQ_DEPLOY_FP32_MATRIX = 1 };
 aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags, aiq_deployed **out);
 void aiq_deploy_destroy(aiq_deployed *d); /* NULL-safe */
-/* Number of layers that run from their integer codes on the bf16 matrix pipe; -1 for NULL. */
+/* Number of layers that run from their integer codes (bf16 or INT8 matrix pipe); -1 for NULL. */
 int32_t aiq_deploy_code_layers(const aiq_deployed *d);
 aiq_status aiq_deploy_workspace_bytes(const aiq_deployed *d, int32_t chunk, size_t *bytes);
 aiq_status aiq_deploy_forward(aiq_deployed *d, const float *images, int32_t N, int32_t chunk, float *logits,
                               int32_t *top1, void *workspace, size_t workspace_bytes, void *hip_stream);
+aiq_status aiq_deploy_forward_nodes(aiq_deployed *d, const float *images, int32_t N, float *const *node_out,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Per-kernel timing for roofline reports.  While enabled, aiq_eval_schemes and aiq_deploy_forward bracket

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = (
     "aiq_profile_enable", "aiq_profile_read", "aiq_search_workspace_bytes",
     "aiq_search_greedy", "aiq_search_coordinate_descent", "aiq_sensitivity_workspace_bytes", "aiq_layer_sensitivity",
     "aiq_deploy_create", "aiq_deploy_destroy", "aiq_deploy_code_layers", "aiq_deploy_workspace_bytes",
-    "aiq_deploy_forward",
+    "aiq_deploy_forward", "aiq_deploy_forward_nodes",
 )
 K_QUANTIZE, K_CONV, K_DEPTHWISE, K_HEAD, K_AGREE, K_FUSED, K_MBCONV, K_CONV_CODES = range(8)
 MODEL_LAYERWISE = 1
@@ -126,6 +126,8 @@ def load_library():
     lib.aiq_deploy_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]
     lib.aiq_deploy_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.aiq_deploy_forward_nodes.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
+                                             C.c_void_p]
     for name in EXPORTED_SYMBOLS:
         getattr(lib, name)
     _lib = lib
@@ -463,14 +465,35 @@ class Deployed:
             if logits is None:
                 logits = torch.empty((N, self._model.classes), dtype=torch.float32, device=dev)
         chunk = max(1, min(int(chunk), max(N, 1)))
-        nbytes = self.workspace_bytes(chunk)
+        ws = self._get_workspace(self.workspace_bytes(chunk), dev)
+        _check(self._lib.aiq_deploy_forward(self._h, images.data_ptr(), N, chunk,
+                                            None if logits is None else logits.data_ptr(), top1.data_ptr(),
+                                            ws.data_ptr(), ws.numel(), _stream_ptr(stream)), "aiq_deploy_forward")
+        return dict(top1=top1[:N], logits=logits)
+
+    def _get_workspace(self, nbytes, dev):
+        import torch
         if self._workspace is None or self._workspace.numel() < nbytes or self._workspace.device != dev:
             if self._workspace is not None:
                 torch.cuda.synchronize(dev)  # earlier forwards, on whatever stream, may still use the old one
             self._workspace = None
             self._workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
-        ws = self._workspace
-        _check(self._lib.aiq_deploy_forward(self._h, images.data_ptr(), N, chunk,
-                                            None if logits is None else logits.data_ptr(), top1.data_ptr(),
-                                            ws.data_ptr(), ws.numel(), _stream_ptr(stream)), "aiq_deploy_forward")
-        return dict(top1=top1[:N], logits=logits)
+        return self._workspace
+
+    def forward_nodes(self, images, stream=None):
+        """aiq_deploy_forward_nodes: every node's output of the deployed scheme.  Returns a list of CUDA fp32
+        tensors [N][elems] in node order (the last holds the logits), not synchronised."""
+        import torch
+        N, dev = images.shape[0], images.device
+        lib, mh = self._lib, self._model._h
+        n_nodes = int(lib.aiq_model_nodes(mh))
+        outs = []
+        for l in range(n_nodes):
+            e = C.c_size_t(0)
+            _check(lib.aiq_node_output_elems(mh, l, C.byref(e)), "aiq_node_output_elems")
+            outs.append(torch.empty((max(N, 1), e.value), dtype=torch.float32, device=dev))
+        ptrs = (C.c_void_p * n_nodes)(*[t.data_ptr() for t in outs])
+        ws = self._get_workspace(self.workspace_bytes(max(N, 1)), dev)
+        _check(lib.aiq_deploy_forward_nodes(self._h, images.data_ptr(), N, ptrs, ws.data_ptr(), ws.numel(),
+                                            _stream_ptr(stream)), "aiq_deploy_forward_nodes")
+        return [t[:N] for t in outs]

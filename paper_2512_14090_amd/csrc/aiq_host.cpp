@@ -245,6 +245,58 @@ bool plan_code_conv(const Node &nd, CodePlan &p)
     return false;
 }
 
+// Tiling of the int8 convolution (conv_i8_kernel): a wavefront holds 64 pixels x one or two
+// output-channel tiles of 32; all output channels go to one workgroup where four wavefronts can hold
+// them, so that the region's activations are staged once.  Per pass the LDS holds the region's input
+// rows (32 or 64 channels of int8 per pixel + 16 bytes of padding) and the weight codes of the
+// workgroup's tiles for those channels.  False if no tiling fits.
+struct I8Plan {
+    int nt, wave_px_split, R, G, regions_per_image, CBK, CKB, RIN, LW, PSB, cout_tiles, tiles_per_wg, grid_y, code_off;
+    size_t lds_bytes;
+};
+
+bool plan_i8_conv(const Node &nd, I8Plan &p)
+{
+    const aiq_layer_desc &d = nd.d;
+    if (d.cin % 16 != 0 || d.cout % 4 != 0) return false;
+    const int T = d.kh * d.kw;
+    p = I8Plan{};
+    p.cout_tiles = (d.cout + 31) / 32;
+    p.nt = p.cout_tiles >= 2 ? 2 : 1;
+    const int groups = (p.cout_tiles + p.nt - 1) / p.nt; // wavefronts along the output channels, if all fit
+    // first choice: two workgroups or more per compute unit; regions whose input rows are long (stride 2
+    // at 32x32) get what one workgroup per unit can hold
+    for (size_t lds_limit : {(size_t)64 * 1024, (size_t)160 * 1024})
+    for (int wco = groups >= 4 ? 4 : (groups >= 2 ? 2 : 1); wco >= 1; wco /= 2) {
+        p.wave_px_split = 4 / wco;
+        p.tiles_per_wg = p.nt * wco;
+        p.grid_y = (p.cout_tiles + p.tiles_per_wg - 1) / p.tiles_per_wg;
+        const int region_px = 64 * p.wave_px_split;
+        const int px_img = nd.hout * nd.wout;
+        if (px_img >= region_px) {
+            p.G = 1;
+            p.R = std::min(region_px / nd.wout, nd.hout);
+            if (p.R < 1) continue;
+            p.regions_per_image = (nd.hout + p.R - 1) / p.R;
+        } else {
+            p.G = region_px / px_img;
+            p.R = nd.hout;
+            p.regions_per_image = 1;
+        }
+        p.CBK = (d.cin + 31) / 32;
+        p.RIN = (p.R - 1) * d.stride + d.kh;
+        p.LW = d.win + 2 * d.pad;
+        for (p.CKB = std::min(p.CBK, 2); p.CKB >= 1; --p.CKB) {
+            p.PSB = 32 * p.CKB + 16;
+            p.code_off = (p.G * p.RIN * p.LW * p.PSB + 255) / 256 * 256;
+            const size_t staged = (size_t)p.code_off + (size_t)p.tiles_per_wg * T * p.CKB * 1024;
+            p.lds_bytes = std::max(staged, (size_t)4 * 32 * 32 * p.nt * sizeof(float));
+            if (p.lds_bytes <= lds_limit) return true;
+        }
+    }
+    return false;
+}
+
 // Recognises stem -> basic blocks (identity, or stride-2 with a 1x1 projection) -> classifier
 // with 16/32/64 channels at 32/16/8 pixels, and lays the tensors out in two LDS regions:
 // a block reads its input from one region, writes the intermediate to the other and the
@@ -475,7 +527,10 @@ WorkspaceLayout workspace_layout(const aiq_model *m, int S, int chunk, bool shar
     w.buf_stride = align_up(sizeof(float) * m->buf_elems * (size_t)(S + 1) * chunk, 256);
     off += w.buf_stride * m->n_bufs;
     w.aq_off = off; // activation fake-quantization: the quantized copy of the input of the node being launched
-    if (m->act_quant) off += align_up(sizeof(float) * m->aq_elems * (size_t)(S + 1) * chunk, 256);
+    // (+ one float per image: the deployed int8 layers keep the images' activation scales behind their codes)
+    if (m->act_quant)
+        off += align_up(sizeof(float) * m->aq_elems * (size_t)(S + 1) * chunk, 256) +
+               align_up(sizeof(float) * (size_t)(S + 1) * chunk, 256);
     if (shared && (m->fused_ckpt_floats > 0 || !m->fused)) {
         off = align_up(off, 256);
         w.ref_off = off;
@@ -1641,9 +1696,12 @@ struct aiq_deployed {
     std::vector<uint8_t> scheme;
     uint8_t *scheme_dev = nullptr;
     struct Layer {
-        uint16_t *codes = nullptr; // non-null: this node runs from its integer codes
+        uint16_t *codes = nullptr; // non-null: this node runs from its integer codes on the bf16 pipe
+        int8_t *codes8 = nullptr;  // non-null: activation variant, weights and activations as int8 codes
         float *scales = nullptr;
         CodePlan plan{};
+        I8Plan plan8{};
+        int bits = 32;
     };
     std::vector<Layer> layer; // per node
     std::vector<void *> allocations;
@@ -1707,9 +1765,21 @@ aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags
         if (nd.d.scheme_slot < 0) continue;
         const int bits = scheme[nd.d.scheme_slot], bi = bits_index(bits);
         if (bi == 0) continue;
-        const bool on_codes = !(flags & AIQ_DEPLOY_FP32_MATRIX) && !m->act_quant && bits <= 8 && nd.d.kind == 0 && nd.d.input >= 0 &&
-                              nd.layout == kLayoutMfma && plan_code_conv(nd, d->layer[l].plan);
-        if (on_codes) {
+        const bool dense = !(flags & AIQ_DEPLOY_FP32_MATRIX) && bits <= 8 && nd.d.kind == 0 && nd.d.input >= 0 &&
+                           nd.layout == kLayoutMfma;
+        const bool on_codes = dense && !m->act_quant && plan_code_conv(nd, d->layer[l].plan);
+        const bool on_int8 = dense && m->act_quant && nd.in_elems % 16 == 0 && plan_i8_conv(nd, d->layer[l].plan8);
+        d->layer[l].bits = bits;
+        if (on_int8) {
+            const I8Plan &p = d->layer[l].plan8;
+            const size_t code_bytes = (size_t)p.cout_tiles * nd.d.kh * nd.d.kw * p.CBK * 1024;
+            if (!alloc(reinterpret_cast<void **>(&d->layer[l].codes8), code_bytes) ||
+                !alloc(reinterpret_cast<void **>(&d->layer[l].scales), (size_t)nd.d.cout * sizeof(float)) ||
+                !hip_ok(hipMemset(d->layer[l].codes8, 0, code_bytes)))
+                return fail(AIQ_DEVICE_ERROR);
+            tmp_elems = std::max(tmp_elems, (size_t)nd.d.cout * nd.k);
+            ++d->n_code_layers;
+        } else if (on_codes) {
             const CodePlan &p = d->layer[l].plan;
             const size_t code_elems = (size_t)p.cout_tiles * nd.d.kh * nd.d.kw * p.CB * 512;
             if (!alloc(reinterpret_cast<void **>(&d->layer[l].codes), code_elems * sizeof(uint16_t)) ||
@@ -1733,14 +1803,16 @@ aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags
                   hip_ok(hipMalloc(&tmp_out, tmp_elems * sizeof(float)));
         for (size_t l = 0; ok && l < m->nodes.size(); ++l) {
             const Node &nd = m->nodes[l];
-            if (!d->layer[l].codes) continue;
+            if (!d->layer[l].codes && !d->layer[l].codes8) continue;
             QuantJob j = m->jobs_host[nd.job0 + bits_index(scheme[nd.d.scheme_slot]) - 1];
             j.out = static_cast<float *>(tmp_out);
             j.layout = kLayoutPlain;
             j.scales = d->layer[l].scales;
             j.codes = static_cast<int32_t *>(tmp_codes);
             ok = hip_ok(launch_quantize_single(j, nullptr)) &&
-                 hip_ok(launch_pack_codes(j.codes, d->layer[l].codes, nd.d.cout, nd.d.cin, nd.d.kh * nd.d.kw, nullptr));
+                 hip_ok(d->layer[l].codes8
+                            ? launch_pack_codes_i8(j.codes, d->layer[l].codes8, nd.d.cout, nd.d.cin, nd.d.kh * nd.d.kw, nullptr)
+                            : launch_pack_codes(j.codes, d->layer[l].codes, nd.d.cout, nd.d.cin, nd.d.kh * nd.d.kw, nullptr));
         }
         ok = hip_ok(hipDeviceSynchronize()) && ok;
         if (tmp_codes) (void)hipFree(tmp_codes);
@@ -1759,6 +1831,107 @@ aiq_status aiq_deploy_workspace_bytes(const aiq_deployed *d, int32_t chunk, size
     *bytes = workspace_layout(d->m, d->resident ? 1 : 0, chunk).total;
     return AIQ_OK;
 }
+
+namespace {
+
+// One node of a deployed scheme on n images: from integer codes where the layer has them, else on the
+// scoring kernels.  aq: the activation variant's scratch area (room for the fp32 copy of the largest
+// input tensor of a scheme layer, per image); the int8 path keeps its activation codes in the first
+// quarter of it and the images' scales behind them.
+aiq_status deploy_node(aiq_deployed *d, hipStream_t st, const HeadOut &ho, size_t l, const NodeIO &io, int n, int n0,
+                       char *aq)
+{
+    aiq_model *m = d->m;
+    const Node &nd = m->nodes[l];
+    const aiq_deployed::Layer &cl = d->layer[l];
+    const aiq_layer_desc &ld = nd.d;
+    if (cl.codes8) {
+        const I8Plan &p = cl.plan8;
+        int8_t *xcodes = reinterpret_cast<int8_t *>(aq);
+        float *xscale = reinterpret_cast<float *>(aq + align_up(nd.in_elems * (size_t)n, 256));
+        {
+            ProfScope ps(m, st, AIQ_K_QUANTIZE, 0.0, 9.0 * nd.in_elems * n);
+            AIQ_HIP(launch_act_codes(io.in, xcodes, xscale, n, (int)nd.in_elems, cl.bits, st));
+        }
+        I8ConvArgs a{};
+        a.in = xcodes;
+        a.xscale = xscale;
+        a.out = io.out;
+        a.res = io.res;
+        a.bias = nd.bias;
+        a.codes = cl.codes8;
+        a.scales = cl.scales;
+        a.N = n;
+        a.Hin = ld.hin;
+        a.Win = ld.win;
+        a.Cin = ld.cin;
+        a.Hout = nd.hout;
+        a.Wout = nd.wout;
+        a.Cout = ld.cout;
+        a.act = ld.act;
+        a.R = p.R;
+        a.G = p.G;
+        a.regions_per_image = p.regions_per_image;
+        a.CBK = p.CBK;
+        a.CKB = p.CKB;
+        a.RIN = p.RIN;
+        a.LW = p.LW;
+        a.PSB = p.PSB;
+        a.wave_px_split = p.wave_px_split;
+        a.cout_tiles = p.cout_tiles;
+        a.tiles_per_wg = p.tiles_per_wg;
+        a.code_off = p.code_off;
+        a.div_rin = make_fastdiv(p.RIN);
+        a.div_wout = make_fastdiv(nd.wout);
+        a.div_rw = make_fastdiv(p.R * nd.wout);
+        a.div_per_row = make_fastdiv(p.LW * 2 * p.CKB);
+        a.div_pximg = make_fastdiv(nd.hout * nd.wout);
+        const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
+        ProfScope ps(m, st, AIQ_K_CONV_CODES, nd.flops_per_image * n,
+                     ((double)nd.in_elems + 4.0 * nd.out_elems * (ld.residual >= 0 ? 2 : 1)) * n);
+        AIQ_HIP(launch_conv_i8(a, ld.kh, ld.stride, p.nt, p.lds_bytes, dim3(gx, p.grid_y, 1), st));
+        return AIQ_OK;
+    }
+    if (!cl.codes) return launch_node(m, st, ho, l, io, n, n0);
+    const CodePlan &p = cl.plan;
+    CodeConvArgs a{};
+    a.in = io.in;
+    a.out = io.out;
+    a.res = io.res;
+    a.bias = nd.bias;
+    a.codes = cl.codes;
+    a.scales = cl.scales;
+    a.N = n;
+    a.Hin = ld.hin;
+    a.Win = ld.win;
+    a.Cin = ld.cin;
+    a.Hout = nd.hout;
+    a.Wout = nd.wout;
+    a.Cout = ld.cout;
+    a.act = ld.act;
+    a.R = p.R;
+    a.G = p.G;
+    a.regions_per_image = p.regions_per_image;
+    a.CB = p.CB;
+    a.CKC = p.CKC;
+    a.RIN = p.RIN;
+    a.LW = p.LW;
+    a.PSU = p.PSU;
+    a.wave_px_split = p.wave_px_split;
+    a.cout_tiles = p.cout_tiles;
+    a.tiles_per_wg = p.nt * (4 / p.wave_px_split);
+    a.code_off = p.code_off;
+    a.div_rin = make_fastdiv(p.RIN);
+    a.div_wout = make_fastdiv(nd.wout);
+    a.div_rw = make_fastdiv(p.R * nd.wout);
+    a.div_per_row = make_fastdiv(p.LW * (p.CKC / 8));
+    const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
+    ProfScope ps(m, st, AIQ_K_CONV_CODES, nd.flops_per_image * n, nd.act_bytes_per_image * n);
+    AIQ_HIP(launch_conv_codes(a, ld.kh, ld.stride, p.nt, p.stage_items, p.mt, p.lds_bytes, dim3(gx, p.grid_y, 1), st));
+    return AIQ_OK;
+}
+
+} // namespace
 
 aiq_status aiq_deploy_forward(aiq_deployed *d, const float *images, int32_t N, int32_t chunk, float *logits,
                               int32_t *top1, void *workspace, size_t workspace_bytes, void *hip_stream)
@@ -1790,49 +1963,42 @@ aiq_status aiq_deploy_forward(aiq_deployed *d, const float *images, int32_t N, i
             io.in = nd.d.input < 0 ? images + (size_t)n0 * nd.in_elems : buf_ptr(m->nodes[nd.d.input].buf);
             io.out = nd.buf >= 0 ? buf_ptr(nd.buf) : nullptr;
             io.res = nd.d.residual >= 0 ? buf_ptr(m->nodes[nd.d.residual].buf) : nullptr;
-            const aiq_deployed::Layer &cl = d->layer[l];
-            if (!cl.codes) {
-                aiq_status rc = launch_node(m, st, ho, l, io, n, n0);
-                if (rc != AIQ_OK) return rc;
-                continue;
-            }
-            const aiq_layer_desc &ld = nd.d;
-            const CodePlan &p = cl.plan;
-            CodeConvArgs a{};
-            a.in = io.in;
-            a.out = io.out;
-            a.res = io.res;
-            a.bias = nd.bias;
-            a.codes = cl.codes;
-            a.scales = cl.scales;
-            a.N = n;
-            a.Hin = ld.hin;
-            a.Win = ld.win;
-            a.Cin = ld.cin;
-            a.Hout = nd.hout;
-            a.Wout = nd.wout;
-            a.Cout = ld.cout;
-            a.act = ld.act;
-            a.R = p.R;
-            a.G = p.G;
-            a.regions_per_image = p.regions_per_image;
-            a.CB = p.CB;
-            a.CKC = p.CKC;
-            a.RIN = p.RIN;
-            a.LW = p.LW;
-            a.PSU = p.PSU;
-            a.wave_px_split = p.wave_px_split;
-            a.cout_tiles = p.cout_tiles;
-            a.tiles_per_wg = p.nt * (4 / p.wave_px_split);
-            a.code_off = p.code_off;
-            a.div_rin = make_fastdiv(p.RIN);
-            a.div_wout = make_fastdiv(nd.wout);
-            a.div_rw = make_fastdiv(p.R * nd.wout);
-            a.div_per_row = make_fastdiv(p.LW * (p.CKC / 8));
-            const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
-            ProfScope ps(m, st, AIQ_K_CONV_CODES, nd.flops_per_image * n, nd.act_bytes_per_image * n);
-            AIQ_HIP(launch_conv_codes(a, ld.kh, ld.stride, p.nt, p.stage_items, p.mt, p.lds_bytes, dim3(gx, p.grid_y, 1), st));
+            aiq_status rc = deploy_node(d, st, ho, l, io, n, n0, ws + wl.aq_off);
+            if (rc != AIQ_OK) return rc;
         }
+    }
+    return AIQ_OK;
+}
+
+aiq_status aiq_deploy_forward_nodes(aiq_deployed *d, const float *images, int32_t N, float *const *node_out,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!d || N < 0 || !node_out) return AIQ_INVALID_ARG;
+    if (N > 0 && (!images || !workspace)) return AIQ_INVALID_ARG;
+    aiq_model *m = d->m;
+    if (d->resident) return AIQ_UNSUPPORTED_LAYER;
+    for (size_t l = 0; l < m->nodes.size(); ++l)
+        if (N > 0 && !node_out[l]) return AIQ_INVALID_ARG;
+    if (N == 0) return AIQ_OK;
+    const WorkspaceLayout wl = workspace_layout(m, 0, N);
+    if (workspace_bytes < wl.total) return AIQ_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return AIQ_INVALID_ARG;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char *ws = static_cast<char *>(workspace);
+    m->aq_cur = m->act_quant ? reinterpret_cast<float *>(ws + wl.aq_off) : nullptr;
+    const size_t last = m->nodes.size() - 1;
+    const HeadOut ho{node_out[last], N, nullptr, reinterpret_cast<int32_t *>(ws + wl.top1_off), N};
+    for (size_t l = 0; l < m->nodes.size(); ++l) {
+        const Node &nd = m->nodes[l];
+        NodeIO io{};
+        io.schemes = d->scheme_dev;
+        io.S = 1;
+        io.s_total = 1;
+        io.in = nd.d.input < 0 ? images : node_out[nd.d.input];
+        io.out = node_out[l];
+        io.res = nd.d.residual >= 0 ? node_out[nd.d.residual] : nullptr;
+        aiq_status rc = deploy_node(d, st, ho, l, io, N, 0, ws + wl.aq_off);
+        if (rc != AIQ_OK) return rc;
     }
     return AIQ_OK;
 }

@@ -1,0 +1,362 @@
+// Deployed inference of the activation-quantization variant on the INT8 matrix pipe of gfx950.
+//
+// In that variant a scheme layer at b <= 8 bits reads its input tensor quantized to b bits with
+// one scale per image (paper: Problem Formulation gives a layer its bit-width; the reading of it
+// for activations is the one the scoring path implements).  Then both factors of every product
+// are integer codes: w = q_w * s_w[c], x = q_x * s_x[n], |q| <= 127, and
+//     sum_k w_k x_k = s_w[c] * s_x[n] * sum_k q_w,k q_x,k
+// with the integer sum exact in the MFMA's int32 accumulator.  The layer is two launches:
+//   act_codes_kernel   the producer's fp32 tensor -> int8 codes and the image's scale (the scoring
+//                      path's quantizer, step for step; what it would multiply back is never formed);
+//   conv_i8_kernel     implicit GEMM on v_mfma_i32_32x32x32_i8: A = weight codes (rows = 32 output
+//                      channels), B = 32 output pixels, k = 32 input channels of one tap; epilogue
+//                      float(acc) * (s_w * s_x) + bias (+ residual, read unquantized), activation.
+// One int8 MFMA stands where the fp32 kernels issue 32 and the bf16-code kernels 6, and the consumer
+// reads one byte per activation: the layer is bound by its fp32 output and by the quantizer's pass.
+#include "aiq_internal.h"
+
+#include <algorithm>
+
+namespace aiq {
+
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef int intx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+
+// hardware block b runs on XCD b % 8; XCD k gets the k-th contiguous stretch of logical blocks,
+// so that regions sharing halo rows meet in one L2
+__device__ inline uint32_t xcd_stretch(uint32_t b, uint32_t n)
+{
+    const uint32_t per = n >> 3, rem = n & 7u, xcd = b & 7u, idx = b >> 3;
+    return xcd * per + (xcd < rem ? xcd : rem) + idx;
+}
+
+__device__ inline float wave_max_f(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+// 16 bytes through an explicit global address (global_load, not flat_load)
+__device__ __forceinline__ uintx4 gload16(const void *p)
+{
+    return *(const __attribute__((address_space(1))) uintx4 *)(p);
+}
+
+// code of one value: IEEE division, round half to even, clamp (the quantizer's first three steps)
+__device__ __forceinline__ int code_of(float x, float s, int qmax)
+{
+    const int q = (int)rintf(__fdiv_rn(x, s));
+    return min(max(q, -qmax), qmax);
+}
+
+} // namespace
+
+// ------------------------------------------------------------------ activation codes
+//
+// One workgroup per image: absolute maximum of the image's tensor (exact in any order), scale
+// = amax / qmax (1 for a zero tensor), then sixteen codes per 16-byte store.  elems % 16 == 0.
+__global__ __launch_bounds__(256) void act_codes_kernel(const float *__restrict__ in, int8_t *__restrict__ codes,
+                                                        float *__restrict__ xscale, int elems, int bits)
+{
+    __shared__ float wmax[4];
+    const int n = blockIdx.x, tid = threadIdx.x;
+    const floatx4 *x4 = reinterpret_cast<const floatx4 *>(in + (size_t)n * elems);
+    const int n4 = elems >> 2;
+    float amax = 0.0f;
+    for (int i = tid; i < n4; i += 256) {
+        const floatx4 v = x4[i];
+        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+    }
+    amax = wave_max_f(amax);
+    if ((tid & 63) == 0) wmax[tid >> 6] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    const int qmax = (1 << (bits - 1)) - 1;
+    const float sc = amax > 0.0f ? __fdiv_rn(amax, (float)qmax) : 1.0f;
+    if (tid == 0) xscale[n] = sc;
+    uintx4 *out16 = reinterpret_cast<uintx4 *>(codes + (size_t)n * elems);
+    for (int i = tid; i < (elems >> 4); i += 256) {
+        uintx4 o;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const floatx4 v = x4[i * 4 + g];
+            o[g] = (uint32_t)(code_of(v.x, sc, qmax) & 255) | ((uint32_t)(code_of(v.y, sc, qmax) & 255) << 8) |
+                   ((uint32_t)(code_of(v.z, sc, qmax) & 255) << 16) | ((uint32_t)(code_of(v.w, sc, qmax) & 255) << 24);
+        }
+        out16[i] = o;
+    }
+}
+
+hipError_t launch_act_codes(const float *in, int8_t *codes, float *xscale, int n, int elems, int bits, hipStream_t st)
+{
+    if (n == 0 || elems == 0) return hipSuccess;
+    hipLaunchKernelGGL(act_codes_kernel, dim3(n), dim3(256), 0, st, in, codes, xscale, elems, bits);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ weight code packing
+//
+// int32 codes [cout][cin][taps] -> int8 in the order the MFMA's A operand wants:
+// [cout/32][tap][cin/32][64 lanes][16], lane = 32 * (k / 16) + row, byte = k % 16, where row is the
+// output channel within its tile of 32 and k the input channel within its block of 32.
+// The destination has been cleared: padding rows and channels stay zero.
+__global__ __launch_bounds__(256) void pack_codes_i8_kernel(const int32_t *__restrict__ codes, int8_t *__restrict__ out,
+                                                            int cout, int cin, int taps, int kblocks)
+{
+    const int k = cin * taps;
+    const size_t total = (size_t)cout * k;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int c = (int)(i / k), r = (int)(i - (size_t)c * k);
+        const int ci = r / taps, t = r - ci * taps;
+        const int ct = c >> 5, row = c & 31, kb = ci >> 5, kk = ci & 31;
+        const size_t o = ((((size_t)ct * taps + t) * kblocks + kb) * 64 + (kk >> 4) * 32 + row) * 16 + (kk & 15);
+        out[o] = (int8_t)codes[i]; // |code| <= 127
+    }
+}
+
+hipError_t launch_pack_codes_i8(const int32_t *codes, int8_t *out, int cout, int cin, int taps, hipStream_t st)
+{
+    const size_t total = (size_t)cout * cin * taps;
+    if (total == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 4096);
+    hipLaunchKernelGGL(pack_codes_i8_kernel, dim3(blocks), dim3(256), 0, st, codes, out, cout, cin, taps, (cin + 31) / 32);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ convolution on int8 codes
+//
+// Workgroup = 4 wavefronts; a wavefront owns 64 pixels (two MFMA tiles) x 32*NT output channels.
+// Per pass of CKB blocks of 32 channels the workgroup stages in LDS the input rows of its region
+// (one 16-byte piece = 16 channels of a pixel, copied as it is; pixels outside the image are code
+// 0; the pixel stride carries 16 bytes of padding so that the 32 pixels of an operand read spread
+// over the banks) and the weight codes of its output tiles for those channels.  The taps are
+// unrolled; every operand read is the lane's base address plus an immediate.
+template <int KS, int STRIDE, int NT>
+__global__ __launch_bounds__(256) void conv_i8_kernel(I8ConvArgs a)
+{
+    extern __shared__ float lds_raw[];
+    char *ldsb = reinterpret_cast<char *>(lds_raw);
+    constexpr int T = KS * KS;
+    constexpr int PAD = KS == 3 ? 1 : 0;
+    constexpr int MT = 2;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int bx = (int)xcd_stretch(blockIdx.x, gridDim.x);
+    int img0, oy0;
+    if (a.G > 1) {
+        img0 = bx * a.G;
+        oy0 = 0;
+    } else {
+        img0 = bx / a.regions_per_image;
+        oy0 = (bx - img0 * a.regions_per_image) * a.R;
+    }
+    const int wpx = wave % a.wave_px_split;
+    const int wco = wave / a.wave_px_split;
+    const int first_tile = blockIdx.y * a.tiles_per_wg;
+    const int ct0 = first_tile + wco * NT;
+    const int p = lane & 31, kh = lane >> 5;
+
+    uint32_t lds_base[MT];
+    const int rw = a.R * a.Wout;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const uint32_t P = (uint32_t)(wpx * (32 * MT) + m * 32 + p);
+        const uint32_t g = fd_div(P, a.div_rw);
+        const uint32_t rem = P - g * rw;
+        const uint32_t oy = fd_div(rem, a.div_wout);
+        const uint32_t ox = rem - oy * a.Wout;
+        const bool in_region = g < (uint32_t)a.G; // lanes past the region's last pixel compute nothing useful
+        lds_base[m] = (in_region ? ((g * a.RIN + oy * STRIDE) * a.LW + ox * STRIDE) * (uint32_t)a.PSB : 0u) + kh * 16u;
+    }
+
+    intx16 acc[MT][NT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[m][n][e] = 0;
+
+    const bool active = ct0 < a.cout_tiles; // wavefronts past the last output-channel tile only help staging
+    const int upp = a.CKB * 2;              // 16-byte pieces of one staged pixel (2 or 4)
+    const int upp_shift = upp == 2 ? 1 : 2;
+    const int per_row = a.LW * upp;
+    const int act_items = a.G * a.RIN * per_row;
+    const int iy0 = oy0 * STRIDE - PAD;
+    const int g_lim = min(a.G, a.N - img0);
+    const int8_t *in0 = a.in + (size_t)img0 * a.Hin * a.Win * a.Cin;
+    const int code_run = 64 * a.CKB;                       // pieces of one (tile, tap)
+    const int code_items = a.tiles_per_wg * T * code_run;
+    constexpr int kBatch = 6;                              // 16-byte reads in flight per thread
+
+    for (int kb0 = 0; kb0 < a.CBK; kb0 += a.CKB) {
+        const int ncb = min(a.CKB, a.CBK - kb0);
+        if (kb0) __syncthreads(); // the previous pass's LDS reads are done
+        // ---- activations
+        for (int base = tid; base < act_items; base += 256 * kBatch) {
+            uintx4 v[kBatch];
+            int dst[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int e = base + i * 256;
+                v[i] = uintx4{0u, 0u, 0u, 0u};
+                dst[i] = -1;
+                if (e < act_items) {
+                    const int row = (int)fd_div((uint32_t)e, a.div_per_row);
+                    const int rem = e - row * per_row;
+                    const int col = rem >> upp_shift, u = rem & (upp - 1);
+                    const int g = (int)fd_div((uint32_t)row, a.div_rin);
+                    const int iy = iy0 + row - g * a.RIN, ix = col - PAD;
+                    const int c = kb0 * 32 + u * 16;
+                    dst[i] = (row * a.LW + col) * a.PSB + u * 16;
+                    if ((unsigned)iy < (unsigned)a.Hin && (unsigned)ix < (unsigned)a.Win && g < g_lim && c < a.Cin)
+                        v[i] = gload16(
+                            in0 + ((size_t)(g * a.Hin + iy) * a.Win + ix) * a.Cin + c);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i)
+                if (dst[i] >= 0) *reinterpret_cast<uintx4 *>(ldsb + dst[i]) = v[i];
+        }
+        // ---- weight codes: piece j of the pass goes to code_off + 16 * j, order [tile][tap][block][lane]
+        for (int base = tid; base < code_items; base += 256 * kBatch) {
+            uintx4 v[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int j = base + i * 256;
+                v[i] = uintx4{0u, 0u, 0u, 0u};
+                if (j < code_items) {
+                    const int r = j / code_run, q = j - r * code_run;
+                    const int ctl = r / T, t = r - ctl * T;
+                    const int kbl = q >> 6, ln = q & 63;
+                    const int ct = min(first_tile + ctl, a.cout_tiles - 1);
+                    if (kbl < ncb)
+                        v[i] = gload16(
+                            a.codes + ((((size_t)ct * T + t) * a.CBK + kb0 + kbl) * 64 + ln) * 16);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int j = base + i * 256;
+                if (j < code_items) *reinterpret_cast<uintx4 *>(ldsb + a.code_off + j * 16) = v[i];
+            }
+        }
+        __syncthreads();
+
+        const uint32_t wbase = (uint32_t)a.code_off + (uint32_t)(wco * NT * T * code_run + lane) * 16u;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const uint32_t xoff = (uint32_t)((t / KS) * a.LW + (t % KS)) * (uint32_t)a.PSB;
+#pragma unroll 1
+            for (int kbl = 0; kbl < ncb; ++kbl) {
+                intx4 wa[NT], xb[MT];
+#pragma unroll
+                for (int n = 0; n < NT; ++n)
+                    wa[n] = *reinterpret_cast<const intx4 *>(ldsb + wbase + (uint32_t)(((n * T + t) * a.CKB + kbl) * 1024));
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    xb[m] = *reinterpret_cast<const intx4 *>(ldsb + lds_base[m] + xoff + (uint32_t)kbl * 32u);
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+#pragma unroll
+                    for (int n = 0; n < NT; ++n)
+                        acc[m][n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wa[n], xb[m], acc[m][n], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- epilogue: through LDS (a lane's accumulators are four groups of four consecutive output
+    // channels of one pixel; consecutive lanes then store consecutive 16-byte chunks of a pixel: whole
+    // lines), scale, bias, residual, activation.  Chunk c of row r lives in unit r * U + (c ^ (r % U)).
+    __syncthreads();
+    if (!active) return;
+    constexpr int U = 8 * NT;
+    uintx4 *tile = reinterpret_cast<uintx4 *>(ldsb) + wave * 32 * U;
+    const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
+    const int px_img = a.Hout * a.Wout;
+    const size_t first_px = a.G > 1 ? (size_t)img0 * px_img : ((size_t)img0 * a.Hout + oy0) * a.Wout;
+    const int valid_px = a.G > 1 ? g_lim * px_img : min(a.R, a.Hout - oy0) * a.Wout;
+    float *out0 = a.out + first_px * a.Cout;
+    const float *res0 = a.res ? a.res + first_px * a.Cout : nullptr;
+    constexpr int ROWS = 64 / U, ITS = 32 / ROWS;
+    const int chunk = lane & (U - 1), sub = lane / U;
+    const int co = ct0 * 32 + chunk * 4;
+    floatx4 sc = {0.f, 0.f, 0.f, 0.f}, bi = {0.f, 0.f, 0.f, 0.f};
+    if (co < a.Cout) {
+        sc = *reinterpret_cast<const floatx4 *>(a.scales + co);
+        bi = *reinterpret_cast<const floatx4 *>(a.bias + co);
+    }
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        // accumulator e of a lane is output channel 8 * (e / 4) + 4 * kh + e % 4 of its tile
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int c = n * 8 + g4 * 2 + kh;
+                const floatx4 v = {(float)acc[m][n][g4 * 4], (float)acc[m][n][g4 * 4 + 1], (float)acc[m][n][g4 * 4 + 2],
+                                   (float)acc[m][n][g4 * 4 + 3]};
+                tile[p * U + (c ^ (p & (U - 1)))] = __builtin_bit_cast(uintx4, v);
+            }
+        floatx4 rv[ITS];
+        float xs[ITS];
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            const int P = wpx * (32 * MT) + m * 32 + it * ROWS + sub;
+            rv[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+            xs[it] = 0.0f;
+            if (co < a.Cout && P < valid_px) {
+                const int g = a.G > 1 ? (int)fd_div((uint32_t)P, a.div_pximg) : 0;
+                xs[it] = a.xscale[img0 + g];
+                if (res0) rv[it] = __builtin_bit_cast(floatx4, gload16(res0 + (size_t)P * a.Cout + co));
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            const int row = it * ROWS + sub, P = wpx * (32 * MT) + m * 32 + row;
+            floatx4 v = __builtin_bit_cast(floatx4, tile[row * U + (chunk ^ (row & (U - 1)))]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                v[e] = __builtin_amdgcn_fmed3f(__fmaf_rn(v[e], __fmul_rn(sc[e], xs[it]), bi[e]) + rv[it][e], lo, hi);
+            if (co < a.Cout && P < valid_px) *reinterpret_cast<floatx4 *>(out0 + (size_t)P * a.Cout + co) = v;
+        }
+    }
+}
+
+template <int KS, int STRIDE, int NT>
+static hipError_t i8_launch(const I8ConvArgs &a, size_t lds_bytes, dim3 grid, hipStream_t st)
+{
+    static bool lds_set = false;
+    if (!lds_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_i8_kernel<KS, STRIDE, NT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        lds_set = true;
+    }
+    hipLaunchKernelGGL((conv_i8_kernel<KS, STRIDE, NT>), grid, dim3(256), lds_bytes, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_i8(const I8ConvArgs &a, int ks, int stride, int nt, size_t lds_bytes, dim3 grid, hipStream_t st)
+{
+    if (a.N == 0) return hipSuccess;
+#define AIQ_I8(KS_, ST_)                                                                          \
+    if (ks == KS_ && stride == ST_) {                                                             \
+        if (nt == 1) return i8_launch<KS_, ST_, 1>(a, lds_bytes, grid, st);                       \
+        if (nt == 2) return i8_launch<KS_, ST_, 2>(a, lds_bytes, grid, st);                       \
+    }
+    AIQ_I8(3, 1)
+    AIQ_I8(3, 2)
+    AIQ_I8(1, 1)
+    AIQ_I8(1, 2)
+#undef AIQ_I8
+    return hipErrorInvalidValue;
+}
+
+} // namespace aiq

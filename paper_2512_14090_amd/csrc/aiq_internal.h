@@ -338,4 +338,37 @@ hipError_t launch_conv_codes(const CodeConvArgs &a, int ks, int stride, int nt, 
                              dim3 grid, hipStream_t st);
 hipError_t conv_codes_set_lds_limits();
 
+// Dense convolution of a layer of at most eight bits whose input tensor is quantized as well
+// (activation variant), from int8 codes on both sides on the INT8 matrix pipe (aiq_int8.hip).
+struct I8ConvArgs {
+    const int8_t *in;      // activation codes [N][Hin][Win][Cin], Cin % 16 == 0
+    const float *xscale;   // [N]: the images' activation scales
+    float *out;            // [N][Hout][Wout][Cout]
+    const float *res;      // like out, or nullptr
+    const float *bias;     // [Cout]
+    const int8_t *codes;   // weight codes [ceil(Cout/32)][tap][ceil(Cin/32)][64 lanes][16], zero padded
+    const float *scales;   // [Cout]: weight scales
+    int32_t N;
+    int32_t Hin, Win, Cin, Hout, Wout, Cout;
+    int32_t act;
+    int32_t R;             // output rows per workgroup region
+    int32_t G;             // images per workgroup (R == Hout when G > 1)
+    int32_t regions_per_image;
+    int32_t CBK;           // ceil(Cin/32)
+    int32_t CKB;           // blocks of 32 channels staged per pass (1 or 2)
+    int32_t RIN, LW;       // LDS tile: rows, row width (pixels)
+    int32_t PSB;           // bytes of one staged pixel: 32 * CKB + 16
+    int32_t wave_px_split; // waves along pixels (4, 2 or 1); 4/wave_px_split along output channels
+    int32_t cout_tiles;    // ceil(Cout/32)
+    int32_t tiles_per_wg;  // output-channel tiles of one workgroup: NT * 4 / wave_px_split
+    int32_t code_off;      // LDS byte where the pass's weight codes start (after the activations)
+    FastDiv div_rin, div_wout, div_rw, div_per_row, div_pximg; // RIN, Wout, R*Wout, LW * 2 * CKB, Hout*Wout
+};
+
+// in: fp32 [n][elems] (elems % 16 == 0) -> codes int8 [n][elems], xscale[n]; bits in {8, 6, 4, 2}
+hipError_t launch_act_codes(const float *in, int8_t *codes, float *xscale, int n, int elems, int bits, hipStream_t st);
+// codes: int32 [cout][cin][taps]; out: cleared buffer in the layout above
+hipError_t launch_pack_codes_i8(const int32_t *codes, int8_t *out, int cout, int cin, int taps, hipStream_t st);
+hipError_t launch_conv_i8(const I8ConvArgs &a, int ks, int stride, int nt, size_t lds_bytes, dim3 grid, hipStream_t st);
+
 } // namespace aiq

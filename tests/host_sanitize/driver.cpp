@@ -9,6 +9,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <random>
+#include <memory>
 #include <vector>
 
 extern "C" {
@@ -232,6 +233,23 @@ static void run_library(const Graph &g, uint32_t flags, std::mt19937 &rng)
         Buf ws(need);
         EXPECT(aiq_deploy_forward(dep, f(images), 5, 2, f(logits), i32(top1), ws.p, need, nullptr) == AIQ_OK);
         EXPECT(aiq_deploy_forward(dep, f(images), 5, 2, nullptr, i32(top1), ws.p, need - 1, nullptr) == AIQ_WORKSPACE_TOO_SMALL);
+        if (!aiq_model_is_lds_resident(m) && aiq_model_lds_resident_blocks(m) == 0) {
+            // every node's output of the deployed scheme, on buffers of exactly the advertised size
+            const int nn = aiq_model_nodes(m);
+            std::vector<std::unique_ptr<Buf>> outs;
+            std::vector<float *> ptrs;
+            for (int l = 0; l < nn; ++l) {
+                size_t e = 0;
+                EXPECT(aiq_node_output_elems(m, l, &e) == AIQ_OK);
+                outs.emplace_back(new Buf(e * 3 * sizeof(float)));
+                ptrs.push_back(f(*outs.back()));
+            }
+            size_t need3 = 0;
+            EXPECT(aiq_deploy_workspace_bytes(dep, 3, &need3) == AIQ_OK);
+            Buf ws3(need3);
+            EXPECT(aiq_deploy_forward_nodes(dep, f(images), 3, ptrs.data(), ws3.p, need3, nullptr) == AIQ_OK);
+            EXPECT(aiq_deploy_forward_nodes(dep, f(images), 3, ptrs.data(), ws3.p, need3 - 1, nullptr) == AIQ_WORKSPACE_TOO_SMALL);
+        }
         aiq_deploy_destroy(dep);
     }
     aiq_model_destroy(m);
