@@ -289,6 +289,8 @@ def deploy_mode(args, torch, aiq, synth):
     chunk = min(n_img, args.deploy_chunk)
     model = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=True)
     best = aiq.Model(wl["desc"], wl["weights"], wl["biases"])  # LDS-resident kernels where the graph allows
+    # the activation variant (a layer at b bits also reads its input at b bits): int8 codes on both sides
+    aqmodel = aiq.Model(wl["desc"], wl["weights"], wl["biases"], act_quant=True)
     q_search, trace = best.search(wl["desc"], images[:256], method="greedy", bits=(32, 8, 4), lam=0.9, chunk=256)
     twelve = np.full(L, 32, np.uint8)
     convs = [nd["scheme_slot"] for nd in wl["nodes"] if nd["kind"] == 0 and nd["input"] >= 0 and nd["scheme_slot"] >= 0]
@@ -341,6 +343,33 @@ def deploy_mode(args, torch, aiq, synth):
                         "algorithmic_gbytes_per_s": k["bytes"] / k["total_ms"] / 1e6,
                         "frac_of_hbm_peak": k["bytes"] / k["total_ms"] / 1e6 / PEAK_HBM_GBS}
             d.close()
+        if name != "fp32":
+            for key, fp32m in (("int8_codes", False), ("fp32_matrix", True)):
+                d = aiq.Deployed(aqmodel, q, fp32_matrix=fp32m)
+                dt, r = timed(lambda: d.forward(images, chunk=chunk, out=out, stream=stream))
+                sub = {"images_per_s": n_img / dt, "ms_per_step": dt * 1e3, "code_layers": d.code_layers,
+                       "agree_with_fp32": int((r["top1"] == top1_fp32).sum())}
+                if not fp32m:
+                    aqmodel.profile_enable(True)
+                    for c in range(8):
+                        aqmodel.profile_read(c)
+                    d.forward(images, chunk=chunk, out=out, stream=stream)
+                    torch.cuda.synchronize()
+                    aqmodel.profile_enable(False)
+                    kc8, kq8 = aqmodel.profile_read(aiq.K_CONV_CODES), aqmodel.profile_read(aiq.K_QUANTIZE)
+                    if kc8["launches"]:
+                        sub["conv_i8_kernel"] = {
+                            "launches": kc8["launches"], "avg_launch_ms": kc8["total_ms"] / kc8["launches"],
+                            "algorithmic_gbytes_per_s": kc8["bytes"] / kc8["total_ms"] / 1e6,
+                            "frac_of_hbm_peak": kc8["bytes"] / kc8["total_ms"] / 1e6 / PEAK_HBM_GBS,
+                            "executed_int8_tops": kc8["flops"] / kc8["total_ms"] / 1e9}
+                    if kq8["launches"]:
+                        sub["act_codes_kernel"] = {
+                            "launches": kq8["launches"], "avg_launch_ms": kq8["total_ms"] / kq8["launches"],
+                            "algorithmic_gbytes_per_s": kq8["bytes"] / kq8["total_ms"] / 1e6,
+                            "frac_of_hbm_peak": kq8["bytes"] / kq8["total_ms"] / 1e6 / PEAK_HBM_GBS}
+                row.setdefault("activation_variant", {})[key] = sub
+                d.close()
         if best.lds_resident or best.lds_resident_blocks > 0:
             # the model keeps activations in LDS: the deployment runs the scheme on those kernels
             d = aiq.Deployed(best, q)
@@ -374,6 +403,9 @@ def deploy_mode(args, torch, aiq, synth):
                                                              for k, v in res.items() if "bf16_codes" in v},
             "speedup_over_same_scheme_on_fp32_matrix": {k: v["bf16_codes"]["images_per_s"] / v["fp32_matrix"]["images_per_s"]
                                                         for k, v in res.items() if "bf16_codes" in v},
+            "activation_variant_speedup_over_fp32_model": {
+                k: v["activation_variant"]["int8_codes"]["images_per_s"] / fp32_ips
+                for k, v in res.items() if "activation_variant" in v},
             "schemes": res}
     if kc:
         line["roofline"] = {"bound": "mfma", "kernel": "conv_codes_kernel (3 bf16 MFMA products per fp32-equivalent product)",
@@ -387,6 +419,7 @@ def deploy_mode(args, torch, aiq, synth):
                                     "frac": kc["frac_of_hbm_peak"]}}
     model.close()
     best.close()
+    aqmodel.close()
     print(json.dumps(line))
 
 

@@ -266,7 +266,7 @@ bool plan_i8_conv(const Node &nd, I8Plan &p)
     const int groups = (p.cout_tiles + p.nt - 1) / p.nt; // wavefronts along the output channels, if all fit
     // first choice: two workgroups or more per compute unit; regions whose input rows are long (stride 2
     // at 32x32) get what one workgroup per unit can hold
-    for (size_t lds_limit : {(size_t)64 * 1024, (size_t)160 * 1024})
+    for (size_t lds_limit : {(size_t)80 * 1024, (size_t)160 * 1024})
     for (int wco = groups >= 4 ? 4 : (groups >= 2 ? 2 : 1); wco >= 1; wco /= 2) {
         p.wave_px_split = 4 / wco;
         p.tiles_per_wg = p.nt * wco;
@@ -279,7 +279,7 @@ bool plan_i8_conv(const Node &nd, I8Plan &p)
             if (p.R < 1) continue;
             p.regions_per_image = (nd.hout + p.R - 1) / p.R;
         } else {
-            p.G = region_px / px_img;
+            p.G = std::min(region_px / px_img, 64); // the epilogue keeps one activation scale per lane
             p.R = nd.hout;
             p.regions_per_image = 1;
         }
@@ -288,9 +288,11 @@ bool plan_i8_conv(const Node &nd, I8Plan &p)
         p.LW = d.win + 2 * d.pad;
         for (p.CKB = std::min(p.CBK, 2); p.CKB >= 1; --p.CKB) {
             p.PSB = 32 * p.CKB + 16;
-            p.code_off = (p.G * p.RIN * p.LW * p.PSB + 255) / 256 * 256;
-            const size_t staged = (size_t)p.code_off + (size_t)p.tiles_per_wg * T * p.CKB * 1024;
-            p.lds_bytes = std::max(staged, (size_t)4 * 32 * 32 * p.nt * sizeof(float));
+            // the epilogue's tiles (4 wavefronts x 32 pixels x 32 * nt channels) lie over the activations,
+            // never over the weight codes, which stay for the workgroup's next region
+            p.code_off = (int)std::max<size_t>((size_t)(p.G * p.RIN * p.LW * p.PSB + 255) / 256 * 256,
+                                               (size_t)4 * 32 * 32 * p.nt * sizeof(float));
+            p.lds_bytes = (size_t)p.code_off + (size_t)p.tiles_per_wg * T * p.CKB * 1024;
             if (p.lds_bytes <= lds_limit) return true;
         }
     }
@@ -1850,7 +1852,7 @@ aiq_status deploy_node(aiq_deployed *d, hipStream_t st, const HeadOut &ho, size_
         int8_t *xcodes = reinterpret_cast<int8_t *>(aq);
         float *xscale = reinterpret_cast<float *>(aq + align_up(nd.in_elems * (size_t)n, 256));
         {
-            ProfScope ps(m, st, AIQ_K_QUANTIZE, 0.0, 9.0 * nd.in_elems * n);
+            ProfScope ps(m, st, AIQ_K_QUANTIZE, 0.0, 5.0 * nd.in_elems * n); // one read, one byte written per value
             AIQ_HIP(launch_act_codes(io.in, xcodes, xscale, n, (int)nd.in_elems, cl.bits, st));
         }
         I8ConvArgs a{};
@@ -1886,7 +1888,11 @@ aiq_status deploy_node(aiq_deployed *d, hipStream_t st, const HeadOut &ho, size_
         a.div_rw = make_fastdiv(p.R * nd.wout);
         a.div_per_row = make_fastdiv(p.LW * 2 * p.CKB);
         a.div_pximg = make_fastdiv(nd.hout * nd.wout);
-        const unsigned gx = p.G > 1 ? (unsigned)((n + p.G - 1) / p.G) : (unsigned)(n * p.regions_per_image);
+        a.total_regions = p.G > 1 ? (n + p.G - 1) / p.G : n * p.regions_per_image;
+        // single-pass layers: a workgroup keeps the weight codes for several regions, as long as about a
+        // thousand workgroups remain
+        a.RPW = p.CBK <= p.CKB ? std::max(1, std::min(8, a.total_regions / 1024)) : 1;
+        const unsigned gx = (unsigned)((a.total_regions + a.RPW - 1) / a.RPW);
         ProfScope ps(m, st, AIQ_K_CONV_CODES, nd.flops_per_image * n,
                      ((double)nd.in_elems + 4.0 * nd.out_elems * (ld.residual >= 0 ? 2 : 1)) * n);
         AIQ_HIP(launch_conv_i8(a, ld.kh, ld.stride, p.nt, p.lds_bytes, dim3(gx, p.grid_y, 1), st));

@@ -65,12 +65,23 @@ __global__ __launch_bounds__(256) void act_codes_kernel(const float *__restrict_
 {
     __shared__ float wmax[4];
     const int n = blockIdx.x, tid = threadIdx.x;
-    const floatx4 *x4 = reinterpret_cast<const floatx4 *>(in + (size_t)n * elems);
+    const float *x = in + (size_t)n * elems;
     const int n4 = elems >> 2;
+    // eight 16-byte reads in flight per thread: the pass is a chain of memory latencies otherwise
+    constexpr int kDepth = 8;
     float amax = 0.0f;
-    for (int i = tid; i < n4; i += 256) {
-        const floatx4 v = x4[i];
-        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+    for (int base = tid; base < n4; base += 256 * kDepth) {
+        uintx4 v[kDepth];
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const int i = base + u * 256;
+            v[u] = i < n4 ? gload16(x + (size_t)i * 4) : uintx4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const floatx4 f = __builtin_bit_cast(floatx4, v[u]);
+            amax = fmaxf(fmaxf(amax, fmaxf(fabsf(f.x), fabsf(f.y))), fmaxf(fabsf(f.z), fabsf(f.w)));
+        }
     }
     amax = wave_max_f(amax);
     if ((tid & 63) == 0) wmax[tid >> 6] = amax;
@@ -80,15 +91,29 @@ __global__ __launch_bounds__(256) void act_codes_kernel(const float *__restrict_
     const float sc = amax > 0.0f ? __fdiv_rn(amax, (float)qmax) : 1.0f;
     if (tid == 0) xscale[n] = sc;
     uintx4 *out16 = reinterpret_cast<uintx4 *>(codes + (size_t)n * elems);
-    for (int i = tid; i < (elems >> 4); i += 256) {
-        uintx4 o;
+    const int n16 = elems >> 4;
+    // second pass (from L2): two output pieces = eight reads in flight per thread
+    for (int base = tid; base < n16; base += 512) {
+        uintx4 v[2][4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const floatx4 v = x4[i * 4 + g];
-            o[g] = (uint32_t)(code_of(v.x, sc, qmax) & 255) | ((uint32_t)(code_of(v.y, sc, qmax) & 255) << 8) |
-                   ((uint32_t)(code_of(v.z, sc, qmax) & 255) << 16) | ((uint32_t)(code_of(v.w, sc, qmax) & 255) << 24);
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int i = base + h * 256;
+                v[h][g] = i < n16 ? gload16(x + ((size_t)i * 4 + g) * 4) : uintx4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int i = base + h * 256;
+            uintx4 o;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const floatx4 f = __builtin_bit_cast(floatx4, v[h][g]);
+                o[g] = (uint32_t)(code_of(f.x, sc, qmax) & 255) | ((uint32_t)(code_of(f.y, sc, qmax) & 255) << 8) |
+                       ((uint32_t)(code_of(f.z, sc, qmax) & 255) << 16) | ((uint32_t)(code_of(f.w, sc, qmax) & 255) << 24);
+            }
+            if (i < n16) out16[i] = o;
         }
-        out16[i] = o;
     }
 }
 
@@ -130,32 +155,29 @@ hipError_t launch_pack_codes_i8(const int32_t *codes, int8_t *out, int cout, int
 
 // ------------------------------------------------------------------ convolution on int8 codes
 //
-// Workgroup = 4 wavefronts; a wavefront owns 64 pixels (two MFMA tiles) x 32*NT output channels.
-// Per pass of CKB blocks of 32 channels the workgroup stages in LDS the input rows of its region
-// (one 16-byte piece = 16 channels of a pixel, copied as it is; pixels outside the image are code
-// 0; the pixel stride carries 16 bytes of padding so that the 32 pixels of an operand read spread
-// over the banks) and the weight codes of its output tiles for those channels.  The taps are
-// unrolled; every operand read is the lane's base address plus an immediate.
+// Workgroup = 4 wavefronts; a wavefront owns 64 pixels (two MFMA tiles) x 32*NT output channels of a
+// region (whole rows of one image, or whole small images).  Per pass of CKB blocks of 32 channels the
+// workgroup stages in LDS the region's input rows (one 16-byte piece = 16 channels of a pixel, copied
+// as it is; pixels outside the image are code 0; the pixel stride carries 16 bytes of padding so that
+// the 32 pixels of an operand read spread over the banks) and the weight codes of its output tiles for
+// those channels.  The taps are unrolled; every operand read is the lane's base address plus an
+// immediate.
+//
+// The MFMA work is small (one instruction where the fp32 kernels issue 32), so the kernel is a data
+// mover: where a layer needs a single pass, a workgroup keeps the weight codes in LDS for RPW
+// consecutive regions and requests the next region's activations (registers) before it computes and
+// stores the current one, so that reads, MFMAs and the fp32 stores of neighbouring regions overlap.
 template <int KS, int STRIDE, int NT>
-__global__ __launch_bounds__(256) void conv_i8_kernel(I8ConvArgs a)
+__global__ __launch_bounds__(256, 2) void conv_i8_kernel(I8ConvArgs a)
 {
     extern __shared__ float lds_raw[];
     char *ldsb = reinterpret_cast<char *>(lds_raw);
     constexpr int T = KS * KS;
     constexpr int PAD = KS == 3 ? 1 : 0;
     constexpr int MT = 2;
+    constexpr int KI = 6; // 16-byte pieces a thread holds for the next region
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-
-    const int bx = (int)xcd_stretch(blockIdx.x, gridDim.x);
-    int img0, oy0;
-    if (a.G > 1) {
-        img0 = bx * a.G;
-        oy0 = 0;
-    } else {
-        img0 = bx / a.regions_per_image;
-        oy0 = (bx - img0 * a.regions_per_image) * a.R;
-    }
     const int wpx = wave % a.wave_px_split;
     const int wco = wave / a.wave_px_split;
     const int first_tile = blockIdx.y * a.tiles_per_wg;
@@ -175,56 +197,34 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(I8ConvArgs a)
         lds_base[m] = (in_region ? ((g * a.RIN + oy * STRIDE) * a.LW + ox * STRIDE) * (uint32_t)a.PSB : 0u) + kh * 16u;
     }
 
-    intx16 acc[MT][NT];
-#pragma unroll
-    for (int m = 0; m < MT; ++m)
-#pragma unroll
-        for (int n = 0; n < NT; ++n)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[m][n][e] = 0;
-
     const bool active = ct0 < a.cout_tiles; // wavefronts past the last output-channel tile only help staging
     const int upp = a.CKB * 2;              // 16-byte pieces of one staged pixel (2 or 4)
     const int upp_shift = upp == 2 ? 1 : 2;
     const int per_row = a.LW * upp;
     const int act_items = a.G * a.RIN * per_row;
-    const int iy0 = oy0 * STRIDE - PAD;
-    const int g_lim = min(a.G, a.N - img0);
-    const int8_t *in0 = a.in + (size_t)img0 * a.Hin * a.Win * a.Cin;
-    const int code_run = 64 * a.CKB;                       // pieces of one (tile, tap)
+    const int code_run = 64 * a.CKB;        // pieces of one (tile, tap)
     const int code_items = a.tiles_per_wg * T * code_run;
-    constexpr int kBatch = 6;                              // 16-byte reads in flight per thread
+    const bool single = a.CBK <= a.CKB;     // one pass: the weight codes stay in LDS from region to region
+    const bool ahead = single && act_items <= KI * 256;
+    const size_t img_bytes = (size_t)a.Hin * a.Win * a.Cin;
 
-    for (int kb0 = 0; kb0 < a.CBK; kb0 += a.CKB) {
-        const int ncb = min(a.CKB, a.CBK - kb0);
-        if (kb0) __syncthreads(); // the previous pass's LDS reads are done
-        // ---- activations
-        for (int base = tid; base < act_items; base += 256 * kBatch) {
-            uintx4 v[kBatch];
-            int dst[kBatch];
-#pragma unroll
-            for (int i = 0; i < kBatch; ++i) {
-                const int e = base + i * 256;
-                v[i] = uintx4{0u, 0u, 0u, 0u};
-                dst[i] = -1;
-                if (e < act_items) {
-                    const int row = (int)fd_div((uint32_t)e, a.div_per_row);
-                    const int rem = e - row * per_row;
-                    const int col = rem >> upp_shift, u = rem & (upp - 1);
-                    const int g = (int)fd_div((uint32_t)row, a.div_rin);
-                    const int iy = iy0 + row - g * a.RIN, ix = col - PAD;
-                    const int c = kb0 * 32 + u * 16;
-                    dst[i] = (row * a.LW + col) * a.PSB + u * 16;
-                    if ((unsigned)iy < (unsigned)a.Hin && (unsigned)ix < (unsigned)a.Win && g < g_lim && c < a.Cin)
-                        v[i] = gload16(
-                            in0 + ((size_t)(g * a.Hin + iy) * a.Win + ix) * a.Cin + c);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < kBatch; ++i)
-                if (dst[i] >= 0) *reinterpret_cast<uintx4 *>(ldsb + dst[i]) = v[i];
-        }
-        // ---- weight codes: piece j of the pass goes to code_off + 16 * j, order [tile][tap][block][lane]
+    // where piece e of a pass comes from and goes to; -1: no such piece / always outside the image
+    auto item_plan = [&](int e, int kb0, int &dst, int &src, int &rl, int &g) {
+        dst = src = -1;
+        rl = g = 0;
+        if (e >= act_items) return;
+        const int row = (int)fd_div((uint32_t)e, a.div_per_row);
+        const int rem = e - row * per_row;
+        const int col = rem >> upp_shift, u = rem & (upp - 1);
+        g = (int)fd_div((uint32_t)row, a.div_rin);
+        rl = row - g * a.RIN;
+        const int ix = col - PAD, c = kb0 * 32 + u * 16;
+        dst = (row * a.LW + col) * a.PSB + u * 16;
+        if ((unsigned)ix < (unsigned)a.Win && c < a.Cin) src = (g * a.Hin * a.Win + ix) * a.Cin + c;
+    };
+    // weight codes of a pass: piece j goes to code_off + 16 * j, order [tile][tap][block][lane]
+    auto stage_codes = [&](int kb0, int ncb) {
+        constexpr int kBatch = 6;
         for (int base = tid; base < code_items; base += 256 * kBatch) {
             uintx4 v[kBatch];
 #pragma unroll
@@ -236,9 +236,7 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(I8ConvArgs a)
                     const int ctl = r / T, t = r - ctl * T;
                     const int kbl = q >> 6, ln = q & 63;
                     const int ct = min(first_tile + ctl, a.cout_tiles - 1);
-                    if (kbl < ncb)
-                        v[i] = gload16(
-                            a.codes + ((((size_t)ct * T + t) * a.CBK + kb0 + kbl) * 64 + ln) * 16);
+                    if (kbl < ncb) v[i] = gload16(a.codes + ((((size_t)ct * T + t) * a.CBK + kb0 + kbl) * 64 + ln) * 16);
                 }
             }
 #pragma unroll
@@ -247,85 +245,191 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(I8ConvArgs a)
                 if (j < code_items) *reinterpret_cast<uintx4 *>(ldsb + a.code_off + j * 16) = v[i];
             }
         }
-        __syncthreads();
+    };
 
-        const uint32_t wbase = (uint32_t)a.code_off + (uint32_t)(wco * NT * T * code_run + lane) * 16u;
+    // this thread's pieces of a single-pass region, the same from region to region
+    int it_dst[KI], it_src[KI], it_rg[KI];
+    if (ahead) {
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            const uint32_t xoff = (uint32_t)((t / KS) * a.LW + (t % KS)) * (uint32_t)a.PSB;
+        for (int i = 0; i < KI; ++i) {
+            int rl, g;
+            item_plan(tid + i * 256, 0, it_dst[i], it_src[i], rl, g);
+            it_rg[i] = rl | (g << 16);
+        }
+    }
+    // region index -> first image, first output row
+    auto region_at = [&](int region, int &img0, int &oy0) {
+        if (a.G > 1) {
+            img0 = region * a.G;
+            oy0 = 0;
+        } else {
+            img0 = region / a.regions_per_image;
+            oy0 = (region - img0 * a.regions_per_image) * a.R;
+        }
+    };
+    auto fetch_ahead = [&](int region, uintx4 (&v)[KI]) {
+        int img0, oy0;
+        region_at(region, img0, oy0);
+        const int iy0 = oy0 * STRIDE - PAD, g_lim = min(a.G, a.N - img0);
+        const int8_t *in0 = a.in + (size_t)img0 * img_bytes;
+#pragma unroll
+        for (int i = 0; i < KI; ++i) {
+            v[i] = uintx4{0u, 0u, 0u, 0u};
+            const int iy = iy0 + (it_rg[i] & 0xffff), g = it_rg[i] >> 16;
+            if (it_src[i] >= 0 && (unsigned)iy < (unsigned)a.Hin && g < g_lim)
+                v[i] = gload16(in0 + it_src[i] + (size_t)iy * a.Win * a.Cin);
+        }
+    };
+
+    const int bx = (int)xcd_stretch(blockIdx.x, gridDim.x);
+    const int r_begin = bx * a.RPW, r_end = min(r_begin + a.RPW, a.total_regions);
+    if (r_begin >= r_end) return;
+    if (single) stage_codes(0, a.CBK);
+    // per-channel scale and bias of the chunk this lane stores in the epilogue: the same for every region
+    floatx4 sc = {0.f, 0.f, 0.f, 0.f}, bi = {0.f, 0.f, 0.f, 0.f};
+    {
+        const int co = ct0 * 32 + (lane & (8 * NT - 1)) * 4;
+        if (active && co < a.Cout) {
+            sc = __builtin_bit_cast(floatx4, gload16(a.scales + co));
+            bi = __builtin_bit_cast(floatx4, gload16(a.bias + co));
+        }
+    }
+    uintx4 ahead_v[KI];
+    if (ahead) fetch_ahead(r_begin, ahead_v);
+
+    for (int region = r_begin; region < r_end; ++region) {
+        int img0, oy0;
+        region_at(region, img0, oy0);
+        const int iy0 = oy0 * STRIDE - PAD, g_lim = min(a.G, a.N - img0);
+        const int8_t *in0 = a.in + (size_t)img0 * img_bytes;
+
+        intx16 acc[MT][NT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int n = 0; n < NT; ++n)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[m][n][e] = 0;
+        // The activation scales the epilogue multiplies by are requested here, so that they arrive during
+        // the MFMA loop: a region of one image has one (uniform), a region of several small images one per
+        // image (lane g holds image g's; the epilogue picks by pixel).
+        float xs_img = 0.0f;
+        if (a.G == 1) xs_img = a.xscale[img0];
+        else if (lane < g_lim) xs_img = a.xscale[img0 + lane];
+
+        for (int kb0 = 0; kb0 < a.CBK; kb0 += a.CKB) {
+            const int ncb = min(a.CKB, a.CBK - kb0);
+            if (kb0) __syncthreads(); // the previous pass's LDS reads are done
+            if (ahead) {
+#pragma unroll
+                for (int i = 0; i < KI; ++i)
+                    if (it_dst[i] >= 0) *reinterpret_cast<uintx4 *>(ldsb + it_dst[i]) = ahead_v[i];
+            } else {
+                constexpr int kBatch = 6;
+                for (int base = tid; base < act_items; base += 256 * kBatch) {
+                    uintx4 v[kBatch];
+                    int dst[kBatch];
+#pragma unroll
+                    for (int i = 0; i < kBatch; ++i) {
+                        int src, rl, g;
+                        item_plan(base + i * 256, kb0, dst[i], src, rl, g);
+                        v[i] = uintx4{0u, 0u, 0u, 0u};
+                        const int iy = iy0 + rl;
+                        if (src >= 0 && (unsigned)iy < (unsigned)a.Hin && g < g_lim)
+                            v[i] = gload16(in0 + src + (size_t)iy * a.Win * a.Cin);
+                    }
+#pragma unroll
+                    for (int i = 0; i < kBatch; ++i)
+                        if (dst[i] >= 0) *reinterpret_cast<uintx4 *>(ldsb + dst[i]) = v[i];
+                }
+            }
+            if (!single) stage_codes(kb0, ncb);
+            __syncthreads();
+            if (ahead && region + 1 < r_end) fetch_ahead(region + 1, ahead_v); // travels while this region computes and stores
+
+            const uint32_t wbase = (uint32_t)a.code_off + (uint32_t)(wco * NT * T * code_run + lane) * 16u;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                // a tap's operand reads stay inside the tap: hoisted over the unrolled taps they would take
+                // more registers than the kernel has, and the wavefronts of the other workgroup cover the wait
+                __builtin_amdgcn_sched_barrier(0);
+                const uint32_t xoff = (uint32_t)((t / KS) * a.LW + (t % KS)) * (uint32_t)a.PSB;
 #pragma unroll 1
-            for (int kbl = 0; kbl < ncb; ++kbl) {
-                intx4 wa[NT], xb[MT];
-#pragma unroll
-                for (int n = 0; n < NT; ++n)
-                    wa[n] = *reinterpret_cast<const intx4 *>(ldsb + wbase + (uint32_t)(((n * T + t) * a.CKB + kbl) * 1024));
-#pragma unroll
-                for (int m = 0; m < MT; ++m)
-                    xb[m] = *reinterpret_cast<const intx4 *>(ldsb + lds_base[m] + xoff + (uint32_t)kbl * 32u);
-#pragma unroll
-                for (int m = 0; m < MT; ++m)
+                for (int kbl = 0; kbl < ncb; ++kbl) {
+                    intx4 wa[NT], xb[MT];
 #pragma unroll
                     for (int n = 0; n < NT; ++n)
-                        acc[m][n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wa[n], xb[m], acc[m][n], 0, 0, 0);
+                        wa[n] = *reinterpret_cast<const intx4 *>(ldsb + wbase + (uint32_t)(((n * T + t) * a.CKB + kbl) * 1024));
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+                        xb[m] = *reinterpret_cast<const intx4 *>(ldsb + lds_base[m] + xoff + (uint32_t)kbl * 32u);
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+#pragma unroll
+                        for (int n = 0; n < NT; ++n)
+                            acc[m][n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wa[n], xb[m], acc[m][n], 0, 0, 0);
+                }
             }
         }
-    }
 
-    // ---- epilogue: through LDS (a lane's accumulators are four groups of four consecutive output
-    // channels of one pixel; consecutive lanes then store consecutive 16-byte chunks of a pixel: whole
-    // lines), scale, bias, residual, activation.  Chunk c of row r lives in unit r * U + (c ^ (r % U)).
-    __syncthreads();
-    if (!active) return;
-    constexpr int U = 8 * NT;
-    uintx4 *tile = reinterpret_cast<uintx4 *>(ldsb) + wave * 32 * U;
-    const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
-    const int px_img = a.Hout * a.Wout;
-    const size_t first_px = a.G > 1 ? (size_t)img0 * px_img : ((size_t)img0 * a.Hout + oy0) * a.Wout;
-    const int valid_px = a.G > 1 ? g_lim * px_img : min(a.R, a.Hout - oy0) * a.Wout;
-    float *out0 = a.out + first_px * a.Cout;
-    const float *res0 = a.res ? a.res + first_px * a.Cout : nullptr;
-    constexpr int ROWS = 64 / U, ITS = 32 / ROWS;
-    const int chunk = lane & (U - 1), sub = lane / U;
-    const int co = ct0 * 32 + chunk * 4;
-    floatx4 sc = {0.f, 0.f, 0.f, 0.f}, bi = {0.f, 0.f, 0.f, 0.f};
-    if (co < a.Cout) {
-        sc = *reinterpret_cast<const floatx4 *>(a.scales + co);
-        bi = *reinterpret_cast<const floatx4 *>(a.bias + co);
-    }
+        // ---- epilogue: through LDS (a lane's accumulators are four groups of four consecutive output
+        // channels of one pixel; consecutive lanes then store consecutive 16-byte chunks of a pixel: whole
+        // lines), scale, bias, residual, activation.  Chunk c of row r lives in unit r * U + (c ^ (r % U)).
+        // The tiles lie over the staged activations (never over the weight codes).
+        __syncthreads();
+        if (active) {
+            constexpr int U = 8 * NT;
+            // the lane arithmetic of the epilogue is redone per region: kept across the region loop it
+            // would push the accumulators out of the register file
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            const int p = ln & 31, kh = ln >> 5;
+            uintx4 *tile = reinterpret_cast<uintx4 *>(ldsb) + wave * 32 * U;
+            const float lo = a.act >= 1 ? 0.0f : -__builtin_inff(), hi = a.act == 2 ? 6.0f : __builtin_inff();
+            const int px_img = a.Hout * a.Wout;
+            const size_t first_px = a.G > 1 ? (size_t)img0 * px_img : ((size_t)img0 * a.Hout + oy0) * a.Wout;
+            const int valid_px = a.G > 1 ? g_lim * px_img : min(a.R, a.Hout - oy0) * a.Wout;
+            float *out0 = a.out + first_px * a.Cout;
+            const float *res0 = a.res ? a.res + first_px * a.Cout : nullptr;
+            constexpr int ROWS = 64 / U, ITS = 32 / ROWS;
+            const int chunk = ln & (U - 1), sub = ln / U;
+            const int co = ct0 * 32 + chunk * 4;
 #pragma unroll
-    for (int m = 0; m < MT; ++m) {
-        // accumulator e of a lane is output channel 8 * (e / 4) + 4 * kh + e % 4 of its tile
+            for (int m = 0; m < MT; ++m) {
+                // accumulator e of a lane is output channel 8 * (e / 4) + 4 * kh + e % 4 of its tile
 #pragma unroll
-        for (int n = 0; n < NT; ++n)
+                for (int n = 0; n < NT; ++n)
 #pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const int c = n * 8 + g4 * 2 + kh;
-                const floatx4 v = {(float)acc[m][n][g4 * 4], (float)acc[m][n][g4 * 4 + 1], (float)acc[m][n][g4 * 4 + 2],
-                                   (float)acc[m][n][g4 * 4 + 3]};
-                tile[p * U + (c ^ (p & (U - 1)))] = __builtin_bit_cast(uintx4, v);
-            }
-        floatx4 rv[ITS];
-        float xs[ITS];
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        const int c = n * 8 + g4 * 2 + kh;
+                        const floatx4 v = {(float)acc[m][n][g4 * 4], (float)acc[m][n][g4 * 4 + 1],
+                                           (float)acc[m][n][g4 * 4 + 2], (float)acc[m][n][g4 * 4 + 3]};
+                        tile[p * U + (c ^ (p & (U - 1)))] = __builtin_bit_cast(uintx4, v);
+                    }
+                floatx4 rv[ITS];
+                float xs[ITS];
 #pragma unroll
-        for (int it = 0; it < ITS; ++it) {
-            const int P = wpx * (32 * MT) + m * 32 + it * ROWS + sub;
-            rv[it] = floatx4{0.f, 0.f, 0.f, 0.f};
-            xs[it] = 0.0f;
-            if (co < a.Cout && P < valid_px) {
-                const int g = a.G > 1 ? (int)fd_div((uint32_t)P, a.div_pximg) : 0;
-                xs[it] = a.xscale[img0 + g];
-                if (res0) rv[it] = __builtin_bit_cast(floatx4, gload16(res0 + (size_t)P * a.Cout + co));
+                for (int it = 0; it < ITS; ++it) {
+                    const int P = wpx * (32 * MT) + m * 32 + it * ROWS + sub;
+                    rv[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    // every lane takes part in the shuffle; images past the group's last give 0 and are not stored
+                    const int g = a.G > 1 ? min((int)fd_div((uint32_t)P, a.div_pximg), 63) : 0;
+                    xs[it] = a.G > 1 ? __shfl(xs_img, g, 64) : xs_img;
+                    if (res0 && co < a.Cout && P < valid_px)
+                        rv[it] = __builtin_bit_cast(floatx4, gload16(res0 + (size_t)P * a.Cout + co));
+                }
+#pragma unroll
+                for (int it = 0; it < ITS; ++it) {
+                    const int row = it * ROWS + sub, P = wpx * (32 * MT) + m * 32 + row;
+                    floatx4 v = __builtin_bit_cast(floatx4, tile[row * U + (chunk ^ (row & (U - 1)))]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        v[e] = __builtin_amdgcn_fmed3f(__fmaf_rn(v[e], __fmul_rn(sc[e], xs[it]), bi[e]) + rv[it][e], lo, hi);
+                    if (co < a.Cout && P < valid_px) __builtin_nontemporal_store(v, reinterpret_cast<floatx4 *>(out0 + (size_t)P * a.Cout + co));
+                }
             }
         }
-#pragma unroll
-        for (int it = 0; it < ITS; ++it) {
-            const int row = it * ROWS + sub, P = wpx * (32 * MT) + m * 32 + row;
-            floatx4 v = __builtin_bit_cast(floatx4, tile[row * U + (chunk ^ (row & (U - 1)))]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                v[e] = __builtin_amdgcn_fmed3f(__fmaf_rn(v[e], __fmul_rn(sc[e], xs[it]), bi[e]) + rv[it][e], lo, hi);
-            if (co < a.Cout && P < valid_px) *reinterpret_cast<floatx4 *>(out0 + (size_t)P * a.Cout + co) = v;
-        }
+        if (region + 1 < r_end) __syncthreads(); // the tiles are read before the next region's activations land on them
     }
 }
 

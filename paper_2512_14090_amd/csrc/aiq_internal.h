@@ -361,7 +361,9 @@ struct I8ConvArgs {
     int32_t wave_px_split; // waves along pixels (4, 2 or 1); 4/wave_px_split along output channels
     int32_t cout_tiles;    // ceil(Cout/32)
     int32_t tiles_per_wg;  // output-channel tiles of one workgroup: NT * 4 / wave_px_split
-    int32_t code_off;      // LDS byte where the pass's weight codes start (after the activations)
+    int32_t code_off;      // LDS byte where the pass's weight codes start (after the activations and the epilogue's tiles)
+    int32_t RPW;           // consecutive regions one workgroup works through (1 unless the layer needs a single pass)
+    int32_t total_regions; // regions (G == 1) or image groups (G > 1) of the launch
     FastDiv div_rin, div_wout, div_rw, div_per_row, div_pximg; // RIN, Wout, R*Wout, LW * 2 * CKB, Hout*Wout
 };
 
