@@ -266,7 +266,7 @@ bool plan_i8_conv(const Node &nd, I8Plan &p)
     const int groups = (p.cout_tiles + p.nt - 1) / p.nt; // wavefronts along the output channels, if all fit
     // first choice: two workgroups or more per compute unit; regions whose input rows are long (stride 2
     // at 32x32) get what one workgroup per unit can hold
-    for (size_t lds_limit : {(size_t)80 * 1024, (size_t)160 * 1024})
+    for (size_t lds_limit : {(size_t)79 * 1024, (size_t)159 * 1024})
     for (int wco = groups >= 4 ? 4 : (groups >= 2 ? 2 : 1); wco >= 1; wco /= 2) {
         p.wave_px_split = 4 / wco;
         p.tiles_per_wg = p.nt * wco;
@@ -510,7 +510,7 @@ aiq_status dev_alloc(aiq_model *m, T **p, size_t n)
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WorkspaceLayout {
-    size_t schemes_off, top1_off, act_off, aq_off, total;
+    size_t schemes_off, top1_off, act_off, aq_off, amax_off, total;
     size_t buf_stride; // bytes of one activation buffer
     // prefix sharing only (0 otherwise): reference scheme, first op per scheme, the reference
     // pass's top-1, the checkpoint records of one chunk
@@ -533,6 +533,9 @@ WorkspaceLayout workspace_layout(const aiq_model *m, int S, int chunk, bool shar
     if (m->act_quant)
         off += align_up(sizeof(float) * m->aq_elems * (size_t)(S + 1) * chunk, 256) +
                align_up(sizeof(float) * (size_t)(S + 1) * chunk, 256);
+    // deployed int8 layers: per node and image, the absolute maximum of the node's output (float bit patterns)
+    w.amax_off = off;
+    if (m->act_quant) off += align_up(sizeof(uint32_t) * m->nodes.size() * (size_t)chunk, 256);
     if (shared && (m->fused_ckpt_floats > 0 || !m->fused)) {
         off = align_up(off, 256);
         w.ref_off = off;
@@ -1706,6 +1709,7 @@ struct aiq_deployed {
         int bits = 32;
     };
     std::vector<Layer> layer; // per node
+    std::vector<char> amax_ok; // per node: its kernel leaves max |output| per image for the int8 layers that read it
     std::vector<void *> allocations;
     int n_code_layers = 0;
     bool resident = false; // the model keeps activations in LDS: the scheme runs on those kernels
@@ -1734,6 +1738,7 @@ aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags
     d->m = m;
     d->scheme.assign(scheme, scheme + m->L);
     d->layer.resize(m->nodes.size());
+    d->amax_ok.assign(m->nodes.size(), 0);
     if (resident) {
         // A model whose activations stay in LDS (whole CIFAR-style ResNets, inverted-residual blocks) is
         // deployed on those kernels, the scheme being the one "candidate" of a scoring call: the integer-code
@@ -1781,6 +1786,8 @@ aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags
                 return fail(AIQ_DEVICE_ERROR);
             tmp_elems = std::max(tmp_elems, (size_t)nd.d.cout * nd.k);
             ++d->n_code_layers;
+            // the 32 pixels of an output tile lie in one image: one maximum per tile
+            d->amax_ok[l] = p.G == 1 || (nd.hout * nd.wout) % 32 == 0;
         } else if (on_codes) {
             const CodePlan &p = d->layer[l].plan;
             const size_t code_elems = (size_t)p.cout_tiles * nd.d.kh * nd.d.kw * p.CB * 512;
@@ -1841,7 +1848,7 @@ namespace {
 // input tensor of a scheme layer, per image); the int8 path keeps its activation codes in the first
 // quarter of it and the images' scales behind them.
 aiq_status deploy_node(aiq_deployed *d, hipStream_t st, const HeadOut &ho, size_t l, const NodeIO &io, int n, int n0,
-                       char *aq)
+                       char *aq, uint32_t *amax, size_t amax_stride)
 {
     aiq_model *m = d->m;
     const Node &nd = m->nodes[l];
@@ -1853,7 +1860,8 @@ aiq_status deploy_node(aiq_deployed *d, hipStream_t st, const HeadOut &ho, size_
         float *xscale = reinterpret_cast<float *>(aq + align_up(nd.in_elems * (size_t)n, 256));
         {
             ProfScope ps(m, st, AIQ_K_QUANTIZE, 0.0, 5.0 * nd.in_elems * n); // one read, one byte written per value
-            AIQ_HIP(launch_act_codes(io.in, xcodes, xscale, n, (int)nd.in_elems, cl.bits, st));
+            const uint32_t *in_amax = ld.input >= 0 && d->amax_ok[ld.input] ? amax + amax_stride * ld.input : nullptr;
+            AIQ_HIP(launch_act_codes(io.in, in_amax, xcodes, xscale, n, (int)nd.in_elems, cl.bits, st));
         }
         I8ConvArgs a{};
         a.in = xcodes;
@@ -1863,6 +1871,7 @@ aiq_status deploy_node(aiq_deployed *d, hipStream_t st, const HeadOut &ho, size_
         a.bias = nd.bias;
         a.codes = cl.codes8;
         a.scales = cl.scales;
+        a.amax_out = d->amax_ok[l] ? amax + amax_stride * l : nullptr;
         a.N = n;
         a.Hin = ld.hin;
         a.Win = ld.win;
@@ -1958,8 +1967,11 @@ aiq_status aiq_deploy_forward(aiq_deployed *d, const float *images, int32_t N, i
     auto buf_ptr = [&](int b) { return reinterpret_cast<float *>(ws + wl.act_off + wl.buf_stride * b); };
     m->aq_cur = m->act_quant ? reinterpret_cast<float *>(ws + wl.aq_off) : nullptr;
     const HeadOut ho{logits, N, top1, nullptr, chunk};
+    uint32_t *amax = reinterpret_cast<uint32_t *>(ws + wl.amax_off);
+    const bool any_amax = std::any_of(d->amax_ok.begin(), d->amax_ok.end(), [](char c) { return c != 0; });
     for (int n0 = 0; n0 < N; n0 += chunk) {
         const int n = std::min(chunk, N - n0);
+        if (any_amax) AIQ_HIP(launch_fill_i32(reinterpret_cast<int32_t *>(amax), 0, m->nodes.size() * (size_t)chunk, st));
         for (size_t l = 0; l < m->nodes.size(); ++l) {
             const Node &nd = m->nodes[l];
             NodeIO io{};
@@ -1969,7 +1981,7 @@ aiq_status aiq_deploy_forward(aiq_deployed *d, const float *images, int32_t N, i
             io.in = nd.d.input < 0 ? images + (size_t)n0 * nd.in_elems : buf_ptr(m->nodes[nd.d.input].buf);
             io.out = nd.buf >= 0 ? buf_ptr(nd.buf) : nullptr;
             io.res = nd.d.residual >= 0 ? buf_ptr(m->nodes[nd.d.residual].buf) : nullptr;
-            aiq_status rc = deploy_node(d, st, ho, l, io, n, n0, ws + wl.aq_off);
+            aiq_status rc = deploy_node(d, st, ho, l, io, n, n0, ws + wl.aq_off, amax, (size_t)chunk);
             if (rc != AIQ_OK) return rc;
         }
     }
@@ -1994,6 +2006,8 @@ aiq_status aiq_deploy_forward_nodes(aiq_deployed *d, const float *images, int32_
     m->aq_cur = m->act_quant ? reinterpret_cast<float *>(ws + wl.aq_off) : nullptr;
     const size_t last = m->nodes.size() - 1;
     const HeadOut ho{node_out[last], N, nullptr, reinterpret_cast<int32_t *>(ws + wl.top1_off), N};
+    uint32_t *amax = reinterpret_cast<uint32_t *>(ws + wl.amax_off);
+    if (m->act_quant) AIQ_HIP(launch_fill_i32(reinterpret_cast<int32_t *>(amax), 0, m->nodes.size() * (size_t)N, st));
     for (size_t l = 0; l < m->nodes.size(); ++l) {
         const Node &nd = m->nodes[l];
         NodeIO io{};
@@ -2003,7 +2017,7 @@ aiq_status aiq_deploy_forward_nodes(aiq_deployed *d, const float *images, int32_
         io.in = nd.d.input < 0 ? images : node_out[nd.d.input];
         io.out = node_out[l];
         io.res = nd.d.residual >= 0 ? node_out[nd.d.residual] : nullptr;
-        aiq_status rc = deploy_node(d, st, ho, l, io, N, 0, ws + wl.aq_off);
+        aiq_status rc = deploy_node(d, st, ho, l, io, N, 0, ws + wl.aq_off, amax, (size_t)N);
         if (rc != AIQ_OK) return rc;
     }
     return AIQ_OK;

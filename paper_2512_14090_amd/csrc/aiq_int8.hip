@@ -41,6 +41,25 @@ __device__ inline float wave_max_f(float v)
     return v;
 }
 
+// Maximum of a non-negative value over the wavefront, left in lane 63, by data-parallel-primitive moves
+// (no LDS traffic): shifts within rows of 16 lanes give lane 15 of each row its row's maximum, the two
+// row broadcasts carry it on to lane 63.  Lanes shifted in from outside a row read 0, the identity here.
+template <int CTRL>
+__device__ __forceinline__ float dpp_max_step(float x)
+{
+    return fmaxf(x, __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), CTRL, 0xf, 0xf, true)));
+}
+__device__ __forceinline__ float wave_max_nonneg(float v)
+{
+    v = dpp_max_step<0x111>(v); // row_shr:1
+    v = dpp_max_step<0x112>(v); // row_shr:2
+    v = dpp_max_step<0x114>(v); // row_shr:4
+    v = dpp_max_step<0x118>(v); // row_shr:8
+    v = dpp_max_step<0x142>(v); // row_bcast:15
+    v = dpp_max_step<0x143>(v); // row_bcast:31
+    return v;
+}
+
 // 16 bytes through an explicit global address (global_load, not flat_load)
 __device__ __forceinline__ uintx4 gload16(const void *p)
 {
@@ -52,6 +71,13 @@ __device__ __forceinline__ int code_of(float x, float s, int qmax)
 {
     const int q = (int)rintf(__fdiv_rn(x, s));
     return min(max(q, -qmax), qmax);
+}
+
+// four values -> four codes in one dword, first value in the low byte
+__device__ __forceinline__ uint32_t pack_codes4(floatx4 f, float s, int qmax)
+{
+    return (uint32_t)(code_of(f.x, s, qmax) & 255) | ((uint32_t)(code_of(f.y, s, qmax) & 255) << 8) |
+           ((uint32_t)(code_of(f.z, s, qmax) & 255) << 16) | ((uint32_t)(code_of(f.w, s, qmax) & 255) << 24);
 }
 
 } // namespace
@@ -90,37 +116,66 @@ __global__ __launch_bounds__(256) void act_codes_kernel(const float *__restrict_
     const int qmax = (1 << (bits - 1)) - 1;
     const float sc = amax > 0.0f ? __fdiv_rn(amax, (float)qmax) : 1.0f;
     if (tid == 0) xscale[n] = sc;
-    uintx4 *out16 = reinterpret_cast<uintx4 *>(codes + (size_t)n * elems);
-    const int n16 = elems >> 4;
-    // second pass (from L2): two output pieces = eight reads in flight per thread
-    for (int base = tid; base < n16; base += 512) {
-        uintx4 v[2][4];
+    // second pass: a lane turns one 16-byte read into four codes, one 4-byte store; consecutive lanes
+    // on consecutive addresses both ways
+    uint32_t *out32 = reinterpret_cast<uint32_t *>(codes + (size_t)n * elems);
+    for (int base = tid; base < n4; base += 256 * kDepth) {
+        uintx4 v[kDepth];
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int u = 0; u < kDepth; ++u) {
+            const int i = base + u * 256;
+            v[u] = i < n4 ? gload16(x + (size_t)i * 4) : uintx4{0u, 0u, 0u, 0u};
+        }
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int i = base + h * 256;
-                v[h][g] = i < n16 ? gload16(x + ((size_t)i * 4 + g) * 4) : uintx4{0u, 0u, 0u, 0u};
-            }
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int i = base + h * 256;
-            uintx4 o;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const floatx4 f = __builtin_bit_cast(floatx4, v[h][g]);
-                o[g] = (uint32_t)(code_of(f.x, sc, qmax) & 255) | ((uint32_t)(code_of(f.y, sc, qmax) & 255) << 8) |
-                       ((uint32_t)(code_of(f.z, sc, qmax) & 255) << 16) | ((uint32_t)(code_of(f.w, sc, qmax) & 255) << 24);
-            }
-            if (i < n16) out16[i] = o;
+        for (int u = 0; u < kDepth; ++u) {
+            const int i = base + u * 256;
+            if (i < n4) out32[i] = pack_codes4(__builtin_bit_cast(floatx4, v[u]), sc, qmax);
         }
     }
 }
 
-hipError_t launch_act_codes(const float *in, int8_t *codes, float *xscale, int n, int elems, int bits, hipStream_t st)
+// The same codes when the producing kernel has left the images' absolute maxima (bit patterns of
+// non-negative floats, combined by integer atomic maxima: exact in any order): one streaming pass,
+// blockIdx.y = image, a thread converts kPieces 16-byte pieces.
+constexpr int kCodeReads = 8; // 16-byte reads in flight per thread
+
+__global__ __launch_bounds__(256) void act_codes_known_amax_kernel(const float *__restrict__ in,
+                                                                   const uint32_t *__restrict__ amax_bits,
+                                                                   int8_t *__restrict__ codes, float *__restrict__ xscale,
+                                                                   int elems, int bits)
+{
+    const int n = blockIdx.y, tid = threadIdx.x;
+    const uintx4 *x4 = reinterpret_cast<const uintx4 *>(in + (size_t)n * elems);
+    const float amax = __uint_as_float(amax_bits[n]);
+    const int qmax = (1 << (bits - 1)) - 1;
+    const float sc = amax > 0.0f ? __fdiv_rn(amax, (float)qmax) : 1.0f;
+    if (blockIdx.x == 0 && tid == 0) xscale[n] = sc;
+    uint32_t *out32 = reinterpret_cast<uint32_t *>(codes + (size_t)n * elems);
+    const int n4 = elems >> 2;
+    const int base = blockIdx.x * (256 * kCodeReads) + tid;
+    uintx4 v[kCodeReads];
+#pragma unroll
+    for (int u = 0; u < kCodeReads; ++u) {
+        const int i = base + u * 256;
+        v[u] = i < n4 ? __builtin_nontemporal_load(x4 + i) : uintx4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int u = 0; u < kCodeReads; ++u) {
+        const int i = base + u * 256;
+        if (i < n4) out32[i] = pack_codes4(__builtin_bit_cast(floatx4, v[u]), sc, qmax);
+    }
+}
+
+hipError_t launch_act_codes(const float *in, const uint32_t *amax_bits, int8_t *codes, float *xscale, int n, int elems,
+                            int bits, hipStream_t st)
 {
     if (n == 0 || elems == 0) return hipSuccess;
-    hipLaunchKernelGGL(act_codes_kernel, dim3(n), dim3(256), 0, st, in, codes, xscale, elems, bits);
+    if (amax_bits) {
+        const unsigned bx = (unsigned)(((elems >> 2) + 256 * kCodeReads - 1) / (256 * kCodeReads));
+        hipLaunchKernelGGL(act_codes_known_amax_kernel, dim3(bx, n), dim3(256), 0, st, in, amax_bits, codes, xscale, elems, bits);
+    } else {
+        hipLaunchKernelGGL(act_codes_kernel, dim3(n), dim3(256), 0, st, in, codes, xscale, elems, bits);
+    }
     return hipGetLastError();
 }
 
@@ -396,6 +451,7 @@ __global__ __launch_bounds__(256, 2) void conv_i8_kernel(I8ConvArgs a)
             const int co = ct0 * 32 + chunk * 4;
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
+                float vmax = 0.0f; // largest magnitude this lane stores of tile m
                 // accumulator e of a lane is output channel 8 * (e / 4) + 4 * kh + e % 4 of its tile
 #pragma unroll
                 for (int n = 0; n < NT; ++n)
@@ -425,7 +481,21 @@ __global__ __launch_bounds__(256, 2) void conv_i8_kernel(I8ConvArgs a)
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         v[e] = __builtin_amdgcn_fmed3f(__fmaf_rn(v[e], __fmul_rn(sc[e], xs[it]), bi[e]) + rv[it][e], lo, hi);
-                    if (co < a.Cout && P < valid_px) __builtin_nontemporal_store(v, reinterpret_cast<floatx4 *>(out0 + (size_t)P * a.Cout + co));
+                    if (co < a.Cout && P < valid_px) {
+                        __builtin_nontemporal_store(v, reinterpret_cast<floatx4 *>(out0 + (size_t)P * a.Cout + co));
+                        vmax = fmaxf(fmaxf(vmax, fmaxf(fabsf(v[0]), fabsf(v[1]))), fmaxf(fabsf(v[2]), fabsf(v[3])));
+                    }
+                }
+                // The image's absolute maximum for the layer that reads this output quantized: the host asks
+                // for it only where the 32 pixels of a tile lie in one image.  Bit patterns of non-negative
+                // floats order like the floats, and an integer maximum does not depend on the order.
+                if (a.amax_out) {
+                    vmax = wave_max_nonneg(vmax); // in lane 63
+                    const int P0 = wpx * (32 * MT) + m * 32;
+                    if (lane == 63 && P0 < valid_px) {
+                        const int g = a.G > 1 ? (int)fd_div((uint32_t)P0, a.div_pximg) : 0;
+                        atomicMax(a.amax_out + img0 + g, __float_as_uint(vmax));
+                    }
                 }
             }
         }
@@ -439,7 +509,7 @@ static hipError_t i8_launch(const I8ConvArgs &a, size_t lds_bytes, dim3 grid, hi
     static bool lds_set = false;
     if (!lds_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_i8_kernel<KS, STRIDE, NT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024);
         if (e != hipSuccess) return e;
         lds_set = true;
     }

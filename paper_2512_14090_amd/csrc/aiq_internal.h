@@ -348,6 +348,7 @@ struct I8ConvArgs {
     const float *bias;     // [Cout]
     const int8_t *codes;   // weight codes [ceil(Cout/32)][tap][ceil(Cin/32)][64 lanes][16], zero padded
     const float *scales;   // [Cout]: weight scales
+    uint32_t *amax_out;    // nullable: [N], cleared by the caller; receives max |out| per image as float bit patterns
     int32_t N;
     int32_t Hin, Win, Cin, Hout, Wout, Cout;
     int32_t act;
@@ -367,8 +368,10 @@ struct I8ConvArgs {
     FastDiv div_rin, div_wout, div_rw, div_per_row, div_pximg; // RIN, Wout, R*Wout, LW * 2 * CKB, Hout*Wout
 };
 
-// in: fp32 [n][elems] (elems % 16 == 0) -> codes int8 [n][elems], xscale[n]; bits in {8, 6, 4, 2}
-hipError_t launch_act_codes(const float *in, int8_t *codes, float *xscale, int n, int elems, int bits, hipStream_t st);
+// in: fp32 [n][elems] (elems % 16 == 0) -> codes int8 [n][elems], xscale[n]; bits in {8, 6, 4, 2}.
+// amax_bits: nullable, [n]: the images' absolute maxima as float bit patterns, if the producer has left them
+hipError_t launch_act_codes(const float *in, const uint32_t *amax_bits, int8_t *codes, float *xscale, int n, int elems,
+                            int bits, hipStream_t st);
 // codes: int32 [cout][cin][taps]; out: cleared buffer in the layout above
 hipError_t launch_pack_codes_i8(const int32_t *codes, int8_t *out, int cout, int cin, int taps, hipStream_t st);
 hipError_t launch_conv_i8(const I8ConvArgs &a, int ks, int stride, int nt, size_t lds_bytes, dim3 grid, hipStream_t st);

@@ -353,10 +353,12 @@ hipError_t launch_conv_codes(const CodeConvArgs &a, int ks, int stride, int nt, 
     return hipSuccess;
 }
 
-hipError_t launch_act_codes(const float *in, int8_t *codes, float *xscale, int n, int elems, int bits, hipStream_t)
+hipError_t launch_act_codes(const float *in, const uint32_t *amax_bits, int8_t *codes, float *xscale, int n, int elems,
+                            int bits, hipStream_t)
 {
     ++g_launches;
     if (bits < 2 || bits > 8 || (elems & 15)) return hipErrorInvalidValue;
+    if (amax_bits) touch_read(amax_bits, (size_t)n);
     touch_read(in, (size_t)n * elems);
     touch_write(codes, (size_t)n * elems);
     touch_write(xscale, (size_t)n);
@@ -374,9 +376,10 @@ hipError_t launch_pack_codes_i8(const int32_t *codes, int8_t *out, int cout, int
 hipError_t launch_conv_i8(const I8ConvArgs &a, int ks, int stride, int nt, size_t lds_bytes, dim3 grid, hipStream_t)
 {
     ++g_launches;
-    if (lds_bytes > 160 * 1024 || nt < 1 || nt > 2 || grid.x == 0 || (a.Cin & 15)) return hipErrorInvalidValue;
+    if (lds_bytes > 159 * 1024 || nt < 1 || nt > 2 || grid.x == 0 || (a.Cin & 15)) return hipErrorInvalidValue;
     touch_read(a.in, (size_t)a.N * a.Hin * a.Win * a.Cin);
     touch_read(a.xscale, (size_t)a.N);
+    if (a.amax_out) touch_write(a.amax_out, (size_t)a.N);
     touch_write(a.out, (size_t)a.N * a.Hout * a.Wout * a.Cout);
     if (a.res) touch_read(a.res, (size_t)a.N * a.Hout * a.Wout * a.Cout);
     touch_read(a.codes, (size_t)a.cout_tiles * ks * ks * a.CBK * 1024);
