@@ -51,8 +51,20 @@ def build_copy_probe():
     return out
 
 
+def build_mfma_mix_probe():
+    """Optional, not part of build(): the stand-alone microbenchmark of what instructions issued between MFMAs
+    cost (profiles/mfma_valu_issue_microbenchmark.md).  Returns the path of the executable."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = os.path.join(HERE, "mfma_mix_probe")
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                    "-packed-fp32-ops", os.path.join(CSRC, "mfma_mix_probe.hip"), "-o", out], check=True)
+    return out
+
+
 if __name__ == "__main__":
-    if "--copy-probe" in sys.argv:
+    if "--mfma-mix-probe" in sys.argv:
+        print(build_mfma_mix_probe())
+    elif "--copy-probe" in sys.argv:
         print(build_copy_probe())
     else:
         print(build(force=True, verbose="-v" in sys.argv))
