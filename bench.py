@@ -27,9 +27,9 @@ TRAFFIC = {
     ("resnet20_greedy_step_n1024_s40", "resnet_fused"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_fused.hip",
         "sha256": "56d1c2d483b20bd9b6d21cb09afec8e50edc7f4cc62b2032687c978bf27bee5e",
-        # six counter runs of the same source on four boxes (the first two known to 0.1 MB only): the weights'
+        # nine counter runs of the same source on five boxes (the first two known to 0.1 MB only): the weights'
         # share of L2 misses varies from box to box; the images, 12.6 MB, are the floor
-        "bytes_per_launch_runs": [47800000, 48600000, 62087680, 105634176, 105667114, 105651221],
+        "bytes_per_launch_runs": [47800000, 48600000, 62087680, 105634176, 105667114, 105651221, 80636480, 80739370, 80714922],
     },
     ("mobilenetv2_32_n512_s16", "mbconv"): {  # average over the 16 block launches of a step
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_mbconv.hip",
@@ -45,13 +45,13 @@ TRAFFIC = {
     ("plainconvnet20_sensitivity_n256_s42", "conv_mfma"): {  # average over the 20 convolution launches of a step
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
         "sections": ["helpers", "dense convolution", "network stems"],
-        "sha256": "94a0512bc46511dd3bfcf6789a765a570fd919620254a258a93e5a2b169d7fae",
-        "bytes_per_launch_runs": [2694850414, 2694908681, 2694684770],
+        "sha256": "40d7c5f7a0a5233286b30afd40e5a8f11911eec90e3612693488d3cacbf3310f",
+        "bytes_per_launch_runs": [2706341604, 2705904289],
     },
     ("plainconvnet20_deploy_n2048", "conv_codes"): {  # average over the 19 launches of one deployed forward pass
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_deploy.hip",
-        "sha256": "d300d3db0c2df217244dcabcd424076616bcaeaf412946c01c4578ba0d456635",
-        "bytes_per_launch_runs": [496839411],
+        "sha256": "65306e5f64c86191366076a01f054998d26a006ea5a6f76f4c822b9d15c7217d",
+        "bytes_per_launch_runs": [495600000, 495800000],
     },
     ("quantize_stress_8192x4608_b8", "quantize"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
