@@ -145,7 +145,8 @@ def extra_legs(args, torch, aiq, synth):
     """Short secondary measurements that ride along with the default run (the headline stays the ResNet-20 greedy
     step): the quantizer on a bandwidth-stress shape, the MobileNetV2 configuration on its LDS-resident block kernel,
     the stand-alone depthwise kernel (the same configuration forced layer by layer), and the ResNet-20 greedy step on
-    the model with the centred classifier, whose agreement counts are not all N."""
+    the model with the centred classifier, whose agreement counts are not all N, and deployed inference of
+    PlainConvNet20 at 8 bits (FP32 model, bf16 integer codes, int8 codes of the activation variant)."""
     legs = {}
     # quantizer, 8192 x 4608 at 8 bits: 8 bytes moved per weight (+ 4 per row for the scale)
     cout, k = 8192, 4608
@@ -195,6 +196,38 @@ def extra_legs(args, torch, aiq, synth):
                                    "agree_min_max": [int(agree.min()), int(agree.max())],
                                    "agree_8bit_moves": [int(v) for v in agree[0::2]],
                                    "agree_4bit_moves": [int(v) for v in agree[1::2]]}
+    # deployed inference of PlainConvNet20 (workload 5's model), every layer at 8 bits: the FP32 model, the scheme on
+    # bf16 integer codes (weight-only function) and the activation variant on int8 codes; one forward = 2048 images
+    import numpy as np
+    n_img = 2048
+    wl = synth.make_workload(5, n_images=n_img)
+    images = torch.from_numpy(wl["images"]).cuda()
+    q8, q32 = np.full(wl["L"], 8, np.uint8), np.full(wl["L"], 32, np.uint8)
+    plain = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=True)
+    actq = aiq.Model(wl["desc"], wl["weights"], wl["biases"], act_quant=True)
+    out = {"top1": torch.empty(n_img, dtype=torch.int32, device="cuda")}
+    leg = {"workload": "plainconvnet20_deploy_n2048", "images": n_img, "scheme": "all_int8", "steps": 5, "unit": "images/s"}
+    top1_fp32 = None
+    for key, model, q in (("fp32_model", plain, q32), ("bf16_codes", plain, q8), ("int8_codes_activation_variant", actq, q8)):
+        d = aiq.Deployed(model, q)
+        for _ in range(2):
+            d.forward(images, chunk=n_img, out=out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            r = d.forward(images, chunk=n_img, out=out)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 5
+        if top1_fp32 is None:
+            top1_fp32 = r["top1"].clone()
+        leg[key] = {"images_per_s": n_img / dt, "ms_per_forward": dt * 1e3, "code_layers": d.code_layers,
+                    "agree_with_fp32": int((r["top1"] == top1_fp32).sum())}
+        d.close()
+    leg["speedup_over_fp32_model"] = {k: leg[k]["images_per_s"] / leg["fp32_model"]["images_per_s"]
+                                      for k in ("bf16_codes", "int8_codes_activation_variant")}
+    legs["deploy"] = leg
+    plain.close()
+    actq.close()
     return legs
 
 
