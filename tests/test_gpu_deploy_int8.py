@@ -148,3 +148,41 @@ def test_narrow_random_graphs_fall_back_where_the_shape_does_not_fit(env):
         images = rng.standard_normal((3, h, h, ci)).astype(np.float32)
         print(f"int8 narrow random graph {seed}: {len(nodes)} nodes, input {h}x{h}x{ci}", flush=True)
         _check(env, nodes, synth.desc_array(nodes), w, b, images, _schemes(len(nodes), rng)[:4])
+
+
+def test_many_images_so_that_workgroups_walk_several_regions(env):
+    """At benchmark-like batch sizes a workgroup of the int8 kernel keeps its weight codes for up to eight consecutive
+    regions and fetches the next region's activations ahead; the last workgroup's share is ragged and the last
+    group of small images incomplete.  2049 images through ResNet-8 (16 / 32 / 64 channels at 32 / 16 / 8 pixels);
+    every node of sampled images - the first and last regions of workgroups, the tail - against the oracle on the
+    GPU's own input tensors."""
+    torch, aiq, oracle = env["torch"], env["aiq"], env["oracle"]
+    N = 2049
+    wl = env["synth"].make_workload(0, n_images=N)
+    nodes, desc, w, b = wl["nodes"], wl["desc"], wl["weights"], wl["biases"]
+    m = aiq.Model(desc, w, b, act_quant=True)
+    img = torch.from_numpy(wl["images"]).cuda()
+    sample = [0, 1, 2, 3, 7, 8, 511, 512, 1023, 1024, 1025, 2040, 2043, 2044, 2046, 2047, 2048]
+    worst = 0.0
+    for scheme in (np.full(wl["L"], 8, np.uint8), np.full(wl["L"], 4, np.uint8)):
+        dep = aiq.Deployed(m, scheme)
+        assert dep.code_layers == _eligible(nodes, scheme) > 0
+        print(f"int8 deployment, {N} images, scheme of {int(scheme[0])} bits: {dep.code_layers} layers on int8 codes", flush=True)
+        outs = dep.forward_nodes(img)
+        torch.cuda.synchronize()
+        idx = torch.tensor(sample, device="cuda")
+        outs = [o.index_select(0, idx).cpu().numpy() for o in outs]
+        for k, n in enumerate(sample):
+            per_image = [o[k] for o in outs]
+            for l in range(len(nodes)):
+                ref = _node_reference(oracle, nodes, desc, w, b, scheme, wl["images"][n], per_image, l)
+                err = np.abs(per_image[l] - ref).max() / max(np.abs(ref).max(), 1e-30)
+                assert err <= TOL, f"node {l} image {n} scheme {scheme.tolist()}: {err:.3e}"
+                worst = max(worst, err)
+        # the chunked forward (chunks of 1000 + a remainder of 49) gives the same logits
+        r = dep.forward(img, chunk=1000, want_logits=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(r["logits"].index_select(0, idx).cpu().numpy(), outs[-1])
+        dep.close()
+    print("  worst node error %.3e of the node's range" % worst, flush=True)
+    m.close()
