@@ -405,11 +405,28 @@ def deploy_mode(args, torch, aiq, synth):
                 d.close()
         if best.lds_resident or best.lds_resident_blocks > 0:
             # the model keeps activations in LDS: the deployment runs the scheme on those kernels
-            d = aiq.Deployed(best, q)
-            dt, r = timed(lambda: d.forward(images, chunk=chunk, out=out, stream=stream))
-            row["lds_resident_kernels"] = {"images_per_s": n_img / dt, "ms_per_step": dt * 1e3, "code_layers": d.code_layers,
-                                           "agree_with_fp32": int((r["top1"] == top1_fp32).sum()) if top1_fp32 is not None else None}
-            d.close()
+            # (inverted-residual blocks whose 1x1 layers carry at most 8 bits take their matrix products from integer
+            # codes inside the block kernel; with the fp32-matrix flag every block runs the scoring kernel)
+            for key, fp32m in (("lds_resident_kernels", False), ("lds_resident_kernels_fp32_matrix", True)):
+                d = aiq.Deployed(best, q, fp32_matrix=fp32m)
+                if fp32m and d.code_layers == row["lds_resident_kernels"]["code_layers"]:
+                    d.close()
+                    continue
+                dt, r = timed(lambda: d.forward(images, chunk=chunk, out=out, stream=stream))
+                row[key] = {"images_per_s": n_img / dt, "ms_per_step": dt * 1e3, "code_layers": d.code_layers,
+                            "agree_with_fp32": int((r["top1"] == top1_fp32).sum()) if top1_fp32 is not None else None}
+                if best.lds_resident_blocks > 0:
+                    best.profile_enable(True)
+                    for c in range(8):
+                        best.profile_read(c)
+                    d.forward(images, chunk=chunk, out=out, stream=stream)
+                    torch.cuda.synchronize()
+                    best.profile_enable(False)
+                    kb = best.profile_read(aiq.K_MBCONV)
+                    if kb["launches"]:
+                        row[key]["block_kernels"] = {"launches": kb["launches"], "total_ms": kb["total_ms"],
+                                                     "fp32_equivalent_tflops": kb["flops"] / kb["total_ms"] / 1e9}
+                d.close()
         res[name] = row
     # the FP32 model on its fastest path (whole network or blocks LDS-resident where the graph allows)
     o = {"top1_base": torch.empty(n_img, dtype=torch.int32, device="cuda"), "agree": torch.empty(1, dtype=torch.int32, device="cuda")}

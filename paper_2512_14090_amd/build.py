@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaiq.so")
-SOURCES = ["aiq_host.cpp", "aiq_kernels.hip", "aiq_fused.hip", "aiq_mbconv.hip", "aiq_deploy.hip", "aiq_int8.hip"]
+SOURCES = ["aiq_host.cpp", "aiq_kernels.hip", "aiq_fused.hip", "aiq_mbconv.hip", "aiq_deploy.hip", "aiq_int8.hip",
+           "aiq_mbconv_codes.hip"]
 HEADERS = ["aiq_internal.h", os.path.join("..", "..", "include", "aiq.h")]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",

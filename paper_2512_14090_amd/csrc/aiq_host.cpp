@@ -60,6 +60,13 @@ struct Node {
     bool pooled = false; // 1x1 layer feeding only the classifier: writes the per-image mean of its output instead
 };
 
+// Integer codes of a deployed inverted-residual block (at its expand node): null codes = the block runs on
+// the fp32 block kernel.
+struct MbCodes {
+    uint16_t *codes_e = nullptr, *codes_p = nullptr;
+    float *scale_e = nullptr, *scale_p = nullptr;
+};
+
 struct ProfRec {
     hipEvent_t start, stop;
     int cls;
@@ -87,6 +94,8 @@ struct aiq_model {
     float *aq_cur = nullptr;       // quantized-input buffer of the call in progress (part of its workspace)
     uint32_t *layer_amax = nullptr; // device: bit pattern of max |w| of every layer (per-tensor scales)
     int mb_blocks = 0;  // inverted-residual blocks run by the LDS-resident block kernel
+    const MbCodes *mb_codes_cur = nullptr; // per node, of the deployed forward call in progress (else null)
+    const uint8_t *mb_scheme_cur = nullptr; // host copy of that call's scheme
     std::vector<FusedOp> fused_ops;
     FusedOp *fused_ops_dev = nullptr;
     double fused_flops_per_image = 0.0;
@@ -1016,7 +1025,31 @@ aiq_status launch_node(aiq_model *m, hipStream_t st, const HeadOut &ho, size_t l
         io.in = m->aq_cur;
         io.in_stride = (size_t)n * nd.in_elems;
     }
-    if (nd.mb_role == 1) {
+    if (nd.mb_role == 1 && m->mb_codes_cur && m->mb_codes_cur[l].codes_e && io.S == 1 && io.s_total == 1) {
+        // deployed scheme, expand and project at most eight bits wide: both products from integer codes
+        const Node &dwn = m->nodes[l + 1], &pjn = m->nodes[l + 2];
+        const MbCodes &mc = m->mb_codes_cur[l];
+        const int bi_d = dwn.d.scheme_slot >= 0 ? bits_index(m->mb_scheme_cur[dwn.d.scheme_slot]) : 0;
+        MbCodeArgs a{};
+        a.in = io.in;
+        a.out = io.out;
+        a.codes_e = mc.codes_e;
+        a.codes_p = mc.codes_p;
+        a.scale_e = mc.scale_e;
+        a.scale_p = mc.scale_p;
+        a.w_d = dwn.bank[bi_d] ? dwn.bank[bi_d] : dwn.bank[0];
+        a.bias_e = nd.bias;
+        a.bias_d = dwn.bias;
+        a.bias_p = pjn.bias;
+        a.N = n;
+        a.act_e = d.act;
+        a.act_d = dwn.d.act;
+        a.act_p = pjn.d.act;
+        const double flops = nd.flops_per_image + dwn.flops_per_image + pjn.flops_per_image;
+        const double bytes = 4.0 * (nd.in_elems + pjn.out_elems + (pjn.d.residual >= 0 ? pjn.out_elems : 0));
+        ProfScope ps(m, st, AIQ_K_MBCONV, flops * work, bytes * work);
+        AIQ_HIP(launch_mbconv_codes(nd.mb_shape, a, st));
+    } else if (nd.mb_role == 1) {
         const Node &dwn = m->nodes[l + 1], &pjn = m->nodes[l + 2];
         MbArgs a{};
         a.in = io.in;
@@ -1713,6 +1746,7 @@ struct aiq_deployed {
     std::vector<void *> allocations;
     int n_code_layers = 0;
     bool resident = false; // the model keeps activations in LDS: the scheme runs on those kernels
+    std::vector<MbCodes> mb; // per node; filled at the expand node of every block that runs from integer codes
 };
 
 void aiq_deploy_destroy(aiq_deployed *d)
@@ -1739,16 +1773,6 @@ aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags
     d->scheme.assign(scheme, scheme + m->L);
     d->layer.resize(m->nodes.size());
     d->amax_ok.assign(m->nodes.size(), 0);
-    if (resident) {
-        // A model whose activations stay in LDS (whole CIFAR-style ResNets, inverted-residual blocks) is
-        // deployed on those kernels, the scheme being the one "candidate" of a scoring call: the integer-code
-        // kernels work layer by layer through HBM and are slower than that for such models, and three bf16
-        // planes per activation do not fit the LDS budget of the resident kernels.  Nothing to prepare: the
-        // weight bank slots are filled by the forward call.
-        d->resident = true;
-        *out = d;
-        return AIQ_OK;
-    }
     auto fail = [&](aiq_status code) {
         aiq_deploy_destroy(d);
         return code;
@@ -1758,6 +1782,61 @@ aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags
         d->allocations.push_back(*p);
         return true;
     };
+    if (resident) {
+        // A model whose activations stay in LDS (whole CIFAR-style ResNets, inverted-residual blocks) is
+        // deployed on those kernels, the scheme being the one "candidate" of a scoring call: the layer-by-layer
+        // integer-code kernels work through HBM and are slower than that for such models.  The weight bank
+        // slots are filled by the forward call.  Inverted-residual blocks whose expand and project layers both
+        // carry at most eight bits run on the block kernel that takes its two matrix products from integer
+        // codes; what is prepared here are those codes and scales.
+        d->resident = true;
+        d->mb.resize(m->nodes.size());
+        size_t tmp_elems = 0;
+        std::vector<size_t> blocks;
+        if (!m->act_quant && !(flags & AIQ_DEPLOY_FP32_MATRIX))
+            for (size_t l = 0; l + 2 < m->nodes.size(); ++l) {
+                const Node &e = m->nodes[l], &pj = m->nodes[l + 2];
+                if (e.mb_role != 1 || e.d.scheme_slot < 0 || pj.d.scheme_slot < 0) continue;
+                if (scheme[e.d.scheme_slot] > 8 || scheme[pj.d.scheme_slot] > 8 || !mbconv_codes_supported(e.mb_shape)) continue;
+                blocks.push_back(l);
+                tmp_elems = std::max(tmp_elems, std::max((size_t)e.d.cout * e.k, (size_t)pj.d.cout * pj.k));
+            }
+        if (blocks.empty()) {
+            *out = d;
+            return AIQ_OK;
+        }
+        void *tmp_codes = nullptr, *tmp_out = nullptr;
+        bool ok = hip_ok(hipMalloc(&tmp_codes, tmp_elems * sizeof(int32_t))) && hip_ok(hipMalloc(&tmp_out, tmp_elems * sizeof(float)));
+        for (size_t bi = 0; ok && bi < blocks.size(); ++bi) {
+            const size_t l = blocks[bi];
+            MbCodes &mc = d->mb[l];
+            for (int which = 0; ok && which < 2; ++which) {
+                const Node &nd = m->nodes[which ? l + 2 : l];
+                const int kstep = which ? 16 : 32;
+                const size_t code_elems = (size_t)((nd.d.cout + 15) / 16) * ((nd.k + kstep - 1) / kstep) * 64 * (kstep / 4);
+                uint16_t *&codes = which ? mc.codes_p : mc.codes_e;
+                float *&scales = which ? mc.scale_p : mc.scale_e;
+                ok = alloc(reinterpret_cast<void **>(&codes), code_elems * sizeof(uint16_t)) &&
+                     alloc(reinterpret_cast<void **>(&scales), (size_t)nd.d.cout * sizeof(float)) &&
+                     hip_ok(hipMemset(codes, 0, code_elems * sizeof(uint16_t)));
+                if (!ok) break;
+                QuantJob j = m->jobs_host[nd.job0 + bits_index(scheme[nd.d.scheme_slot]) - 1];
+                j.out = static_cast<float *>(tmp_out);
+                j.layout = kLayoutPlain;
+                j.scales = scales;
+                j.codes = static_cast<int32_t *>(tmp_codes);
+                ok = hip_ok(launch_quantize_single(j, nullptr)) &&
+                     hip_ok(launch_pack_mb_codes(j.codes, codes, nd.d.cout, nd.k, kstep, nullptr));
+            }
+            d->n_code_layers += 2;
+        }
+        ok = hip_ok(hipDeviceSynchronize()) && ok;
+        if (tmp_codes) (void)hipFree(tmp_codes);
+        if (tmp_out) (void)hipFree(tmp_out);
+        if (!ok) return fail(AIQ_DEVICE_ERROR);
+        *out = d;
+        return AIQ_OK;
+    }
     if (!alloc(reinterpret_cast<void **>(&d->scheme_dev), (size_t)std::max(m->L, 1))) return fail(AIQ_DEVICE_ERROR);
     if (m->L && !hip_ok(hipMemcpy(d->scheme_dev, scheme, (size_t)m->L, hipMemcpyHostToDevice)))
         return fail(AIQ_DEVICE_ERROR);
@@ -1956,9 +2035,15 @@ aiq_status aiq_deploy_forward(aiq_deployed *d, const float *images, int32_t N, i
     if (N == 0) return AIQ_OK;
     aiq_model *m = d->m;
     chunk = std::min(chunk, N);
-    if (d->resident)
-        return eval_impl(m, images, N, d->scheme.data(), 1, nullptr, chunk, nullptr, 1, logits, top1, nullptr, workspace,
-                         workspace_bytes, hip_stream, nullptr, false);
+    if (d->resident) {
+        m->mb_codes_cur = d->n_code_layers ? d->mb.data() : nullptr;
+        m->mb_scheme_cur = d->scheme.data();
+        const aiq_status rc = eval_impl(m, images, N, d->scheme.data(), 1, nullptr, chunk, nullptr, 1, logits, top1, nullptr,
+                                        workspace, workspace_bytes, hip_stream, nullptr, false);
+        m->mb_codes_cur = nullptr;
+        m->mb_scheme_cur = nullptr;
+        return rc;
+    }
     const WorkspaceLayout wl = workspace_layout(m, 0, chunk);
     if (workspace_bytes < wl.total) return AIQ_WORKSPACE_TOO_SMALL;
     if (reinterpret_cast<uintptr_t>(workspace) & 255) return AIQ_INVALID_ARG;

@@ -296,6 +296,26 @@ struct MbArgs {
 bool mbconv_supported(const MbShape &sh);
 hipError_t launch_mbconv(const MbShape &sh, const MbArgs &a, int s_total, hipStream_t st);
 
+// The same blocks for one deployed scheme whose expand and project layers carry at most eight bits: both
+// matrix products from integer codes on the bf16 matrix pipe (aiq_mbconv_codes.hip).
+struct MbCodeArgs {
+    const float *in;         // [N][H][W][CIN]
+    float *out;              // [N][HO][WO][COUT]
+    const uint16_t *codes_e; // bf16 bit patterns [HID/16][ceil(CIN/32)][64 lanes][8], zero padded
+    const uint16_t *codes_p; // bf16 bit patterns [ceil(COUT/16)][HID/16][64 lanes][4], zero padded
+    const float *scale_e;    // [HID]
+    const float *scale_p;    // [COUT]
+    const float *w_d;        // depthwise weights at the width the scheme gives them, tap-major [9][HID]
+    const float *bias_e, *bias_d, *bias_p;
+    int32_t N;
+    int32_t act_e, act_d, act_p;
+};
+
+bool mbconv_codes_supported(const MbShape &sh);
+hipError_t launch_mbconv_codes(const MbShape &sh, const MbCodeArgs &a, hipStream_t st);
+// codes: int32 [rows][k]; out: cleared buffer [ceil(rows/16)][ceil(k/kstep)][64 lanes][kstep/4], kstep 32 or 16
+hipError_t launch_pack_mb_codes(const int32_t *codes, uint16_t *out, int rows, int k, int kstep, hipStream_t st);
+
 } // namespace aiq
 
 // ---------------------------------------------------------------- deployed inference

@@ -331,6 +331,35 @@ hipError_t launch_mbconv(const MbShape &sh, const MbArgs &a, int s_total, hipStr
     return hipSuccess;
 }
 
+bool mbconv_codes_supported(const MbShape &sh) { return mbconv_supported(sh); }
+
+hipError_t launch_mbconv_codes(const MbShape &sh, const MbCodeArgs &a, hipStream_t)
+{
+    ++g_launches;
+    if (!mbconv_codes_supported(sh)) return hipErrorInvalidValue;
+    const int ho = sh.h / sh.stride;
+    touch_read(a.in, (size_t)a.N * sh.h * sh.h * sh.cin);
+    touch_write(a.out, (size_t)a.N * ho * ho * sh.cout);
+    touch_read(a.codes_e, (size_t)(sh.hid / 16) * ((sh.cin + 31) / 32) * 512);
+    touch_read(a.codes_p, (size_t)((sh.cout + 15) / 16) * (sh.hid / 16) * 256);
+    touch_read(a.scale_e, (size_t)sh.hid);
+    touch_read(a.scale_p, (size_t)sh.cout);
+    touch_read(a.w_d, (size_t)9 * sh.hid);
+    touch_read(a.bias_e, (size_t)sh.hid);
+    touch_read(a.bias_d, (size_t)sh.hid);
+    touch_read(a.bias_p, (size_t)sh.cout);
+    return hipSuccess;
+}
+
+hipError_t launch_pack_mb_codes(const int32_t *codes, uint16_t *out, int rows, int k, int kstep, hipStream_t)
+{
+    ++g_launches;
+    if (kstep != 16 && kstep != 32) return hipErrorInvalidValue;
+    touch_read(codes, (size_t)rows * k);
+    touch_write(out, (size_t)((rows + 15) / 16) * ((k + kstep - 1) / kstep) * 64 * (kstep / 4));
+    return hipSuccess;
+}
+
 hipError_t launch_pack_codes(const int32_t *codes, uint16_t *out, int cout, int cin, int taps, hipStream_t)
 {
     ++g_launches;

@@ -208,8 +208,11 @@ def test_lds_resident_models_deploy_on_their_own_kernels(env, index, n, chunk):
     ref = oracle.eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], np.stack(schemes))
     scored = m.eval_schemes(img, np.stack(schemes), chunk=chunk, want_logits=True, want_top1=True)
     torch.cuda.synchronize()
+    blocks = m.lds_resident_blocks
     for i, q in enumerate(schemes):
-        d = aiq.Deployed(m, q)
+        # inverted-residual blocks whose 1x1 layers carry at most 8 bits run from integer codes (another
+        # summation order); with the fp32-matrix flag every model runs the scoring kernels bit for bit
+        d = aiq.Deployed(m, q, fp32_matrix=blocks > 0)
         assert d.code_layers == 0
         out = d.forward(img, chunk=chunk, want_logits=True)
         torch.cuda.synchronize()
@@ -219,5 +222,92 @@ def test_lds_resident_models_deploy_on_their_own_kernels(env, index, n, chunk):
         only_top1 = d.forward(img[:3], chunk=2)
         torch.cuda.synchronize()
         assert torch.equal(only_top1["top1"], scored["top1"][i][:3]) and only_top1["logits"] is None
+        d.close()
+    m.close()
+
+
+def _block_code_layers(nodes, scheme):
+    """Layers of inverted-residual blocks (1x1 expand, depthwise, 1x1 project with no other reader of the hidden
+    tensors) whose expand and project both carry at most 8 bits: two per such block."""
+    n = 0
+    for i in range(len(nodes) - 2):
+        e, dw, pj = nodes[i], nodes[i + 1], nodes[i + 2]
+        if e["kind"] == 0 and e["kh"] == 1 and e["input"] >= 0 and dw["kind"] == 1 and dw["input"] == i and \
+                pj["kind"] == 0 and pj["kh"] == 1 and pj["input"] == i + 1 and \
+                scheme[e["scheme_slot"]] <= 8 and scheme[pj["scheme_slot"]] <= 8:
+            n += 2
+    return n
+
+
+def test_inverted_residual_blocks_from_integer_codes_one_by_one(env):
+    """Each block shape of MobileNetV2-32 as a tiny network of its own, deployed: expand and project at 8 / 6 / 4 /
+    2 bits run from integer codes inside the block kernel (the depthwise layer at any width); a wider expand or
+    project sends the block to the fp32 block kernel.  Logits against the oracle's scoring of the same scheme."""
+    synth, oracle, aiq, torch = env["synth"], env["oracle"], env["aiq"], env["torch"]
+    shapes = [(16, 96, 24, 32, 1), (24, 144, 24, 32, 1), (24, 144, 32, 32, 1), (32, 192, 32, 32, 1),
+              (32, 192, 64, 32, 2), (64, 384, 64, 16, 1), (64, 384, 96, 16, 1), (96, 576, 96, 16, 1),
+              (96, 576, 160, 16, 2), (160, 960, 160, 8, 1), (160, 960, 320, 8, 1)]
+    schemes = np.array([[32, 8, 8, 8, 32], [32, 8, 32, 8, 32], [8, 4, 16, 6, 8], [32, 2, 4, 2, 32], [32, 6, 2, 4, 4],
+                        [32, 16, 8, 8, 32], [32, 8, 8, 32, 32]], dtype=np.uint8)
+    on_codes = [2, 2, 2, 2, 2, 0, 0]
+    worst = 0.0
+    for k, (cin, hid, cout, h, stride) in enumerate(shapes):
+        res = stride == 1 and cin == cout
+        G = synth.graphs
+        nodes = [G._node(G.KIND_CONV, 4, cin, 1, 1, h, -1, act=G.ACT_NONE, slot=0, name="in"),
+                 G._node(G.KIND_CONV, cin, hid, 1, 1, h, 0, act=G.ACT_RELU6, slot=1, name="expand"),
+                 G._node(G.KIND_DEPTHWISE, hid, hid, 3, stride, h, 1, act=G.ACT_RELU6, slot=2, name="dw"),
+                 G._node(G.KIND_CONV, hid, cout, 1, 1, h // stride, 2, residual=0 if res else -1, act=G.ACT_NONE,
+                         slot=3, name="project"),
+                 G._node(G.KIND_FC, cout, 10, 1, 1, h // stride, 3, act=G.ACT_NONE, slot=4, name="fc")]
+        rng = np.random.Generator(np.random.PCG64(700 + k))
+        w, b = synth.make_model(nodes, rng)
+        n = 5  # an odd count: the 8x8 shapes take two images per workgroup
+        images = rng.standard_normal((n, h, h, 4)).astype(np.float32)
+        desc = synth.desc_array(nodes)
+        print(f"block {cin}->{hid}->{cout} h{h} s{stride} res={res}", flush=True)
+        ref = oracle.eval_schemes(desc, w, b, images, schemes)
+        m = aiq.Model(desc, w, b)
+        assert m.lds_resident_blocks == 1
+        img = torch.from_numpy(images).cuda()
+        for i, q in enumerate(schemes):
+            d = aiq.Deployed(m, q)
+            assert d.code_layers == on_codes[i], (d.code_layers, q)
+            out = d.forward(img, chunk=3, want_logits=True)
+            torch.cuda.synchronize()
+            err = logits_rel_error(out["logits"].cpu().numpy(), ref["logits"][i])
+            assert err <= LOGIT_REL_TOL, f"scheme {q}: logit relative error {err:.3e}"
+            diff = out["top1"].cpu().numpy() != ref["top1"][i]
+            assert not (diff & ~near_tied(ref["logits"][i])).any()
+            worst = max(worst, err)
+            d.close()
+        m.close()
+    print("worst logit rel err %.3e" % worst, flush=True)
+
+
+@pytest.mark.parametrize("n,chunk", [(9, 4), (24, 24)])
+def test_mobilenetv2_blocks_from_integer_codes(env, n, chunk):
+    """MobileNetV2 deployed on its block kernels: blocks whose 1x1 layers carry at most 8 bits from integer codes,
+    the others (and stem, first block, last layer, classifier) on the fp32 kernels; against the oracle."""
+    torch, aiq, oracle = env["torch"], env["aiq"], env["oracle"]
+    wl = env["synth"].make_workload(3, n_images=n)
+    L = wl["L"]
+    rng = np.random.Generator(np.random.PCG64(123))
+    mixed = rng.choice(np.array([32, 16, 8, 6, 4, 2], np.uint8), size=L)
+    low = rng.choice(np.array([8, 6, 4], np.uint8), size=L)
+    schemes = [np.full(L, 8, np.uint8), mixed, low, wl["schemes"][0]]
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    assert m.lds_resident_blocks == 16
+    img = torch.from_numpy(wl["images"]).cuda()
+    ref = oracle.eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], np.stack(schemes))
+    for i, q in enumerate(schemes):
+        d = aiq.Deployed(m, q)
+        assert d.code_layers == _block_code_layers(wl["nodes"], q), (d.code_layers, q)
+        out = d.forward(img, chunk=chunk, want_logits=True)
+        torch.cuda.synchronize()
+        err = _check(out["logits"].cpu().numpy(), out["top1"].cpu().numpy(), dict(logits=ref["logits"][i], top1=ref["top1"][i]))
+        print("scheme %d: %d layers on codes, logit rel err %.3e" % (i, d.code_layers, err), flush=True)
+        if i == 0:
+            assert d.code_layers == 32
         d.close()
     m.close()
