@@ -145,8 +145,9 @@ def extra_legs(args, torch, aiq, synth):
     """Short secondary measurements that ride along with the default run (the headline stays the ResNet-20 greedy
     step): the quantizer on a bandwidth-stress shape, the MobileNetV2 configuration on its LDS-resident block kernel,
     the stand-alone depthwise kernel (the same configuration forced layer by layer), and the ResNet-20 greedy step on
-    the model with the centred classifier, whose agreement counts are not all N, and deployed inference of
-    PlainConvNet20 at 8 bits (FP32 model, bf16 integer codes, int8 codes of the activation variant)."""
+    the model with the centred classifier, whose agreement counts are not all N, deployed inference of
+    PlainConvNet20 at 8 bits (FP32 model, bf16 integer codes, int8 codes of the activation variant) and of
+    MobileNetV2 at 8 bits on its block kernels (FP32 model, integer codes inside the block kernel)."""
     legs = {}
     # quantizer, 8192 x 4608 at 8 bits: 8 bytes moved per weight (+ 4 per row for the scale)
     cout, k = 8192, 4608
@@ -228,6 +229,32 @@ def extra_legs(args, torch, aiq, synth):
     legs["deploy"] = leg
     plain.close()
     actq.close()
+    # deployed inference of MobileNetV2 (the paper's throughput experiment), every layer at 8 bits, on its
+    # LDS-resident block kernels: the FP32 model and the scheme with the blocks' 1x1 layers from integer codes
+    wl = synth.make_workload(3, n_images=n_img)
+    images = torch.from_numpy(wl["images"]).cuda()
+    q8, q32 = np.full(wl["L"], 8, np.uint8), np.full(wl["L"], 32, np.uint8)
+    mb = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    leg = {"workload": "mobilenetv2_32_deploy_n2048", "images": n_img, "scheme": "all_int8", "steps": 5, "unit": "images/s"}
+    top1_fp32 = None
+    for key, q in (("fp32_model", q32), ("bf16_codes_in_block_kernels", q8)):
+        d = aiq.Deployed(mb, q)
+        for _ in range(2):
+            d.forward(images, chunk=n_img, out=out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            r = d.forward(images, chunk=n_img, out=out)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 5
+        if top1_fp32 is None:
+            top1_fp32 = r["top1"].clone()
+        leg[key] = {"images_per_s": n_img / dt, "ms_per_forward": dt * 1e3, "code_layers": d.code_layers,
+                    "agree_with_fp32": int((r["top1"] == top1_fp32).sum())}
+        d.close()
+    leg["speedup_over_fp32_model"] = leg["bf16_codes_in_block_kernels"]["images_per_s"] / leg["fp32_model"]["images_per_s"]
+    legs["deploy_mobilenetv2"] = leg
+    mb.close()
     return legs
 
 

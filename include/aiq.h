@@ -343,10 +343,15 @@ aiq_status aiq_forward_nodes(aiq_model *m, const float *images, int32_t N, const
  * aiq_deploy_create: m must outlive the deployment; scheme: host uint8[L].  A model that keeps its
  * activations in LDS (created without AIQ_MODEL_LAYERWISE: CIFAR-style ResNets, inverted-residual
  * blocks) is deployed on those kernels - the scheme runs as the single candidate of a scoring
- * call, bit-identical to aiq_eval_schemes, at the FP32 model's own rate: for such models that is
- * faster than any layer-by-layer path, and three bf16 planes per activation do not fit their LDS
- * budget (aiq_deploy_code_layers is then 0).  Integer-code layers need AIQ_MODEL_LAYERWISE.  flags: AIQ_DEPLOY_FP32_MATRIX keeps
- * every layer on the fp32 kernels (the same model without the bf16 path, for comparison).
+ * call: for such models that is faster than any layer-by-layer path.  The whole-network ResNet
+ * kernel stays in fp32 (bit-identical to aiq_eval_schemes, the FP32 model's own rate).  An
+ * inverted-residual block whose expand and project layers both carry at most 8 bits runs with
+ * both 1x1 products taken from integer codes inside the block kernel (same three-term
+ * arithmetic, v_mfma_f32_16x16x32_bf16 / 16x16x16_bf16; the depthwise layer and the hidden
+ * tensor stay fp32), two layers per such block in aiq_deploy_code_layers; results agree with
+ * aiq_eval_schemes to fp32 rounding.  Layer-by-layer integer-code layers need
+ * AIQ_MODEL_LAYERWISE.  flags: AIQ_DEPLOY_FP32_MATRIX keeps every layer and block on the fp32
+ * kernels (the same model without the bf16 path, for comparison; bit-identical to scoring).
  * Quantizes and packs the weights; allocates device memory (codes and scales), freed by
  * aiq_deploy_destroy.  Synchronous.  It fills weight-bank slots of m: do not overlap it with
  * other calls on m.  Errors: INVALID_ARG, UNSUPPORTED_BITS, UNSUPPORTED_LAYER, DEVICE_ERROR.
