@@ -1078,6 +1078,23 @@ aiq_status launch_node(aiq_model *m, hipStream_t st, const HeadOut &ho, size_t l
         const double bytes = 4.0 * (nd.in_elems + pjn.out_elems + (pjn.d.residual >= 0 ? pjn.out_elems : 0));
         ProfScope ps(m, st, AIQ_K_MBCONV, flops * work, bytes * work);
         AIQ_HIP(launch_mbconv(nd.mb_shape, a, io.s_total, st));
+    } else if (nd.pooled && m->mb_codes_cur && m->mb_codes_cur[l].codes_e && io.S == 1 && io.s_total == 1) {
+        // deployed scheme: the last 1x1 layer (with the classifier's pooling) from integer codes
+        const MbCodes &mc = m->mb_codes_cur[l];
+        PoolCodeArgs a{};
+        a.in = io.in;
+        a.out = io.out;
+        a.codes = mc.codes_e;
+        a.scales = mc.scale_e;
+        a.bias = nd.bias;
+        a.N = n;
+        a.Cin = d.cin;
+        a.Cout = d.cout;
+        a.act = d.act;
+        a.KS = (d.cin + 31) / 32;
+        if (!pooled_codes_plan(d.cin, d.cout, &a.CG, &a.groups)) return AIQ_INVALID_ARG;
+        ProfScope ps(m, st, AIQ_K_CONV_CODES, nd.flops_per_image * work, nd.act_bytes_per_image * work);
+        AIQ_HIP(launch_pooled_codes(a, st));
     } else if (d.kind == 0 && d.kh == 1 && d.stride == 1 && d.input >= 0) {
         // 1x1 stride 1: flat pixel axis
         const ConvPlan &p = nd.plan;
@@ -1788,47 +1805,60 @@ aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags
         // integer-code kernels work through HBM and are slower than that for such models.  The weight bank
         // slots are filled by the forward call.  Inverted-residual blocks whose expand and project layers both
         // carry at most eight bits run on the block kernel that takes its two matrix products from integer
-        // codes; what is prepared here are those codes and scales.
+        // codes, and so does a last 1x1 layer of at most eight bits that forms the classifier's pooling in its
+        // epilogue; what is prepared here are those codes and scales.
         d->resident = true;
         d->mb.resize(m->nodes.size());
-        size_t tmp_elems = 0;
-        std::vector<size_t> blocks;
+        // layers to prepare: node, k step of the operand layout, rows the packed buffer is padded to,
+        // destination (expand / pooled layer: codes_e of its own node; project: codes_p of the block's expand node)
+        struct CodeJob {
+            size_t node, owner;
+            int kstep, tiles;
+            bool project;
+        };
+        std::vector<CodeJob> jobs;
         if (!m->act_quant && !(flags & AIQ_DEPLOY_FP32_MATRIX))
-            for (size_t l = 0; l + 2 < m->nodes.size(); ++l) {
-                const Node &e = m->nodes[l], &pj = m->nodes[l + 2];
-                if (e.mb_role != 1 || e.d.scheme_slot < 0 || pj.d.scheme_slot < 0) continue;
-                if (scheme[e.d.scheme_slot] > 8 || scheme[pj.d.scheme_slot] > 8 || !mbconv_codes_supported(e.mb_shape)) continue;
-                blocks.push_back(l);
-                tmp_elems = std::max(tmp_elems, std::max((size_t)e.d.cout * e.k, (size_t)pj.d.cout * pj.k));
+            for (size_t l = 0; l < m->nodes.size(); ++l) {
+                const Node &e = m->nodes[l];
+                if (e.mb_role == 1 && l + 2 < m->nodes.size()) {
+                    const Node &pj = m->nodes[l + 2];
+                    if (e.d.scheme_slot < 0 || pj.d.scheme_slot < 0) continue;
+                    if (scheme[e.d.scheme_slot] > 8 || scheme[pj.d.scheme_slot] > 8 || !mbconv_codes_supported(e.mb_shape)) continue;
+                    jobs.push_back({l, l, 32, (e.d.cout + 15) / 16, false});
+                    jobs.push_back({l + 2, l, 16, (pj.d.cout + 15) / 16, true});
+                } else if (e.pooled && e.d.scheme_slot >= 0 && scheme[e.d.scheme_slot] <= 8) {
+                    int cg = 0, groups = 0;
+                    if (!pooled_codes_plan(e.d.cin, e.d.cout, &cg, &groups)) continue;
+                    jobs.push_back({l, l, 32, cg * groups, false});
+                }
             }
-        if (blocks.empty()) {
+        if (jobs.empty()) {
             *out = d;
             return AIQ_OK;
         }
+        size_t tmp_elems = 0;
+        for (const CodeJob &cj : jobs) tmp_elems = std::max(tmp_elems, (size_t)m->nodes[cj.node].d.cout * m->nodes[cj.node].k);
         void *tmp_codes = nullptr, *tmp_out = nullptr;
         bool ok = hip_ok(hipMalloc(&tmp_codes, tmp_elems * sizeof(int32_t))) && hip_ok(hipMalloc(&tmp_out, tmp_elems * sizeof(float)));
-        for (size_t bi = 0; ok && bi < blocks.size(); ++bi) {
-            const size_t l = blocks[bi];
-            MbCodes &mc = d->mb[l];
-            for (int which = 0; ok && which < 2; ++which) {
-                const Node &nd = m->nodes[which ? l + 2 : l];
-                const int kstep = which ? 16 : 32;
-                const size_t code_elems = (size_t)((nd.d.cout + 15) / 16) * ((nd.k + kstep - 1) / kstep) * 64 * (kstep / 4);
-                uint16_t *&codes = which ? mc.codes_p : mc.codes_e;
-                float *&scales = which ? mc.scale_p : mc.scale_e;
-                ok = alloc(reinterpret_cast<void **>(&codes), code_elems * sizeof(uint16_t)) &&
-                     alloc(reinterpret_cast<void **>(&scales), (size_t)nd.d.cout * sizeof(float)) &&
-                     hip_ok(hipMemset(codes, 0, code_elems * sizeof(uint16_t)));
-                if (!ok) break;
-                QuantJob j = m->jobs_host[nd.job0 + bits_index(scheme[nd.d.scheme_slot]) - 1];
-                j.out = static_cast<float *>(tmp_out);
-                j.layout = kLayoutPlain;
-                j.scales = scales;
-                j.codes = static_cast<int32_t *>(tmp_codes);
-                ok = hip_ok(launch_quantize_single(j, nullptr)) &&
-                     hip_ok(launch_pack_mb_codes(j.codes, codes, nd.d.cout, nd.k, kstep, nullptr));
-            }
-            d->n_code_layers += 2;
+        for (size_t ji = 0; ok && ji < jobs.size(); ++ji) {
+            const CodeJob &cj = jobs[ji];
+            const Node &nd = m->nodes[cj.node];
+            MbCodes &mc = d->mb[cj.owner];
+            const size_t code_elems = (size_t)cj.tiles * ((nd.k + cj.kstep - 1) / cj.kstep) * 64 * (cj.kstep / 4);
+            uint16_t *&codes = cj.project ? mc.codes_p : mc.codes_e;
+            float *&scales = cj.project ? mc.scale_p : mc.scale_e;
+            ok = alloc(reinterpret_cast<void **>(&codes), code_elems * sizeof(uint16_t)) &&
+                 alloc(reinterpret_cast<void **>(&scales), (size_t)nd.d.cout * sizeof(float)) &&
+                 hip_ok(hipMemset(codes, 0, code_elems * sizeof(uint16_t)));
+            if (!ok) break;
+            QuantJob j = m->jobs_host[nd.job0 + bits_index(scheme[nd.d.scheme_slot]) - 1];
+            j.out = static_cast<float *>(tmp_out);
+            j.layout = kLayoutPlain;
+            j.scales = scales;
+            j.codes = static_cast<int32_t *>(tmp_codes);
+            ok = hip_ok(launch_quantize_single(j, nullptr)) &&
+                 hip_ok(launch_pack_mb_codes(j.codes, codes, nd.d.cout, nd.k, cj.kstep, nullptr));
+            ++d->n_code_layers;
         }
         ok = hip_ok(hipDeviceSynchronize()) && ok;
         if (tmp_codes) (void)hipFree(tmp_codes);

@@ -313,6 +313,21 @@ struct MbCodeArgs {
 
 bool mbconv_codes_supported(const MbShape &sh);
 hipError_t launch_mbconv_codes(const MbShape &sh, const MbCodeArgs &a, hipStream_t st);
+// A 1x1 layer on 8x8 pixels that writes the per-image mean of its activated outputs (the classifier's pooling),
+// from integer codes.
+struct PoolCodeArgs {
+    const float *in;       // [N][64][Cin]
+    float *out;            // [N][Cout]
+    const uint16_t *codes; // bf16 bit patterns [groups * CG][KS][64 lanes][8], zero padded
+    const float *scales;   // [Cout]
+    const float *bias;     // [Cout]
+    int32_t N, Cin, Cout, act;
+    int32_t KS;            // ceil(Cin/32)
+    int32_t CG, groups;    // tiles of 16 output channels a wavefront takes at a time; ceil(tiles / CG)
+};
+// false: the layer does not fit (Cin % 8, Cout % 4, LDS); else the tile grouping the kernel will use
+bool pooled_codes_plan(int cin, int cout, int *cg, int *groups);
+hipError_t launch_pooled_codes(const PoolCodeArgs &a, hipStream_t st);
 // codes: int32 [rows][k]; out: cleared buffer [ceil(rows/16)][ceil(k/kstep)][64 lanes][kstep/4], kstep 32 or 16
 hipError_t launch_pack_mb_codes(const int32_t *codes, uint16_t *out, int rows, int k, int kstep, hipStream_t st);
 

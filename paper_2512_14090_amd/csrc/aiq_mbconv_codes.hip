@@ -451,6 +451,135 @@ void mbconv_codes_kernel(MbCodeArgs a)
     }
 }
 
+// ------------------------------------------------------------------ last 1x1 layer with the classifier's pooling
+//
+// A 1x1 layer on 8x8 pixels whose only reader is the classifier (MobileNetV2's last convolution)
+// writes the mean of its activated outputs over the image instead of the outputs.  From integer
+// codes: one workgroup of 8 wavefronts per image; the image's 64 pixels x Cin values are split once
+// into LDS planes (64 bytes per pixel, 32-channel step and term); a wavefront takes groups of CG
+// tiles of 16 output channels, each against the four pixel tiles of the image (A operands from
+// global memory one step ahead, 12 LDS reads per 12 * CG MFMAs), then applies scale, bias and
+// activation, adds the four tiles in registers and the 16 pixels of a tile across lanes.
+template <int CG>
+__global__ __launch_bounds__(512) void pooled_codes_kernel(PoolCodeArgs a)
+{
+    extern __shared__ float lds[];
+    char *X = reinterpret_cast<char *>(lds);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, p = lane & 15, kq = lane >> 4;
+    const int img = blockIdx.x;
+    const int KS = a.KS, units = KS * 4, items = 64 * units;
+    const float *src = a.in + (size_t)img * 64 * a.Cin;
+    constexpr int UN = 2;
+    for (int base = tid; base < items; base += 512 * UN) {
+        floatx4 v[UN][2];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int idx = base + u * 512;
+            const int unit = idx % units, pix = idx / units;
+            v[u][0] = v[u][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (idx < items && unit * 8 < a.Cin) {
+                v[u][0] = mc_gload4(src + (size_t)pix * a.Cin + unit * 8);
+                v[u][1] = mc_gload4(src + (size_t)pix * a.Cin + unit * 8 + 4);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int idx = base + u * 512;
+            if (idx < items) {
+                const int unit = idx % units, pix = idx / units;
+                uintx4 t[3];
+                mc_split8(v[u][0], v[u][1], t);
+#pragma unroll
+                for (int i = 0; i < 3; ++i)
+                    *reinterpret_cast<uintx4 *>(X + ((size_t)((unit >> 2) * 3 + i) * 64 + pix) * 64 + (unit & 3) * 16) = t[i];
+            }
+        }
+    }
+    __syncthreads();
+
+    const float lo = mc_lo(a.act), hi = mc_hi(a.act);
+    const char *xl = X + p * 64 + kq * 16;
+    for (int g = wave; g < a.groups; g += 8) {
+        floatx4 acc[CG][4];
+#pragma unroll
+        for (int i = 0; i < CG; ++i)
+#pragma unroll
+            for (int pt = 0; pt < 4; ++pt) acc[i][pt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        const uint16_t *wc = a.codes + ((size_t)(g * CG) * KS * 64 + lane) * 8;
+        uintx4 wa[CG], wn[CG];
+#pragma unroll
+        for (int i = 0; i < CG; ++i) wa[i] = mc_gload_u4(wc + (size_t)(i * KS) * 512);
+        for (int ks = 0; ks < KS; ++ks) {
+            const int kn = ks + 1 < KS ? ks + 1 : ks;
+#pragma unroll
+            for (int i = 0; i < CG; ++i) wn[i] = mc_gload_u4(wc + (size_t)(i * KS + kn) * 512);
+#pragma unroll
+            for (int t = 0; t < 3; ++t)
+#pragma unroll
+                for (int pt = 0; pt < 4; ++pt) {
+                    const uintx4 xb = *reinterpret_cast<const uintx4 *>(xl + ((size_t)(ks * 3 + t) * 64 + pt * 16) * 64);
+#pragma unroll
+                    for (int i = 0; i < CG; ++i)
+                        acc[i][pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wa[i]),
+                                                                             __builtin_bit_cast(bf16x8, xb), acc[i][pt], 0, 0, 0);
+                }
+#pragma unroll
+            for (int i = 0; i < CG; ++i) wa[i] = wn[i];
+        }
+#pragma unroll
+        for (int i = 0; i < CG; ++i) {
+            const int co = (g * CG + i) * 16 + kq * 4; // uniform over the 16 lanes that are reduced together
+            floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (co < a.Cout) {
+                const floatx4 sc = mc_gload4(a.scales + co), bi = mc_gload4(a.bias + co);
+#pragma unroll
+                for (int pt = 0; pt < 4; ++pt) sum += mc_clamp4(acc[i][pt] * sc + bi, lo, hi);
+            }
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) {
+                sum.x += __shfl_xor(sum.x, off);
+                sum.y += __shfl_xor(sum.y, off);
+                sum.z += __shfl_xor(sum.z, off);
+                sum.w += __shfl_xor(sum.w, off);
+            }
+            if (p == 0 && co < a.Cout) *reinterpret_cast<floatx4 *>(a.out + (size_t)img * a.Cout + co) = sum * (1.0f / 64.0f);
+        }
+    }
+}
+
+template <int CG>
+static hipError_t pooled_launch(const PoolCodeArgs &a, size_t lds_bytes, hipStream_t st)
+{
+    static bool lds_set = false;
+    if (!lds_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pooled_codes_kernel<CG>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        lds_set = true;
+    }
+    hipLaunchKernelGGL((pooled_codes_kernel<CG>), dim3((unsigned)a.N), dim3(512), lds_bytes, st, a);
+    return hipGetLastError();
+}
+
+bool pooled_codes_plan(int cin, int cout, int *cg, int *groups)
+{
+    const int ks = (cin + 31) / 32, tiles = (cout + 15) / 16;
+    if (cin % 8 != 0 || cout % 4 != 0 || ks * 12288 > 160 * 1024) return false;
+    *cg = tiles % 5 == 0 ? 5 : 2;
+    *groups = (tiles + *cg - 1) / *cg;
+    return true;
+}
+
+hipError_t launch_pooled_codes(const PoolCodeArgs &a, hipStream_t st)
+{
+    if (a.N == 0) return hipSuccess;
+    int cg = 0, groups = 0;
+    if (!pooled_codes_plan(a.Cin, a.Cout, &cg, &groups) || cg != a.CG || groups != a.groups || a.KS != (a.Cin + 31) / 32)
+        return hipErrorInvalidValue;
+    const size_t lds_bytes = (size_t)a.KS * 12288;
+    return cg == 5 ? pooled_launch<5>(a, lds_bytes, st) : pooled_launch<2>(a, lds_bytes, st);
+}
+
 // ------------------------------------------------------------------ configurations
 //
 // One instantiation per block shape of MobileNetV2 for 32x32 inputs.  The split block input needs

@@ -351,6 +351,29 @@ hipError_t launch_mbconv_codes(const MbShape &sh, const MbCodeArgs &a, hipStream
     return hipSuccess;
 }
 
+bool pooled_codes_plan(int cin, int cout, int *cg, int *groups)
+{
+    const int ks = (cin + 31) / 32, tiles = (cout + 15) / 16;
+    if (cin % 8 != 0 || cout % 4 != 0 || ks * 12288 > 160 * 1024) return false;
+    *cg = tiles % 5 == 0 ? 5 : 2;
+    *groups = (tiles + *cg - 1) / *cg;
+    return true;
+}
+
+hipError_t launch_pooled_codes(const PoolCodeArgs &a, hipStream_t)
+{
+    ++g_launches;
+    int cg = 0, groups = 0;
+    if (!pooled_codes_plan(a.Cin, a.Cout, &cg, &groups) || cg != a.CG || groups != a.groups || a.KS != (a.Cin + 31) / 32)
+        return hipErrorInvalidValue;
+    touch_read(a.in, (size_t)a.N * 64 * a.Cin);
+    touch_write(a.out, (size_t)a.N * a.Cout);
+    touch_read(a.codes, (size_t)a.groups * a.CG * a.KS * 512);
+    touch_read(a.scales, (size_t)a.Cout);
+    touch_read(a.bias, (size_t)a.Cout);
+    return hipSuccess;
+}
+
 hipError_t launch_pack_mb_codes(const int32_t *codes, uint16_t *out, int rows, int k, int kstep, hipStream_t)
 {
     ++g_launches;

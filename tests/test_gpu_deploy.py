@@ -302,12 +302,51 @@ def test_mobilenetv2_blocks_from_integer_codes(env, n, chunk):
     ref = oracle.eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], np.stack(schemes))
     for i, q in enumerate(schemes):
         d = aiq.Deployed(m, q)
-        assert d.code_layers == _block_code_layers(wl["nodes"], q), (d.code_layers, q)
+        last_conv = wl["nodes"][-2]  # the 1x1 layer whose epilogue forms the classifier's pooling
+        assert d.code_layers == _block_code_layers(wl["nodes"], q) + (1 if q[last_conv["scheme_slot"]] <= 8 else 0), (d.code_layers, q)
         out = d.forward(img, chunk=chunk, want_logits=True)
         torch.cuda.synchronize()
         err = _check(out["logits"].cpu().numpy(), out["top1"].cpu().numpy(), dict(logits=ref["logits"][i], top1=ref["top1"][i]))
         print("scheme %d: %d layers on codes, logit rel err %.3e" % (i, d.code_layers, err), flush=True)
         if i == 0:
-            assert d.code_layers == 32
+            assert d.code_layers == 33
         d.close()
     m.close()
+
+
+def test_last_1x1_layer_with_pooling_from_integer_codes(env):
+    """A 1x1 layer on 8x8 pixels that only the classifier reads writes the mean of its outputs; deployed at 8 bits or
+    less it runs from integer codes.  Channel counts that leave partial 32-channel steps, partial tiles of 16 output
+    channels and both tile groupings (five tiles at a time when the tile count is a multiple of five, else two)."""
+    synth, oracle, aiq, torch = env["synth"], env["oracle"], env["aiq"], env["torch"]
+    G = synth.graphs
+    cases = [(320, 1280, G.ACT_RELU6), (24, 36, G.ACT_RELU), (40, 80, G.ACT_NONE), (96, 100, G.ACT_RELU6), (8, 16, G.ACT_RELU6),
+             (416, 64, G.ACT_RELU6)]
+    schemes = np.array([[32, 8, 32], [8, 4, 8], [32, 2, 4], [32, 6, 32], [32, 16, 32]], dtype=np.uint8)
+    worst = 0.0
+    for k, (cin, cout, act) in enumerate(cases):
+        nodes = [G._node(G.KIND_CONV, 4, cin, 1, 1, 8, -1, act=G.ACT_RELU, slot=0, name="in"),
+                 G._node(G.KIND_CONV, cin, cout, 1, 1, 8, 0, act=act, slot=1, name="last"),
+                 G._node(G.KIND_FC, cout, 10, 1, 1, 8, 1, act=G.ACT_NONE, slot=2, name="fc")]
+        rng = np.random.Generator(np.random.PCG64(900 + k))
+        w, b = synth.make_model(nodes, rng)
+        n = 7
+        images = rng.standard_normal((n, 8, 8, 4)).astype(np.float32)
+        desc = synth.desc_array(nodes)
+        ref = oracle.eval_schemes(desc, w, b, images, schemes)
+        m = aiq.Model(desc, w, b)
+        img = torch.from_numpy(images).cuda()
+        for i, q in enumerate(schemes):
+            d = aiq.Deployed(m, q)
+            assert d.code_layers == (1 if q[1] <= 8 else 0), (d.code_layers, q)
+            out = d.forward(img, chunk=4, want_logits=True)
+            torch.cuda.synchronize()
+            err = logits_rel_error(out["logits"].cpu().numpy(), ref["logits"][i])
+            assert err <= LOGIT_REL_TOL, f"{cin}->{cout} scheme {q}: logit relative error {err:.3e}"
+            diff = out["top1"].cpu().numpy() != ref["top1"][i]
+            assert not (diff & ~near_tied(ref["logits"][i])).any()
+            worst = max(worst, err)
+            d.close()
+        m.close()
+        print(f"{cin}->{cout}: ok", flush=True)
+    print("worst logit rel err %.3e" % worst, flush=True)
