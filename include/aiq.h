@@ -348,8 +348,9 @@ aiq_status aiq_forward_nodes(aiq_model *m, const float *images, int32_t N, const
  * inverted-residual block whose expand and project layers both carry at most 8 bits runs with
  * both 1x1 products taken from integer codes inside the block kernel (same three-term
  * arithmetic, v_mfma_f32_16x16x32_bf16 / 16x16x16_bf16; the depthwise layer and the hidden
- * tensor stay fp32), two layers per such block in aiq_deploy_code_layers; results agree with
- * aiq_eval_schemes to fp32 rounding.  Layer-by-layer integer-code layers need
+ * tensor stay fp32), two layers per such block in aiq_deploy_code_layers; a last 1x1 layer of at
+ * most 8 bits on 8x8 pixels that only the classifier reads (its epilogue forms the average pool)
+ * runs from codes as well; results agree with aiq_eval_schemes to fp32 rounding.  Layer-by-layer integer-code layers need
  * AIQ_MODEL_LAYERWISE.  flags: AIQ_DEPLOY_FP32_MATRIX keeps every layer and block on the fp32
  * kernels (the same model without the bf16 path, for comparison; bit-identical to scoring).
  * Quantizes and packs the weights; allocates device memory (codes and scales), freed by
