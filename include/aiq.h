@@ -345,10 +345,11 @@ aiq_status aiq_forward_nodes(aiq_model *m, const float *images, int32_t N, const
  * blocks) is deployed on those kernels - the scheme runs as the single candidate of a scoring
  * call: for such models that is faster than any layer-by-layer path.  The whole-network ResNet
  * kernel stays in fp32 (bit-identical to aiq_eval_schemes, the FP32 model's own rate).  An
- * inverted-residual block whose expand and project layers both carry at most 8 bits runs with
- * both 1x1 products taken from integer codes inside the block kernel (same three-term
- * arithmetic, v_mfma_f32_16x16x32_bf16 / 16x16x16_bf16; the depthwise layer and the hidden
- * tensor stay fp32), two layers per such block in aiq_deploy_code_layers; a last 1x1 layer of at
+ * inverted-residual block whose expand or project layer carries at most 8 bits runs with
+ * those 1x1 products taken from integer codes inside the block kernel (same three-term
+ * arithmetic, v_mfma_f32_16x16x32_bf16 / 16x16x16_bf16; the depthwise layer, the hidden
+ * tensor and a 16- or 32-bit 1x1 layer beside a low-bit one stay fp32), counted per layer in
+ * aiq_deploy_code_layers; a last 1x1 layer of at
  * most 8 bits on 8x8 pixels that only the classifier reads (its epilogue forms the average pool)
  * runs from codes as well; results agree with aiq_eval_schemes to fp32 rounding.  Layer-by-layer integer-code layers need
  * AIQ_MODEL_LAYERWISE.  flags: AIQ_DEPLOY_FP32_MATRIX keeps every layer and block on the fp32

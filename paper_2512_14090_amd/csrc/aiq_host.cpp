@@ -1025,11 +1025,15 @@ aiq_status launch_node(aiq_model *m, hipStream_t st, const HeadOut &ho, size_t l
         io.in = m->aq_cur;
         io.in_stride = (size_t)n * nd.in_elems;
     }
-    if (nd.mb_role == 1 && m->mb_codes_cur && m->mb_codes_cur[l].codes_e && io.S == 1 && io.s_total == 1) {
-        // deployed scheme, expand and project at most eight bits wide: both products from integer codes
+    if (nd.mb_role == 1 && m->mb_codes_cur && (m->mb_codes_cur[l].codes_e || m->mb_codes_cur[l].codes_p) && io.S == 1 &&
+        io.s_total == 1) {
+        // deployed scheme, expand and / or project at most eight bits wide: those products from integer codes
         const Node &dwn = m->nodes[l + 1], &pjn = m->nodes[l + 2];
         const MbCodes &mc = m->mb_codes_cur[l];
-        const int bi_d = dwn.d.scheme_slot >= 0 ? bits_index(m->mb_scheme_cur[dwn.d.scheme_slot]) : 0;
+        auto bank_of = [&](const Node &x) {
+            const int bi = x.d.scheme_slot >= 0 ? bits_index(m->mb_scheme_cur[x.d.scheme_slot]) : 0;
+            return x.bank[bi] ? x.bank[bi] : x.bank[0];
+        };
         MbCodeArgs a{};
         a.in = io.in;
         a.out = io.out;
@@ -1037,7 +1041,9 @@ aiq_status launch_node(aiq_model *m, hipStream_t st, const HeadOut &ho, size_t l
         a.codes_p = mc.codes_p;
         a.scale_e = mc.scale_e;
         a.scale_p = mc.scale_p;
-        a.w_d = dwn.bank[bi_d] ? dwn.bank[bi_d] : dwn.bank[0];
+        a.w_d = bank_of(dwn);
+        a.w_e = bank_of(nd);
+        a.w_p = bank_of(pjn);
         a.bias_e = nd.bias;
         a.bias_d = dwn.bias;
         a.bias_p = pjn.bias;
@@ -1803,9 +1809,9 @@ aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags
         // A model whose activations stay in LDS (whole CIFAR-style ResNets, inverted-residual blocks) is
         // deployed on those kernels, the scheme being the one "candidate" of a scoring call: the layer-by-layer
         // integer-code kernels work through HBM and are slower than that for such models.  The weight bank
-        // slots are filled by the forward call.  Inverted-residual blocks whose expand and project layers both
-        // carry at most eight bits run on the block kernel that takes its two matrix products from integer
-        // codes, and so does a last 1x1 layer of at most eight bits that forms the classifier's pooling in its
+        // slots are filled by the forward call.  Inverted-residual blocks whose expand or project layer carries
+        // at most eight bits run on the block kernel that takes those matrix products from integer codes (a
+        // 16- or 32-bit layer beside one keeps the fp32 MFMA), and so does a last 1x1 layer of at most eight bits that forms the classifier's pooling in its
         // epilogue; what is prepared here are those codes and scales.
         d->resident = true;
         d->mb.resize(m->nodes.size());
@@ -1822,10 +1828,11 @@ aiq_status aiq_deploy_create(aiq_model *m, const uint8_t *scheme, uint32_t flags
                 const Node &e = m->nodes[l];
                 if (e.mb_role == 1 && l + 2 < m->nodes.size()) {
                     const Node &pj = m->nodes[l + 2];
-                    if (e.d.scheme_slot < 0 || pj.d.scheme_slot < 0) continue;
-                    if (scheme[e.d.scheme_slot] > 8 || scheme[pj.d.scheme_slot] > 8 || !mbconv_codes_supported(e.mb_shape)) continue;
-                    jobs.push_back({l, l, 32, (e.d.cout + 15) / 16, false});
-                    jobs.push_back({l + 2, l, 16, (pj.d.cout + 15) / 16, true});
+                    const bool ec = e.d.scheme_slot >= 0 && scheme[e.d.scheme_slot] <= 8;
+                    const bool pc = pj.d.scheme_slot >= 0 && scheme[pj.d.scheme_slot] <= 8;
+                    if (!mbconv_codes_supported(e.mb_shape, ec, pc)) continue;
+                    if (ec) jobs.push_back({l, l, 32, (e.d.cout + 15) / 16, false});
+                    if (pc) jobs.push_back({l + 2, l, 16, (pj.d.cout + 15) / 16, true});
                 } else if (e.pooled && e.d.scheme_slot >= 0 && scheme[e.d.scheme_slot] <= 8) {
                     int cg = 0, groups = 0;
                     if (!pooled_codes_plan(e.d.cin, e.d.cout, &cg, &groups)) continue;

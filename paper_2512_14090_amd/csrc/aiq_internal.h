@@ -296,22 +296,25 @@ struct MbArgs {
 bool mbconv_supported(const MbShape &sh);
 hipError_t launch_mbconv(const MbShape &sh, const MbArgs &a, int s_total, hipStream_t st);
 
-// The same blocks for one deployed scheme whose expand and project layers carry at most eight bits: both
+// The same blocks for one deployed scheme whose expand and / or project layer carries at most eight bits: those
 // matrix products from integer codes on the bf16 matrix pipe (aiq_mbconv_codes.hip).
 struct MbCodeArgs {
     const float *in;         // [N][H][W][CIN]
     float *out;              // [N][HO][WO][COUT]
-    const uint16_t *codes_e; // bf16 bit patterns [HID/16][ceil(CIN/32)][64 lanes][8], zero padded
-    const uint16_t *codes_p; // bf16 bit patterns [ceil(COUT/16)][HID/16][64 lanes][4], zero padded
-    const float *scale_e;    // [HID]
-    const float *scale_p;    // [COUT]
+    const uint16_t *codes_e; // bf16 bit patterns [HID/16][ceil(CIN/32)][64 lanes][8], zero padded; null: expand in fp32 from w_e
+    const uint16_t *codes_p; // bf16 bit patterns [ceil(COUT/16)][HID/16][64 lanes][4], zero padded; null: project in fp32 from w_p
+    const float *scale_e;    // [HID] (with codes_e)
+    const float *scale_p;    // [COUT] (with codes_p)
+    const float *w_e, *w_p;  // fp32 weights of a layer without codes, at its width, in the scoring kernel's MFMA layout
     const float *w_d;        // depthwise weights at the width the scheme gives them, tap-major [9][HID]
     const float *bias_e, *bias_d, *bias_p;
     int32_t N;
     int32_t act_e, act_d, act_p;
 };
 
-bool mbconv_codes_supported(const MbShape &sh);
+// at least one of the two layers on codes; a block with one fp32 layer is covered where the tiling keeps the block
+// input in registers
+bool mbconv_codes_supported(const MbShape &sh, bool expand_codes, bool project_codes);
 hipError_t launch_mbconv_codes(const MbShape &sh, const MbCodeArgs &a, hipStream_t st);
 // A 1x1 layer on 8x8 pixels that writes the per-image mean of its activated outputs (the classifier's pooling),
 // from integer codes.

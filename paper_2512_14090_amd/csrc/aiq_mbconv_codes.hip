@@ -1,6 +1,7 @@
 // Deployed inverted-residual blocks (1x1 expand -> depthwise 3x3 -> 1x1 project, MobileNetV2)
-// whose two 1x1 layers carry at most eight bits: the block kernel of aiq_mbconv.hip with the
-// two matrix products taken from integer codes on the bf16 matrix pipe.
+// with 1x1 layers of at most eight bits: the block kernel of aiq_mbconv.hip with the matrix
+// products of those layers taken from integer codes on the bf16 matrix pipe (a 16- or 32-bit
+// 1x1 layer beside a low-bit one keeps the fp32 MFMA of the scoring kernel).
 //
 // The paper deploys the searched scheme and compares end-to-end throughput with the FP32 model,
 // MobileNetV2 being its headline case (Implementation, experiment (3); Results, Analysis of AIQ
@@ -177,10 +178,15 @@ hipError_t launch_pack_mb_codes(const int32_t *codes, uint16_t *out, int rows, i
 
 // ------------------------------------------------------------------ the block kernel
 
-template <class C>
+// EC / PC: the expand / project layer runs from codes; a layer of 16 or 32 bits beside a low-bit one keeps its
+// quantize-dequantized fp32 weights and the fp32 MFMA of the scoring kernel (its operand then needs no split).
+template <class C, bool EC, bool PC>
 __global__ __launch_bounds__(C::THREADS) __attribute__((amdgpu_waves_per_eu(C::WAVES_PER_SIMD, C::WAVES_PER_SIMD)))
 void mbconv_codes_kernel(MbCodeArgs a)
 {
+    static_assert(EC || PC, "at least one layer on codes");
+    static_assert(EC || C::XREG, "an fp32 expand layer keeps the block input in registers");
+    constexpr int CB = (C::CIN + 15) / 16; // 16-channel steps of an fp32 expand product
     extern __shared__ float lds[];
     char *X = reinterpret_cast<char *>(lds);
     float *E = lds + C::X_BYTES / 4;
@@ -199,7 +205,8 @@ void mbconv_codes_kernel(MbCodeArgs a)
     const int h0 = C::HS > 1 ? (wave % C::HS) * C::HTW : 0;
     bool x_ok[C::XT];
     int e_off[C::XT], x_pix[C::XT];
-    uintx4 xr[C::XREG ? C::XT : 1][C::XREG ? C::KS : 1][3];
+    uintx4 xr[(C::XREG && EC) ? C::XT : 1][(C::XREG && EC) ? C::KS : 1][3];
+    floatx4 xf[EC ? 1 : C::XT][EC ? 1 : CB];
 #pragma unroll
     for (int k = 0; k < C::XT; ++k) {
         const int e = C::HS > 1 ? wave / C::HS : wave + k * C::NW;
@@ -214,7 +221,15 @@ void mbconv_codes_kernel(MbCodeArgs a)
         x_ok[k] = e < n_exp_tiles;
         e_off[k] = (g * C::EPIX + r * C::EW + x + 1) * 4 + kq * C::EPL;
         x_pix[k] = (g * C::XROWS + (r - C::XOFF)) * C::W + x;
-        if (C::XREG) {
+        if (!EC) {
+            const int img = img0 + g;
+            const float *px = a.in + (((size_t)img * C::H + (iy0 + r)) * C::W + x) * C::CIN;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                const int ch = cb * 16 + kq * 4;
+                xf[EC ? 0 : k][EC ? 0 : cb] = (x_ok[k] && img < a.N && ch < C::CIN) ? mc_gload4(px + ch) : floatx4{0.f, 0.f, 0.f, 0.f};
+            }
+        } else if (C::XREG) {
             const int img = img0 + g;
             const float *px = a.in + (((size_t)img * C::H + (iy0 + r)) * C::W + x) * C::CIN;
 #pragma unroll
@@ -225,7 +240,7 @@ void mbconv_codes_kernel(MbCodeArgs a)
                     v0 = mc_gload4(px + ch);
                     v1 = mc_gload4(px + ch + 4);
                 }
-                mc_split8(v0, v1, xr[C::XREG ? k : 0][C::XREG ? ks : 0]);
+                mc_split8(v0, v1, xr[(C::XREG && EC) ? k : 0][(C::XREG && EC) ? ks : 0]);
             }
         }
     }
@@ -233,7 +248,7 @@ void mbconv_codes_kernel(MbCodeArgs a)
     // ---- clear E (borders and out-of-image rows stay zero for good); stage X unless it is in registers
     for (int i = tid; i < 2 * C::E_FLOATS / 4; i += C::THREADS)
         reinterpret_cast<floatx4 *>(E)[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-    if (!C::XREG) {
+    if (!C::XREG && EC) {
         // item = eight channels of one pixel: two 16-byte global reads, one 16-byte LDS write per term;
         // units past CIN are written as zeros (they meet zero codes, but must not hold NaN patterns)
         const int per_img = nrows * C::W * C::UNITS;
@@ -297,22 +312,31 @@ void mbconv_codes_kernel(MbCodeArgs a)
     // Weights of one expand step of this wavefront: bias, scale and the code operands of its hidden tiles.
     constexpr bool EPRE = C::EPRE;
     struct ExpW {
-        floatx4 be[C::HTW], se[C::HTW];
-        uintx4 wa[EPRE ? C::HTW : 1][EPRE ? C::KS : 1];
+        floatx4 be[C::HTW], se[EC ? C::HTW : 1];
+        uintx4 wa[(EPRE && EC) ? C::HTW : 1][(EPRE && EC) ? C::KS : 1];
+        floatx4 wf[(EPRE && !EC) ? C::HTW : 1][(EPRE && !EC) ? CB : 1];
     };
     auto load_expw = [&](int c, ExpW &w) {
 #pragma unroll
         for (int h = 0; h < C::HTW; ++h) {
             w.be[h] = mc_gload4(a.bias_e + (c * C::HT + h0 + h) * 16 + kq * 4);
-            w.se[h] = mc_gload4(a.scale_e + (c * C::HT + h0 + h) * 16 + kq * 4);
+            if (EC) w.se[EC ? h : 0] = mc_gload4(a.scale_e + (c * C::HT + h0 + h) * 16 + kq * 4);
         }
-        if (EPRE) {
+        if (EPRE && !EC) {
+            const float *wc = a.w_e + ((size_t)(c * C::HT + h0) * CB * 64 + lane) * 4;
+#pragma unroll
+            for (int h = 0; h < C::HTW; ++h)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    w.wf[(EPRE && !EC) ? h : 0][(EPRE && !EC) ? cb : 0] = mc_gload4(wc + (size_t)((h * CB + cb) * 64) * 4);
+        }
+        if (EPRE && EC) {
             const uint16_t *wc = a.codes_e + ((size_t)(c * C::HT + h0) * C::KS * 64 + lane) * 8;
 #pragma unroll
             for (int h = 0; h < C::HTW; ++h)
 #pragma unroll
                 for (int ks = 0; ks < C::KS; ++ks)
-                    w.wa[EPRE ? h : 0][EPRE ? ks : 0] = mc_gload_u4(wc + (size_t)((h * C::KS + ks) * 64) * 8);
+                    w.wa[(EPRE && EC) ? h : 0][(EPRE && EC) ? ks : 0] = mc_gload_u4(wc + (size_t)((h * C::KS + ks) * 64) * 8);
         }
     };
     // expand of hidden chunk c into E buffer eb
@@ -325,20 +349,40 @@ void mbconv_codes_kernel(MbCodeArgs a)
             floatx4 ea[C::HTW];
 #pragma unroll
             for (int h = 0; h < C::HTW; ++h) ea[h] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (!EC) {
+                const float *wcf = a.w_e + ((size_t)(c * C::HT + h0) * CB * 64 + lane) * 4;
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    const floatx4 xb = xf[EC ? 0 : k][EC ? 0 : cb];
+                    floatx4 wa[C::HTW];
+#pragma unroll
+                    for (int h = 0; h < C::HTW; ++h)
+                        wa[h] = EPRE ? w.wf[(EPRE && !EC) ? h : 0][(EPRE && !EC) ? cb : 0] : mc_gload4(wcf + (size_t)((h * CB + cb) * 64) * 4);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int h = 0; h < C::HTW; ++h)
+                            ea[h] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[h][j], xb[j], ea[h], 0, 0, 0);
+                }
+#pragma unroll
+                for (int h = 0; h < C::HTW; ++h)
+                    *reinterpret_cast<floatx4 *>(Eb + h * 4 * C::EPL + e_off[k]) = mc_clamp4(ea[h] + w.be[h], lo_e, hi_e);
+                continue;
+            }
 #pragma unroll
             for (int ks = 0; ks < C::KS; ++ks) {
                 uintx4 xb[3];
 #pragma unroll
                 for (int t = 0; t < 3; ++t) {
                     if (C::XREG)
-                        xb[t] = xr[C::XREG ? k : 0][C::XREG ? ks : 0][t];
+                        xb[t] = xr[(C::XREG && EC) ? k : 0][(C::XREG && EC) ? ks : 0][t];
                     else
                         xb[t] = *reinterpret_cast<const uintx4 *>(X + ((size_t)(ks * 3 + t) * C::NPX + x_pix[k]) * 64 + kq * 16);
                 }
                 uintx4 wa[C::HTW];
 #pragma unroll
                 for (int h = 0; h < C::HTW; ++h)
-                    wa[h] = EPRE ? w.wa[EPRE ? h : 0][EPRE ? ks : 0] : mc_gload_u4(wc + (size_t)((h * C::KS + ks) * 64) * 8);
+                    wa[h] = EPRE ? w.wa[(EPRE && EC) ? h : 0][(EPRE && EC) ? ks : 0] : mc_gload_u4(wc + (size_t)((h * C::KS + ks) * 64) * 8);
 #pragma unroll
                 for (int t = 0; t < 3; ++t)
 #pragma unroll
@@ -348,22 +392,27 @@ void mbconv_codes_kernel(MbCodeArgs a)
             }
 #pragma unroll
             for (int h = 0; h < C::HTW; ++h)
-                *reinterpret_cast<floatx4 *>(Eb + h * 4 * C::EPL + e_off[k]) = mc_clamp4(ea[h] * w.se[h] + w.be[h], lo_e, hi_e);
+                *reinterpret_cast<floatx4 *>(Eb + h * 4 * C::EPL + e_off[k]) = mc_clamp4(ea[h] * w.se[EC ? h : 0] + w.be[h], lo_e, hi_e);
         }
     };
 
     // Weights of one 16-channel hidden block for the depthwise + project step.
     struct DwW {
         floatx4 wd[9], bd;
-        uintx2 wp[C::CTW];
+        uintx2 wp[PC ? C::CTW : 1];
+        floatx4 wpf[PC ? 1 : C::CTW];
     };
     auto load_dww = [&](int hb, DwW &w) {
 #pragma unroll
         for (int t = 0; t < 9; ++t) w.wd[t] = mc_gload4(a.w_d + (size_t)t * C::HID + hb * 16 + kq * 4);
         w.bd = mc_gload4(a.bias_d + hb * 16 + kq * 4);
 #pragma unroll
-        for (int i = 0; i < C::CTW; ++i)
-            w.wp[i] = mc_gload_u2(a.codes_p + (((size_t)(ct0 + i) * C::HB + hb) * 64 + lane) * 4);
+        for (int i = 0; i < C::CTW; ++i) {
+            if (PC)
+                w.wp[PC ? i : 0] = mc_gload_u2(a.codes_p + (((size_t)(ct0 + i) * C::HB + hb) * 64 + lane) * 4);
+            else
+                w.wpf[PC ? 0 : i] = mc_gload4(a.w_p + (((size_t)(ct0 + i) * C::HB + hb) * 64 + lane) * 4);
+        }
     };
     auto dw_project = [&](int sb, int eb, const DwW &w) {
         const float *Eb = E + eb * C::E_FLOATS + sb * 4 * C::EPL + e_base[0];
@@ -384,13 +433,22 @@ void mbconv_codes_kernel(MbCodeArgs a)
             }
 #pragma unroll
         for (int m = 0; m < C::MT; ++m) {
+            const floatx4 dc = mc_clamp4(d[m], lo_d, hi_d);
+            if (!PC) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int i = 0; i < C::CTW; ++i)
+                        acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w.wpf[PC ? 0 : i][j], dc[j], acc[m][i], 0, 0, 0);
+                continue;
+            }
             uintx2 t[3];
-            mc_split4(mc_clamp4(d[m], lo_d, hi_d), t);
+            mc_split4(dc, t);
 #pragma unroll
             for (int j = 0; j < 3; ++j)
 #pragma unroll
                 for (int i = 0; i < C::CTW; ++i)
-                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, w.wp[i]),
+                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, w.wp[PC ? i : 0]),
                                                                           __builtin_bit_cast(shortx4, t[j]), acc[m][i], 0, 0, 0);
         }
     };
@@ -437,14 +495,15 @@ void mbconv_codes_kernel(MbCodeArgs a)
     for (int i = 0; i < C::CTW; ++i) {
         const int co = (ct0 + i) * 16 + kq * 4;
         if (co >= C::COUT) continue;
-        const floatx4 bp = mc_gload4(a.bias_p + co), sp = mc_gload4(a.scale_p + co);
+        const floatx4 bp = mc_gload4(a.bias_p + co);
+        const floatx4 sp = PC ? mc_gload4(a.scale_p + co) : floatx4{1.f, 1.f, 1.f, 1.f};
 #pragma unroll
         for (int m = 0; m < C::MT; ++m) {
             const int img = img0 + o_g[m];
             if (img >= a.N) continue;
             const int oy = band * C::R + o_y[m];
             const size_t o = (((size_t)img * C::HO + oy) * C::WO + o_x[m]) * C::COUT + co;
-            floatx4 v = acc[m][i] * sp + bp;
+            floatx4 v = PC ? acc[m][i] * sp + bp : acc[m][i] + bp;
             if (C::RES) v += mc_gload4(a.in + o); // same shape as the output
             *reinterpret_cast<floatx4 *>(a.out + o) = mc_clamp4(v, lo_p, hi_p);
         }
@@ -616,28 +675,45 @@ bool mc_matches(const MbShape &sh)
            (sh.res != 0) == C::RES;
 }
 
-template <class C>
-hipError_t mc_launch(const MbCodeArgs &a, hipStream_t st)
+template <class C, bool EC, bool PC>
+hipError_t mc_launch_as(const MbCodeArgs &a, hipStream_t st)
 {
     static bool lds_set = false;
     if (!lds_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&mbconv_codes_kernel<C>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&mbconv_codes_kernel<C, EC, PC>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
         lds_set = true;
     }
     const unsigned gx = (unsigned)((a.N + C::G - 1) / C::G) * C::BANDS;
-    hipLaunchKernelGGL((mbconv_codes_kernel<C>), dim3(gx), dim3(C::THREADS), C::LDS_BYTES, st, a);
+    hipLaunchKernelGGL((mbconv_codes_kernel<C, EC, PC>), dim3(gx), dim3(C::THREADS), C::LDS_BYTES, st, a);
     return hipGetLastError();
+}
+
+// a block with one fp32 layer needs the block input in registers
+template <class C>
+constexpr bool mc_mixed_ok() { return C::XREG; }
+
+template <class C>
+hipError_t mc_launch(const MbCodeArgs &a, hipStream_t st)
+{
+    const bool ec = a.codes_e != nullptr, pc = a.codes_p != nullptr;
+    if (ec && pc) return mc_launch_as<C, true, true>(a, st);
+    if constexpr (C::XREG) {
+        if (ec) return mc_launch_as<C, true, false>(a, st);
+        if (pc) return mc_launch_as<C, false, true>(a, st);
+    }
+    return hipErrorInvalidValue;
 }
 
 } // namespace
 
 #define AIQ_MC_CONFIGS(F) F(Mc0) F(Mc1) F(Mc2) F(Mc3) F(Mc4) F(Mc5) F(Mc6) F(Mc7) F(Mc8) F(Mc9) F(Mc10)
 
-bool mbconv_codes_supported(const MbShape &sh)
+bool mbconv_codes_supported(const MbShape &sh, bool expand_codes, bool project_codes)
 {
-#define AIQ_MC_MATCH(C) if (mc_matches<C>(sh)) return true;
+    if (!expand_codes && !project_codes) return false;
+#define AIQ_MC_MATCH(C) if (mc_matches<C>(sh)) return (expand_codes && project_codes) || mc_mixed_ok<C>();
     AIQ_MC_CONFIGS(AIQ_MC_MATCH)
 #undef AIQ_MC_MATCH
     return false;

@@ -331,19 +331,31 @@ hipError_t launch_mbconv(const MbShape &sh, const MbArgs &a, int s_total, hipStr
     return hipSuccess;
 }
 
-bool mbconv_codes_supported(const MbShape &sh) { return mbconv_supported(sh); }
+bool mbconv_codes_supported(const MbShape &sh, bool expand_codes, bool project_codes)
+{
+    if (!expand_codes && !project_codes) return false;
+    return mbconv_supported(sh) && ((expand_codes && project_codes) || sh.cout != 320);
+}
 
 hipError_t launch_mbconv_codes(const MbShape &sh, const MbCodeArgs &a, hipStream_t)
 {
     ++g_launches;
-    if (!mbconv_codes_supported(sh)) return hipErrorInvalidValue;
+    if (!mbconv_codes_supported(sh, a.codes_e != nullptr, a.codes_p != nullptr)) return hipErrorInvalidValue;
     const int ho = sh.h / sh.stride;
     touch_read(a.in, (size_t)a.N * sh.h * sh.h * sh.cin);
     touch_write(a.out, (size_t)a.N * ho * ho * sh.cout);
-    touch_read(a.codes_e, (size_t)(sh.hid / 16) * ((sh.cin + 31) / 32) * 512);
-    touch_read(a.codes_p, (size_t)((sh.cout + 15) / 16) * (sh.hid / 16) * 256);
-    touch_read(a.scale_e, (size_t)sh.hid);
-    touch_read(a.scale_p, (size_t)sh.cout);
+    if (a.codes_e) {
+        touch_read(a.codes_e, (size_t)(sh.hid / 16) * ((sh.cin + 31) / 32) * 512);
+        touch_read(a.scale_e, (size_t)sh.hid);
+    } else {
+        touch_read(a.w_e, (size_t)((sh.hid + 15) / 16) * 16 * ((sh.cin + 15) / 16) * 16);
+    }
+    if (a.codes_p) {
+        touch_read(a.codes_p, (size_t)((sh.cout + 15) / 16) * (sh.hid / 16) * 256);
+        touch_read(a.scale_p, (size_t)sh.cout);
+    } else {
+        touch_read(a.w_p, (size_t)((sh.cout + 15) / 16) * 16 * ((sh.hid + 15) / 16) * 16);
+    }
     touch_read(a.w_d, (size_t)9 * sh.hid);
     touch_read(a.bias_e, (size_t)sh.hid);
     touch_read(a.bias_d, (size_t)sh.hid);
