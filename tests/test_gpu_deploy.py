@@ -356,3 +356,39 @@ def test_last_1x1_layer_with_pooling_from_integer_codes(env):
         m.close()
         print(f"{cin}->{cout}: ok", flush=True)
     print("worst logit rel err %.3e" % worst, flush=True)
+
+
+@pytest.mark.parametrize("index", [3, 8])
+def test_mobilenetv2_full_size_sampled_from_integer_codes(env, index):
+    """The configuration the deployment benchmark times on MobileNetV2 (2048 images in one chunk, every layer at 8
+    bits: 33 layers from integer codes inside the block kernels; and a mixed scheme), on sampled images including
+    the first and last of the launch; on the model with the centred classifier also the agreement with FP32."""
+    torch, aiq, oracle = env["torch"], env["aiq"], env["oracle"]
+    wl = env["synth"].make_workload(index, n_images=2048)
+    L = wl["L"]
+    rng = np.random.Generator(np.random.PCG64(77))
+    mixed = rng.choice(np.array([32, 8, 4], np.uint8), size=L)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"])
+    img = torch.from_numpy(wl["images"]).cuda()
+    sample = np.array([0, 1, 2, 255, 256, 511, 512, 1000, 1023, 1024, 1025, 2046, 2047])
+    for q, layers in ((np.full(L, 8, np.uint8), 33), (mixed, None)):
+        d = aiq.Deployed(m, q)
+        if layers is not None:
+            assert d.code_layers == layers
+        r = d.forward(img, chunk=2048, want_logits=True)
+        torch.cuda.synchronize()
+        ref = oracle.eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"][sample], q[None, :])
+        if index == 8:
+            # centred classifier: every logit is a small difference of the classifier's response and a bias of about
+            # the same size, so the response (logit minus bias) is what the 1e-3 bar is applied to (parity.py), and
+            # the integer decision must be the argmax of the GPU's own logits
+            b = np.asarray(wl["biases"][-1], np.float64)
+            zg = r["logits"].cpu().numpy().astype(np.float64)
+            err = logits_rel_error(zg[sample][None] - b, ref["logits"] - b)
+            assert err <= LOGIT_REL_TOL, err
+            np.testing.assert_array_equal(r["top1"].cpu().numpy(), zg.argmax(axis=1))
+        else:
+            err = _check(r["logits"].cpu().numpy()[sample][None], r["top1"].cpu().numpy()[sample][None], ref)
+        print("workload %d: %d layers on codes, sampled error %.3e" % (index, d.code_layers, err), flush=True)
+        d.close()
+    m.close()
