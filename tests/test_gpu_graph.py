@@ -84,3 +84,47 @@ def test_captured_scoring_call_replays_bit_for_bit(env, index):
         _same(torch, want[which], out)
     del graph
     m.close()
+
+
+@pytest.mark.parametrize("index,layerwise,act_quant", [(3, False, False), (5, True, False), (5, False, True)])
+def test_captured_deployed_forward_replays_bit_for_bit(env, index, layerwise, act_quant):
+    """aiq_deploy_forward launches kernels only once its workspace exists (the binding allocates it on the first
+    call), so a serving loop may record a forward and replay it: MobileNetV2 on its block kernels from integer codes,
+    PlainConvNet20 layer by layer on bf16 codes, and its activation variant on int8 codes (whose per-image maxima are
+    cleared by a fill kernel inside the recording).  Replays with other eager work between them and with new images
+    in the recorded input tensor give what the eager call gives."""
+    torch, aiq = env["torch"], env["aiq"]
+    N = 24
+    wl = env["synth"].make_workload(index, n_images=2 * N)
+    L = wl["L"]
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"], layerwise=layerwise, act_quant=act_quant)
+    d = aiq.Deployed(m, np.full(L, 8, np.uint8))
+    assert d.code_layers > 0
+    all_img = torch.from_numpy(wl["images"]).cuda()
+    img = all_img[:N].clone()
+    want = []
+    for part in (all_img[:N], all_img[N:]):
+        r = d.forward(part, chunk=N, want_logits=True)
+        torch.cuda.synchronize()
+        want.append({k: r[k].clone() for k in ("logits", "top1")})
+    out = {"logits": torch.full((N, m.classes), -9.0, device="cuda"), "top1": torch.full((N,), -9, dtype=torch.int32, device="cuda")}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    print(f"capturing: deployed workload {index}, layerwise={layerwise}, act_quant={act_quant}, N={N}", flush=True)
+    with torch.cuda.graph(graph, stream=side):
+        d.forward(img, chunk=N, want_logits=True, out=out, stream=side)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for v in out.values():
+            v.fill_(-7)
+        d.forward(all_img[3:20], chunk=17)  # eager work on the same deployment (its workspace) between the replays
+        which = 0 if rep < 2 else 1
+        img.copy_(all_img[:N] if which == 0 else all_img[N:])
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out["top1"], want[which]["top1"]), rep
+        assert torch.equal(out["logits"].view(torch.int32), want[which]["logits"].view(torch.int32)), rep
+    d.close()
+    m.close()
