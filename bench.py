@@ -494,6 +494,30 @@ def deploy_mode(args, torch, aiq, synth):
                             "avg_launch_ms": kc["avg_launch_ms"],
                             "hbm": {"achieved": kc["algorithmic_gbytes_per_s"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                     "frac": kc["frac_of_hbm_peak"]}}
+    hb = head.get("block_kernels")
+    if hb and head.get("code_layers"):
+        # the headline path runs the inverted-residual blocks from integer codes: that kernel is the dominant one.
+        # Executed matrix work = three bf16 products per multiply-add of the blocks' 1x1 layers on codes (an upper
+        # bound when some 1x1 layers of the scheme stay fp32); the depthwise layers run on the vector ALU.
+        nodes = wl["nodes"]
+        dw_flops = sum(2.0 * 9 * nd["cout"] * (nd["hin"] // nd["stride"]) ** 2 for i, nd in enumerate(nodes)
+                       if nd["kind"] == 1 and i > 0 and nodes[i - 1]["kind"] == 0 and nodes[i - 1]["kh"] == 1 and nodes[i - 1]["input"] >= 0)
+        total_flops = hb["fp32_equivalent_tflops"] * 1e12 * hb["total_ms"] * 1e-3
+        bf16_tflops = 3.0 * (total_flops - dw_flops * n_img) / (hb["total_ms"] * 1e-3) / 1e12
+        bytes_blocks = sum(4.0 * n_img * (nodes[i - 1]["cin"] * nodes[i - 1]["hin"] ** 2 +
+                                          nodes[i + 1]["cout"] * (nd["hin"] // nd["stride"]) ** 2 * (2 if nodes[i + 1]["residual"] >= 0 else 1))
+                           for i, nd in enumerate(nodes)
+                           if nd["kind"] == 1 and i > 0 and nodes[i - 1]["kind"] == 0 and nodes[i - 1]["kh"] == 1 and nodes[i - 1]["input"] >= 0)
+        line["roofline"] = {"bound": "mfma", "kernel": "mbconv_codes_kernel (1x1 layers as 3 bf16 MFMA products per multiply-add, "
+                            "depthwise on the vector ALU, hidden tensor in LDS)",
+                            "achieved": bf16_tflops, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
+                            "frac": bf16_tflops / PEAK_MFMA_BF16_TFLOPS, "traffic": None,
+                            "launches": hb["launches"], "avg_launch_ms": hb["total_ms"] / hb["launches"],
+                            "fp32_equivalent_tflops": hb["fp32_equivalent_tflops"],
+                            "frac_of_fp32_mfma_peak": hb["fp32_equivalent_tflops"] / PEAK_MFMA_F32_TFLOPS,
+                            "algorithmic_gbytes_per_launch": bytes_blocks / hb["launches"] / 1e9,
+                            "hbm": {"achieved": bytes_blocks / (hb["total_ms"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                    "frac": bytes_blocks / (hb["total_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS}}
     model.close()
     best.close()
     aqmodel.close()
