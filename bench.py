@@ -53,6 +53,11 @@ TRAFFIC = {
         "sha256": "65306e5f64c86191366076a01f054998d26a006ea5a6f76f4c822b9d15c7217d",
         "bytes_per_launch_runs": [495600000, 495800000],
     },
+    ("mobilenetv2_deploy_n2048", "mbconv_codes"): {  # average over the 16 block launches of one deployed forward pass
+        "kernel_source": "paper_2512_14090_amd/csrc/aiq_mbconv_codes.hip",
+        "sha256": "db9dc30fef7ce7a97763948e602514ce3b50c666e6c93b315e39fb2d270def02",
+        "bytes_per_launch_runs": [463676736, 463686784],
+    },
     ("quantize_stress_8192x4608_b8", "quantize"): {
         "kernel_source": "paper_2512_14090_amd/csrc/aiq_kernels.hip",
         "sections": ["helpers", "quantizer"],
@@ -511,7 +516,9 @@ def deploy_mode(args, torch, aiq, synth):
         line["roofline"] = {"bound": "mfma", "kernel": "mbconv_codes_kernel (1x1 layers as 3 bf16 MFMA products per multiply-add, "
                             "depthwise on the vector ALU, hidden tensor in LDS)",
                             "achieved": bf16_tflops, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
-                            "frac": bf16_tflops / PEAK_MFMA_BF16_TFLOPS, "traffic": None,
+                            "frac": bf16_tflops / PEAK_MFMA_BF16_TFLOPS,
+                            "traffic": measured_traffic(line["config"]["workload"], "mbconv_codes"),
+                            "traffic_min_max": traffic_min_max(line["config"]["workload"], "mbconv_codes"),
                             "launches": hb["launches"], "avg_launch_ms": hb["total_ms"] / hb["launches"],
                             "fp32_equivalent_tflops": hb["fp32_equivalent_tflops"],
                             "frac_of_fp32_mfma_peak": hb["fp32_equivalent_tflops"] / PEAK_MFMA_F32_TFLOPS,
