@@ -392,3 +392,27 @@ def test_mobilenetv2_full_size_sampled_from_integer_codes(env, index):
         print("workload %d: %d layers on codes, sampled error %.3e" % (index, d.code_layers, err), flush=True)
         d.close()
     m.close()
+
+
+def test_per_tensor_scales_on_block_kernels(env):
+    """One quantization scale per layer on a model deployed on its block kernels: the codes and the (constant)
+    scale vectors of the blocks' 1x1 layers and of the pooled last layer come from the per-tensor quantizer."""
+    torch, aiq, oracle = env["torch"], env["aiq"], env["oracle"]
+    wl = env["synth"].make_workload(3, n_images=10)
+    L = wl["L"]
+    rng = np.random.Generator(np.random.PCG64(31))
+    schemes = np.stack([np.full(L, 8, np.uint8), rng.choice(np.array([32, 8, 6, 4], np.uint8), size=L)])
+    ref = oracle.eval_schemes(wl["desc"], wl["weights"], wl["biases"], wl["images"], schemes, per_tensor=True)
+    m = aiq.Model(wl["desc"], wl["weights"], wl["biases"], per_tensor=True)
+    assert m.lds_resident_blocks == 16
+    img = torch.from_numpy(wl["images"]).cuda()
+    for i, q in enumerate(schemes):
+        d = aiq.Deployed(m, q)
+        assert d.code_layers > 0
+        out = d.forward(img, chunk=6, want_logits=True)
+        torch.cuda.synchronize()
+        err = _check(out["logits"].cpu().numpy()[None], out["top1"].cpu().numpy()[None],
+                     dict(logits=ref["logits"][i][None], top1=ref["top1"][i][None]))
+        print("scheme %d: %d layers on codes, logit rel err %.3e" % (i, d.code_layers, err), flush=True)
+        d.close()
+    m.close()
