@@ -379,6 +379,16 @@ def deploy_mode(args, torch, aiq, synth):
     top1_fp32 = None
     for name, q in schemes.items():
         row = {"scheme": [int(v) for v in q]}
+        # weights a deployment of the scheme holds in HBM: 2 bytes per weight of a dense layer on bf16 codes (1 byte on the
+        # int8 codes of the activation variant), 4 bytes elsewhere (a layer's quantize-dequantized fp32 copy)
+        def weight_bytes(code_bytes):
+            total = 0
+            for nd in wl["nodes"]:
+                k = nd["kh"] * nd["kw"] * (1 if nd["kind"] == 1 else nd["cin"])
+                on_codes = nd["kind"] == 0 and nd["input"] >= 0 and nd["scheme_slot"] >= 0 and q[nd["scheme_slot"]] <= 8
+                total += nd["cout"] * k * (code_bytes if on_codes else 4)
+            return total
+        row["weight_bytes"] = {"fp32": weight_bytes(4), "bf16_codes": weight_bytes(2), "int8_codes": weight_bytes(1)}
         for variant in (("bf16_codes", False), ("fp32_matrix", True)):
             if name == "fp32" and not variant[1]:
                 continue
